@@ -1,0 +1,165 @@
+"""ctypes wrapper around oracle/libpod_oracle.so (the CPU oracle, test infrastructure only).
+
+Marshalling only: every number comes out of pod_oracle.c.  bf16 tensors travel as
+numpy uint16 arrays holding the raw bit patterns; outputs are float64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+OK, ERR_ARG, ERR_CAPACITY, ERR_STATE = 0, -1, -2, -3
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        u16p, i32p, f64p, lp = (C.POINTER(C.c_uint16), C.POINTER(C.c_int32),
+                                C.POINTER(C.c_double), C.POINTER(C.c_long))
+        L.oracle_pod_attention.restype = C.c_int
+        L.oracle_pod_attention.argtypes = [C.c_long, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_double, u16p, u16p, u16p, u16p, u16p, lp, C.c_long, f64p]
+        L.oracle_pod_attention_gate.restype = C.c_int
+        L.oracle_pod_attention_gate.argtypes = L.oracle_pod_attention.argtypes + [f64p]
+        L.oracle_cache_create.restype = C.c_void_p
+        L.oracle_cache_create.argtypes = [C.c_int] * 7 + [C.c_long]
+        L.oracle_cache_destroy.restype = None
+        L.oracle_cache_destroy.argtypes = [C.c_void_p]
+        L.oracle_cache_len.restype = C.c_long
+        L.oracle_cache_len.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        L.oracle_cache_append.restype = C.c_int
+        L.oracle_cache_append.argtypes = [C.c_void_p, C.c_int, u16p, u16p, i32p, C.c_int]
+        L.oracle_cache_fill.restype = C.c_int
+        L.oracle_cache_fill.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, u16p, u16p]
+        L.oracle_cache_export.restype = C.c_int
+        L.oracle_cache_export.argtypes = [C.c_void_p, C.c_int, C.c_int, lp] + [u16p] * 6
+        L.oracle_cache_stored_elems.restype = C.c_long
+        L.oracle_cache_stored_elems.argtypes = [C.c_void_p]
+        L.oracle_cache_bytes_formula.restype = None
+        L.oracle_cache_bytes_formula.argtypes = [C.c_int] * 6 + [C.c_long, C.c_int, f64p, f64p]
+        L.oracle_decode_attention.restype = C.c_int
+        L.oracle_decode_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, u16p, u16p,
+                                              i32p, C.c_int, f64p]
+        L.oracle_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _u16(a):
+    if a is None:
+        return None
+    assert a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.POINTER(C.c_uint16))
+
+
+def _chk(rc, what):
+    if rc != OK:
+        raise OracleError(rc, what)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: oracle error {code}")
+        self.code = code
+
+
+def num_threads() -> int:
+    return lib().oracle_num_threads()
+
+
+def pod_attention(q, k, v, q_shared, k_shared, rows, S, W, scale, gate=False):
+    """Attention by definition.  q/q_shared: uint16 [nrows][Hq][d]; k/v/k_shared: uint16 [n][Hkv][d];
+    rows: positions of the query rows.  Returns float64 [nrows][Hq][d] (and the gate if asked)."""
+    n, Hkv, d = k.shape
+    nrows, Hq, _ = q.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.shape == (nrows,)
+    out = np.empty((nrows, Hq, d), dtype=np.float64)
+    rp = rows.ctypes.data_as(C.POINTER(C.c_long))
+    op = out.ctypes.data_as(C.POINTER(C.c_double))
+    if gate:
+        g = np.empty((nrows, Hq), dtype=np.float64)
+        rc = lib().oracle_pod_attention_gate(n, Hq, Hkv, d, S, W, float(scale), _u16(q), _u16(k), _u16(v),
+                                             _u16(q_shared), _u16(k_shared), rp, nrows, op,
+                                             g.ctypes.data_as(C.POINTER(C.c_double)))
+        _chk(rc, "oracle_pod_attention_gate")
+        return out, g
+    rc = lib().oracle_pod_attention(n, Hq, Hkv, d, S, W, float(scale), _u16(q), _u16(k), _u16(v),
+                                    _u16(q_shared), _u16(k_shared), rp, nrows, op)
+    _chk(rc, "oracle_pod_attention")
+    return out
+
+
+def cache_bytes_formula(L, G, Hkv, d, S, W, n, elem_bytes=2):
+    p, dn = C.c_double(), C.c_double()
+    lib().oracle_cache_bytes_formula(L, G, Hkv, d, S, W, n, elem_bytes, C.byref(p), C.byref(dn))
+    return p.value, dn.value
+
+
+class Cache:
+    """Logical model of the split cache (lists per layer and sequence)."""
+
+    def __init__(self, L, G, Hkv, d, S, W, B, max_ctx):
+        self.L, self.G, self.Hkv, self.d, self.S, self.W, self.B, self.max_ctx = L, G, Hkv, d, S, W, B, max_ctx
+        self._h = lib().oracle_cache_create(L, G, Hkv, d, S, W, B, max_ctx)
+        if not self._h:
+            raise OracleError(ERR_ARG, "oracle_cache_create")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().oracle_cache_destroy(self._h)
+            self._h = None
+
+    def length(self, layer, seq):
+        return lib().oracle_cache_len(self._h, layer, seq)
+
+    def append(self, layer, k_new, v_new, positions):
+        positions = np.ascontiguousarray(positions, dtype=np.int32)
+        B = positions.shape[0]
+        assert k_new.shape == (B, self.Hkv, self.d) and v_new.shape == k_new.shape
+        rc = lib().oracle_cache_append(self._h, layer, _u16(k_new), _u16(v_new),
+                                       positions.ctypes.data_as(C.POINTER(C.c_int32)), B)
+        _chk(rc, "oracle_cache_append")
+
+    def fill(self, layer, seq, k, v):
+        n = k.shape[0]
+        assert k.shape == (n, self.Hkv, self.d) and v.shape == k.shape
+        _chk(lib().oracle_cache_fill(self._h, layer, seq, n, _u16(k), _u16(v)), "oracle_cache_fill")
+
+    def export(self, layer, seq):
+        """dict of uint16 arrays [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV and,
+        at a block's lowest layer, distK."""
+        counts = (C.c_long * 3)()
+        _chk(lib().oracle_cache_export(self._h, layer, seq, counts, *([None] * 6)), "oracle_cache_export")
+        ns, nr, nd = counts[0], counts[1], counts[2]
+        mk = lambda t: np.zeros((t, self.Hkv, self.d), dtype=np.uint16)
+        out = dict(sinkK=mk(ns), sinkV=mk(ns), recentK=mk(nr), recentV=mk(nr), distV=mk(nd))
+        lowest = layer % self.G == 0
+        if lowest:
+            out["distK"] = mk(nd)
+        rc = lib().oracle_cache_export(self._h, layer, seq, counts, _u16(out["sinkK"]), _u16(out["sinkV"]),
+                                       _u16(out["recentK"]), _u16(out["recentV"]),
+                                       _u16(out["distK"]) if lowest else None, _u16(out["distV"]))
+        _chk(rc, "oracle_cache_export")
+        return out
+
+    def stored_elems(self):
+        return lib().oracle_cache_stored_elems(self._h)
+
+    def decode_attention(self, layer, q, q_shared, ctx_lens, scale):
+        B, Hq, d = q.shape
+        ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        out = np.empty((B, Hq, d), dtype=np.float64)
+        rc = lib().oracle_decode_attention(self._h, layer, Hq, float(scale), _u16(q), _u16(q_shared),
+                                           ctx_lens.ctypes.data_as(C.POINTER(C.c_int32)), B,
+                                           out.ctypes.data_as(C.POINTER(C.c_double)))
+        _chk(rc, "oracle_decode_attention")
+        return out

@@ -1,0 +1,386 @@
+"""Pins for the CPU oracle (no GPU): what the paper and the mathematics fix.
+
+Each test is chosen so that one plausible mistake in oracle/pod_oracle.c (wrong
+window edge, own keys used for distant tokens, a shared value, a dropped region,
+a transposed head mapping ...) fails it.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pod_oracle as po
+from pod_inputs import gen
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_facts.txt")
+
+
+def paper_facts():
+    facts = {}
+    for line in open(GOLDEN):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            facts[k.strip()] = float(v)
+    return facts
+
+
+def rand_qkv(seed, n, Hq, Hkv, d, layer=0):
+    q = gen.queries_bf16(seed, layer, 0, n, Hq, d)
+    k = gen.keys_bf16(seed, layer, 0, n, Hkv, d)
+    v = gen.values_bf16(seed, layer, 0, n, Hkv, d)
+    return q, k, v
+
+
+def bits(x):
+    return gen.bf16_bits(x)
+
+
+def sdpa_causal(q, k, v, scale):
+    """Library routine: torch's scaled_dot_product_attention, float64, causal, GQA by repetition."""
+    Hq, Hkv = q.shape[1], k.shape[1]
+    qq = q.double().permute(1, 0, 2)[None]
+    kk = k.double().repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)[None]
+    vv = v.double().repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(qq, kk, vv, is_causal=True, scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+# ---------------------------------------------------------------- textbook reductions
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 2, 16), (6, 1, 8), (3, 3, 32)])
+def test_lowest_layer_is_textbook_causal_attention(Hq, Hkv, d):
+    """Eq. 3 with l = l_a: every logit is q_l . k_l, so the joint softmax is plain attention."""
+    n, S, W = 96, 4, 16
+    q, k, v = rand_qkv(11, n, Hq, Hkv, d)
+    scale = 1.0 / math.sqrt(d)
+    got = po.pod_attention(bits(q), bits(k), bits(v), None, None, np.arange(n), S, W, scale)
+    np.testing.assert_allclose(got, sdpa_causal(q, k, v, scale), rtol=0, atol=1e-12)
+
+
+def test_no_distant_tokens_is_textbook_even_for_upper_layer():
+    """Footnote to Eq. 3: without distant tokens the distant term is omitted -> plain attention
+    with the layer's own q and k, whatever the shared tensors hold."""
+    n, S, W, Hq, Hkv, d = 40, 8, 32, 4, 2, 16   # n <= S + W
+    q, k, v = rand_qkv(12, n, Hq, Hkv, d, layer=1)
+    qa, ka, _ = rand_qkv(12, n, Hq, Hkv, d, layer=0)
+    scale = 0.3
+    got = po.pod_attention(bits(q), bits(k), bits(v), bits(qa), bits(ka), np.arange(n), S, W, scale)
+    np.testing.assert_allclose(got, sdpa_causal(q, k, v, scale), rtol=0, atol=1e-12)
+
+
+def test_identical_shared_tensors_give_textbook_attention():
+    n, S, W, Hq, Hkv, d = 80, 3, 9, 4, 2, 8
+    q, k, v = rand_qkv(13, n, Hq, Hkv, d)
+    scale = 1.0 / math.sqrt(d)
+    got = po.pod_attention(bits(q), bits(k), bits(v), bits(q), bits(k), np.arange(n), S, W, scale)
+    np.testing.assert_allclose(got, sdpa_causal(q, k, v, scale), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- brute force on a tiny case
+
+# Which (query i, key j) pairs are proximal for S = 1, W = 2, written out by hand:
+# 'P' proximal (sink j=0, or j in {i-1, i}), 'D' distant, '.' not visible (j > i).
+TINY_TABLE = [
+    "P.......",
+    "PP......",
+    "PPP.....",
+    "PDPP....",
+    "PDDPP...",
+    "PDDDPP..",
+    "PDDDDPP.",
+    "PDDDDDPP",
+]
+
+
+def test_brute_force_tiny_against_handwritten_region_table():
+    n, S, W, Hq, Hkv, d = 8, 1, 2, 2, 1, 4
+    q, k, v = rand_qkv(21, n, Hq, Hkv, d, layer=1)
+    qa, ka, _ = rand_qkv(21, n, Hq, Hkv, d, layer=0)
+    scale = 0.5
+    got = po.pod_attention(bits(q), bits(k), bits(v), bits(qa), bits(ka), np.arange(n), S, W, scale)
+    Q, K, V, QA, KA = (t.double().numpy() for t in (q, k, v, qa, ka))
+    for i in range(n):
+        for h in range(Hq):
+            logits, vals = [], []
+            for j in range(n):
+                c = TINY_TABLE[i][j]
+                if c == "P":
+                    logits.append(scale * float(Q[i, h] @ K[j, 0]))
+                elif c == "D":
+                    logits.append(scale * float(QA[i, h] @ KA[j, 0]))
+                else:
+                    continue
+                vals.append(V[j, 0])
+            w = np.exp(np.array(logits))
+            ref = (w[:, None] * np.array(vals)).sum(0) / w.sum()
+            np.testing.assert_allclose(got[i, h], ref, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- gate form == joint form
+
+def test_gate_form_equals_joint_softmax():
+    """Appendix derivation: g*o^P + (1-g)*o^D is the softmax over the union."""
+    n, S, W, Hq, Hkv, d = 70, 4, 8, 4, 2, 16
+    q, k, v = rand_qkv(31, n, Hq, Hkv, d, layer=1)
+    qa, ka, _ = rand_qkv(31, n, Hq, Hkv, d, layer=0)
+    rows = np.arange(n)
+    joint = po.pod_attention(bits(q), bits(k), bits(v), bits(qa), bits(ka), rows, S, W, 0.25)
+    gated, g = po.pod_attention(bits(q), bits(k), bits(v), bits(qa), bits(ka), rows, S, W, 0.25, gate=True)
+    np.testing.assert_allclose(gated, joint, rtol=0, atol=1e-12)
+    assert np.all(g[: S + W] == 1.0)                # no distant tokens yet: term omitted
+    assert np.all((g[S + W:] > 0) & (g[S + W:] < 1))
+
+
+def test_gate_value_matches_eq4_by_hand():
+    """g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)) for one row, from raw exponentials."""
+    n, S, W, d = 12, 2, 3, 4
+    q, k, v = rand_qkv(32, n, 1, 1, d, layer=1)
+    qa, ka, _ = rand_qkv(32, n, 1, 1, d, layer=0)
+    i = n - 1
+    _, g = po.pod_attention(bits(q[i:i + 1]), bits(k), bits(v), bits(qa[i:i + 1]), bits(ka), [i], S, W, 0.5, gate=True)
+    Q, K, QA, KA = (t.double().numpy() for t in (q, k, qa, ka))
+    prox = [0, 1, 9, 10, 11]
+    dist = [2, 3, 4, 5, 6, 7, 8]
+    eP = sum(math.exp(0.5 * float(Q[i, 0] @ K[j, 0])) for j in prox)
+    eD = sum(math.exp(0.5 * float(QA[i, 0] @ KA[j, 0])) for j in dist)
+    assert abs(g[0, 0] - eP / (eP + eD)) < 1e-12
+
+
+# ---------------------------------------------------------------- the sharing rule
+
+def _upper_layer_case(seed=41, n=64, S=4, W=8, Hq=4, Hkv=2, d=16):
+    q, k, v = rand_qkv(seed, n, Hq, Hkv, d, layer=1)
+    qa, ka, _ = rand_qkv(seed, n, Hq, Hkv, d, layer=0)
+    return n, S, W, q, k, v, qa, ka
+
+
+def test_upper_layer_ignores_its_own_distant_keys():
+    n, S, W, q, k, v, qa, ka = _upper_layer_case()
+    i = n - 1
+    row = lambda t: bits(t[i:i + 1])
+    base = po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka), [i], S, W, 0.25)
+    k2 = k.clone()
+    k2[S:i - W + 1] = k2[S:i - W + 1] * 3 + 1          # own keys at distant positions
+    same = po.pod_attention(row(q), bits(k2), bits(v), row(qa), bits(ka), [i], S, W, 0.25)
+    assert np.array_equal(base, same)
+    ka2 = ka.clone()
+    ka2[S:i - W + 1] = ka2[S:i - W + 1] * 3 + 1        # lowest layer's keys there
+    diff = po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka2), [i], S, W, 0.25)
+    assert np.abs(diff - base).max() > 1e-3
+    qa2 = qa.clone()
+    qa2[i] = -qa2[i]                                   # lowest layer's query
+    diff = po.pod_attention(row(q), bits(k), bits(v), bits(qa2[i:i + 1]), bits(ka), [i], S, W, 0.25)
+    assert np.abs(diff - base).max() > 1e-3
+
+
+def test_upper_layer_ignores_shared_keys_at_proximal_positions():
+    n, S, W, q, k, v, qa, ka = _upper_layer_case(seed=42)
+    i = n - 1
+    row = lambda t: bits(t[i:i + 1])
+    base = po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka), [i], S, W, 0.25)
+    ka2 = ka.clone()
+    ka2[:S] = 7.0
+    ka2[i - W + 1:] = -7.0
+    same = po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka2), [i], S, W, 0.25)
+    assert np.array_equal(base, same)
+    # the edge tokens: i-W is the newest distant token, i-W+1 the oldest recent one
+    ka3 = ka.clone(); ka3[i - W] += 1.0
+    assert np.abs(po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka3), [i], S, W, 0.25) - base).max() > 1e-6
+    k3 = k.clone(); k3[i - W + 1] += 1.0
+    assert np.abs(po.pod_attention(row(q), bits(k3), bits(v), row(qa), bits(ka), [i], S, W, 0.25) - base).max() > 1e-6
+    k4 = k.clone(); k4[S - 1] += 1.0
+    assert np.abs(po.pod_attention(row(q), bits(k4), bits(v), row(qa), bits(ka), [i], S, W, 0.25) - base).max() > 1e-6
+    ka4 = ka.clone(); ka4[S] += 1.0
+    assert np.abs(po.pod_attention(row(q), bits(k), bits(v), row(qa), bits(ka4), [i], S, W, 0.25) - base).max() > 1e-6
+
+
+def test_values_always_come_from_the_layer_itself():
+    n, S, W, q, k, v, qa, ka = _upper_layer_case(seed=43)
+    ones = torch.ones_like(v)
+    out = po.pod_attention(bits(q), bits(k), bits(ones), bits(qa), bits(ka), np.arange(n), S, W, 0.25)
+    np.testing.assert_allclose(out, 1.0, rtol=0, atol=1e-12)   # softmax weights sum to one
+
+
+def test_gqa_head_mapping():
+    """Query head h reads KV head h // (Hq/Hkv): make KV head 1 the only one that matters."""
+    n, S, W, Hq, Hkv, d = 32, 2, 4, 4, 2, 8
+    q, k, v = rand_qkv(44, n, Hq, Hkv, d)
+    v2 = v.clone(); v2[:, 0] = 0.0
+    out = po.pod_attention(bits(q), bits(k), bits(v2), None, None, np.arange(n), S, W, 0.3)
+    assert np.all(out[:, :2] == 0.0) and np.abs(out[:, 2:]).max() > 0.1
+
+
+# ---------------------------------------------------------------- closed forms
+
+def test_zero_keys_give_running_mean_of_values():
+    n, S, W, Hq, Hkv, d = 50, 3, 5, 2, 1, 8
+    q, k, v = rand_qkv(51, n, Hq, Hkv, d)
+    z = torch.zeros_like(k)
+    out = po.pod_attention(bits(q), bits(z), bits(v), bits(q), bits(z), np.arange(n), S, W, 1.0)
+    V = v.double().numpy()[:, 0]
+    ref = np.cumsum(V, 0) / np.arange(1, n + 1)[:, None]
+    np.testing.assert_allclose(out[:, 0], ref, rtol=0, atol=1e-12)
+
+
+def test_zero_shared_query_weights_each_distant_token_by_one():
+    n, S, W, Hq, Hkv, d = 40, 2, 6, 1, 1, 8
+    q, k, v = rand_qkv(52, n, Hq, Hkv, d, layer=1)
+    _, ka, _ = rand_qkv(52, n, Hq, Hkv, d, layer=0)
+    i = n - 1
+    qa0 = torch.zeros_like(q[i:i + 1])
+    out = po.pod_attention(bits(q[i:i + 1]), bits(k), bits(v), bits(qa0), bits(ka), [i], S, W, 0.4)
+    Q, K, V = (t.double().numpy() for t in (q, k, v))
+    prox = [j for j in range(n) if j < S or j > i - W]
+    dist = [j for j in range(n) if j not in prox]
+    e = np.array([math.exp(0.4 * float(Q[i, 0] @ K[j, 0])) for j in prox])
+    ref = ((e[:, None] * V[prox, 0]).sum(0) + V[dist, 0].sum(0)) / (e.sum() + len(dist))
+    assert len(dist) == n - S - W
+    np.testing.assert_allclose(out[0, 0], ref, rtol=0, atol=1e-12)
+
+
+def test_dominant_key_returns_its_value():
+    n, S, W, Hq, Hkv, d = 48, 2, 6, 1, 1, 8
+    q, k, v = rand_qkv(53, n, Hq, Hkv, d, layer=1)
+    qa, ka, _ = rand_qkv(53, n, Hq, Hkv, d, layer=0)
+    i, t = n - 1, 20                                   # t is a distant position
+    ka = ka.clone(); ka[t, 0] = qa[i, 0] * 64.0
+    out = po.pod_attention(bits(q[i:i + 1]), bits(k), bits(v), bits(qa[i:i + 1]), bits(ka), [i], S, W, 1.0)
+    np.testing.assert_allclose(out[0, 0], v[t, 0].double().numpy(), rtol=0, atol=1e-9)
+
+
+def test_permuting_distant_tokens_changes_nothing():
+    n, S, W, q, k, v, qa, ka = _upper_layer_case(seed=54)
+    i = n - 1
+    perm = torch.arange(n)
+    perm[S:i - W + 1] = torch.flip(perm[S:i - W + 1], dims=[0])
+    a = po.pod_attention(bits(q[i:i + 1]), bits(k), bits(v), bits(qa[i:i + 1]), bits(ka), [i], S, W, 0.25)
+    v2 = v.clone(); v2[S:i - W + 1] = v[perm[S:i - W + 1]]
+    ka2 = ka.clone(); ka2[S:i - W + 1] = ka[perm[S:i - W + 1]]
+    b = po.pod_attention(bits(q[i:i + 1]), bits(k), bits(v2), bits(qa[i:i + 1]), bits(ka2), [i], S, W, 0.25)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- region arithmetic, cache model
+
+def test_region_sizes_match_the_papers_window_column():
+    f = paper_facts()
+    n, S, W = int(f["context_32k"]), int(f["n_s"]), int(f["n_r"])
+    c = po.Cache(1, 1, 1, 1, S, W, 1, n)
+    z = np.zeros((n, 1, 1), dtype=np.uint16)
+    c.fill(0, 0, z, z)
+    e = c.export(0, 0)
+    assert (len(e["sinkK"]), len(e["recentK"]), len(e["distV"])) == (S, W, int(f["distant_at_32k"]))
+
+
+def test_toy_config_has_1776_distant_tokens():
+    c = po.Cache(2, 2, 1, 1, 16, 256, 1, 2048)
+    z = np.zeros((2047, 1, 1), dtype=np.uint16)
+    c.fill(0, 0, z, z)
+    c.append(0, z[:1], z[:1], [2047])
+    assert len(c.export(0, 0)["distV"]) == 1776
+
+
+def _tagged_kv(n, Hkv, d, layer):
+    """K/V whose every element encodes (layer, kind, position, head, dim) so misplaced rows show."""
+    pos = np.arange(n, dtype=np.uint32)[:, None, None]
+    head = np.arange(Hkv, dtype=np.uint32)[None, :, None]
+    dim = np.arange(d, dtype=np.uint32)[None, None, :]
+    base = (pos * 31 + head * 7 + dim * 3 + layer * 1009) % 60000
+    k = (base * 2).astype(np.uint16) % np.uint16(0x7F00)      # finite bf16 patterns
+    v = (base * 2 + 1).astype(np.uint16) % np.uint16(0x7F00)
+    return np.ascontiguousarray(k), np.ascontiguousarray(v)
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 11, 12, 13, 40])
+def test_appends_equal_fill_and_views_are_slices(n):
+    L, G, Hkv, d, S, W = 2, 2, 2, 4, 4, 8
+    a = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    b = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    for layer in range(L):
+        k, v = _tagged_kv(n, Hkv, d, layer)
+        for p in range(n):
+            a.append(layer, k[p:p + 1], v[p:p + 1], [p])
+        b.fill(layer, 0, k, v)
+        ea, eb = a.export(layer, 0), b.export(layer, 0)
+        lo = max(S, n - W)
+        want = dict(sinkK=k[:min(n, S)], sinkV=v[:min(n, S)], recentK=k[lo:n], recentV=v[lo:n],
+                    distV=v[S:max(S, n - W)])
+        if layer % G == 0:
+            want["distK"] = k[S:max(S, n - W)]
+        assert set(ea) == set(eb) == set(want)
+        for name in want:
+            assert np.array_equal(ea[name], want[name]), name
+            assert np.array_equal(eb[name], want[name]), name
+        assert len(ea["distV"]) == max(0, n - S - W)
+    assert a.stored_elems() == b.stored_elems()
+
+
+def test_upper_layer_keeps_no_distant_keys():
+    c = po.Cache(2, 2, 1, 2, 1, 2, 1, 16)
+    k, v = _tagged_kv(10, 1, 2, 1)
+    c.fill(1, 0, k, v)
+    assert "distK" not in c.export(1, 0)
+    per_row = 1 * 2
+    assert c.stored_elems() == per_row * (2 * 1 + 2 * 2 + 7)      # sink K,V + recent K,V + distant V only
+
+
+def test_append_rejects_wrong_position_and_overflow():
+    c = po.Cache(1, 1, 1, 2, 1, 2, 1, 4)
+    k, v = _tagged_kv(5, 1, 2, 0)
+    with pytest.raises(po.OracleError):
+        c.append(0, k[:1], v[:1], [1])
+    for p in range(4):
+        c.append(0, k[p:p + 1], v[p:p + 1], [p])
+    with pytest.raises(po.OracleError):
+        c.append(0, k[4:5], v[4:5], [4])
+
+
+# ---------------------------------------------------------------- memory accounting
+
+@pytest.mark.parametrize("L,G,n", [(4, 2, 100), (4, 1, 100), (4, 4, 9), (6, 3, 57), (2, 2, 12)])
+def test_counted_entries_match_closed_form(L, G, n):
+    Hkv, d, S, W = 2, 4, 4, 8
+    c = po.Cache(L, G, Hkv, d, S, W, 1, 128)
+    for layer in range(L):
+        k, v = _tagged_kv(n, Hkv, d, layer)
+        c.fill(layer, 0, k, v)
+    pod, dense = po.cache_bytes_formula(L, G, Hkv, d, S, W, n)
+    assert c.stored_elems() * 2 == pod
+    assert dense == 2 * 2 * Hkv * d * L * n
+    n_dist = max(0, n - S - W)
+    assert abs((1 - pod / dense) - (1 - 1 / G) * n_dist / (2 * n)) < 1e-12
+
+
+def test_saving_limits_and_config_values():
+    f = paper_facts()
+    sav = lambda L, G, S, W, n: 1 - np.divide(*po.cache_bytes_formula(L, G, 8, 128, S, W, n))
+    assert sav(32, 1, 64, 2048, 32768) == 0.0                       # no sharing
+    assert sav(32, 2, 64, 2048, 2000) == 0.0                        # nothing distant yet
+    assert abs(sav(2, 2, 64, 2048, 32768) - 0.234) < 5e-4           # (1-1/2)*30656/65536
+    assert abs(sav(32, 4, 128, 4096, 131072) - 0.363) < 5e-4        # (1-1/4)*126848/262144
+    # sharing K only (not V) between 2 layers saves half of what sharing both saves
+    assert abs(sav(2, 2, 0, 1, 10 ** 7) - f["cla_factor2_saving"] / 2) < 1e-6
+    assert sav(64, 64, 0, 1, 10 ** 7) < 0.5 and sav(64, 64, 0, 1, 10 ** 7) > 0.49
+
+
+# ---------------------------------------------------------------- decode from the cache model
+
+@pytest.mark.parametrize("layer", [0, 1])
+@pytest.mark.parametrize("n", [5, 12, 13, 37])
+def test_decode_from_cache_equals_definition(layer, n):
+    L, G, Hq, Hkv, d, S, W = 2, 2, 4, 2, 8, 4, 8
+    c = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    ks, vs, qs = {}, {}, {}
+    for l in range(L):
+        qs[l], ks[l], vs[l] = rand_qkv(61, n, Hq, Hkv, d, layer=l)
+        c.fill(l, 0, bits(ks[l][: n - 1]), bits(vs[l][: n - 1]))
+        c.append(l, bits(ks[l][n - 1:]), bits(vs[l][n - 1:]), [n - 1])
+    i = n - 1
+    q, qa = bits(qs[layer][i:i + 1]), bits(qs[0][i:i + 1])
+    got = c.decode_attention(layer, q, qa if layer else None, [n], 0.35)
+    ref = po.pod_attention(q, bits(ks[layer]), bits(vs[layer]), qa if layer else None,
+                           bits(ks[0]) if layer else None, [i], S, W, 0.35)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13)
