@@ -1,0 +1,194 @@
+/*
+ * libpod — PoD ("Proximal tokens over Distant tokens", arXiv 2412.02252) attention
+ * over a split KV cache, for AMD MI355X (gfx950).  C ABI, no C++ or framework
+ * types in any signature.
+ *
+ * The method (paper, Methodology, "Attention Sharing within Each Block"):
+ * layers are grouped in blocks of consecutive layers.  For a query at position i
+ * the earlier tokens are split in *proximal* tokens (the first S "sink" tokens
+ * and the W most recent ones, i included) and *distant* tokens (the rest).
+ * Proximal logits use the layer's own query and keys (Eq. 3, line 1); distant
+ * logits are those of the block's lowest layer, i.e. that layer's query times
+ * that layer's keys (Eq. 3, line 3).  One softmax runs over both sets (Eq. 4
+ * and the appendix derivation show the gate form equals it) and weights the
+ * layer's own values (Eq. 3, lines 2 and 4).  Consequence for storage: distant
+ * keys are kept once per block, everything else per layer.
+ *
+ * Here blocks are uniform: layer l belongs to block l / group_size, whose lowest
+ * layer is l - l % group_size.  GQA: query head h reads KV head
+ * h / (num_q_heads / num_kv_heads).
+ *
+ * Conventions
+ *  - Every call returns POD_OK (0) or a negative pod_status; pod_last_error()
+ *    gives a thread-local message for the last failure on the calling thread.
+ *  - "dev" pointers are device memory of the current HIP device, "host" pointers
+ *    are ordinary host memory.  The caller owns every buffer it passes; the
+ *    library never allocates or frees device memory and never synchronises the
+ *    device, except pod_cache_check (which waits on the given stream).
+ *  - All device work is enqueued on the stream argument (a hipStream_t passed as
+ *    void*; NULL = the default stream).  Calls that touch one cache must be
+ *    issued in program order on one stream (or be ordered by the caller).
+ *  - Tensors are bf16 (raw 16-bit, round-to-nearest-even where the library
+ *    rounds), contiguous, row-major with the last index fastest.
+ *  - head_dim must be 64 or 128; num_q_heads / num_kv_heads must be <= 16.
+ *  - Sequences live in slots 0 .. max_batch-1.  A batched call with B entries
+ *    addresses slots 0 .. B-1 (entry b <-> slot b).
+ *  - The library mirrors each (layer, slot) length on the host from the calls it
+ *    has seen, to validate arguments.  Contracts it cannot see from the host
+ *    (values inside device arrays) are checked inside the kernels: a violating
+ *    entry is skipped (nothing written for it, output rows zeroed), a sticky flag
+ *    is raised in device memory, and pod_cache_check reports it.  No input can
+ *    make a kernel read or write outside the buffers described here.
+ */
+#ifndef POD_H
+#define POD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pod_status {
+    POD_OK = 0,
+    POD_ERR_INVALID_ARG = -1, /* bad pointer, index, shape or unsupported configuration */
+    POD_ERR_CAPACITY = -2,    /* more tokens / sequences / bytes than the buffer was sized for */
+    POD_ERR_STATE = -3,       /* call does not fit the cache's state (e.g. fill of a non-empty slot) */
+    POD_ERR_HIP = -4          /* the HIP runtime reported an error */
+} pod_status;
+
+typedef struct pod_config {
+    int32_t num_layers;   /* L, a multiple of group_size */
+    int32_t group_size;   /* G: layers per block; G = 1 is ordinary attention */
+    int32_t num_q_heads;  /* Hq */
+    int32_t num_kv_heads; /* Hkv, divides Hq */
+    int32_t head_dim;     /* d: 64 or 128 */
+    int32_t sink;         /* S = n_s >= 0 */
+    int32_t window;       /* W = n_r >= 1; counts the query's own token */
+    int32_t max_batch;    /* sequence slots */
+    int32_t max_context;  /* tokens per sequence the buffers are sized for */
+} pod_config;
+
+typedef struct pod_cache pod_cache; /* host-side handle; holds no device allocation of its own */
+
+/* Message for the last error on this thread ("" if none).  Never NULL. */
+const char *pod_last_error(void);
+
+/*
+ * Bytes of device memory a cache for cfg needs (all regions at max_context, plus
+ * a small header of per-sequence lengths and the error flag).  host out.
+ */
+int pod_cache_bytes(const pod_config *cfg, size_t *bytes);
+
+/*
+ * The paper's memory accounting for one sequence holding n tokens: bytes of K/V
+ * actually live in the PoD cache (distant keys once per block: abstract, Eq. 3)
+ * and in a dense cache (K and V of every token at every layer).  host outs.
+ *   pod   = 2*d*Hkv * [ L*(2*min(n,S+W) + n_dist) + (L/G)*n_dist ],  n_dist = max(0, n-S-W)
+ *   dense = 2*d*Hkv * 2*L*n
+ */
+int pod_cache_live_bytes(const pod_config *cfg, int64_t n, size_t *pod_bytes, size_t *dense_bytes);
+
+/*
+ * Lay a cache out in dev_buf (device memory, 256-byte aligned, >= pod_cache_bytes).
+ * Enqueues a clear of the header on stream; K/V regions are left as they are
+ * (never read before written).  *out receives the handle.
+ */
+int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes, void *stream, pod_cache **out);
+
+/* Free the host handle.  The device buffer stays the caller's. */
+int pod_cache_destroy(pod_cache *cache);
+
+/* Forget the contents of slot seq_slot (or of every slot if seq_slot < 0) at every layer. */
+int pod_cache_reset(pod_cache *cache, int seq_slot, void *stream);
+
+/* Host mirror of the number of tokens stored for (layer, seq_slot).  host out. */
+int pod_cache_seq_len(const pod_cache *cache, int layer, int seq_slot, int64_t *n);
+
+/*
+ * Wait for stream, then report whether any kernel since the last check skipped an
+ * entry because a device-side contract was violated (wrong position, wrong
+ * context length, overflow): POD_ERR_STATE if so (the flag is cleared), else POD_OK.
+ */
+int pod_cache_check(pod_cache *cache, void *stream);
+
+/* Bytes of device scratch pod_decode_attention needs for cfg (split-K partial results). host out. */
+int pod_workspace_bytes(const pod_config *cfg, size_t *bytes);
+
+/*
+ * Cache update at decode time (derived from Eq. 3's index ranges): one new token per
+ * sequence enters `layer`.
+ *   k_new, v_new : dev bf16 [B][Hkv][d]
+ *   positions    : dev int32 [B]; positions[b] must equal the number of tokens slot b
+ *                  already holds at this layer (checked in the kernel)
+ * Token p goes to sink slot p if p < S, else into the ring of W recent tokens.
+ * If the ring is full, the token it displaces (position p-W) becomes distant first:
+ * its value moves to this layer's distant-V store, and its key moves to the block's
+ * distant-K store only if `layer` is the block's lowest layer (other layers drop it).
+ * POD_ERR_CAPACITY if the host mirror shows a slot already at max_context.
+ */
+int pod_cache_append(pod_cache *cache, int layer, const void *k_new, const void *v_new,
+                     const int32_t *positions, int B, void *stream);
+
+/*
+ * Cache construction from a whole prompt; same result as n appends.
+ *   k, v : dev bf16 [n][Hkv][d], positions 0..n-1 of slot seq_slot at `layer`
+ * The slot must be empty at this layer (POD_ERR_STATE otherwise); n <= max_context.
+ */
+int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, const void *k, const void *v,
+                   void *stream);
+
+/*
+ * Decode attention (Eq. 3 + Eq. 4 as one joint softmax), one query token per sequence,
+ * over what the cache holds for `layer` after the token's own K/V was appended.
+ *   q            : dev bf16 [B][Hq][d], this layer's query
+ *   q_shared     : dev bf16 [B][Hq][d], the query of the block's lowest layer for the
+ *                  same token; may be NULL when `layer` is the lowest layer of its block
+ *                  (then q serves).  Passing q itself on an upper layer gives the
+ *                  "shared keys, own queries" variant, which is not the paper's rule.
+ *   context_lens : dev int32 [B]; tokens held for slot b including the query's own;
+ *                  0 skips the entry (output row zeroed); any other value must equal the
+ *                  cache's length for (layer, slot b) (checked in the kernel)
+ *   max_context_len : host upper bound on context_lens (sizes the launch); 0 = use the
+ *                  host mirror's maximum over the B slots
+ *   scale        : logits multiplier, 1/sqrt(d) in the paper
+ *   workspace    : dev scratch of >= pod_workspace_bytes(cfg); contents undefined afterwards
+ *   out          : dev bf16 [B][Hq][d]
+ * The block's lowest layer must hold the same number of distant tokens as `layer`
+ * (append/fill the lowest layer first).
+ */
+int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                         const int32_t *context_lens, int B, int max_context_len, float scale,
+                         void *workspace, size_t workspace_bytes, void *out, void *stream);
+
+/*
+ * Prefill attention for one sequence (Eq. 3 with the window taken at each query's own
+ * position: key j is proximal for query i if j < S or j > i - W), causal, joint softmax.
+ *   q        : dev bf16 [n][Hq][d];  k, v : dev bf16 [n][Hkv][d] of `layer`
+ *   q_shared, k_shared : the lowest layer's q and k (same shapes); both NULL when `layer`
+ *              is the lowest of its block
+ *   out      : dev bf16 [n][Hq][d]
+ *   write_cache : nonzero = also build the cache for (layer, seq_slot) from k, v as
+ *              pod_cache_fill does (slot must be empty at this layer); with 0 the cache
+ *              is not touched and seq_slot is ignored
+ */
+int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, const void *q, const void *k,
+                          const void *v, const void *q_shared, const void *k_shared, float scale,
+                          void *out, int write_cache, void *stream);
+
+/*
+ * Test hook: copy the cache's logical content for (layer, seq_slot) out in position
+ * order, each as dev bf16 [tokens][Hkv][d]:
+ *   sink   : positions [0, min(n,S))           recent : [max(S, n-W), n), oldest first
+ *   dist   : positions [S, n-W)                (distK only at a block's lowest layer)
+ * Any pointer may be NULL (skipped).  Asking distK of an upper layer is POD_ERR_INVALID_ARG.
+ * n is the host mirror's length; buffers must hold that many rows per region.
+ */
+int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slot, void *sinkK, void *sinkV,
+                             void *recentK, void *recentV, void *distK, void *distV, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POD_H */

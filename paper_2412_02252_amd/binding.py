@@ -1,0 +1,197 @@
+"""ctypes binding of libpod.so: the same calls as include/pod.h, argument marshalling only.
+
+Tensors are torch CUDA tensors (PyTorch serves as the device allocator and stream
+provider, nothing else); every step of the path runs inside libpod's HIP kernels.
+There is no CPU fallback: without the built library, importing the symbols fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_STATE, ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "pod_last_error", "pod_cache_bytes", "pod_cache_live_bytes", "pod_cache_init", "pod_cache_destroy",
+    "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
+    "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
+]
+
+
+class PodConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("num_layers", "group_size", "num_q_heads", "num_kv_heads", "head_dim",
+                                          "sink", "window", "max_batch", "max_context")]
+
+
+class PodError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libpod error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libpod.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = C.CDLL(_build.LIB)
+    vp, i32p, szp = C.c_void_p, C.c_void_p, C.POINTER(C.c_size_t)
+    cfgp = C.POINTER(PodConfig)
+    L.pod_last_error.restype = C.c_char_p
+    L.pod_last_error.argtypes = []
+    sig = {
+        "pod_cache_bytes": [cfgp, szp],
+        "pod_cache_live_bytes": [cfgp, C.c_int64, szp, szp],
+        "pod_cache_init": [cfgp, vp, C.c_size_t, vp, C.POINTER(vp)],
+        "pod_cache_destroy": [vp],
+        "pod_cache_reset": [vp, C.c_int, vp],
+        "pod_cache_seq_len": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64)],
+        "pod_cache_check": [vp, vp],
+        "pod_workspace_bytes": [cfgp, szp],
+        "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
+        "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
+        "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
+        "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
+        "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
+    }
+    for name, args in sig.items():
+        fn = getattr(L, name)
+        fn.restype = C.c_int
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != OK:
+        raise PodError(rc, load().pod_last_error().decode())
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_config(num_layers, group_size, num_q_heads, num_kv_heads, head_dim, sink, window, max_batch,
+                max_context) -> PodConfig:
+    return PodConfig(num_layers, group_size, num_q_heads, num_kv_heads, head_dim, sink, window, max_batch,
+                     max_context)
+
+
+def pod_cache_bytes(cfg: PodConfig) -> int:
+    out = C.c_size_t()
+    _check(load().pod_cache_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def pod_cache_live_bytes(cfg: PodConfig, n: int):
+    a, b = C.c_size_t(), C.c_size_t()
+    _check(load().pod_cache_live_bytes(C.byref(cfg), n, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def pod_workspace_bytes(cfg: PodConfig) -> int:
+    out = C.c_size_t()
+    _check(load().pod_workspace_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+class PodCache:
+    """Owns the torch buffers (cache + decode workspace) and the libpod handle."""
+
+    def __init__(self, cfg: PodConfig, device="cuda:0"):
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = pod_cache_bytes(cfg)
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(pod_workspace_bytes(cfg), dtype=torch.uint8, device=self.device)
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(load().pod_cache_init(C.byref(cfg), self.buf.data_ptr(), nbytes, _stream(), C.byref(h)))
+        self.handle = h
+
+    def __del__(self):
+        h = getattr(self, "handle", None)
+        if h:
+            load().pod_cache_destroy(h)
+            self.handle = None
+
+    # -- the C ABI, one method per call -------------------------------------------------
+    def pod_cache_reset(self, seq_slot=-1):
+        _check(load().pod_cache_reset(self.handle, seq_slot, _stream()))
+
+    def pod_cache_seq_len(self, layer, seq_slot) -> int:
+        n = C.c_int64()
+        _check(load().pod_cache_seq_len(self.handle, layer, seq_slot, C.byref(n)))
+        return n.value
+
+    def pod_cache_check(self):
+        _check(load().pod_cache_check(self.handle, _stream()))
+
+    def pod_cache_append(self, layer, k_new, v_new, positions):
+        B = positions.shape[0]
+        _check(load().pod_cache_append(self.handle, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+                                       _ptr(positions, torch.int32), B, _stream()))
+
+    def pod_cache_fill(self, layer, seq_slot, k, v):
+        n = k.shape[0]
+        _check(load().pod_cache_fill(self.handle, layer, seq_slot, n, _ptr(k, torch.bfloat16),
+                                     _ptr(v, torch.bfloat16), _stream()))
+
+    def pod_decode_attention(self, layer, q, q_shared, context_lens, scale, out=None, max_context_len=0):
+        B = q.shape[0]
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_decode_attention(self.handle, layer, _ptr(q, torch.bfloat16), _ptr(q_shared, torch.bfloat16),
+                                           _ptr(context_lens, torch.int32), B, max_context_len, scale,
+                                           self.workspace.data_ptr(), self.workspace.numel(), _ptr(out, torch.bfloat16),
+                                           _stream()))
+        return out
+
+    def pod_prefill_attention(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, out=None, write_cache=False):
+        n = q.shape[0]
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_prefill_attention(self.handle, layer, seq_slot, n, _ptr(q, torch.bfloat16),
+                                            _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16),
+                                            _ptr(q_shared, torch.bfloat16), _ptr(k_shared, torch.bfloat16), scale,
+                                            _ptr(out, torch.bfloat16), int(bool(write_cache)), _stream()))
+        return out
+
+    def pod_cache_export_logical(self, layer, seq_slot):
+        """dict of bf16 tensors [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV (+ distK at a lowest layer)."""
+        c = self.cfg
+        n = self.pod_cache_seq_len(layer, seq_slot)
+        ns = min(n, c.sink)
+        nr = min(c.window, max(0, n - c.sink))
+        nd = max(0, n - c.sink - c.window)
+        mk = lambda t: torch.zeros((t, c.num_kv_heads, c.head_dim), dtype=torch.bfloat16, device=self.device)
+        out = dict(sinkK=mk(ns), sinkV=mk(ns), recentK=mk(nr), recentV=mk(nr), distV=mk(nd))
+        lowest = layer % c.group_size == 0
+        if lowest:
+            out["distK"] = mk(nd)
+        _check(load().pod_cache_export_logical(self.handle, layer, seq_slot, _ptr(out["sinkK"]), _ptr(out["sinkV"]),
+                                               _ptr(out["recentK"]), _ptr(out["recentV"]),
+                                               _ptr(out["distK"]) if lowest else None, _ptr(out["distV"]), _stream()))
+        return out

@@ -1,0 +1,288 @@
+// C ABI of libpod: argument validation, the host mirror of sequence lengths, and
+// dispatch to the kernel launchers.  No device memory is allocated or freed here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "pod_internal.h"
+
+static thread_local char g_err[512] = "";
+
+int pod_fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int pod_hip_fail(hipError_t e, const char *what)
+{
+    return pod_fail(POD_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int make_layout(const pod_config *cfg, pod_layout *ly)
+{
+    if (!cfg) return pod_fail(POD_ERR_INVALID_ARG, "config is NULL");
+    if (cfg->num_layers < 1 || cfg->group_size < 1 || cfg->num_layers % cfg->group_size)
+        return pod_fail(POD_ERR_INVALID_ARG, "num_layers (%d) must be a positive multiple of group_size (%d)",
+                        cfg->num_layers, cfg->group_size);
+    if (cfg->num_kv_heads < 1 || cfg->num_q_heads < 1 || cfg->num_q_heads % cfg->num_kv_heads)
+        return pod_fail(POD_ERR_INVALID_ARG, "num_q_heads (%d) must be a positive multiple of num_kv_heads (%d)",
+                        cfg->num_q_heads, cfg->num_kv_heads);
+    if (cfg->num_q_heads / cfg->num_kv_heads > 16)
+        return pod_fail(POD_ERR_INVALID_ARG, "more than 16 query heads per KV head is not supported");
+    if (cfg->head_dim != 64 && cfg->head_dim != 128)
+        return pod_fail(POD_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", cfg->head_dim);
+    if (cfg->sink < 0 || cfg->window < 1)
+        return pod_fail(POD_ERR_INVALID_ARG, "need sink >= 0 and window >= 1");
+    if (cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_context < 1)
+        return pod_fail(POD_ERR_INVALID_ARG, "need 1 <= max_batch <= 65535 and max_context >= 1");
+    if ((int64_t)cfg->sink + cfg->window > (int64_t)INT32_MAX / 2)
+        return pod_fail(POD_ERR_INVALID_ARG, "sink + window too large");
+    memset(ly, 0, sizeof *ly);
+    ly->L = cfg->num_layers; ly->G = cfg->group_size; ly->Hq = cfg->num_q_heads; ly->Hkv = cfg->num_kv_heads;
+    ly->D = cfg->head_dim; ly->S = cfg->sink; ly->W = cfg->window; ly->B = cfg->max_batch;
+    ly->maxctx = cfg->max_context;
+    ly->P = ly->S + ly->W;
+    ly->Cd = ly->maxctx > ly->P ? ly->maxctx - ly->P : 0;
+    ly->rep = ly->Hq / ly->Hkv;
+    const size_t row = (size_t)ly->D * 2;
+    const size_t per_layer_heads = (size_t)ly->L * ly->B * ly->Hkv;
+    size_t off = 0;
+    ly->off_lens = off; off += (size_t)ly->L * ly->B * sizeof(int32_t);
+    off = align_up(off, 16);
+    ly->off_flag = off; off += 16;
+    off = align_up(off, 256);
+    ly->off_proxK = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
+    ly->off_proxV = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
+    ly->off_distV = off; off = align_up(off + per_layer_heads * ly->Cd * row, 256);
+    ly->off_distK = off; off = align_up(off + (per_layer_heads / ly->G) * ly->Cd * row, 256);
+    ly->total_bytes = off;
+    return POD_OK;
+}
+
+extern "C" const char *pod_last_error(void) { return g_err; }
+
+extern "C" int pod_cache_bytes(const pod_config *cfg, size_t *bytes)
+{
+    pod_layout ly;
+    if (!bytes) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL");
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    *bytes = ly.total_bytes;
+    return POD_OK;
+}
+
+extern "C" int pod_cache_live_bytes(const pod_config *cfg, int64_t n, size_t *pod_bytes, size_t *dense_bytes)
+{
+    pod_layout ly;
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    if (n < 0) return pod_fail(POD_ERR_INVALID_ARG, "n must be >= 0");
+    const size_t row = (size_t)ly.D * 2 * ly.Hkv;
+    const size_t n_prox = (size_t)(n < ly.P ? n : ly.P);
+    const size_t n_dist = (size_t)(n > ly.P ? n - ly.P : 0);
+    if (pod_bytes) *pod_bytes = row * ((size_t)ly.L * (2 * n_prox + n_dist) + (size_t)(ly.L / ly.G) * n_dist);
+    if (dense_bytes) *dense_bytes = row * 2 * (size_t)ly.L * (size_t)n;
+    return POD_OK;
+}
+
+extern "C" int pod_workspace_bytes(const pod_config *cfg, size_t *bytes)
+{
+    pod_layout ly;
+    if (!bytes) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL");
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    *bytes = pod_decode_workspace_bytes(ly);
+    return POD_OK;
+}
+
+extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes, void *stream, pod_cache **out)
+{
+    pod_layout ly;
+    if (!out) return pod_fail(POD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    if (!dev_buf) return pod_fail(POD_ERR_INVALID_ARG, "dev_buf is NULL");
+    if ((uintptr_t)dev_buf % 256) return pod_fail(POD_ERR_INVALID_ARG, "dev_buf must be 256-byte aligned");
+    if (bytes < ly.total_bytes)
+        return pod_fail(POD_ERR_CAPACITY, "buffer has %zu bytes, cache needs %zu", bytes, ly.total_bytes);
+    pod_cache *c = new (std::nothrow) pod_cache;
+    if (!c) return pod_fail(POD_ERR_CAPACITY, "out of host memory");
+    c->ly = ly;
+    c->base = (char *)dev_buf;
+    c->host_len = (int64_t *)calloc((size_t)ly.L * ly.B, sizeof(int64_t));
+    c->device = -1;
+    if (!c->host_len) { delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { free(c->host_len); delete c; return pod_hip_fail(e, "hipGetDevice"); }
+    rc = pod_launch_clear_header(c, (hipStream_t)stream);
+    if (rc) { free(c->host_len); delete c; return rc; }
+    *out = c;
+    return POD_OK;
+}
+
+extern "C" int pod_cache_destroy(pod_cache *cache)
+{
+    if (!cache) return POD_OK;
+    free(cache->host_len);
+    delete cache;
+    return POD_OK;
+}
+
+static int check_cache_layer(const pod_cache *c, int layer)
+{
+    if (!c) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    if (layer < 0 || layer >= c->ly.L)
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d outside [0, %d)", layer, c->ly.L);
+    return POD_OK;
+}
+
+extern "C" int pod_cache_reset(pod_cache *cache, int seq_slot, void *stream)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    if (seq_slot >= cache->ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, cache->ly.B);
+    int rc = pod_launch_reset(cache, seq_slot, (hipStream_t)stream);
+    if (rc) return rc;
+    for (int l = 0; l < cache->ly.L; ++l)
+        for (int b = 0; b < cache->ly.B; ++b)
+            if (seq_slot < 0 || b == seq_slot) cache->host_len[(size_t)l * cache->ly.B + b] = 0;
+    return POD_OK;
+}
+
+extern "C" int pod_cache_seq_len(const pod_cache *cache, int layer, int seq_slot, int64_t *n)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    if (seq_slot < 0 || seq_slot >= cache->ly.B || !n)
+        return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d) or n is NULL", seq_slot, cache->ly.B);
+    *n = cache->host_len[(size_t)layer * cache->ly.B + seq_slot];
+    return POD_OK;
+}
+
+extern "C" int pod_cache_check(pod_cache *cache, void *stream)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    int32_t flag = 0;
+    hipStream_t st = (hipStream_t)stream;
+    POD_HIP_TRY(hipMemcpyAsync(&flag, cache->base + cache->ly.off_flag, sizeof flag, hipMemcpyDeviceToHost, st));
+    POD_HIP_TRY(hipStreamSynchronize(st));
+    if (flag) {
+        int32_t zero = 0;
+        POD_HIP_TRY(hipMemcpyAsync(cache->base + cache->ly.off_flag, &zero, sizeof zero, hipMemcpyHostToDevice, st));
+        POD_HIP_TRY(hipStreamSynchronize(st));
+        return pod_fail(POD_ERR_STATE, "a kernel skipped at least one entry: device-side contract violated (flag %d)", flag);
+    }
+    return POD_OK;
+}
+
+extern "C" int pod_cache_append(pod_cache *cache, int layer, const void *k_new, const void *v_new,
+                                const int32_t *positions, int B, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!k_new || !v_new || !positions) return pod_fail(POD_ERR_INVALID_ARG, "k_new, v_new and positions must not be NULL");
+    if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
+    int64_t *len = cache->host_len + (size_t)layer * ly.B;
+    for (int b = 0; b < B; ++b)
+        if (len[b] >= ly.maxctx)
+            return pod_fail(POD_ERR_CAPACITY, "slot %d at layer %d already holds max_context = %d tokens", b, layer, ly.maxctx);
+    rc = pod_launch_append(cache, layer, k_new, v_new, positions, B, (hipStream_t)stream);
+    if (rc) return rc;
+    for (int b = 0; b < B; ++b) len[b] += 1;
+    return POD_OK;
+}
+
+extern "C" int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, const void *k, const void *v,
+                              void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
+    if (!k || !v) return pod_fail(POD_ERR_INVALID_ARG, "k and v must not be NULL");
+    if (n < 1) return pod_fail(POD_ERR_INVALID_ARG, "n must be >= 1");
+    if (n > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n = %d exceeds max_context = %d", n, ly.maxctx);
+    int64_t *len = cache->host_len + (size_t)layer * ly.B + seq_slot;
+    if (*len != 0) return pod_fail(POD_ERR_STATE, "slot %d at layer %d is not empty (%lld tokens)", seq_slot, layer, (long long)*len);
+    rc = pod_launch_fill(cache, layer, seq_slot, n, k, v, (hipStream_t)stream);
+    if (rc) return rc;
+    *len = n;
+    return POD_OK;
+}
+
+extern "C" int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                                    const int32_t *context_lens, int B, int max_context_len, float scale,
+                                    void *workspace, size_t workspace_bytes, void *out, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!q || !context_lens || !out || !workspace)
+        return pod_fail(POD_ERR_INVALID_ARG, "q, context_lens, workspace and out must not be NULL");
+    if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
+    if (workspace_bytes < pod_decode_workspace_bytes(ly))
+        return pod_fail(POD_ERR_CAPACITY, "workspace has %zu bytes, needs %zu", workspace_bytes, pod_decode_workspace_bytes(ly));
+    if (max_context_len < 0 || max_context_len > ly.maxctx)
+        return pod_fail(POD_ERR_INVALID_ARG, "max_context_len %d outside [0, %d]", max_context_len, ly.maxctx);
+    const int64_t *len = cache->host_len + (size_t)layer * ly.B;
+    int64_t longest = 0;
+    for (int b = 0; b < B; ++b) longest = len[b] > longest ? len[b] : longest;
+    const bool lowest = layer % ly.G == 0;
+    if (!lowest && !q_shared && longest > ly.P)
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and holds distant tokens: q_shared is required", layer);
+    if (max_context_len == 0) max_context_len = (int)longest;
+    if (max_context_len == 0) max_context_len = 1;
+    return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
+                             workspace, workspace_bytes, out, (hipStream_t)stream);
+}
+
+extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, const void *q, const void *k,
+                                     const void *v, const void *q_shared, const void *k_shared, float scale,
+                                     void *out, int write_cache, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!q || !k || !v || !out) return pod_fail(POD_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
+    if (n < 1) return pod_fail(POD_ERR_INVALID_ARG, "n must be >= 1");
+    const bool lowest = layer % ly.G == 0;
+    if ((q_shared == nullptr) != (k_shared == nullptr))
+        return pod_fail(POD_ERR_INVALID_ARG, "q_shared and k_shared must be given together");
+    if (!lowest && !q_shared && n > ly.P)
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and the prompt has distant tokens: q_shared and k_shared are required", layer);
+    if (write_cache) {
+        if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
+        if (n > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n = %d exceeds max_context = %d", n, ly.maxctx);
+        if (cache->host_len[(size_t)layer * ly.B + seq_slot] != 0)
+            return pod_fail(POD_ERR_STATE, "slot %d at layer %d is not empty", seq_slot, layer);
+    }
+    if (lowest) { q_shared = nullptr; k_shared = nullptr; }
+    rc = pod_launch_prefill(ly, layer, n, q, k, v, q_shared, k_shared, scale, out, (hipStream_t)stream);
+    if (rc) return rc;
+    if (write_cache) return pod_cache_fill(cache, layer, seq_slot, n, k, v, stream);
+    return POD_OK;
+}
+
+extern "C" int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slot, void *sinkK, void *sinkV,
+                                        void *recentK, void *recentV, void *distK, void *distV, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
+    if (distK && layer % ly.G != 0)
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d keeps no distant keys (not the lowest layer of its block)", layer);
+    const int64_t n = cache->host_len[(size_t)layer * ly.B + seq_slot];
+    if (n == 0) return POD_OK;
+    return pod_launch_export(cache, layer, seq_slot, n, sinkK, sinkV, recentK, recentV, distK, distV, (hipStream_t)stream);
+}

@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of libpod (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/pod.h"
+
+// ---------------------------------------------------------------------------
+// Device-memory layout of one cache.
+//
+// header   : int32 lens[L][B] (tokens held per layer and slot), int32 flag
+// proxK/V  : [L][B][Hkv][P][D]   P = S + W slots per (layer, slot, kv head):
+//            slots [0,S) are the sink tokens, slot S + (p - S) % W is the ring
+//            slot of position p >= S.  While fewer than W tokens >= S exist
+//            the ring fills from its first slot, so the live proximal rows are
+//            always the contiguous slots [0, min(n, P)).
+// distV    : [L][B][Hkv][Cd][D]  Cd = max_context - P; row t = position S + t
+// distK    : [L/G][B][Hkv][Cd][D] keys of the block's lowest layer only
+//
+// Head-major on purpose: the rows one (sequence, kv head) pair streams at decode
+// time are one contiguous run, so a split-K chunk is a single linear read.
+// Offsets are in bytes from the buffer start; every region is 256-byte aligned.
+// ---------------------------------------------------------------------------
+struct pod_layout {
+    int32_t L, G, Hq, Hkv, D, S, W, B, maxctx;
+    int32_t P;   // S + W
+    int32_t Cd;  // distant rows per (layer, slot, head)
+    int32_t rep; // Hq / Hkv
+    size_t off_lens, off_flag, off_proxK, off_proxV, off_distV, off_distK, total_bytes;
+};
+
+typedef unsigned short pod_bf16; // raw bits
+
+__host__ __device__ inline size_t pod_prox_row0(const pod_layout &ly, int layer, int b, int h)
+{
+    return (((size_t)layer * ly.B + b) * ly.Hkv + h) * (size_t)ly.P;
+}
+__host__ __device__ inline size_t pod_dist_row0(const pod_layout &ly, int layer_or_group, int b, int h)
+{
+    return (((size_t)layer_or_group * ly.B + b) * ly.Hkv + h) * (size_t)ly.Cd;
+}
+
+struct pod_cache {
+    pod_layout ly;
+    char *base;        // device buffer (caller's)
+    int64_t *host_len; // [L][B] mirror
+    int device;
+};
+
+// error reporting (pod_api.hip)
+int pod_fail(int code, const char *fmt, ...);
+int pod_hip_fail(hipError_t e, const char *what);
+
+#define POD_HIP_TRY(expr)                                        \
+    do {                                                         \
+        hipError_t e__ = (expr);                                 \
+        if (e__ != hipSuccess) return pod_hip_fail(e__, #expr);  \
+    } while (0)
+
+// launchers (each validates nothing: the API layer did)
+int pod_launch_clear_header(const pod_cache *c, hipStream_t st);
+int pod_launch_reset(const pod_cache *c, int seq_slot, hipStream_t st);
+int pod_launch_append(const pod_cache *c, int layer, const void *k_new, const void *v_new,
+                      const int32_t *positions, int B, hipStream_t st);
+int pod_launch_fill(const pod_cache *c, int layer, int seq_slot, int n, const void *k, const void *v,
+                    hipStream_t st);
+int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, void *sinkK, void *sinkV,
+                      void *recK, void *recV, void *distK, void *distV, hipStream_t st);
+int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
+                      const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
+                      void *out, hipStream_t st);
+size_t pod_decode_workspace_bytes(const pod_layout &ly);
+int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
+                       const void *q_shared, const void *k_shared, float scale, void *out, hipStream_t st);

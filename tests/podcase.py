@@ -1,0 +1,85 @@
+"""Shared set-up for the GPU parity tests: the same seeded inputs go into libpod's cache on
+the GPU and into the CPU oracle's cache model.  Inputs are generated separately on each side
+(the generator is counter-based and bit-identical across devices)."""
+import math
+
+import numpy as np
+import torch
+
+import paper_2412_02252_amd as pod
+from oracle import pod_oracle as po
+from pod_inputs import gen
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3   # bf16 inputs, fp32 accumulation, bf16 output
+
+
+def assert_close(got_bf16: torch.Tensor, ref_f64: np.ndarray, what=""):
+    got = got_bf16.float().cpu().numpy().astype(np.float64)
+    assert got.shape == ref_f64.shape, (got.shape, ref_f64.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - ref_f64)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, f"{what}: max {err.max():.3e} mean {err.mean():.3e}"
+
+
+class Case:
+    def __init__(self, L, G, Hq, Hkv, d, S, W, B, max_ctx, seed=1, device="cuda:0", with_oracle_cache=True, **kgen):
+        self.L, self.G, self.Hq, self.Hkv, self.d, self.S, self.W, self.B = L, G, Hq, Hkv, d, S, W, B
+        self.max_ctx, self.seed, self.dev, self.kgen = max_ctx, seed, device, kgen
+        self.cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx)
+        self.gpu = pod.PodCache(self.cfg, device)
+        self.cpu = po.Cache(L, G, Hkv, d, S, W, B, max_ctx) if with_oracle_cache else None
+        self.scale = 1.0 / math.sqrt(d)
+
+    # ---- inputs (device = "cpu" or the GPU) -------------------------------------------
+    def keys(self, layer, seq, n, device, pos0=0, **kw):
+        return gen.keys_bf16(self.seed, layer, seq, n, self.Hkv, self.d, device=device, pos0=pos0, **self.kgen, **kw)
+
+    def values(self, layer, seq, n, device, pos0=0, **kw):
+        return gen.values_bf16(self.seed, layer, seq, n, self.Hkv, self.d, device=device, pos0=pos0, **kw)
+
+    def queries(self, layer, seq, n, device, pos0=0):
+        return gen.queries_bf16(self.seed, layer, seq, n, self.Hq, self.d, device=device, pos0=pos0)
+
+    # ---- both sides ---------------------------------------------------------------------
+    def fill(self, layer, seq, n):
+        self.gpu.pod_cache_fill(layer, seq, self.keys(layer, seq, n, self.dev), self.values(layer, seq, n, self.dev))
+        if self.cpu is not None:
+            self.cpu.fill(layer, seq, gen.bf16_bits(self.keys(layer, seq, n, "cpu")),
+                          gen.bf16_bits(self.values(layer, seq, n, "cpu")))
+
+    def append(self, layer, positions):
+        """positions: list with one entry per sequence 0..len-1."""
+        B = len(positions)
+        k = torch.cat([self.keys(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)])
+        v = torch.cat([self.values(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)])
+        pos = torch.tensor(positions, dtype=torch.int32, device=self.dev)
+        self.gpu.pod_cache_append(layer, k.contiguous(), v.contiguous(), pos)
+        if self.cpu is not None:
+            kc = torch.cat([self.keys(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            vc = torch.cat([self.values(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            self.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), positions)
+        assert B <= self.B
+
+    def decode_queries(self, layer, ctx, device):
+        """Query of the token at position ctx[b]-1 of each sequence: [B][Hq][d]."""
+        return torch.cat([self.queries(layer, b, 1, device, pos0=max(n, 1) - 1) for b, n in enumerate(ctx)]).contiguous()
+
+    def decode(self, layer, ctx, max_context_len=0):
+        lowest = layer - layer % self.G
+        q = self.decode_queries(layer, ctx, self.dev)
+        qs = self.decode_queries(lowest, ctx, self.dev) if lowest != layer else None
+        ctx_t = torch.tensor(ctx, dtype=torch.int32, device=self.dev)
+        return self.gpu.pod_decode_attention(layer, q, qs, ctx_t, self.scale, max_context_len=max_context_len)
+
+    def decode_ref(self, layer, ctx):
+        lowest = layer - layer % self.G
+        q = gen.bf16_bits(self.decode_queries(layer, ctx, "cpu"))
+        qs = gen.bf16_bits(self.decode_queries(lowest, ctx, "cpu")) if lowest != layer else None
+        return self.cpu.decode_attention(layer, q, qs, ctx, self.scale)
+
+    def assert_cache_equal(self, layer, seq):
+        g = self.gpu.pod_cache_export_logical(layer, seq)
+        c = self.cpu.export(layer, seq)
+        assert set(g) == set(c)
+        for name in c:
+            assert np.array_equal(gen.bf16_bits(g[name]), c[name]), f"layer {layer} seq {seq} {name}"
