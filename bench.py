@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the PoD attention hot path on one MI355X.
+
+Workload (benchmark configs[1]): LLaMA3-8B-shaped decode, one layer block of G=2 layers,
+32 query / 8 KV heads, head_dim 128, batch 1, context 32768 (+1 per step), S=64, W=2048, bf16,
+RoPE-rotated keys (base 500000).  A *step* is one pass of the whole path for one new token:
+append its K/V to both layers (with window-to-distant demotion), decode attention on the
+block's lowest layer, decode attention on the upper layer (shared distant logits).
+
+The chip has a 256 MB last-level cache and one block's cache is only 206 MB, so the bench
+keeps `--rotate` independent blocks (same shape, different data) and visits them round-robin:
+each step streams K/V that left the cache long ago, as a 32-layer model would.
+
+Prints ONE JSON line: whole-step throughput (`value`, algorithmic K/V bytes per second), the
+roofline of the dominant kernel (split-K partial kernel, timed with HIP events through
+pod_profile_*), the CPU oracle timed on the host cores, and the prefill figures (configs[3]).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X datasheet
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--rotate", type=int, default=4, help="independent layer blocks visited round-robin")
+    ap.add_argument("--context", type=int, default=32768)
+    ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of one HIP graph replay")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--prefill-n", type=int, default=16384)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def traffic_from_profiles():
+    """HBM bytes per launch of the decode partial kernel from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", "decode_partial_kernel_cfg2_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here shards across GPUs)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2412_02252_amd as pod
+    from pod_inputs import gen
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    G, Hq, Hkv, d, S, W = 2, 32, 8, 128, 64, 2048
+    R, n0, K, Wm, P = a.rotate, a.context, a.steps, a.warmup, a.profile_steps
+    seed = 20241202 + 2
+    total_steps = Wm + K + P
+    per_block = (total_steps + R - 1) // R
+    max_ctx = n0 + per_block + 1
+    L = G * R
+    cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, 1, max_ctx)
+    cache = pod.PodCache(cfg, dev)
+    scale = 1.0 / math.sqrt(d)
+    row = Hkv * d * 2
+    rope = dict(rope_base=500000.0, rope_max_pos=max_ctx)
+
+    # ---- fill every block to n0 tokens
+    for layer in range(L):
+        k = gen.keys_bf16(seed, layer, 0, n0, Hkv, d, device=dev, **rope)
+        v = gen.values_bf16(seed, layer, 0, n0, Hkv, d, device=dev)
+        cache.pod_cache_fill(layer, 0, k, v)
+        del k, v
+    # ---- per-step inputs, generated up front
+    steps = []
+    for s in range(total_steps):
+        g, p = s % R, n0 + s // R
+        ent = dict(layers=(G * g, G * g + 1), n=p + 1,
+                   pos=torch.tensor([p], dtype=torch.int32, device=dev),
+                   ctx=torch.tensor([p + 1], dtype=torch.int32, device=dev))
+        for j, layer in enumerate(ent["layers"]):
+            ent[f"k{j}"] = gen.keys_bf16(seed, layer, 0, 1, Hkv, d, device=dev, pos0=p, **rope)
+            ent[f"v{j}"] = gen.values_bf16(seed, layer, 0, 1, Hkv, d, device=dev, pos0=p)
+            ent[f"q{j}"] = gen.queries_bf16(seed, layer, 0, 1, Hq, d, device=dev, pos0=p)
+            ent[f"o{j}"] = torch.empty((1, Hq, d), dtype=torch.bfloat16, device=dev)
+        steps.append(ent)
+
+    def run_step(e):
+        l0, l1 = e["layers"]
+        cache.pod_cache_append(l0, e["k0"], e["v0"], e["pos"])
+        cache.pod_cache_append(l1, e["k1"], e["v1"], e["pos"])
+        cache.pod_decode_attention(l0, e["q0"], None, e["ctx"], scale, out=e["o0"], max_context_len=e["n"])
+        cache.pod_decode_attention(l1, e["q1"], e["q0"], e["ctx"], scale, out=e["o1"], max_context_len=e["n"])
+
+    def step_bytes(e):
+        return 2 * (2 * e["n"] * row)   # two layers, K and V rows of every token once
+
+    # ---- warm-up
+    for e in steps[:Wm]:
+        run_step(e)
+    torch.cuda.synchronize()
+    cache.pod_cache_check()
+
+    # ---- timed region: exactly K steps
+    timed = steps[Wm:Wm + K]
+    mode = "eager"
+    graph = None
+    if not a.no_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for e in timed:
+                    run_step(e)
+            mode = "hipgraph"
+        except Exception as ex:  # capture unsupported: fall back to eager launches of the same kernels
+            print(f"bench.py: graph capture failed ({ex}); timing eager launches", file=sys.stderr)
+            graph = None
+            a.no_graph = True
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    else:
+        for e in timed:
+            run_step(e)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    cache.pod_cache_check()
+    elapsed = t1 - t0
+    nbytes = sum(step_bytes(e) for e in timed)
+    value = nbytes / elapsed / 1e9
+
+    # ---- dominant kernel (decode partial kernel) with HIP events, eager launches
+    prof = steps[Wm + K:]
+    cache.pod_profile_enable(2 * len(prof) + 4)
+    for e in prof:
+        run_step(e)
+    torch.cuda.synchronize()
+    ms, launches = cache.pod_profile_read()
+    cache.pod_profile_disable()
+    cache.pod_cache_check()
+    kernel_s = ms / 1e3 / max(launches, 1)
+    bytes_per_launch = sum(step_bytes(e) for e in prof) / max(launches, 1)
+    achieved = bytes_per_launch / kernel_s / 1e9
+
+    out = {
+        "metric": "decode attn HBM GB/s @32K ctx",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(elapsed / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: LLaMA3-8B-shaped PoD decode, one layer block G=2, 32q/8kv heads, d=128, "
+                               f"batch 1, context {n0}+step, S=64, W=2048, RoPE keys; step = append x2 + decode x2",
+                   "rotating_blocks": R, "launch": mode, "bytes_per_step": step_bytes(timed[0])},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic_from_profiles(), "bytes_per_launch": int(bytes_per_launch),
+                     "avg_kernel_us": round(kernel_s * 1e6, 3), "launches": launches},
+    }
+
+    # ---- CPU oracle on the host cores, a bounded sample of the same steps (block 0's)
+    if not a.no_cpu:
+        from oracle import pod_oracle as po
+        oc = po.Cache(G, G, Hkv, d, S, W, 1, max_ctx)
+        for layer in range(G):
+            k = gen.keys_bf16(seed, layer, 0, n0, Hkv, d, device=dev, **rope)
+            v = gen.values_bf16(seed, layer, 0, n0, Hkv, d, device=dev)
+            oc.fill(layer, 0, gen.bf16_bits(k), gen.bf16_bits(v))
+            del k, v
+        mine = [e for i, e in enumerate(steps) if i % R == 0]
+        host = [{key: gen.bf16_bits(e[key]) for key in ("k0", "v0", "q0", "k1", "v1", "q1")} for e in mine]
+        cpu_t, cpu_bytes, done, worst = 0.0, 0, 0, 0.0
+        for e, h in zip(mine, host):
+            p = e["n"] - 1
+            c0 = time.perf_counter()
+            oc.append(0, h["k0"], h["v0"], [p])
+            oc.append(1, h["k1"], h["v1"], [p])
+            r0 = oc.decode_attention(0, h["q0"], None, [p + 1], scale)
+            r1 = oc.decode_attention(1, h["q1"], h["q0"], [p + 1], scale)
+            cpu_t += time.perf_counter() - c0
+            cpu_bytes += step_bytes(e)
+            done += 1
+            for r, o in ((r0, e["o0"]), (r1, e["o1"])):
+                worst = max(worst, float(np.abs(o.float().cpu().numpy() - r).max()))
+            if cpu_t > a.cpu_seconds:
+                break
+        out["cpu_baseline"] = {"value": round(cpu_bytes / cpu_t / 1e9, 3), "unit": "GB/s", "cores": po.num_threads(),
+                               "kind": "oracle", "sample": f"{done} of the same decode steps (one block, both layers)",
+                               "ms_per_step": round(cpu_t / done * 1e3, 2), "gpu_vs_oracle_max_abs_err": worst}
+
+    # ---- prefill (configs[3]): one block, n tokens, causal, attention + cache construction
+    if not a.no_prefill:
+        n = a.prefill_n
+        pcfg = pod.make_config(G, G, Hq, Hkv, d, S, W, 1, n)
+        del cache
+        torch.cuda.empty_cache()
+        pc = pod.PodCache(pcfg, dev)
+        pseed = 20241202 + 4
+        q = [gen.queries_bf16(pseed, l, 0, n, Hq, d, device=dev) for l in range(G)]
+        k = [gen.keys_bf16(pseed, l, 0, n, Hkv, d, device=dev) for l in range(G)]
+        v = [gen.values_bf16(pseed, l, 0, n, Hkv, d, device=dev) for l in range(G)]
+        o = torch.empty_like(q[0])
+        flops = 4.0 * d * Hq * n * (n + 1) / 2
+        res = {}
+        for layer, name in ((0, "lowest_layer"), (1, "upper_layer")):
+            times = []
+            for it in range(4):
+                pc.pod_cache_reset(-1)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                pc.pod_prefill_attention(layer, 0, q[layer], k[layer], v[layer], q[0] if layer else None,
+                                         k[0] if layer else None, scale, out=o, write_cache=True)
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) / 1e3)
+            t = min(times[1:])
+            res[name] = {"ms": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 2),
+                         "frac_of_bf16_mfma_peak": round(flops / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        pc.pod_cache_check()
+        out["prefill"] = {"workload": f"configs[3]: one block G=2, 32q/8kv, d=128, prompt {n}, S=64, W=2048, "
+                                      "attention + cache construction", "flops_per_layer": flops,
+                          "peak_tflops": MFMA_BF16_PEAK_TFLOPS, **res}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -188,6 +188,18 @@ int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, cons
 int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slot, void *sinkK, void *sinkV,
                              void *recentK, void *recentV, void *distK, void *distV, void *stream);
 
+/*
+ * Measurement aid: while enabled, pod_decode_attention brackets its dominant kernel (the
+ * split-K partial kernel that streams K and V) with HIP events on the call's stream, up to
+ * max_records launches.  pod_profile_read waits for the recorded events and returns the
+ * summed kernel time in milliseconds and the number of launches, then forgets them.
+ * Events are host objects: no device memory is allocated.  Do not enable while the stream is
+ * being captured into a graph.
+ */
+int pod_profile_enable(pod_cache *cache, int max_records);
+int pod_profile_disable(pod_cache *cache);
+int pod_profile_read(pod_cache *cache, double *total_ms, int *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@ EXPORTS = [
     "pod_last_error", "pod_cache_bytes", "pod_cache_live_bytes", "pod_cache_init", "pod_cache_destroy",
     "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
+    "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
 ]
 
 
@@ -66,6 +67,9 @@ def load():
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
         "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
         "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
+        "pod_profile_enable": [vp, C.c_int],
+        "pod_profile_disable": [vp],
+        "pod_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -178,6 +182,17 @@ class PodCache:
                                             _ptr(q_shared, torch.bfloat16), _ptr(k_shared, torch.bfloat16), scale,
                                             _ptr(out, torch.bfloat16), int(bool(write_cache)), _stream()))
         return out
+
+    def pod_profile_enable(self, max_records):
+        _check(load().pod_profile_enable(self.handle, max_records))
+
+    def pod_profile_disable(self):
+        _check(load().pod_profile_disable(self.handle))
+
+    def pod_profile_read(self):
+        ms, cnt = C.c_double(), C.c_int()
+        _check(load().pod_profile_read(self.handle, C.byref(ms), C.byref(cnt)))
+        return ms.value, cnt.value
 
     def pod_cache_export_logical(self, layer, seq_slot):
         """dict of bf16 tensors [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV (+ distK at a lowest layer)."""

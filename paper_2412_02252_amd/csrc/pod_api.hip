@@ -121,6 +121,7 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
     c->base = (char *)dev_buf;
     c->host_len = (int64_t *)calloc((size_t)ly.L * ly.B, sizeof(int64_t));
     c->device = -1;
+    c->prof_ev = nullptr; c->prof_cap = 0; c->prof_n = 0;
     if (!c->host_len) { delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { free(c->host_len); delete c; return pod_hip_fail(e, "hipGetDevice"); }
@@ -133,8 +134,52 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
 extern "C" int pod_cache_destroy(pod_cache *cache)
 {
     if (!cache) return POD_OK;
+    pod_profile_disable(cache);
     free(cache->host_len);
     delete cache;
+    return POD_OK;
+}
+
+extern "C" int pod_profile_disable(pod_cache *cache)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    for (int i = 0; i < 2 * cache->prof_cap; ++i) (void)hipEventDestroy(cache->prof_ev[i]);
+    free(cache->prof_ev);
+    cache->prof_ev = nullptr; cache->prof_cap = 0; cache->prof_n = 0;
+    return POD_OK;
+}
+
+extern "C" int pod_profile_enable(pod_cache *cache, int max_records)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    if (max_records < 1 || max_records > (1 << 20)) return pod_fail(POD_ERR_INVALID_ARG, "max_records out of range");
+    pod_profile_disable(cache);
+    cache->prof_ev = (hipEvent_t *)calloc((size_t)2 * max_records, sizeof(hipEvent_t));
+    if (!cache->prof_ev) return pod_fail(POD_ERR_CAPACITY, "out of host memory");
+    for (int i = 0; i < 2 * max_records; ++i) {
+        hipError_t e = hipEventCreate(&cache->prof_ev[i]);
+        if (e != hipSuccess) {
+            for (int k = 0; k < i; ++k) (void)hipEventDestroy(cache->prof_ev[k]);
+            free(cache->prof_ev); cache->prof_ev = nullptr;
+            return pod_hip_fail(e, "hipEventCreate");
+        }
+    }
+    cache->prof_cap = max_records; cache->prof_n = 0;
+    return POD_OK;
+}
+
+extern "C" int pod_profile_read(pod_cache *cache, double *total_ms, int *launches)
+{
+    if (!cache || !total_ms || !launches) return pod_fail(POD_ERR_INVALID_ARG, "NULL argument");
+    double sum = 0.0;
+    for (int i = 0; i < cache->prof_n; ++i) {
+        POD_HIP_TRY(hipEventSynchronize(cache->prof_ev[2 * i + 1]));
+        float ms = 0.f;
+        POD_HIP_TRY(hipEventElapsedTime(&ms, cache->prof_ev[2 * i], cache->prof_ev[2 * i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum; *launches = cache->prof_n;
+    cache->prof_n = 0;
     return POD_OK;
 }
 

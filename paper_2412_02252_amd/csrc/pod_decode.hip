@@ -34,6 +34,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4; // native 128-bit vector (plain loads/stores, no struct copies)
 
 constexpr int kWaves = 4;          // waves per workgroup
 constexpr int kTile = 32;          // tokens per wave iteration
@@ -72,7 +73,7 @@ __device__ inline int decode_seq_len(const decode_params &p, int b, bool *bad)
     return n;
 }
 
-__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ inline unsigned pack_bf16(float lo, float hi)
 {
@@ -105,10 +106,10 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int end = min(start + p.chunk, region_len);
 
     const int group = p.layer / ly.G;
-    const uint4 *Kb = distant ? (const uint4 *)(p.base + ly.off_distK) + pod_dist_row0(ly, group, b, h) * CPR
-                              : (const uint4 *)(p.base + ly.off_proxK) + pod_prox_row0(ly, p.layer, b, h) * CPR;
-    const uint4 *Vb = distant ? (const uint4 *)(p.base + ly.off_distV) + pod_dist_row0(ly, p.layer, b, h) * CPR
-                              : (const uint4 *)(p.base + ly.off_proxV) + pod_prox_row0(ly, p.layer, b, h) * CPR;
+    const u32x4 *Kb = distant ? (const u32x4 *)(p.base + ly.off_distK) + pod_dist_row0(ly, group, b, h) * CPR
+                              : (const u32x4 *)(p.base + ly.off_proxK) + pod_prox_row0(ly, p.layer, b, h) * CPR;
+    const u32x4 *Vb = distant ? (const u32x4 *)(p.base + ly.off_distV) + pod_dist_row0(ly, p.layer, b, h) * CPR
+                              : (const u32x4 *)(p.base + ly.off_proxV) + pod_prox_row0(ly, p.layer, b, h) * CPR;
     const pod_bf16 *qsrc = (distant && p.q_shared) ? p.q_shared : p.q;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -116,17 +117,17 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 
     // kWaves K tiles of kTile rows; the same bytes later hold the merge buffer
     // [kWaves][rep <= 16][D] floats, which is exactly as large.
-    __shared__ uint4 lds[kWaves][kTile * CPR];
-    static_assert(sizeof(uint4) * kTile * CPR == sizeof(float) * 16 * D, "merge buffer must fit the K tiles");
-    uint4 *ldsK = lds[wave];
+    __shared__ u32x4 lds[kWaves][kTile * CPR];
+    static_assert(sizeof(u32x4) * kTile * CPR == sizeof(float) * 16 * D, "merge buffer must fit the K tiles");
+    u32x4 *ldsK = lds[wave];
 
     // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
     bf16x8 qf[KST];
     {
-        const uint4 *qrow = (const uint4 *)(qsrc + ((size_t)b * ly.Hq + (size_t)h * ly.rep + m16) * D);
+        const u32x4 *qrow = (const u32x4 *)(qsrc + ((size_t)b * ly.Hq + (size_t)h * ly.rep + m16) * D);
 #pragma unroll
         for (int s = 0; s < KST; ++s) {
-            uint4 t = make_uint4(0, 0, 0, 0);
+            u32x4 t = u32x4{0u, 0u, 0u, 0u};
             if (m16 < ly.rep) t = qrow[4 * s + j];
             qf[s] = as_bf16x8(t);
         }
@@ -142,23 +143,22 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int vx = (lane / CPR) % XN;           // which of the XN dims per piece pair this lane serves
     const int last = end - 1;
 
-    uint4 kreg[NLD], vreg[8];
-    auto load_tile = [&](int t0, uint4(&kk)[NLD], uint4(&vv)[8]) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int row = min(t0 + RPI * i + kr, last);
-            kk[i] = Kb[(size_t)row * CPR + kc];
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);
-            const int row = min(t0 + tok, last);
-            vv[e] = Vb[(size_t)row * CPR + vc];
-        }
-    };
+    // Tile loads.  Rows past the chunk are clamped to its last row (valid memory, masked later),
+    // so the loads are unconditional: the software pipeline below needs no branches around them.
+    u32x4 kreg[NLD], vreg[8];
+#define POD_LOAD_TILE(T0)                                                         \
+    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                             \
+        const int row = min((T0) + RPI * i + kr, last);                           \
+        kreg[i] = Kb[(size_t)row * CPR + kc];                                     \
+    }                                                                             \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e) {                               \
+        const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);               \
+        const int row = min((T0) + tok, last);                                    \
+        vreg[e] = Vb[(size_t)row * CPR + vc];                                     \
+    }
 
     int t0 = start + wave * kTile;
-    if (t0 < end) load_tile(t0, kreg, vreg);
+    POD_LOAD_TILE(t0)
 
     for (; t0 < end; t0 += kWaves * kTile) {
         // ---- K tile through LDS into A-operand order
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
             const int r = RPI * i + kr;
             ldsK[r * CPR + (kc ^ (r % CPR))] = kreg[i];
         }
-        uint4 vcur[8];
+        u32x4 vcur[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) vcur[e] = vreg[e];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -177,8 +177,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int s = 0; s < KST; ++s) {
             const int col = 4 * s + j;
-            const uint4 a0 = ldsK[m16 * CPR + (col ^ (m16 % CPR))];
-            const uint4 a1 = ldsK[(16 + m16) * CPR + (col ^ ((16 + m16) % CPR))];
+            const u32x4 a0 = ldsK[m16 * CPR + (col ^ (m16 % CPR))];
+            const u32x4 a1 = ldsK[(16 + m16) * CPR + (col ^ ((16 + m16) % CPR))];
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), qf[s], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), qf[s], s1, 0, 0, 0);
         }
@@ -186,8 +186,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         __builtin_amdgcn_wave_barrier();
 
         // ---- next tile's loads go out before the softmax / PV work of this one
-        const int tn = t0 + kWaves * kTile;
-        if (tn < end) load_tile(tn, kreg, vreg);
+        POD_LOAD_TILE(t0 + kWaves * kTile)
 
         // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
         float sc[8];
@@ -213,7 +212,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         m_run = m_new;
 #pragma unroll
         for (int x = 0; x < NPV; ++x) acc[x] *= alpha;
-        uint4 pw;
+        u32x4 pw;
         pw.x = pack_bf16(sc[0], sc[1]); pw.y = pack_bf16(sc[2], sc[3]);
         pw.z = pack_bf16(sc[4], sc[5]); pw.w = pack_bf16(sc[6], sc[7]);
         const bf16x8 pf = as_bf16x8(pw);
@@ -223,9 +222,9 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int x = 0; x < NPV; ++x) {
             // dim index inside the piece: XN = 1 -> x ; XN = 2 -> 2x + vx
-            uint4 tlo, thi; // candidates for the even / odd dim of dword pair
+            u32x4 tlo, thi; // candidates for the even / odd dim of dword pair
             const int w = (XN == 1) ? (x >> 1) : x; // dword of the piece holding the dim(s)
-            auto dw = [&](const uint4 &u) -> unsigned { return w == 0 ? u.x : w == 1 ? u.y : w == 2 ? u.z : u.w; };
+            auto dw = [&](const u32x4 &u) -> unsigned { return u[w]; };
             tlo.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x05040100u);
             tlo.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x05040100u);
             tlo.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x05040100u);
@@ -234,7 +233,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
             thi.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x07060302u);
             thi.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x07060302u);
             thi.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x07060302u);
-            uint4 vt;
+            u32x4 vt;
             if (XN == 1) {
                 vt = (x & 1) ? thi : tlo;
             } else {
@@ -245,6 +244,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         }
     }
 
+#undef POD_LOAD_TILE
     // ---- merge the waves of this workgroup, write one partial per (head, chunk)
     // acc[x][i] is O^T[dim slot 4j+i][head m16]; the slot's dim is
     //   XN = 1: 8*(4j+i) + x        XN = 2: 8*((4j+i) % 8) + 2x + (4j+i)/8
@@ -394,13 +394,18 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 
     const dim3 grid((unsigned)NC, (unsigned)ly.Hkv, (unsigned)B);
     const dim3 cgrid((unsigned)ly.Hq, (unsigned)B);
-    if (ly.D == 128) {
+    pod_cache *mc = const_cast<pod_cache *>(c);
+    const bool prof = mc->prof_ev && mc->prof_n < mc->prof_cap;
+    if (prof) POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n], st));
+    if (ly.D == 128)
         hipLaunchKernelGGL(decode_partial_kernel<128>, grid, dim3(kWaves * 64), 0, st, p);
-        hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(256), 0, st, p);
-    } else {
+    else
         hipLaunchKernelGGL(decode_partial_kernel<64>, grid, dim3(kWaves * 64), 0, st, p);
+    if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }
+    if (ly.D == 128)
+        hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(256), 0, st, p);
+    else
         hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(256), 0, st, p);
-    }
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }

@@ -47,6 +47,9 @@ struct pod_cache {
     char *base;        // device buffer (caller's)
     int64_t *host_len; // [L][B] mirror
     int device;
+    // optional event pairs around the decode partial kernel (pod_profile_*)
+    hipEvent_t *prof_ev; // [2 * prof_cap]
+    int prof_cap, prof_n;
 };
 
 // error reporting (pod_api.hip)
