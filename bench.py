@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--prefill-n", type=int, default=16384)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run plain copy kernels of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -112,6 +114,14 @@ def main():
 
     def step_bytes(e):
         return 2 * (2 * e["n"] * row)   # two layers, K and V rows of every token once
+
+    if a.pmc_calibration:   # a plain copy kernel of known size: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up
     for e in steps[:Wm]:

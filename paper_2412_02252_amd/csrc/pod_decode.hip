@@ -28,6 +28,8 @@
 //    summation index, so the 8 tokens a lane holds are chosen to be exactly the 8 tokens
 //    whose probabilities the same lane already holds in the S^T accumulators of two
 //    16-token MFMA tiles: tokens {4j..4j+3} of tile 0 and of tile 1.
+#include <stddef.h>
+
 #include "pod_internal.h"
 
 namespace {
@@ -40,33 +42,77 @@ constexpr int kWaves = 4;          // waves per workgroup
 constexpr int kTile = 32;          // tokens per wave iteration
 constexpr float kNegBig = -1.0e30f; // stands in for -inf (keeps exp2 arguments finite)
 constexpr int kMinChunk = 128;     // smallest chunk (tokens) a workgroup takes
+constexpr int kMaxHostLens = 256;  // batch sizes up to this pass the host mirror's lengths as kernel arguments
+
+// Kernel arguments.  Everything is resolved on the host so that the kernel's way to its first
+// K/V load is short: the fields a workgroup needs for its first load addresses sit at the start
+// of the argument block, and with the host mirror's sequence length among the arguments no
+// device memory has to be read first (a dependent load there costs 1-8 us once the other
+// workgroups saturate the memory system).
+struct decode_hot { // exactly two 64-byte lines, read in one go at kernel entry
+    // line 0: what a workgroup needs for its first load addresses
+    const u32x4 *kdist, *vdist, *kprox, *vprox; // row 0 of (slot 0, head 0) in this layer's / block's regions
+    int32_t cd, prows;   // rows per (slot, head) in the distant / proximal regions (Cd, P = S + W)
+    int32_t hkv, rep;
+    int32_t chunk;       // tokens per workgroup
+    int32_t max_nd;      // distant chunk slots per (sequence, head)
+    int32_t nc;          // all chunk slots per (sequence, head): max_nd + proximal slots
+    int32_t use_hlen;    // 1: hlen[] holds the host mirror's length of every slot < B
+    // line 1: queries, partial results, device-side lengths
+    const pod_bf16 *q, *q_shared;
+    float scale_log2e;
+    int32_t hq;
+    float *part_acc; // [B][Hq][nc][D]
+    float *part_ml;  // [B][Hq][nc][2]
+    const int32_t *ctx;         // context_lens
+    const int32_t *lens_layer;  // device-side lengths of this layer   [B]
+    const int32_t *lens_lowest; // ... of the block's lowest layer     [B]
+};
+static_assert(sizeof(decode_hot) == 128, "decode_hot must be two 64-byte lines");
 
 struct decode_params {
-    const char *base;
-    pod_layout ly;
-    int layer, B;
-    const pod_bf16 *q, *q_shared;
-    const int32_t *ctx;
-    float scale_log2e;
-    int chunk;   // tokens per workgroup
-    int max_nd;  // distant chunk slots per (sequence, head)
-    int max_np;  // proximal chunk slots
-    float *part_acc; // [B][Hq][NC][D]
-    float *part_ml;  // [B][Hq][NC][2]
+    decode_hot hot;
+    int32_t *flag;
+    int32_t maxctx;
     pod_bf16 *out;   // [B][Hq][D]
+    int32_t hlen[kMaxHostLens];
 };
+static_assert(offsetof(decode_params, hot) == 0, "hot lines first");
 
-// Length of sequence b as the decode kernels see it: 0 = skip (inactive, or contract
-// violated: then *bad is set).  Also requires the block's lowest layer to be in step.
+// The compiler places each kernel-argument load next to its first use, which turns a kernel
+// prologue into a chain of dependent round trips to the argument block.  These two helpers read
+// the hot line and one hlen entry with volatile scalar loads at the point of call, so both are in
+// flight together before the first branch.
+typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+typedef int32_t i32x32 __attribute__((ext_vector_type(32)));
+__device__ inline decode_hot load_hot_args()
+{
+    const volatile __attribute__((address_space(4))) i32x16 *ka =
+        (const volatile __attribute__((address_space(4))) i32x16 *)__builtin_amdgcn_kernarg_segment_ptr();
+    const i32x16 lo = ka[0], hi = ka[1];
+    const i32x32 raw = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19,
+                                               20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
+    return __builtin_bit_cast(decode_hot, raw);
+}
+__device__ inline int load_hlen_arg(int b)
+{
+    const volatile __attribute__((address_space(4))) int32_t *ka =
+        (const volatile __attribute__((address_space(4))) int32_t *)__builtin_amdgcn_kernarg_segment_ptr();
+    return ka[offsetof(decode_params, hlen) / 4 + (b < kMaxHostLens ? b : 0)];
+}
+
+// Length of sequence b as validated on the device: 0 = skip (inactive, or contract violated:
+// then *bad is set).  context_lens must equal the device-side length of this layer, the block's
+// lowest layer must be in step once distant tokens exist, and the host mirror (which the partial
+// kernel may have worked from) must agree.  The three loads are independent and issued together.
 __device__ inline int decode_seq_len(const decode_params &p, int b, bool *bad)
 {
-    const int32_t *lens = (const int32_t *)(p.base + p.ly.off_lens);
-    const int n = p.ctx[b];
+    const int n = p.hot.ctx[b];
+    const int dev = p.hot.lens_layer[b];
+    const int low = p.hot.lens_lowest[b];
     *bad = false;
     if (n == 0) return 0;
-    const int lowest = p.layer - p.layer % p.ly.G;
-    if (n < 0 || n > p.ly.maxctx || n != lens[(size_t)p.layer * p.ly.B + b] ||
-        (n > p.ly.P && lens[(size_t)lowest * p.ly.B + b] != n)) {
+    if (n < 0 || n > p.maxctx || n != dev || (n > p.hot.prows && low != n) || (p.hot.use_hlen && n != p.hlen[b])) {
         *bad = true;
         return 0;
     }
@@ -92,25 +138,36 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     constexpr int XN = 16 / CPR;      // lanes sharing one V piece (1 for D=128, 2 for D=64)
     constexpr int NPV = 8 / XN;       // PV MFMAs per tile
 
-    const pod_layout &ly = p.ly;
     const int b = blockIdx.z, h = blockIdx.y, c = blockIdx.x;
-    bool bad;
-    const int n = decode_seq_len(p, b, &bad);
-    if (n == 0) return; // the combine kernel zeroes the output and raises the flag
-    const int n_prox = n < ly.P ? n : ly.P;
+    // The arguments the first loads depend on, in one round trip to the argument block.
+    const decode_hot hot = load_hot_args();
+    const int n_host = load_hlen_arg(b);
+    const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
+    const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, chunk = hot.chunk, max_nd = hot.max_nd;
+    const bool use_hlen = hot.use_hlen != 0;
+    // The host mirror's length is always within the buffers; whether it agrees with context_lens
+    // and the device-side lengths is checked by the combine kernel, which zeroes the output and
+    // raises the flag if not.  Only batches beyond kMaxHostLens read the device arrays here.
+    int n = n_host;
+    if (!use_hlen) {
+        bool bad;
+        n = decode_seq_len(p, b, &bad);
+    }
+    if (n <= 0) return;
+    const int n_prox = n < prows ? n : prows;
     const int n_dist = n - n_prox;
-    const bool distant = c < p.max_nd;
+    const bool distant = c < max_nd;
     const int region_len = distant ? n_dist : n_prox;
-    const int start = (distant ? c : c - p.max_nd) * p.chunk;
+    const int start = (distant ? c : c - max_nd) * chunk;
     if (start >= region_len) return;
-    const int end = min(start + p.chunk, region_len);
+    const int end = min(start + chunk, region_len);
 
-    const int group = p.layer / ly.G;
-    const u32x4 *Kb = distant ? (const u32x4 *)(p.base + ly.off_distK) + pod_dist_row0(ly, group, b, h) * CPR
-                              : (const u32x4 *)(p.base + ly.off_proxK) + pod_prox_row0(ly, p.layer, b, h) * CPR;
-    const u32x4 *Vb = distant ? (const u32x4 *)(p.base + ly.off_distV) + pod_dist_row0(ly, p.layer, b, h) * CPR
-                              : (const u32x4 *)(p.base + ly.off_proxV) + pod_prox_row0(ly, p.layer, b, h) * CPR;
-    const pod_bf16 *qsrc = (distant && p.q_shared) ? p.q_shared : p.q;
+    // (pointers rebuilt from the raw argument words are generic; say they are global memory)
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+    const size_t pair = (size_t)b * hkv + h;
+    const gvec_ptr Kb = (gvec_ptr)(distant ? kdist + pair * cd * CPR : kprox + pair * prows * CPR);
+    const gvec_ptr Vb = (gvec_ptr)(distant ? vdist + pair * cd * CPR : vprox + pair * prows * CPR);
+    const pod_bf16 *qsrc = (distant && hot.q_shared) ? hot.q_shared : hot.q;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m16 = lane & 15, j = lane >> 4;
@@ -120,18 +177,6 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     __shared__ u32x4 lds[kWaves][kTile * CPR];
     static_assert(sizeof(u32x4) * kTile * CPR == sizeof(float) * 16 * D, "merge buffer must fit the K tiles");
     u32x4 *ldsK = lds[wave];
-
-    // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
-    bf16x8 qf[KST];
-    {
-        const u32x4 *qrow = (const u32x4 *)(qsrc + ((size_t)b * ly.Hq + (size_t)h * ly.rep + m16) * D);
-#pragma unroll
-        for (int s = 0; s < KST; ++s) {
-            u32x4 t = u32x4{0u, 0u, 0u, 0u};
-            if (m16 < ly.rep) t = qrow[4 * s + j];
-            qf[s] = as_bf16x8(t);
-        }
-    }
 
     f32x4 acc[NPV];
 #pragma unroll
@@ -159,6 +204,19 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 
     int t0 = start + wave * kTile;
     POD_LOAD_TILE(t0)
+
+    // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
+    bf16x8 qf[KST];
+    {
+        const gvec_ptr qrow = (gvec_ptr)(qsrc + ((size_t)b * hot.hq + (size_t)h * hot.rep + m16) * D);
+#pragma unroll
+        for (int s = 0; s < KST; ++s) {
+            u32x4 t = u32x4{0u, 0u, 0u, 0u};
+            if (m16 < hot.rep) t = qrow[4 * s + j];
+            qf[s] = as_bf16x8(t);
+        }
+    }
+
 
     for (; t0 < end; t0 += kWaves * kTile) {
         // ---- K tile through LDS into A-operand order
@@ -193,8 +251,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tok0 = t0 + 4 * j + i, tok1 = tok0 + 16;
-            sc[i] = tok0 < end ? s0[i] * p.scale_log2e : kNegBig;
-            sc[4 + i] = tok1 < end ? s1[i] * p.scale_log2e : kNegBig;
+            sc[i] = tok0 < end ? s0[i] * hot.scale_log2e : kNegBig;
+            sc[4 + i] = tok1 < end ? s1[i] * hot.scale_log2e : kNegBig;
         }
         float mx = sc[0];
 #pragma unroll
@@ -251,20 +309,20 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     __syncthreads(); // all waves are done with their K tiles
     float *sm_acc = (float *)&lds[0][0];              // [kWaves][rep][D]
     __shared__ float sm_m[kWaves][16], sm_l[kWaves][16];
-    if (m16 < ly.rep) {
+    if (m16 < hot.rep) {
 #pragma unroll
         for (int x = 0; x < NPV; ++x)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int slot = 4 * j + i;
                 const int dim = (XN == 1) ? 8 * slot + x : 8 * (slot % 8) + 2 * x + slot / 8;
-                sm_acc[((size_t)wave * ly.rep + m16) * D + dim] = acc[x][i];
+                sm_acc[((size_t)wave * hot.rep + m16) * D + dim] = acc[x][i];
             }
         if (j == 0) { sm_m[wave][m16] = m_run; sm_l[wave][m16] = l_run; }
     }
     __syncthreads();
-    const int NC = p.max_nd + p.max_np;
-    for (int t = threadIdx.x; t < ly.rep * D; t += blockDim.x) {
+    const int NC = hot.nc;
+    for (int t = threadIdx.x; t < hot.rep * D; t += blockDim.x) {
         const int head = t / D, dim = t % D;
         float M = sm_m[0][head];
 #pragma unroll
@@ -273,81 +331,114 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float f = exp2f(sm_m[w][head] - M);
-            A += f * sm_acc[((size_t)w * ly.rep + head) * D + dim];
+            A += f * sm_acc[((size_t)w * hot.rep + head) * D + dim];
             Lsum += f * sm_l[w][head];
         }
-        const size_t slot = ((size_t)b * ly.Hq + (size_t)h * ly.rep + head) * NC + c;
-        p.part_acc[slot * D + dim] = A;
-        if (dim == 0) { p.part_ml[slot * 2] = M; p.part_ml[slot * 2 + 1] = Lsum; }
+        typedef __attribute__((address_space(1))) float *gfloat_ptr;
+        const size_t slot = ((size_t)b * hot.hq + (size_t)h * hot.rep + head) * NC + c;
+        ((gfloat_ptr)hot.part_acc)[slot * D + dim] = A;
+        if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
     }
 }
 
 // One workgroup per (query head, sequence): merge the chunk partials, normalise, round to bf16.
+// Merging two partials brought to a common max is the paper's gate (Eq. 4) applied to unnormalised
+// sums; over many chunks it is the same running-max merge the partial kernel uses over tiles.
+// Like the partial kernel it starts from the host mirror's length so that its loads of the
+// partials go out together with the loads that validate that length; the validation only gates
+// the final store.
 template <int D>
 __global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
 {
     constexpr int LPR = D / 4;       // lanes per partial row (float4 each)
     constexpr int NG = 256 / LPR;    // chunk groups
-    const pod_layout &ly = p.ly;
+    constexpr int UN = 8;            // partial rows in flight per thread
+    typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+    typedef const __attribute__((address_space(1))) f32x4 *gf4_ptr;
+    typedef const __attribute__((address_space(1))) int32_t *gint_ptr;
     const int head = blockIdx.x, b = blockIdx.y;
-    bool bad;
-    const int n = decode_seq_len(p, b, &bad);
-    pod_bf16 *orow = p.out + ((size_t)b * ly.Hq + head) * D;
-    if (n == 0) {
-        if (bad && head == 0 && threadIdx.x == 0) atomicOr((int32_t *)(p.base + ly.off_flag), 2);
-        for (int t = threadIdx.x; t < D; t += blockDim.x) orow[t] = 0;
-        return;
-    }
-    const int n_prox = n < ly.P ? n : ly.P;
-    const int n_dist = n - n_prox;
-    const int nd = (n_dist + p.chunk - 1) / p.chunk;
-    const int np = (n_prox + p.chunk - 1) / p.chunk;
-    const int NC = p.max_nd + p.max_np;
-    const int nvalid = nd + np;
-    const float *ml = p.part_ml + ((size_t)b * ly.Hq + head) * NC * 2;
-    const float4 *pa = (const float4 *)(p.part_acc + ((size_t)b * ly.Hq + head) * NC * D);
-    auto chunk_slot = [&](int v) { return v < nd ? v : p.max_nd + (v - nd); };
+    const decode_hot hot = load_hot_args();
+    const int n_host = load_hlen_arg(b);
+    bool bad = false;
+    int n = n_host;
+    if (!hot.use_hlen) n = decode_seq_len(p, b, &bad);
+    // validation inputs (independent loads, consumed at the very end)
+    const int v_ctx = ((gint_ptr)hot.ctx)[b], v_dev = ((gint_ptr)hot.lens_layer)[b], v_low = ((gint_ptr)hot.lens_lowest)[b];
 
-    __shared__ float red[256];
-    float mx = kNegBig;
-    for (int v = threadIdx.x; v < nvalid; v += 256) mx = fmaxf(mx, ml[chunk_slot(v) * 2]);
-    red[threadIdx.x] = mx;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
-        __syncthreads();
-    }
-    const float M = red[0];
-    __syncthreads();
+    const int n_prox = n < hot.prows ? n : hot.prows;
+    const int n_dist = n - n_prox;
+    const int nd = (n_dist + hot.chunk - 1) / hot.chunk;
+    const int np = (n_prox + hot.chunk - 1) / hot.chunk;
+    const int NC = hot.nc;
+    const int nvalid = n > 0 ? nd + np : 0;
+    const gfloat_ptr ml = (gfloat_ptr)hot.part_ml + ((size_t)b * hot.hq + head) * NC * 2;
+    const gf4_ptr pa = (gf4_ptr)hot.part_acc + ((size_t)b * hot.hq + head) * NC * LPR;
+    auto chunk_slot = [&](int v) { return v < nd ? v : hot.max_nd + (v - nd); };
 
     const int g = threadIdx.x / LPR, x = threadIdx.x % LPR;
-    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f;
-    for (int v = g; v < nvalid; v += NG) {
-        const int cs = chunk_slot(v);
-        const float f = exp2f(ml[cs * 2] - M);
-        const float4 t = pa[(size_t)cs * LPR + x];
-        a.x += f * t.x; a.y += f * t.y; a.z += f * t.z; a.w += f * t.w;
-        lsum += f * ml[cs * 2 + 1];
-    }
-    __shared__ float4 sa[NG][LPR];
-    __shared__ float sl[NG];
-    sa[g][x] = a;
-    if (x == 0) sl[g] = lsum;
-    __syncthreads();
-    if (g == 0) {
-        float L = sl[0];
-        for (int k = 1; k < NG; ++k) {
-            const float4 t = sa[k][x];
-            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
-            L += sl[k];
+    float m_run = kNegBig, l_run = 0.f;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int v0 = g; v0 < nvalid; v0 += NG * UN) {
+        float mk[UN], lk[UN];
+        f32x4 ak[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int v = v0 + k * NG;
+            const int cs = chunk_slot(v < nvalid ? v : v0);
+            mk[k] = ml[cs * 2];
+            lk[k] = ml[cs * 2 + 1];
+            ak[k] = pa[(size_t)cs * LPR + x];
+            if (v >= nvalid) { mk[k] = kNegBig; lk[k] = 0.f; ak[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
         }
-        const float inv = 1.f / L;
-        uint2 o;
-        o.x = pack_bf16(a.x * inv, a.y * inv);
-        o.y = pack_bf16(a.z * inv, a.w * inv);
-        ((uint2 *)orow)[x] = o;
+        float mb = mk[0];
+#pragma unroll
+        for (int k = 1; k < UN; ++k) mb = fmaxf(mb, mk[k]);
+        const float m_new = fmaxf(m_run, mb);
+        const float alpha = exp2f(m_run - m_new);
+        a *= alpha;
+        l_run *= alpha;
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const float f = exp2f(mk[k] - m_new);
+            a += f * ak[k];
+            l_run += f * lk[k];
+        }
+        m_run = m_new;
     }
+    __shared__ f32x4 sa[NG][LPR];
+    __shared__ float sm[NG], sl[NG];
+    sa[g][x] = a;
+    if (x == 0) { sm[g] = m_run; sl[g] = l_run; }
+    __syncthreads();
+    if (g != 0) return;
+    float M = sm[0];
+#pragma unroll
+    for (int k = 1; k < NG; ++k) M = fmaxf(M, sm[k]);
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    float L = 0.f;
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+        const float f = exp2f(sm[k] - M);
+        o += f * sa[k][x];
+        L += f * sl[k];
+    }
+    // validation: the same rule as decode_seq_len, on the values loaded at the top
+    if (hot.use_hlen) {
+        if (v_ctx == 0) n = 0;
+        else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx != v_dev || (v_ctx > hot.prows && v_low != v_ctx) || v_ctx != n_host) {
+            bad = true;
+            n = 0;
+        }
+    }
+    uint2 res = make_uint2(0u, 0u);
+    if (n > 0) {
+        const float inv = 1.f / L;
+        res.x = pack_bf16(o.x * inv, o.y * inv);
+        res.y = pack_bf16(o.z * inv, o.w * inv);
+    } else if (bad && head == 0 && x == 0) {
+        atomicOr(p.flag, 2);
+    }
+    ((uint2 *)(p.out + ((size_t)b * hot.hq + head) * D))[x] = res;
 }
 
 int chunk_slots(int rows, int chunk) { return (rows + chunk - 1) / chunk; }
@@ -365,32 +456,46 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
                       int max_len, float scale, void *ws, size_t ws_bytes, void *out, hipStream_t st)
 {
     const pod_layout &ly = c->ly;
+    const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
+    const int lowest = layer - layer % ly.G;
     decode_params p;
-    p.base = c->base; p.ly = ly; p.layer = layer; p.B = B;
-    p.q = (const pod_bf16 *)q; p.q_shared = (const pod_bf16 *)q_shared; p.ctx = ctx;
-    p.scale_log2e = scale * 1.4426950408889634f;
+    p.hot.kdist = (const u32x4 *)(c->base + ly.off_distK) + pod_dist_row0(ly, layer / ly.G, 0, 0) * row16;
+    p.hot.vdist = (const u32x4 *)(c->base + ly.off_distV) + pod_dist_row0(ly, layer, 0, 0) * row16;
+    p.hot.kprox = (const u32x4 *)(c->base + ly.off_proxK) + pod_prox_row0(ly, layer, 0, 0) * row16;
+    p.hot.vprox = (const u32x4 *)(c->base + ly.off_proxV) + pod_prox_row0(ly, layer, 0, 0) * row16;
+    p.hot.cd = ly.Cd; p.hot.prows = ly.P; p.hot.hkv = ly.Hkv; p.hot.rep = ly.rep; p.hot.hq = ly.Hq;
+    p.hot.q = (const pod_bf16 *)q; p.hot.q_shared = (const pod_bf16 *)q_shared;
+    p.hot.scale_log2e = scale * 1.4426950408889634f;
+    p.hot.ctx = ctx;
+    p.hot.lens_layer = (const int32_t *)(c->base + ly.off_lens) + (size_t)layer * ly.B;
+    p.hot.lens_lowest = (const int32_t *)(c->base + ly.off_lens) + (size_t)lowest * ly.B;
+    p.flag = (int32_t *)(c->base + ly.off_flag);
+    p.maxctx = ly.maxctx;
     p.out = (pod_bf16 *)out;
+    p.hot.use_hlen = B <= kMaxHostLens;
+    if (p.hot.use_hlen)
+        for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
 
-    // Chunk size: enough workgroups to fill 256 CUs a few times over, but no smaller than
-    // kMinChunk tokens so the partials stay a small fraction of the K/V bytes.
+    // Chunk size: enough workgroups to fill 256 CUs, but no smaller than kMinChunk tokens so the
+    // partials stay a small fraction of the K/V bytes.
     const char *env = getenv("POD_DECODE_CHUNK"); // tuning / test override
     const int env_chunk = env ? atoi(env) : 0;
     const long rows = (long)max_len * ly.Hkv * B;
-    long chunk = env_chunk > 0 ? env_chunk : rows / 1024;
-    chunk = (chunk + kMinChunk - 1) / kMinChunk * kMinChunk;
+    long chunk = env_chunk > 0 ? env_chunk : rows / 512;
+    chunk = (chunk + kTile - 1) / kTile * kTile;
     if (chunk < kMinChunk) chunk = kMinChunk;
     if (chunk > 8192) chunk = 8192;
-    p.chunk = (int)chunk;
+    p.hot.chunk = (int)chunk;
     const int max_prox = max_len < ly.P ? max_len : ly.P;
     const int max_dist = max_len - max_prox;
-    p.max_nd = chunk_slots(max_dist, p.chunk);
-    p.max_np = chunk_slots(max_prox, p.chunk);
-    const size_t NC = (size_t)p.max_nd + p.max_np;
+    p.hot.max_nd = chunk_slots(max_dist, p.hot.chunk);
+    p.hot.nc = p.hot.max_nd + chunk_slots(max_prox, p.hot.chunk);
+    const size_t NC = (size_t)p.hot.nc;
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
     if (acc_bytes + ml_bytes > ws_bytes) return pod_fail(POD_ERR_CAPACITY, "decode workspace too small");
-    p.part_acc = (float *)ws;
-    p.part_ml = (float *)((char *)ws + acc_bytes);
+    p.hot.part_acc = (float *)ws;
+    p.hot.part_ml = (float *)((char *)ws + acc_bytes);
 
     const dim3 grid((unsigned)NC, (unsigned)ly.Hkv, (unsigned)B);
     const dim3 cgrid((unsigned)ly.Hq, (unsigned)B);
