@@ -3,14 +3,23 @@
 // For query i and key j <= i (Eq. 3 of the paper with the window taken at the query's own
 // position): j is proximal if j < S or j > i - W and its logit is q_l[i].k_l[j]; otherwise it is
 // distant and its logit is the block's lowest layer's, q_a[i].k_a[j].  One softmax over all
-// j <= i (Eq. 4 / appendix), values always v_l.  A key tile is "own" (all proximal), "shared"
-// (all distant) or mixed; mixed tiles compute both products and select per element.
+// j <= i (Eq. 4 / appendix), values always v_l.
 //
-// Tiling: a workgroup of 4 waves takes BM = 128*NQ query rows of one head; each wave owns
-// 32*NQ rows and keeps Q (and the shared Q) as MFMA B operands in registers for the whole
-// key loop.  Key/value tiles of BN = 64 tokens go through LDS, written in MFMA A-operand
-// *fragment order* (64 lanes x 16 bytes per fragment) so that every read is one conflict-free
-// ds_read_b128:
+// Because a softmax accumulates in any order, the key loop runs in two phases, each with ONE
+// query operand in registers and ONE key source:
+//   phase D (upper layers only): key tiles that hold a distant key for some row of the
+//            workgroup, with q_a and k_a; elements that are not distant for their row are masked;
+//   phase P: sink tiles and band tiles, with q_l and k_l; elements that are not proximal (or not
+//            causal) are masked.
+// A tile that straddles a region edge is visited by both phases with complementary masks (its V
+// tile is loaded twice: ~4 of 256 tiles per row block at the paper's window sizes).  At the
+// block's lowest layer there is only phase P over all tiles, with the causal mask.
+//
+// Tiling: a workgroup of 4 waves takes BM = 128*NQ query rows of one head; each wave owns 32*NQ
+// rows.  Key/value tiles of BN = 64 tokens go through LDS (double-buffered, one barrier per
+// tile), written in MFMA A-operand *fragment order* (64 lanes x 16 bytes per fragment) so that
+// every read is one conflict-free ds_read_b128.  Global loads of tile t+1 are issued before the
+// arithmetic of tile t and parked in registers.
 //   S^T[key][row] = K[key][:] . Q[row][:]     v_mfma_f32_32x32x16_bf16, A = K frag, B = Q
 //   O^T[dim][row] = sum_key V[key][dim] P[key][row]               A = V^T frag, B = P
 // Query row = MFMA column (lane % 32) in both, so softmax state, P and the output slice of a
@@ -18,15 +27,22 @@
 // (the 8 keys a lane holds for one PV k-step are the keys of its 8 consecutive accumulators;
 // V^T fragments are built for that key order).  V is transposed on the way into LDS: a thread
 // loads the same 16-byte dim piece of 4 tokens and transposes the 4x8 block with v_perm_b32.
+//
+// Softmax: base-2 with the logit scale folded into the exponent; the running maximum is only
+// moved when a tile exceeds it by more than 2^8 (probabilities then stay below 256, harmless in
+// fp32 sums and in bf16), which removes most rescaling passes over the output accumulators.
 #include "pod_internal.h"
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 constexpr int kBN = 64;
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazy = 8.0f; // how far (log2) a tile's maximum may exceed the reference before rescaling
 
 struct prefill_params {
     int n, Hq, Hkv, rep, S, W;
@@ -35,7 +51,7 @@ struct prefill_params {
     float scale_log2e;
 };
 
-__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ inline unsigned pack_bf16(float lo, float hi)
 {
@@ -44,7 +60,31 @@ __device__ inline unsigned pack_bf16(float lo, float hi)
     return __builtin_bit_cast(unsigned, t);
 }
 
-__device__ inline unsigned dword_of(const uint4 &u, int w) { return w == 0 ? u.x : w == 1 ? u.y : w == 2 ? u.z : u.w; }
+// Exchange between the two lanes (l, l ^ 32) that share a query row: v_permlane32_swap gives
+// lane l its partner's value in one of the two results.  Operands and results go through empty
+// asm statements: given the same value twice the compiler otherwise folds max(r0, r1) to r0.
+__device__ inline void pair_exchange(float x, float &mine_or_partner0, float &mine_or_partner1)
+{
+    unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+    asm volatile("" : "+v"(b));
+    const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1)); // (the two results are not interchangeable either)
+    mine_or_partner0 = __builtin_bit_cast(float, r0);
+    mine_or_partner1 = __builtin_bit_cast(float, r1);
+}
+__device__ inline float pair_max(float x)
+{
+    float a, b;
+    pair_exchange(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ inline float pair_sum(float x)
+{
+    float a, b;
+    pair_exchange(x, a, b);
+    return a + b;
+}
 
 template <int D, int NQ>
 __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
@@ -55,10 +95,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
     constexpr int NKB = kBN / 32;    // key blocks per tile
     constexpr int NPS = kBN / 16;    // PV k-steps per tile
     constexpr int BM = 128 * NQ;
+    constexpr int KIT = kBN * CPR / 256; // K pieces per thread per tile
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
 
-    __shared__ uint4 ldsK[NKB * KST * 64];  // own-key fragments   [kb][s][64 lanes]
-    __shared__ uint4 ldsKs[NKB * KST * 64]; // shared-key fragments
-    __shared__ uint4 ldsV[NDB * NPS * 64];  // V^T fragments       [db][ks][64 lanes]
+    __shared__ u32x4 ldsK[2][NKB * KST * 64]; // key fragments   [kb][s][64 lanes]
+    __shared__ u32x4 ldsV[2][NDB * NPS * 64]; // V^T fragments   [db][ks][64 lanes]
 
     const int nqt = (p.n + BM - 1) / BM;
     const int qt = nqt - 1 - blockIdx.x; // heaviest tiles first
@@ -67,201 +108,230 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
     const int i_last = min(i0 + BM, p.n) - 1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n32 = lane & 31, jj = lane >> 5;
-    const int iw0 = i0 + wave * 32 * NQ;           // first row of this wave
+    const int iw0 = i0 + wave * 32 * NQ;             // first row of this wave
     const int iw_last = min(iw0 + 32 * NQ, p.n) - 1; // may be < iw0: the wave has no rows
     const bool has_shared = p.qs != nullptr;
+    const int S = p.S, W = p.W;
 
-    // Q (and shared Q) as B operands: lane (row n32, jj) holds dims 16s + 8jj .. +7
-    bf16x8 qf[NQ][KST], qsf[NQ][KST];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int row = min(iw0 + 32 * nq + n32, p.n - 1);
-        const uint4 *qr = (const uint4 *)(p.q + ((size_t)row * p.Hq + head) * D);
-        const uint4 *qsr = (const uint4 *)((has_shared ? p.qs : p.q) + ((size_t)row * p.Hq + head) * D);
-#pragma unroll
-        for (int s = 0; s < KST; ++s) {
-            qf[nq][s] = as_bf16x8(qr[2 * s + jj]);
-            qsf[nq][s] = as_bf16x8(qsr[2 * s + jj]);
-        }
+    // ---- the tile schedule of this workgroup: nD distant-phase tiles, then sink tiles, then band tiles
+    int tD0 = 0, nD = 0, nP1 = 0, tB = 0;
+    if (has_shared) {
+        if (i_last - W >= S) { tD0 = S / kBN; nD = (i_last - W) / kBN - tD0 + 1; }
+        if (S > 0) nP1 = (min(S, i_last + 1) - 1) / kBN + 1;
+        tB = max(nP1, max(0, i0 - W + 1) / kBN);
     }
+    const int tEnd = i_last / kBN;
+    const int nP2 = tEnd >= tB ? tEnd - tB + 1 : 0;
+    const int T = nD + nP1 + nP2;
+    auto tile_of = [&](int t, int &kt, bool &phaseD) {
+        phaseD = t < nD;
+        kt = phaseD ? tD0 + t : (t < nD + nP1 ? t - nD : tB + (t - nD - nP1));
+    };
+
+    // ---- global -> register loads of one tile (K pieces in fragment order, V pieces for the transpose)
+    const int kc = tid % CPR, kr0 = tid / CPR;                  // K: piece, first row
+    const int vrest = tid / CPR;                                // V: 4-token group of this thread
+    const bool vact = vrest < 16;
+    const int vhalf = vrest & 1, vj = (vrest >> 1) & 1, vku = vrest >> 2;
+    u32x4 kreg[KIT], vreg[4];
+    auto load_tile = [&](int t) {
+        int kt; bool phaseD;
+        tile_of(t, kt, phaseD);
+        const int j0 = kt * kBN;
+        const gvec_ptr ksrc = (gvec_ptr)(phaseD ? p.ks : p.k);
+#pragma unroll
+        for (int it = 0; it < KIT; ++it) {
+            const int key = min(j0 + kr0 + (256 / CPR) * it, p.n - 1);
+            kreg[it] = ksrc[((size_t)key * p.Hkv + kvh) * CPR + kc];
+        }
+        if (vact) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int key = min(j0 + 16 * vku + 8 * vhalf + 4 * vj + e, p.n - 1);
+                vreg[e] = ((gvec_ptr)p.v)[((size_t)key * p.Hkv + kvh) * CPR + kc];
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < KIT; ++it) {
+            const int r = kr0 + (256 / CPR) * it; // key within the tile
+            const int s = kc >> 1, cj = kc & 1;
+            const int slot = ((r & 31) + 32 * cj) ^ ((s & 3) | (cj << 2));
+            ldsK[buf][((r >> 5) * KST + s) * 64 + slot] = kreg[it];
+        }
+        if (vact) {
+#pragma unroll
+            for (int dlt = 0; dlt < 8; ++dlt) {
+                const unsigned sel = (dlt & 1) ? 0x07060302u : 0x05040100u;
+                u32x2 pk;
+                pk.x = __builtin_amdgcn_perm(vreg[1][dlt >> 1], vreg[0][dlt >> 1], sel);
+                pk.y = __builtin_amdgcn_perm(vreg[3][dlt >> 1], vreg[2][dlt >> 1], sel);
+                const int dim = 8 * kc + dlt, db = dim >> 5;
+                const int l = (dim & 31) + 32 * vj;
+                const int slot = l ^ (((l >> 3) & 3) | (((l >> 5) ^ (db & 1)) << 2));
+                u32x2 *dst = (u32x2 *)&ldsV[buf][(db * NPS + vku) * 64 + slot];
+                dst[vhalf] = pk;
+            }
+        }
+    };
+
+    // ---- query operand of the current phase: lane (row n32, jj) holds dims 16s + 8jj .. +7
+    bf16x8 qf[NQ][KST];
+    auto load_q = [&](const pod_bf16 *src) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            const int row = min(iw0 + 32 * nq + n32, p.n - 1);
+            const gvec_ptr qr = (gvec_ptr)(src + ((size_t)row * p.Hq + head) * D);
+#pragma unroll
+            for (int s = 0; s < KST; ++s) qf[nq][s] = as_bf16x8(qr[2 * s + jj]);
+        }
+    };
 
     f32x16 oacc[NQ][NDB];
-    float m_run[NQ], l_run[NQ];
+    float m_ref[NQ], l_run[NQ]; // l_run: this lane's keys only; the two lanes of a row are added at the end
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-        m_run[nq] = kNegBig; l_run[nq] = 0.f;
+        m_ref[nq] = kNegBig; l_run[nq] = 0.f;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[nq][db][r] = 0.f;
     }
 
-    const int ntiles = i_last / kBN + 1;
-    for (int kt = 0; kt < ntiles; ++kt) {
+    if (T > 0) {
+        load_tile(0);
+        load_q(nD > 0 ? p.qs : p.q);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < T; ++t) {
+        const int buf = t & 1;
+        int kt; bool phaseD;
+        tile_of(t, kt, phaseD);
+        if (t + 1 < T) load_tile(t + 1);
+        if (t == nD && nD > 0) load_q(p.q); // phase switch: own queries from here on
+
         const int j0 = kt * kBN, j1 = j0 + kBN - 1;
-        // what this workgroup's rows need from the tile
-        bool need_own = true, need_sh = false;
-        if (has_shared) {
-            const bool all_prox = (j1 < p.S) || (j0 > i_last - p.W);
-            const bool all_dist = (j0 >= p.S) && (j1 <= i0 - p.W);
-            need_own = !all_dist; need_sh = !all_prox;
+        // does this wave have anything in the tile, and is every (row, key) pair of it valid?
+        bool any, full;
+        if (phaseD) {
+            any = j0 <= iw_last - W && j1 >= S;
+            full = j0 >= S && j1 <= iw0 - W;
+        } else if (has_shared) {
+            any = j0 <= iw_last && (j0 < S || j1 > iw0 - W);
+            full = j1 <= iw0 && (j1 < S || j0 > iw_last - W);
+        } else {
+            any = j0 <= iw_last;
+            full = j1 <= iw0;
         }
-        __syncthreads(); // previous tile's fragments are no longer read
-        // ---- K tiles -> fragment order.  Thread: piece c of row r0 + (256/CPR)*it
-        {
-            const int c = tid % CPR, r0 = tid / CPR;
+        if (any && iw0 <= iw_last) {
+            // ---- S^T = K Q^T
+            f32x16 sc[NQ][NKB];
 #pragma unroll
-            for (int it = 0; it < kBN * CPR / 256; ++it) {
-                const int r = r0 + (256 / CPR) * it; // key within the tile
-                const int key = min(j0 + r, p.n - 1);
-                const size_t g = ((size_t)key * p.Hkv + kvh) * CPR + c;
-                const int s = c >> 1, cj = c & 1;
-                const int slot = ((r & 31) + 32 * cj) ^ ((s & 3) | (cj << 2));
-                const int f = ((r >> 5) * KST + s) * 64 + slot;
-                if (need_own) ldsK[f] = ((const uint4 *)p.k)[g];
-                if (need_sh) ldsKs[f] = ((const uint4 *)p.ks)[g];
-            }
-        }
-        // ---- V tile -> V^T fragments.  Thread: piece c, 4 tokens 16*ku + 8*half + 4*vj + {0..3}
-        {
-            const int c = tid % CPR, rest = tid / CPR;
-            if (rest < 16) {
-                const int half = rest & 1, vj = (rest >> 1) & 1, ku = rest >> 2;
-                uint4 t[4];
+            for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int key = min(j0 + 16 * ku + 8 * half + 4 * vj + e, p.n - 1);
-                    t[e] = ((const uint4 *)p.v)[((size_t)key * p.Hkv + kvh) * CPR + c];
+                for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sc[nq][kb][r] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                for (int s = 0; s < KST; ++s) {
+                    const u32x4 a = ldsK[buf][(kb * KST + s) * 64 + (lane ^ ((s & 3) | (jj << 2)))];
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        sc[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[nq][s], sc[nq][kb], 0, 0, 0);
                 }
+            // ---- softmax per row block
+            u32x4 pw[NQ][NPS];
 #pragma unroll
-                for (int dlt = 0; dlt < 8; ++dlt) {
-                    const unsigned sel = (dlt & 1) ? 0x07060302u : 0x05040100u;
-                    uint2 pk;
-                    pk.x = __builtin_amdgcn_perm(dword_of(t[1], dlt >> 1), dword_of(t[0], dlt >> 1), sel);
-                    pk.y = __builtin_amdgcn_perm(dword_of(t[3], dlt >> 1), dword_of(t[2], dlt >> 1), sel);
-                    const int dim = 8 * c + dlt, db = dim >> 5;
-                    const int l = (dim & 31) + 32 * vj;
-                    const int slot = l ^ (((l >> 3) & 3) | (((l >> 5) ^ (db & 1)) << 2));
-                    uint2 *dst = (uint2 *)&ldsV[(db * NPS + ku) * 64 + slot];
-                    dst[half] = pk;
-                }
-            }
-        }
-        __syncthreads();
-
-        if (j0 > iw_last) continue; // tile lies above this wave's diagonal (wave-uniform)
-        // wave-level needs
-        bool own_w = true, sh_w = false;
-        if (has_shared) {
-            const bool all_prox = (j1 < p.S) || (j0 > iw_last - p.W);
-            const bool all_dist = (j0 >= p.S) && (j1 <= iw0 - p.W);
-            own_w = !all_dist; sh_w = !all_prox;
-        }
-        const bool diag = j1 > iw0; // some (row, key) pair of this wave is not visible
-
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            f32x16 sc[NKB];
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                f32x16 so, ss;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { so[r] = 0.f; ss[r] = 0.f; }
-                if (own_w) {
-#pragma unroll
-                    for (int s = 0; s < KST; ++s) {
-                        const uint4 a = ldsK[(kb * KST + s) * 64 + (lane ^ ((s & 3) | (jj << 2)))];
-                        so = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[nq][s], so, 0, 0, 0);
-                    }
-                }
-                if (sh_w) {
-#pragma unroll
-                    for (int s = 0; s < KST; ++s) {
-                        const uint4 a = ldsKs[(kb * KST + s) * 64 + (lane ^ ((s & 3) | (jj << 2)))];
-                        ss = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qsf[nq][s], ss, 0, 0, 0);
-                    }
-                }
+            for (int nq = 0; nq < NQ; ++nq) {
                 const int i = iw0 + 32 * nq + n32;
-                if (own_w && sh_w) {
+                float mx = kNegBig;
+                if (full) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
-                        const bool prox = (j < p.S) || (j > i - p.W);
-                        sc[kb][r] = prox ? so[r] : ss[r];
-                    }
+                    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[nq][kb][r]);
                 } else {
-                    sc[kb] = own_w ? so : ss;
-                }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sc[kb][r] *= p.scale_log2e;
-                if (diag) {
+                    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
+                            bool ok;
+                            if (phaseD) ok = j >= S && j <= i - W;
+                            else ok = j <= i && (!has_shared || j < S || j > i - W);
+                            sc[nq][kb][r] = ok ? sc[nq][kb][r] : kNegBig;
+                            mx = fmaxf(mx, sc[nq][kb][r]);
+                        }
+                }
+                mx = pair_max(mx) * p.scale_log2e; // scale > 0: max and scaling commute
+                if (mx > m_ref[nq] + kLazy) {      // (masked rows have mx = -inf-like and never trigger)
+                    const float m_new = mx;
+                    const float alpha = exp2f(m_ref[nq] - m_new);
+                    l_run[nq] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[nq][db][r] *= alpha;
+                    m_ref[nq] = m_new;
+                }
+                const float mr = m_ref[nq];
+                float ps = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
-                        if (j > i) sc[kb][r] = kNegBig;
+                        float e = exp2f(fmaf(sc[nq][kb][r], p.scale_log2e, -mr));
+                        if (!full) e = sc[nq][kb][r] <= kNegBig ? 0.f : e;
+                        sc[nq][kb][r] = e;
+                        ps += e;
                     }
+                l_run[nq] += ps;
+#pragma unroll
+                for (int ks = 0; ks < NPS; ++ks) {
+                    const int kb = ks >> 1, u = ks & 1;
+                    pw[nq][ks].x = pack_bf16(sc[nq][kb][8 * u + 0], sc[nq][kb][8 * u + 1]);
+                    pw[nq][ks].y = pack_bf16(sc[nq][kb][8 * u + 2], sc[nq][kb][8 * u + 3]);
+                    pw[nq][ks].z = pack_bf16(sc[nq][kb][8 * u + 4], sc[nq][kb][8 * u + 5]);
+                    pw[nq][ks].w = pack_bf16(sc[nq][kb][8 * u + 6], sc[nq][kb][8 * u + 7]);
                 }
             }
-            // online softmax for row n32 (this lane holds half of the tile's keys)
-            float mx = kNegBig;
+            // ---- O^T += V^T P
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[nq], mx);
-            const float alpha = exp2f(m_run[nq] - m_new);
-            float ps = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // a fully masked row keeps m = kNegBig: exp2(0) would count masked keys
-                    const float e = sc[kb][r] <= kNegBig ? 0.f : exp2f(sc[kb][r] - m_new);
-                    sc[kb][r] = e;
-                    ps += e;
-                }
-            ps += __shfl_xor(ps, 32);
-            l_run[nq] = l_run[nq] * alpha + ps;
-            m_run[nq] = m_new;
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[nq][db][r] *= alpha;
-            // O^T += V^T P
-#pragma unroll
-            for (int ks = 0; ks < NPS; ++ks) {
-                const int kb = ks >> 1, u = ks & 1;
-                uint4 pw;
-                pw.x = pack_bf16(sc[kb][8 * u + 0], sc[kb][8 * u + 1]);
-                pw.y = pack_bf16(sc[kb][8 * u + 2], sc[kb][8 * u + 3]);
-                pw.z = pack_bf16(sc[kb][8 * u + 4], sc[kb][8 * u + 5]);
-                pw.w = pack_bf16(sc[kb][8 * u + 6], sc[kb][8 * u + 7]);
+            for (int ks = 0; ks < NPS; ++ks)
 #pragma unroll
                 for (int db = 0; db < NDB; ++db) {
                     const int slot = lane ^ (((lane >> 3) & 3) | (((lane >> 5) ^ (db & 1)) << 2));
-                    const uint4 a = ldsV[(db * NPS + ks) * 64 + slot];
-                    oacc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pw), oacc[nq][db], 0, 0, 0);
+                    const u32x4 a = ldsV[buf][(db * NPS + ks) * 64 + slot];
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        oacc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pw[nq][ks]), oacc[nq][db], 0, 0, 0);
                 }
-            }
         }
+        if (t + 1 < T) store_tile(buf ^ 1);
+        __syncthreads();
     }
 
     // ---- normalise and store: lane (row n32, jj) holds dims 32db + 8a + 4jj + {0..3}
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         const int i = iw0 + 32 * nq + n32;
+        const float l = pair_sum(l_run[nq]);
         if (i >= p.n) continue;
-        const float inv = 1.f / l_run[nq];
+        const float inv = 1.f / l;
         pod_bf16 *orow = p.out + ((size_t)i * p.Hq + head) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                uint2 o;
+                u32x2 o;
                 o.x = pack_bf16(oacc[nq][db][4 * a + 0] * inv, oacc[nq][db][4 * a + 1] * inv);
                 o.y = pack_bf16(oacc[nq][db][4 * a + 2] * inv, oacc[nq][db][4 * a + 3] * inv);
-                *(uint2 *)(orow + 32 * db + 8 * a + 4 * jj) = o;
+                *(u32x2 *)(orow + 32 * db + 8 * a + 4 * jj) = o;
             }
     }
 }
@@ -278,6 +348,7 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     p.qs = (const pod_bf16 *)q_shared; p.ks = (const pod_bf16 *)k_shared;
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
+    if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
     constexpr int NQ = 1;
     const int BM = 128 * NQ;
     const dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)ly.Hq);
