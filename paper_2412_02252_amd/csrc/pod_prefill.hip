@@ -31,6 +31,8 @@
 // Softmax: base-2 with the logit scale folded into the exponent; the running maximum is only
 // moved when a tile exceeds it by more than 2^8 (probabilities then stay below 256, harmless in
 // fp32 sums and in bf16), which removes most rescaling passes over the output accumulators.
+#include <type_traits>
+
 #include "pod_internal.h"
 
 namespace {
@@ -87,7 +89,7 @@ __device__ inline float pair_sum(float x)
 }
 
 template <int D, int NQ>
-__global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
+__global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 {
     constexpr int CPR = D / 8;       // 16-byte pieces per row
     constexpr int KST = D / 16;      // QK k-steps (32x32x16)
@@ -101,9 +103,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
     __shared__ u32x4 ldsK[2][NKB * KST * 64]; // key fragments   [kb][s][64 lanes]
     __shared__ u32x4 ldsV[2][NDB * NPS * 64]; // V^T fragments   [db][ks][64 lanes]
 
+    // Workgroup -> (kv head, query head of the group, row block).  Consecutive workgroup ids land
+    // on consecutive XCDs (8 of them, each with its own L2), so the kv head is taken from the low
+    // bits of the id: with 8 kv heads every XCD works on ONE kv head, and the workgroups resident
+    // on it (the 4 query heads of the group x neighbouring row blocks) stream the same K/V tiles
+    // at the same time and share them through that L2.  Heaviest row blocks first.
     const int nqt = (p.n + BM - 1) / BM;
-    const int qt = nqt - 1 - blockIdx.x; // heaviest tiles first
-    const int head = blockIdx.y, kvh = head / p.rep;
+    const int wg = blockIdx.x;
+    const int kvh = wg % p.Hkv;
+    const int rest = wg / p.Hkv;
+    const int head = kvh * p.rep + rest % p.rep;
+    const int qt = nqt - 1 - rest / p.rep;
     const int i0 = qt * BM;
     const int i_last = min(i0 + BM, p.n) - 1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -226,7 +236,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
             any = j0 <= iw_last;
             full = j1 <= iw0;
         }
-        if (any && iw0 <= iw_last) {
+        // The arithmetic of one tile, compiled twice: FULL = every (row, key) pair of the wave is
+        // valid (no mask arithmetic at all) and the general case with the per-element predicate.
+        auto tile_body = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
             // ---- S^T = K Q^T
             f32x16 sc[NQ][NKB];
 #pragma unroll
@@ -250,7 +263,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
             for (int nq = 0; nq < NQ; ++nq) {
                 const int i = iw0 + 32 * nq + n32;
                 float mx = kNegBig;
-                if (full) {
+                if constexpr (FULL) {
 #pragma unroll
                     for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -261,9 +274,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
-                            bool ok;
-                            if (phaseD) ok = j >= S && j <= i - W;
-                            else ok = j <= i && (!has_shared || j < S || j > i - W);
+                            // branch-free predicate (bitwise on purpose: no short-circuit control flow)
+                            const bool okD = (j >= S) & (j <= i - W);
+                            const bool okP = (j <= i) & ((!has_shared) | (j < S) | (j > i - W));
+                            const bool ok = phaseD ? okD : okP;
                             sc[nq][kb][r] = ok ? sc[nq][kb][r] : kNegBig;
                             mx = fmaxf(mx, sc[nq][kb][r]);
                         }
@@ -271,7 +285,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
                 mx = pair_max(mx) * p.scale_log2e; // scale > 0: max and scaling commute
                 if (mx > m_ref[nq] + kLazy) {      // (masked rows have mx = -inf-like and never trigger)
                     const float m_new = mx;
-                    const float alpha = exp2f(m_ref[nq] - m_new);
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref[nq] - m_new);
                     l_run[nq] *= alpha;
 #pragma unroll
                     for (int db = 0; db < NDB; ++db)
@@ -285,8 +299,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
                 for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float e = exp2f(fmaf(sc[nq][kb][r], p.scale_log2e, -mr));
-                        if (!full) e = sc[nq][kb][r] <= kNegBig ? 0.f : e;
+                        float e = __builtin_amdgcn_exp2f(fmaf(sc[nq][kb][r], p.scale_log2e, -mr)); // raw v_exp_f32: tiny results flush to 0
+                        if constexpr (!FULL) e = sc[nq][kb][r] <= kNegBig ? 0.f : e;
                         sc[nq][kb][r] = e;
                         ps += e;
                     }
@@ -311,6 +325,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(prefill_params p)
                     for (int nq = 0; nq < NQ; ++nq)
                         oacc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pw[nq][ks]), oacc[nq][db], 0, 0, 0);
                 }
+        };
+        if (any && iw0 <= iw_last) {
+            if (full) tile_body(std::true_type{});
+            else tile_body(std::false_type{});
         }
         if (t + 1 < T) store_tile(buf ^ 1);
         __syncthreads();
@@ -351,7 +369,7 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
     constexpr int NQ = 1;
     const int BM = 128 * NQ;
-    const dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)ly.Hq);
+    const dim3 grid((unsigned)((n + BM - 1) / BM) * (unsigned)ly.Hq);
     if (ly.D == 128)
         hipLaunchKernelGGL((prefill_kernel<128, NQ>), grid, dim3(256), 0, st, p);
     else
