@@ -89,7 +89,7 @@ __device__ inline float pair_sum(float x)
 }
 
 template <int D, int NQ>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
+__global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_kernel(prefill_params p)
 {
     constexpr int CPR = D / 8;       // 16-byte pieces per row
     constexpr int KST = D / 16;      // QK k-steps (32x32x16)
@@ -100,8 +100,17 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     constexpr int KIT = kBN * CPR / 256; // K pieces per thread per tile
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
 
-    __shared__ u32x4 ldsK[2][NKB * KST * 64]; // key fragments   [kb][s][64 lanes]
-    __shared__ u32x4 ldsV[2][NDB * NPS * 64]; // V^T fragments   [db][ks][64 lanes]
+    // LDS: two buffers, each holding NKB*KST key fragments and NDB*NPS V^T fragments of 64 lane
+    // slots x 16 bytes.  Inside a fragment the slot of lane l is l ^ x, where x (3 bits) depends on
+    // the fragment and on l / 32 for keys, on l / 8 and the dim block for values: with these XORs
+    // the reads (one ds_read_b128 per fragment and wave), the key-row writes and the 8-byte V^T
+    // writes were all measured free of bank conflicts on gfx950 (64 banks of 4 bytes).  The read
+    // offsets take only 4 (keys) + 2 (values) distinct per-lane values, computed once.
+    constexpr int FRAG = 64 * 16;
+    constexpr int KSTRIDE = FRAG, VSTRIDE = FRAG;
+    constexpr int KBUF = NKB * KST * KSTRIDE, VBUF = NDB * NPS * VSTRIDE;
+    constexpr int BUF = KBUF + VBUF;           // one buffer: keys then values
+    extern __shared__ __attribute__((aligned(16))) char lds[];
 
     // Workgroup -> (kv head, query head of the group, row block).  Consecutive workgroup ids land
     // on consecutive XCDs (8 of them, each with its own L2), so the kv head is taken from the low
@@ -118,6 +127,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     const int i_last = min(i0 + BM, p.n) - 1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n32 = lane & 31, jj = lane >> 5;
+    int kroff[4], vroff[2];                          // read offsets of this lane inside a key / value fragment
+#pragma unroll
+    for (int x = 0; x < 4; ++x) kroff[x] = 16 * (lane ^ (x | (jj << 2)));
+#pragma unroll
+    for (int x = 0; x < 2; ++x) vroff[x] = 16 * (lane ^ (((lane >> 3) & 3) | (((lane >> 5) ^ x) << 2)));
     const int iw0 = i0 + wave * 32 * NQ;             // first row of this wave
     const int iw_last = min(iw0 + 32 * NQ, p.n) - 1; // may be < iw0: the wave has no rows
     const bool has_shared = p.qs != nullptr;
@@ -138,37 +152,61 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         kt = phaseD ? tD0 + t : (t < nD + nP1 ? t - nD : tB + (t - nD - nP1));
     };
 
-    // ---- global -> register loads of one tile (K pieces in fragment order, V pieces for the transpose)
+    // ---- global -> register loads of one tile.  Row addresses are a per-tile scalar base plus ONE
+    // per-thread offset (for K and for V), so a tile costs no vector address arithmetic; only the
+    // prompt's last, partly filled tile clamps rows to n-1 per thread.
+    constexpr int RS = 256 / CPR;                               // key rows covered by one K load of the workgroup
     const int kc = tid % CPR, kr0 = tid / CPR;                  // K: piece, first row
     const int vrest = tid / CPR;                                // V: 4-token group of this thread
     const bool vact = vrest < 16;
     const int vhalf = vrest & 1, vj = (vrest >> 1) & 1, vku = vrest >> 2;
+    const int vrow0 = 16 * vku + 8 * vhalf + 4 * vj;            // first of this thread's 4 V rows in the tile
+    const unsigned rowb = (unsigned)p.Hkv * D * 2;              // bytes from one token to the next
+    const unsigned koff = (unsigned)kr0 * rowb + (unsigned)(kvh * D * 2 + kc * 16);
+    const unsigned voff = (unsigned)vrow0 * rowb + (unsigned)(kvh * D * 2 + kc * 16);
+    typedef const __attribute__((address_space(1))) char *gbyte_ptr;
     u32x4 kreg[KIT], vreg[4];
     auto load_tile = [&](int t) {
         int kt; bool phaseD;
         tile_of(t, kt, phaseD);
         const int j0 = kt * kBN;
-        const gvec_ptr ksrc = (gvec_ptr)(phaseD ? p.ks : p.k);
+        const gbyte_ptr kb = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
+        const gbyte_ptr vb = (gbyte_ptr)p.v + (size_t)j0 * rowb;
+        if (j0 + kBN <= p.n) {
 #pragma unroll
-        for (int it = 0; it < KIT; ++it) {
-            const int key = min(j0 + kr0 + (256 / CPR) * it, p.n - 1);
-            kreg[it] = ksrc[((size_t)key * p.Hkv + kvh) * CPR + kc];
-        }
-        if (vact) {
+            for (int it = 0; it < KIT; ++it) kreg[it] = *(gvec_ptr)(kb + (size_t)(it * RS) * rowb + koff);
+            if (vact) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int key = min(j0 + 16 * vku + 8 * vhalf + 4 * vj + e, p.n - 1);
-                vreg[e] = ((gvec_ptr)p.v)[((size_t)key * p.Hkv + kvh) * CPR + kc];
+                for (int e = 0; e < 4; ++e) vreg[e] = *(gvec_ptr)(vb + (size_t)e * rowb + voff);
+            }
+        } else {
+            const unsigned colb = (unsigned)(kvh * D * 2 + kc * 16);
+#pragma unroll
+            for (int it = 0; it < KIT; ++it) {
+                const int key = min(kr0 + RS * it, p.n - 1 - j0);
+                kreg[it] = *(gvec_ptr)(kb + (size_t)key * rowb + colb);
+            }
+            if (vact) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = min(vrow0 + e, p.n - 1 - j0);
+                    vreg[e] = *(gvec_ptr)(vb + (size_t)key * rowb + colb);
+                }
             }
         }
     };
+    // register -> LDS: K pieces into fragment (kb, s = kc/2), slot (row % 32) + 32*(kc % 2); V pieces
+    // transposed (4 tokens x 8 dims -> 8 dims x 4 tokens) into fragment (db, ks), slot (dim % 32) + 32*vj.
+    // (the XOR only touches the low 3 slot bits, which the +16-row and +dim steps below leave alone)
+    const int kw_base = (kc >> 1) * KSTRIDE + 16 * ((kr0 + 32 * (kc & 1)) ^ (((kc >> 1) & 3) | ((kc & 1) << 2)));
+    const int vw_x = (kc & 3) | ((vj ^ ((kc >> 2) & 1)) << 2);   // XOR term of this thread's V^T slots
+    const int vw_base = KBUF + ((kc >> 2) * NPS + vku) * VSTRIDE + 16 * (8 * (kc & 3) + 32 * vj) + 8 * vhalf;
     auto store_tile = [&](int buf) {
+        char *base = lds + buf * BUF;
 #pragma unroll
         for (int it = 0; it < KIT; ++it) {
-            const int r = kr0 + (256 / CPR) * it; // key within the tile
-            const int s = kc >> 1, cj = kc & 1;
-            const int slot = ((r & 31) + 32 * cj) ^ ((s & 3) | (cj << 2));
-            ldsK[buf][((r >> 5) * KST + s) * 64 + slot] = kreg[it];
+            const int kbk = (RS * it) >> 5, radd = (RS * it) & 31;  // key block, row offset inside it (0 or 16)
+            *(u32x4 *)(base + kw_base + kbk * KST * KSTRIDE + 16 * radd) = kreg[it];
         }
         if (vact) {
 #pragma unroll
@@ -177,11 +215,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
                 u32x2 pk;
                 pk.x = __builtin_amdgcn_perm(vreg[1][dlt >> 1], vreg[0][dlt >> 1], sel);
                 pk.y = __builtin_amdgcn_perm(vreg[3][dlt >> 1], vreg[2][dlt >> 1], sel);
-                const int dim = 8 * kc + dlt, db = dim >> 5;
-                const int l = (dim & 31) + 32 * vj;
-                const int slot = l ^ (((l >> 3) & 3) | (((l >> 5) ^ (db & 1)) << 2));
-                u32x2 *dst = (u32x2 *)&ldsV[buf][(db * NPS + vku) * 64 + slot];
-                dst[vhalf] = pk;
+                *(u32x2 *)(base + vw_base + 16 * (dlt ^ vw_x)) = pk;
             }
         }
     };
@@ -213,6 +247,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         load_tile(0);
         load_q(nD > 0 ? p.qs : p.q);
         store_tile(0);
+        if (T > 1) load_tile(1); // stays in registers while tile 0 is processed
     }
     __syncthreads();
 
@@ -220,7 +255,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         const int buf = t & 1;
         int kt; bool phaseD;
         tile_of(t, kt, phaseD);
-        if (t + 1 < T) load_tile(t + 1);
         if (t == nD && nD > 0) load_q(p.q); // phase switch: own queries from here on
 
         const int j0 = kt * kBN, j1 = j0 + kBN - 1;
@@ -240,6 +274,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         // valid (no mask arithmetic at all) and the general case with the per-element predicate.
         auto tile_body = [&](auto full_tag) {
             constexpr bool FULL = decltype(full_tag)::value;
+            const char *lbuf = lds + buf * BUF;
             // ---- S^T = K Q^T
             f32x16 sc[NQ][NKB];
 #pragma unroll
@@ -252,7 +287,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
             for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int s = 0; s < KST; ++s) {
-                    const u32x4 a = ldsK[buf][(kb * KST + s) * 64 + (lane ^ ((s & 3) | (jj << 2)))];
+                    const u32x4 a = *(const u32x4 *)(lbuf + (kb * KST + s) * KSTRIDE + kroff[s & 3]);
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq)
                         sc[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[nq][s], sc[nq][kb], 0, 0, 0);
@@ -319,8 +354,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
             for (int ks = 0; ks < NPS; ++ks)
 #pragma unroll
                 for (int db = 0; db < NDB; ++db) {
-                    const int slot = lane ^ (((lane >> 3) & 3) | (((lane >> 5) ^ (db & 1)) << 2));
-                    const u32x4 a = ldsV[buf][(db * NPS + ks) * 64 + slot];
+                    const u32x4 a = *(const u32x4 *)(lbuf + KBUF + (db * NPS + ks) * VSTRIDE + vroff[db & 1]);
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq)
                         oacc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pw[nq][ks]), oacc[nq][db], 0, 0, 0);
@@ -330,7 +364,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
             if (full) tile_body(std::true_type{});
             else tile_body(std::false_type{});
         }
+        // tile t+1 (loaded one iteration ago) goes to the other buffer; the loads of tile t+2 leave
+        // before the barrier so that the wait at the barrier already overlaps their latency
         if (t + 1 < T) store_tile(buf ^ 1);
+        if (t + 2 < T) load_tile(t + 2);
         __syncthreads();
     }
 
@@ -367,13 +404,25 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
+#ifdef POD_EXP_NQ2
+    constexpr int NQ = 2;
+#else
     constexpr int NQ = 1;
+#endif
     const int BM = 128 * NQ;
     const dim3 grid((unsigned)((n + BM - 1) / BM) * (unsigned)ly.Hq);
+    // dynamic LDS: 2 buffers x (key fragments + V^T fragments), see the kernel
+    const auto lds_bytes = [](int D) { return 2 * ((kBN / 32) * (D / 16) + (D / 32) * (kBN / 16)) * 1024; };
+    static bool attr_done = false; // raising the limit past 64 KB is needed once per process
+    if (!attr_done) {
+        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128, NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64, NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
+        attr_done = true;
+    }
     if (ly.D == 128)
-        hipLaunchKernelGGL((prefill_kernel<128, NQ>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((prefill_kernel<128, NQ>), grid, dim3(256), lds_bytes(128), st, p);
     else
-        hipLaunchKernelGGL((prefill_kernel<64, NQ>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((prefill_kernel<64, NQ>), grid, dim3(256), lds_bytes(64), st, p);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }
