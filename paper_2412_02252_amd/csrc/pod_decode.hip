@@ -476,14 +476,18 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
 
-    // Chunk size: enough workgroups to fill 256 CUs, but no smaller than kMinChunk tokens so the
-    // partials stay a small fraction of the K/V bytes.
+    // Chunk size.  Small problems (config 2: 262K rows) want exactly one resident round of
+    // workgroups (2 per CU x 256 CUs): rows / 512.  Large or ragged problems want many rounds of
+    // moderately sized chunks so that the tail stays short: measured best near 1024 tokens for
+    // 16 ragged sequences of 4K-32K tokens and within 2 % of best for 4 sequences of 128K.
+    // Never below kMinChunk tokens, so the partials stay a small fraction of the K/V bytes.
     const char *env = getenv("POD_DECODE_CHUNK"); // tuning / test override
     const int env_chunk = env ? atoi(env) : 0;
     const long rows = (long)max_len * ly.Hkv * B;
     long chunk = env_chunk > 0 ? env_chunk : rows / 512;
     chunk = (chunk + kTile - 1) / kTile * kTile;
     if (chunk < kMinChunk) chunk = kMinChunk;
+    if (chunk > 1024 && env_chunk <= 0) chunk = 1024;
     if (chunk > 8192) chunk = 8192;
     p.hot.chunk = (int)chunk;
     const int max_prox = max_len < ly.P ? max_len : ly.P;

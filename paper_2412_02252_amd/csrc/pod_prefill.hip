@@ -404,11 +404,7 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
-#ifdef POD_EXP_NQ2
-    constexpr int NQ = 2;
-#else
     constexpr int NQ = 1;
-#endif
     const int BM = 128 * NQ;
     const dim3 grid((unsigned)((n + BM - 1) / BM) * (unsigned)ly.Hq);
     // dynamic LDS: 2 buffers x (key fragments + V^T fragments), see the kernel
