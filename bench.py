@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--rotate", type=int, default=4, help="independent layer blocks visited round-robin")
     ap.add_argument("--context", type=int, default=32768)
     ap.add_argument("--profile-steps", type=int, default=32)
+    ap.add_argument("--reuse-steps", type=int, default=32, help="steps timed through the score-reuse entry point (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of one HIP graph replay")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -74,8 +75,9 @@ def main():
     torch.cuda.set_device(0)
     G, Hq, Hkv, d, S, W = 2, 32, 8, 128, 64, 2048
     R, n0, K, Wm, P = a.rotate, a.context, a.steps, a.warmup, a.profile_steps
+    RU = a.reuse_steps
     seed = 20241202 + 2
-    total_steps = Wm + K + P
+    total_steps = Wm + K + P + RU
     per_block = (total_steps + R - 1) // R
     max_ctx = n0 + per_block + 1
     L = G * R
@@ -114,6 +116,20 @@ def main():
 
     def step_bytes(e):
         return 2 * (2 * e["n"] * row)   # two layers, K and V rows of every token once
+
+    scores = cache.new_score_buffer()
+
+    def run_step_reuse(e):              # same step; the upper layer reads the lowest layer's distant logits
+        l0, l1 = e["layers"]
+        cache.pod_cache_append(l0, e["k0"], e["v0"], e["pos"])
+        cache.pod_cache_append(l1, e["k1"], e["v1"], e["pos"])
+        cache.pod_decode_attention_reuse(l0, e["q0"], e["ctx"], scale, scores, out=e["o0"], max_context_len=e["n"])
+        cache.pod_decode_attention_reuse(l1, e["q1"], e["ctx"], scale, scores, out=e["o1"], max_context_len=e["n"])
+
+    def step_bytes_reuse(e):            # upper layer: V rows, proximal K rows, 4 B per (query head, distant token)
+        n = e["n"]
+        n_prox = min(n, S + W)
+        return 2 * n * row + (n * row + n_prox * row + (n - n_prox) * Hq * 4) + (n - n_prox) * Hq * 4
 
     if a.pmc_calibration:   # a plain copy kernel of known size: reads 1 GiB, writes 1 GiB per launch
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -159,7 +175,7 @@ def main():
     value = nbytes / elapsed / 1e9
 
     # ---- dominant kernel (decode partial kernel) with HIP events, eager launches
-    prof = steps[Wm + K:]
+    prof = steps[Wm + K:Wm + K + P]
     cache.pod_profile_enable(2 * len(prof) + 4)
     for e in prof:
         run_step(e)
@@ -184,6 +200,31 @@ def main():
                      "traffic": traffic_from_profiles(), "bytes_per_launch": int(bytes_per_launch),
                      "avg_kernel_us": round(kernel_s * 1e6, 3), "launches": launches},
     }
+
+    # ---- the same steps through the score-reuse entry point (SURVEY's first "next" row)
+    if RU > 0:
+        ru = steps[Wm + K + P:]
+        g2 = None
+        if not a.no_graph:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                for e in ru:
+                    run_step_reuse(e)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if g2 is not None:
+            g2.replay()
+        else:
+            for e in ru:
+                run_step_reuse(e)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        cache.pod_cache_check()
+        rb = sum(step_bytes_reuse(e) for e in ru)
+        out["score_reuse"] = {"steps": len(ru), "ms_per_step": round(el / len(ru) * 1e3, 5),
+                              "bytes_per_step": step_bytes_reuse(ru[0]),
+                              "value": round(rb / el / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
+                              "speedup_vs_plain_step": round((elapsed / K) / (el / len(ru)), 3)}
 
     # ---- CPU oracle on the host cores, a bounded sample of the same steps (block 0's)
     if not a.no_cpu:

@@ -163,6 +163,25 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
                          void *workspace, size_t workspace_bytes, void *out, void *stream);
 
 /*
+ * Decode attention with score reuse: same result as pod_decode_attention, but the distant
+ * logits are computed once per block.  Eq. 3 line 3 defines the distant logits of every layer of
+ * a block as those of the block's lowest layer; called for the lowest layer, this entry point
+ * also writes them (scaled, fp32) to `scores`; called for an upper layer it reads them from
+ * there instead of streaming the block's distant keys again, which cuts the bytes such a call
+ * has to read from 2*n rows to about n rows + 4 bytes per (query head, distant token).
+ *   scores : dev buffer of >= pod_score_buffer_bytes(cfg), 256-byte aligned, holding the logits
+ *            of ONE block at a time: call the block's lowest layer first, then its upper layers,
+ *            for the same token, batch and scale, before moving to the next block.  A tag in the
+ *            buffer (token count and block per sequence) is checked on the device; a mismatch
+ *            zeroes the output row and raises the flag pod_cache_check reports.
+ * Other arguments as in pod_decode_attention; no q_shared is needed.
+ */
+int pod_score_buffer_bytes(const pod_config *cfg, size_t *bytes);
+int pod_decode_attention_reuse(pod_cache *cache, int layer, const void *q, const int32_t *context_lens, int B,
+                               int max_context_len, float scale, void *workspace, size_t workspace_bytes,
+                               void *scores, size_t scores_bytes, void *out, void *stream);
+
+/*
  * Prefill attention for one sequence (Eq. 3 with the window taken at each query's own
  * position: key j is proximal for query i if j < S or j > i - W), causal, joint softmax.
  *   q        : dev bf16 [n][Hq][d];  k, v : dev bf16 [n][Hkv][d] of `layer`

@@ -20,6 +20,7 @@ EXPORTS = [
     "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
+    "pod_score_buffer_bytes", "pod_decode_attention_reuse",
 ]
 
 
@@ -67,6 +68,9 @@ def load():
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
         "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
         "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
+        "pod_score_buffer_bytes": [cfgp, szp],
+        "pod_decode_attention_reuse": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp,
+                                       C.c_size_t, vp, vp],
         "pod_profile_enable": [vp, C.c_int],
         "pod_profile_disable": [vp],
         "pod_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)],
@@ -113,6 +117,12 @@ def pod_cache_live_bytes(cfg: PodConfig, n: int):
     a, b = C.c_size_t(), C.c_size_t()
     _check(load().pod_cache_live_bytes(C.byref(cfg), n, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def pod_score_buffer_bytes(cfg: PodConfig) -> int:
+    out = C.c_size_t()
+    _check(load().pod_score_buffer_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
 
 
 def pod_workspace_bytes(cfg: PodConfig) -> int:
@@ -172,6 +182,21 @@ class PodCache:
                                            self.workspace.data_ptr(), self.workspace.numel(), _ptr(out, torch.bfloat16),
                                            _stream()))
         return out
+
+    def pod_decode_attention_reuse(self, layer, q, context_lens, scale, scores, out=None, max_context_len=0):
+        B = q.shape[0]
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_decode_attention_reuse(self.handle, layer, _ptr(q, torch.bfloat16),
+                                                 _ptr(context_lens, torch.int32), B, max_context_len, scale,
+                                                 self.workspace.data_ptr(), self.workspace.numel(),
+                                                 scores.data_ptr(), scores.numel() * scores.element_size(),
+                                                 _ptr(out, torch.bfloat16), _stream()))
+        return out
+
+    def new_score_buffer(self):
+        """Device buffer for pod_decode_attention_reuse (one block's distant logits)."""
+        return torch.empty(pod_score_buffer_bytes(self.cfg), dtype=torch.uint8, device=self.device)
 
     def pod_prefill_attention(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, out=None, write_cache=False):
         n = q.shape[0]

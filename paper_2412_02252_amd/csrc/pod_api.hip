@@ -265,9 +265,47 @@ extern "C" int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, 
     return POD_OK;
 }
 
+static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                         const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
+                         size_t workspace_bytes, void *scores, void *out, void *stream);
+
 extern "C" int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void *q_shared,
                                     const int32_t *context_lens, int B, int max_context_len, float scale,
                                     void *workspace, size_t workspace_bytes, void *out, void *stream)
+{
+    return decode_common(cache, layer, q, q_shared, context_lens, B, max_context_len, scale, workspace,
+                         workspace_bytes, nullptr, out, stream);
+}
+
+extern "C" int pod_score_buffer_bytes(const pod_config *cfg, size_t *bytes)
+{
+    pod_layout ly;
+    if (!bytes) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL");
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    *bytes = pod_score_header_bytes(ly) + (size_t)ly.B * ly.Hq * pod_score_stride(ly) * sizeof(float);
+    return POD_OK;
+}
+
+extern "C" int pod_decode_attention_reuse(pod_cache *cache, int layer, const void *q, const int32_t *context_lens,
+                                          int B, int max_context_len, float scale, void *workspace,
+                                          size_t workspace_bytes, void *scores, size_t scores_bytes, void *out,
+                                          void *stream)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    if (!scores) return pod_fail(POD_ERR_INVALID_ARG, "scores is NULL");
+    if ((uintptr_t)scores % 256) return pod_fail(POD_ERR_INVALID_ARG, "scores must be 256-byte aligned");
+    const pod_layout &ly = cache->ly;
+    const size_t need = pod_score_header_bytes(ly) + (size_t)ly.B * ly.Hq * pod_score_stride(ly) * sizeof(float);
+    if (scores_bytes < need) return pod_fail(POD_ERR_CAPACITY, "score buffer has %zu bytes, needs %zu", scores_bytes, need);
+    // upper layers take the distant logits from the buffer: q doubles as the (unused) shared query
+    return decode_common(cache, layer, q, q, context_lens, B, max_context_len, scale, workspace, workspace_bytes,
+                         scores, out, stream);
+}
+
+static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                         const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
+                         size_t workspace_bytes, void *scores, void *out, void *stream)
 {
     int rc = check_cache_layer(cache, layer);
     if (rc) return rc;
@@ -288,7 +326,7 @@ extern "C" int pod_decode_attention(pod_cache *cache, int layer, const void *q, 
     if (max_context_len == 0) max_context_len = (int)longest;
     if (max_context_len == 0) max_context_len = 1;
     return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
-                             workspace, workspace_bytes, out, (hipStream_t)stream);
+                             workspace, workspace_bytes, scores, out, (hipStream_t)stream);
 }
 
 extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, const void *q, const void *k,

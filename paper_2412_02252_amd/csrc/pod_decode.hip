@@ -75,6 +75,16 @@ struct decode_params {
     int32_t *flag;
     int32_t maxctx;
     pod_bf16 *out;   // [B][Hq][D]
+    // score reuse (modes 1 and 2 of the partial kernel): scaled distant logits of the block's
+    // lowest layer, fp32, stored tile by tile in the register order of the S^T accumulators:
+    // [B][Hkv][score_stride / (32 * rep) tiles][4 (lane / 16)][rep heads][8 tokens of the lane],
+    // so that a wave writes (and later reads) 32 contiguous bytes per lane and 128 contiguous bytes
+    // per 4 neighbouring lanes; preceded by a header int32 [B][2] = (n, block)
+    float *scores;
+    int32_t *score_hdr;
+    int32_t score_stride;
+    int32_t block_id;
+    int32_t mode;    // 0 plain, 1 lowest layer writes scores, 2 upper layer reads them
     int32_t hlen[kMaxHostLens];
 };
 static_assert(offsetof(decode_params, hot) == 0, "hot lines first");
@@ -128,7 +138,11 @@ __device__ inline unsigned pack_bf16(float lo, float hi)
     return __builtin_bit_cast(unsigned, t);
 }
 
-template <int D>
+// MODE 0: every logit is computed here.  MODE 1 (lowest layer of a block, score reuse): the same,
+// and the scaled logits of distant chunks are also written to p.scores.  MODE 2 (upper layer, score
+// reuse): distant chunks take their logits from p.scores instead of reading the block's distant
+// keys (Eq. 3 line 3 says they ARE the lowest layer's logits), so such a chunk streams V only.
+template <int D, int MODE>
 __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_params p)
 {
     constexpr int CPR = D / 8;        // 16-byte pieces per row
@@ -162,6 +176,10 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     if (start >= region_len) return;
     const int end = min(start + chunk, region_len);
 
+    if (MODE == 1 && c == 0 && h == 0 && threadIdx.x == 0) { // tag the score buffer: which token, which block
+        p.score_hdr[2 * b] = n;
+        p.score_hdr[2 * b + 1] = p.block_id;
+    }
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
     const size_t pair = (size_t)b * hkv + h;
@@ -203,7 +221,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     }
 
     int t0 = start + wave * kTile;
-    POD_LOAD_TILE(t0)
+    const bool reads_scores = MODE == 2 && distant; // such a chunk needs neither K nor Q
+    if (!reads_scores) { POD_LOAD_TILE(t0) }
 
     // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
     bf16x8 qf[KST];
@@ -212,48 +231,14 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int s = 0; s < KST; ++s) {
             u32x4 t = u32x4{0u, 0u, 0u, 0u};
-            if (m16 < hot.rep) t = qrow[4 * s + j];
+            if (m16 < hot.rep && !reads_scores) t = qrow[4 * s + j];
             qf[s] = as_bf16x8(t);
         }
     }
 
 
-    for (; t0 < end; t0 += kWaves * kTile) {
-        // ---- K tile through LDS into A-operand order
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int r = RPI * i + kr;
-            ldsK[r * CPR + (kc ^ (r % CPR))] = kreg[i];
-        }
-        u32x4 vcur[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vcur[e] = vreg[e];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KST; ++s) {
-            const int col = 4 * s + j;
-            const u32x4 a0 = ldsK[m16 * CPR + (col ^ (m16 % CPR))];
-            const u32x4 a1 = ldsK[(16 + m16) * CPR + (col ^ ((16 + m16) % CPR))];
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), qf[s], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), qf[s], s1, 0, 0, 0);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- next tile's loads go out before the softmax / PV work of this one
-        POD_LOAD_TILE(t0 + kWaves * kTile)
-
-        // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
-        float sc[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int tok0 = t0 + 4 * j + i, tok1 = tok0 + 16;
-            sc[i] = tok0 < end ? s0[i] * hot.scale_log2e : kNegBig;
-            sc[4 + i] = tok1 < end ? s1[i] * hot.scale_log2e : kNegBig;
-        }
+    // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain), then O^T += V^T P
+    auto softmax_pv = [&](float (&sc)[8], const u32x4 (&vcur)[8]) {
         float mx = sc[0];
 #pragma unroll
         for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
@@ -300,6 +285,103 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
             }
             acc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt), pf, acc[x], 0, 0, 0);
         }
+    };
+
+    if (reads_scores) {
+        // Score reuse: this chunk's logits were written by the block's lowest layer (already scaled,
+        // base-2 domain) in exactly the per-lane order of the S^T accumulators: head m16, tokens
+        // 4j..4j+3 of the two 16-token halves of a tile.  Only V is streamed.
+        typedef const __attribute__((address_space(1))) f32x4 *gf4_r;
+        const gf4_r sbase = (gf4_r)(p.scores + ((size_t)b * hkv + h) * p.score_stride * hot.rep) +
+                            ((size_t)j * hot.rep + (m16 < hot.rep ? m16 : 0)) * 2;
+        // Half the bytes per token means half the bytes in flight per wave, so two tiles are kept
+        // in flight here (register sets A and B) instead of one.
+        f32x4 sregA[2], sregB[2];
+        u32x4 vregB[8];
+#define POD_LOAD_SV(SR, VR, T0)                                                   \
+        {                                                                             \
+            const gf4_r sp = sbase + (size_t)(min((T0), last) >> 5) * 8 * hot.rep;     \
+            SR[0] = sp[0];                                                            \
+            SR[1] = sp[1];                                                            \
+        }                                                                             \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                               \
+            const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);               \
+            const int row = min((T0) + tok, last);                                    \
+            VR[e] = Vb[(size_t)row * CPR + vc];                                       \
+        }
+#define POD_CONSUME_SV(SR, VR, T0, TNEXT)                                         \
+        {                                                                             \
+            u32x4 vcur[8];                                                            \
+            float sc[8];                                                              \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) vcur[e] = VR[e];            \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                           \
+                const int tok0 = (T0) + 4 * j + i, tok1 = tok0 + 16;                  \
+                sc[i] = tok0 < end ? SR[0][i] : kNegBig;                              \
+                sc[4 + i] = tok1 < end ? SR[1][i] : kNegBig;                          \
+            }                                                                         \
+            if (m16 >= hot.rep) {                                                     \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) sc[i] = 0.f; /* padding heads: any finite value */ \
+            }                                                                         \
+            POD_LOAD_SV(SR, VR, TNEXT)                                                \
+            softmax_pv(sc, vcur);                                                     \
+        }
+        constexpr int kStep = kWaves * kTile;
+        POD_LOAD_SV(sregA, vreg, t0)
+        POD_LOAD_SV(sregB, vregB, t0 + kStep)
+        for (; t0 < end; t0 += 2 * kStep) {
+            POD_CONSUME_SV(sregA, vreg, t0, t0 + 2 * kStep)
+            if (t0 + kStep < end) POD_CONSUME_SV(sregB, vregB, t0 + kStep, t0 + 3 * kStep)
+        }
+#undef POD_CONSUME_SV
+#undef POD_LOAD_SV
+    } else
+    for (; t0 < end; t0 += kWaves * kTile) {
+        // ---- K tile through LDS into A-operand order
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int r = RPI * i + kr;
+            ldsK[r * CPR + (kc ^ (r % CPR))] = kreg[i];
+        }
+        u32x4 vcur[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vcur[e] = vreg[e];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KST; ++s) {
+            const int col = 4 * s + j;
+            const u32x4 a0 = ldsK[m16 * CPR + (col ^ (m16 % CPR))];
+            const u32x4 a1 = ldsK[(16 + m16) * CPR + (col ^ ((16 + m16) % CPR))];
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), qf[s], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), qf[s], s1, 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- next tile's loads go out before the softmax / PV work of this one
+        POD_LOAD_TILE(t0 + kWaves * kTile)
+
+        // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
+        float sc[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok0 = t0 + 4 * j + i, tok1 = tok0 + 16;
+            sc[i] = tok0 < end ? s0[i] * hot.scale_log2e : kNegBig;
+            sc[4 + i] = tok1 < end ? s1[i] * hot.scale_log2e : kNegBig;
+        }
+        if constexpr (MODE == 1) {
+            if (distant && m16 < hot.rep) { // the lowest layer's distant logits, for the block's upper layers
+                typedef __attribute__((address_space(1))) f32x4 *gf4_w;
+                const size_t tile = (size_t)(t0 >> 5);
+                const gf4_w dst = (gf4_w)(p.scores + ((size_t)b * hkv + h) * p.score_stride * hot.rep) +
+                                  (tile * 4 * hot.rep + (size_t)j * hot.rep + m16) * 2;
+                dst[0] = f32x4{sc[0], sc[1], sc[2], sc[3]};   // tokens past the chunk carry the mask value
+                dst[1] = f32x4{sc[4], sc[5], sc[6], sc[7]};
+            }
+        }
+        softmax_pv(sc, vcur);
     }
 
 #undef POD_LOAD_TILE
@@ -430,6 +512,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
             n = 0;
         }
     }
+    if (p.mode == 2 && n > hot.prows) { // the distant logits must be those of this token and block
+        if (p.score_hdr[2 * b] != n || p.score_hdr[2 * b + 1] != p.block_id) { bad = true; n = 0; }
+    }
     uint2 res = make_uint2(0u, 0u);
     if (n > 0) {
         const float inv = 1.f / L;
@@ -452,8 +537,12 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
     return (bytes + 255) / 256 * 256;
 }
 
+size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
+
+size_t pod_score_header_bytes(const pod_layout &ly) { return ((size_t)ly.B * 2 * sizeof(int32_t) + 255) / 256 * 256; }
+
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared, const int32_t *ctx, int B,
-                      int max_len, float scale, void *ws, size_t ws_bytes, void *out, hipStream_t st)
+                      int max_len, float scale, void *ws, size_t ws_bytes, void *scores, void *out, hipStream_t st)
 {
     const pod_layout &ly = c->ly;
     const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
@@ -472,6 +561,11 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.flag = (int32_t *)(c->base + ly.off_flag);
     p.maxctx = ly.maxctx;
     p.out = (pod_bf16 *)out;
+    p.mode = scores ? (layer == lowest ? 1 : 2) : 0;
+    p.score_hdr = (int32_t *)scores;
+    p.scores = scores ? (float *)((char *)scores + pod_score_header_bytes(ly)) : nullptr;
+    p.score_stride = (int32_t)pod_score_stride(ly);
+    p.block_id = layer / ly.G;
     p.hot.use_hlen = B <= kMaxHostLens;
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
@@ -506,10 +600,17 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     pod_cache *mc = const_cast<pod_cache *>(c);
     const bool prof = mc->prof_ev && mc->prof_n < mc->prof_cap;
     if (prof) POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n], st));
-    if (ly.D == 128)
-        hipLaunchKernelGGL(decode_partial_kernel<128>, grid, dim3(kWaves * 64), 0, st, p);
-    else
-        hipLaunchKernelGGL(decode_partial_kernel<64>, grid, dim3(kWaves * 64), 0, st, p);
+#define POD_LAUNCH_PARTIAL(DD, MM) hipLaunchKernelGGL((decode_partial_kernel<DD, MM>), grid, dim3(kWaves * 64), 0, st, p)
+    if (ly.D == 128) {
+        if (p.mode == 0) POD_LAUNCH_PARTIAL(128, 0);
+        else if (p.mode == 1) POD_LAUNCH_PARTIAL(128, 1);
+        else POD_LAUNCH_PARTIAL(128, 2);
+    } else {
+        if (p.mode == 0) POD_LAUNCH_PARTIAL(64, 0);
+        else if (p.mode == 1) POD_LAUNCH_PARTIAL(64, 1);
+        else POD_LAUNCH_PARTIAL(64, 2);
+    }
+#undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }
     if (ly.D == 128)
         hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(256), 0, st, p);

@@ -71,6 +71,12 @@ class Case:
         ctx_t = torch.tensor(ctx, dtype=torch.int32, device=self.dev)
         return self.gpu.pod_decode_attention(layer, q, qs, ctx_t, self.scale, max_context_len=max_context_len)
 
+    def decode_reuse(self, layer, ctx, scores, max_context_len=0):
+        """Score-reuse entry point: the block's lowest layer must be called first for this token."""
+        q = self.decode_queries(layer, ctx, self.dev)
+        ctx_t = torch.tensor(ctx, dtype=torch.int32, device=self.dev)
+        return self.gpu.pod_decode_attention_reuse(layer, q, ctx_t, self.scale, scores, max_context_len=max_context_len)
+
     def decode_ref(self, layer, ctx):
         lowest = layer - layer % self.G
         q = gen.bf16_bits(self.decode_queries(layer, ctx, "cpu"))

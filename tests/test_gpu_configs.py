@@ -68,6 +68,37 @@ def test_config2_llama_decode_64_steps_with_demotion():
         assert g["distV"].shape[0] == n0 + steps - S - W
 
 
+def test_config2_shape_with_score_reuse():
+    """Config-2 shape, 8 decode steps through the score-reuse entry point, every output compared."""
+    L, G, Hq, Hkv, d, S, W, n0, steps = 2, 2, 32, 8, 128, 64, 2048, 32768, 8
+    seed = SEED0 + 2
+    max_ctx = n0 + steps
+    rope = dict(rope_base=500000.0, rope_max_pos=max_ctx)
+    cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, 1, max_ctx), DEV)
+    oc = po.Cache(L, G, Hkv, d, S, W, 1, max_ctx)
+    scale = 1.0 / math.sqrt(d)
+    K = [gen.keys_bf16(seed, l, 0, max_ctx, Hkv, d, device=DEV, **rope) for l in range(L)]
+    V = [gen.values_bf16(seed, l, 0, max_ctx, Hkv, d, device=DEV) for l in range(L)]
+    Q = [gen.queries_bf16(seed, l, 0, steps, Hq, d, device=DEV, pos0=n0) for l in range(L)]
+    Kh, Vh, Qh = [host_bits(t) for t in K], [host_bits(t) for t in V], [host_bits(t) for t in Q]
+    for l in range(L):
+        cache.pod_cache_fill(l, 0, K[l][:n0].contiguous(), V[l][:n0].contiguous())
+        oc.fill(l, 0, Kh[l][:n0], Vh[l][:n0])
+    scores = cache.new_score_buffer()
+    for s in range(steps):
+        p = n0 + s
+        pos = torch.tensor([p], dtype=torch.int32, device=DEV)
+        ctx = torch.tensor([p + 1], dtype=torch.int32, device=DEV)
+        for l in range(L):
+            cache.pod_cache_append(l, K[l][p:p + 1].contiguous(), V[l][p:p + 1].contiguous(), pos)
+            oc.append(l, Kh[l][p:p + 1], Vh[l][p:p + 1], [p])
+        for l in range(L):
+            out = cache.pod_decode_attention_reuse(l, Q[l][s:s + 1].contiguous(), ctx, scale, scores, max_context_len=p + 1)
+            ref = oc.decode_attention(l, Qh[l][s:s + 1], Qh[0][s:s + 1] if l else None, [p + 1], scale)
+            assert_close(out, ref, f"step {s} layer {l}")
+    cache.pod_cache_check()
+
+
 # ----------------------------------------------------------------------------- configs 3 and 5
 def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0):
     Hq, Hkv, d = 32, 8, 128

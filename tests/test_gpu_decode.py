@@ -133,3 +133,63 @@ def test_outlier_keys_do_not_break_the_softmax():
         c.fill(layer, 0, n)
     for layer in (0, 3):
         assert_close(c.decode(layer, [n]), c.decode_ref(layer, [n]), f"layer {layer}")
+
+
+# ---------------------------------------------------------------- score reuse (distant logits computed once per block)
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 8, 2), (64, 4, 2), (128, 16, 1)])
+@pytest.mark.parametrize("n", [7, 40, 41, 73, 457, 1500])
+def test_score_reuse_matches_oracle_and_plain_path(d, Hq, Hkv, n):
+    """G=4: the lowest layer writes its scaled distant logits, layers 1-3 read them instead of the shared keys."""
+    c = Case(4, 4, Hq, Hkv, d, 8, 32, 1, 1600, seed=300 + n)
+    for layer in range(4):
+        c.fill(layer, 0, n)
+    scores = c.gpu.new_score_buffer()
+    for layer in range(4):
+        out = c.decode_reuse(layer, [n], scores)
+        assert_close(out, c.decode_ref(layer, [n]), f"n={n} layer {layer}")
+        plain = c.decode(layer, [n])
+        assert (out.float() - plain.float()).abs().max() <= 1.6e-2   # two bf16-rounded runs of the same sum
+    c.gpu.pod_cache_check()
+
+
+def test_score_reuse_ragged_batch_and_steps():
+    c = Case(2, 2, 32, 8, 128, 16, 96, 3, 700, seed=41)
+    lens = [650, 100, 330]
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    scores = c.gpu.new_score_buffer()
+    for step in range(6):
+        for layer in range(2):
+            c.append(layer, [n + step for n in lens])
+        ctx = [n + step + 1 for n in lens]
+        for layer in range(2):
+            assert_close(c.decode_reuse(layer, ctx, scores), c.decode_ref(layer, ctx), f"step {step} layer {layer}")
+    c.gpu.pod_cache_check()
+
+
+def test_score_reuse_detects_stale_scores():
+    c = Case(4, 2, 4, 2, 64, 8, 32, 1, 512, seed=42)
+    n = 300
+    for layer in range(4):
+        c.fill(layer, 0, n)
+    scores = c.gpu.new_score_buffer()
+    scores.zero_()
+    out = c.decode_reuse(1, [n], scores)              # upper layer before its lowest layer ran
+    assert torch.all(out == 0)
+    with pytest.raises(pod.PodError) as e:
+        c.gpu.pod_cache_check()
+    assert e.value.code == pod.binding.ERR_STATE
+    c.decode_reuse(0, [n], scores)                    # block 0's logits ...
+    out = c.decode_reuse(3, [n], scores)              # ... are not block 1's
+    assert torch.all(out == 0)
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_cache_check()
+    c.decode_reuse(2, [n], scores)
+    assert_close(c.decode_reuse(3, [n], scores), c.decode_ref(3, [n]), "after the right lowest layer")
+    c.gpu.pod_cache_check()
+    with pytest.raises(pod.PodError) as e:            # undersized buffer
+        c.gpu.pod_decode_attention_reuse(0, c.decode_queries(0, [n], c.dev),
+                                         torch.tensor([n], dtype=torch.int32, device=c.dev), c.scale, scores[:256])
+    assert e.value.code == pod.binding.ERR_CAPACITY
