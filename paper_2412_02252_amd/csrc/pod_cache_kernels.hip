@@ -27,13 +27,17 @@ __global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 
 {
     const int b = blockIdx.x;
     int32_t *lens = lens_ptr(base, ly) + (size_t)layer * ly.B + b;
+    const int cpr = ly.D / 8; // 16-byte pieces per head row
+    const int pieces = ly.Hkv * cpr;
+    // The new rows do not depend on the position check: their loads go out with it.
+    const size_t src0 = (size_t)b * pieces + (threadIdx.x < pieces ? threadIdx.x : 0);
+    uint4 kn = k_new[src0], vn = v_new[src0];
     const int p = positions[b];
     const int cur = *lens;
     if (p != cur || p < 0 || p >= ly.maxctx) { // uniform over the block
         if (threadIdx.x == 0) atomicOr(flag_ptr(base, ly), 1);
         return;
     }
-    const int cpr = ly.D / 8; // 16-byte pieces per head row
     const int slot = p < ly.S ? p : ly.S + (p - ly.S) % ly.W;
     const bool demote = p >= ly.P;          // the ring slot holds position p - W
     const bool lowest = layer % ly.G == 0;
@@ -42,17 +46,20 @@ __global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 
     uint4 *proxV = (uint4 *)(base + ly.off_proxV);
     uint4 *distK = (uint4 *)(base + ly.off_distK);
     uint4 *distV = (uint4 *)(base + ly.off_distV);
-    for (int idx = threadIdx.x; idx < ly.Hkv * cpr; idx += blockDim.x) {
+    for (int idx = threadIdx.x; idx < pieces; idx += blockDim.x) {
         const int h = idx / cpr, c = idx % cpr;
         const size_t pr = (pod_prox_row0(ly, layer, b, h) + slot) * cpr + c;
+        if (idx != (int)threadIdx.x) {
+            kn = k_new[(size_t)b * pieces + idx];
+            vn = v_new[(size_t)b * pieces + idx];
+        }
         if (demote) {
             const size_t t = (size_t)(p - ly.P); // distant row of position p - W
             distV[(pod_dist_row0(ly, layer, b, h) + t) * cpr + c] = proxV[pr];
             if (lowest) distK[(pod_dist_row0(ly, group, b, h) + t) * cpr + c] = proxK[pr];
         }
-        const size_t src = ((size_t)b * ly.Hkv + h) * cpr + c;
-        proxK[pr] = k_new[src];
-        proxV[pr] = v_new[src];
+        proxK[pr] = kn;
+        proxV[pr] = vn;
     }
     __syncthreads(); // every thread has read *lens (through cur) before it changes
     if (threadIdx.x == 0) *lens = p + 1;

@@ -429,12 +429,15 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 // Like the partial kernel it starts from the host mirror's length so that its loads of the
 // partials go out together with the loads that validate that length; the validation only gates
 // the final store.
-template <int D>
-__global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
+template <int D, int kCombineThreads = 256, int UN = 8, int DS = D>
+__global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_params p)
 {
-    constexpr int LPR = D / 4;       // lanes per partial row (float4 each)
-    constexpr int NG = 256 / LPR;    // chunk groups
-    constexpr int UN = 8;            // partial rows in flight per thread
+    // DS = dims per workgroup: blockIdx.z picks a slice of the head dimension, so that a head's
+    // partials are pulled through several CUs; every slice recomputes the same chunk weights
+    constexpr int LPR = DS / 4;      // lanes per partial row slice (float4 each)
+    constexpr int ROW = D / 4;       // float4 per partial row
+    const int xs = blockIdx.z * LPR;
+    constexpr int NG = kCombineThreads / LPR; // chunk groups
     typedef const __attribute__((address_space(1))) float *gfloat_ptr;
     typedef const __attribute__((address_space(1))) f32x4 *gf4_ptr;
     typedef const __attribute__((address_space(1))) int32_t *gint_ptr;
@@ -454,7 +457,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
     const int NC = hot.nc;
     const int nvalid = n > 0 ? nd + np : 0;
     const gfloat_ptr ml = (gfloat_ptr)hot.part_ml + ((size_t)b * hot.hq + head) * NC * 2;
-    const gf4_ptr pa = (gf4_ptr)hot.part_acc + ((size_t)b * hot.hq + head) * NC * LPR;
+    const gf4_ptr pa = (gf4_ptr)hot.part_acc + ((size_t)b * hot.hq + head) * NC * ROW + xs;
     auto chunk_slot = [&](int v) { return v < nd ? v : hot.max_nd + (v - nd); };
 
     const int g = threadIdx.x / LPR, x = threadIdx.x % LPR;
@@ -469,7 +472,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
             const int cs = chunk_slot(v < nvalid ? v : v0);
             mk[k] = ml[cs * 2];
             lk[k] = ml[cs * 2 + 1];
-            ak[k] = pa[(size_t)cs * LPR + x];
+            ak[k] = pa[(size_t)cs * ROW + x];
             if (v >= nvalid) { mk[k] = kNegBig; lk[k] = 0.f; ak[k] = f32x4{0.f, 0.f, 0.f, 0.f}; }
         }
         float mb = mk[0];
@@ -520,10 +523,10 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(decode_params p)
         const float inv = 1.f / L;
         res.x = pack_bf16(o.x * inv, o.y * inv);
         res.y = pack_bf16(o.z * inv, o.w * inv);
-    } else if (bad && head == 0 && x == 0) {
+    } else if (bad && head == 0 && x == 0 && xs == 0) {
         atomicOr(p.flag, 2);
     }
-    ((uint2 *)(p.out + ((size_t)b * hot.hq + head) * D))[x] = res;
+    ((uint2 *)(p.out + ((size_t)b * hot.hq + head) * D))[xs + x] = res;
 }
 
 int chunk_slots(int rows, int chunk) { return (rows + chunk - 1) / chunk; }
@@ -613,9 +616,9 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 #undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }
     if (ly.D == 128)
-        hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((decode_combine_kernel<128, 256, 8, 64>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((decode_combine_kernel<64, 256, 8, 32>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }
