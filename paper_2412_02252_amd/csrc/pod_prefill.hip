@@ -15,23 +15,21 @@
 // tile is loaded twice: ~4 of 256 tiles per row block at the paper's window sizes).  At the
 // block's lowest layer there is only phase P over all tiles, with the causal mask.
 //
-// Tiling: a workgroup of 4 waves takes BM = 128*NQ query rows of one head; each wave owns 32*NQ
-// rows.  Key/value tiles of BN = 64 tokens go through LDS (double-buffered, one barrier per
-// tile), written in MFMA A-operand *fragment order* (64 lanes x 16 bytes per fragment) so that
-// every read is one conflict-free ds_read_b128.  Global loads of tile t+1 are issued before the
-// arithmetic of tile t and parked in registers.
-//   S^T[key][row] = K[key][:] . Q[row][:]     v_mfma_f32_32x32x16_bf16, A = K frag, B = Q
-//   O^T[dim][row] = sum_key V[key][dim] P[key][row]               A = V^T frag, B = P
+// Tiling: a workgroup of 4 waves takes 128 query rows of one head, 32 rows per wave; key/value
+// tiles of 64 tokens go through LDS.
+//   S^T[key][row] = K[key][:] . Q[row][:]     v_mfma_f32_32x32x16_bf16, A = K fragment, B = Q
+//   O^T[dim][row] = sum_key V[key][dim] P[key][row]               A = V^T fragment, B = P
 // Query row = MFMA column (lane % 32) in both, so softmax state, P and the output slice of a
-// row stay in the same lane, and the S^T accumulators become the P operand without moving
-// (the 8 keys a lane holds for one PV k-step are the keys of its 8 consecutive accumulators;
-// V^T fragments are built for that key order).  V is transposed on the way into LDS: a thread
-// loads the same 16-byte dim piece of 4 tokens and transposes the 4x8 block with v_perm_b32.
+// row stay in the same lane, and the S^T accumulators become the P operand without moving: the
+// 8 keys a lane holds for one PV k-step are the keys of its 8 consecutive accumulators (tokens
+// 16 ks + 4 (lane / 32) + {0..3} and + 8 of the tile), and the V^T fragments are read for that order.
 //
-// Softmax: base-2 with the logit scale folded into the exponent; the running maximum is only
+// Softmax: base-2 with the logit scale folded into the exponent; the reference maximum is only
 // moved when a tile exceeds it by more than 2^8 (probabilities then stay below 256, harmless in
 // fp32 sums and in bf16), which removes most rescaling passes over the output accumulators.
+#include <stdlib.h>
 #include <type_traits>
+#include <utility>
 
 #include "pod_internal.h"
 
@@ -44,6 +42,7 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 constexpr int kBN = 64;
 constexpr float kNegBig = -1.0e30f;
+constexpr int kPF = 2;        // LDS fragment reads in flight ahead of the MFMA that uses them (1 is slower, 3 no faster)
 constexpr float kLazy = 8.0f; // how far (log2) a tile's maximum may exceed the reference before rescaling
 
 struct prefill_params {
@@ -88,35 +87,76 @@ __device__ inline float pair_sum(float x)
     return a + b;
 }
 
-template <int D, int NQ>
-__global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_kernel(prefill_params p)
+// ---------------------------------------------------------------------------------------------
+// Order of work inside a wave (software pipeline over three tiles).
+//
+// Measured on gfx950: a wave issues roughly one vector instruction per 5-6 cycles, a 32x32x16
+// MFMA keeps the matrix pipe busy for 32 cycles, and with two waves per SIMD the pipe only
+// stays busy if each wave brings at most ~3 ordinary vector instructions, one transcendental
+// and one or two LDS reads per MFMA.  So an iteration is a sequence of MFMA slots of that shape,
+// taken from three different tiles:
+//   iteration t:  S(t+1) = K(t+1) Q^T        (logits of the next tile)
+//                 O += V(t-1)^T P(t-1)       (output update of the previous tile)
+//                 P(t) = exp2(c S(t) - m)    one pair of elements per slot or two
+//                 row maximum of S(t+1); one barrier.
+// No exponential waits for an MFMA of the same iteration.  Slot order: the 2:1 mix QK, QK, PV
+// for the first three quarters of the slots (all of S(t+1) is then complete), PV only in the
+// last quarter, where the vector work is the row maximum of S(t+1).  It is needed at the top of
+// the next iteration, which moves the reference maximum if the tile exceeds it by more than 2^8
+// and rescales the accumulators (rare).  Masked logits are -infinity (exponential 0 whatever the
+// reference); every wave walks every tile of its workgroup.  The row sum adds the bf16-rounded
+// probabilities (v_dot2c_f32_bf16 with ones), i.e. exactly the weights the PV product uses.
+//
+// Data movement uses no registers: K and V tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: each wave instruction fills 1 KB of consecutive LDS, lane l its 16
+// bytes; which 16 bytes of the tile a lane fetches is free to choose).
+//   K slot: MFMA fragment order, fragment (key block kb, k-step s) = 64 lanes x 16 bytes, lane
+//           (key row l % 32, l / 32) holds dims 16 s + 8 (l / 32) .. + 7: a lane fetches exactly the
+//           piece it will later read with one ds_read_b128.
+//   V slot: row-major [64 tokens][D] as in global memory, 16-byte pieces of a row XOR-permuted by
+//           4 (token % 4).  The A operand of the PV product (V^T: one dim, 8 tokens per lane) comes
+//           out of two ds_read_b64_tr_b16 (the LDS transpose read: inside 16 lanes, lane L receives
+//           element L % 4 of the four 8-byte rows addressed by lanes L / 4 + {0, 4, 8, 12}).
+// K(t+2) and V(t) are requested at the top of iteration t into the slots freed by the barrier
+// before, and awaited (vmcnt) before the barrier that ends the iteration.
+// static_for<N>(f): f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), each call its own
+// instantiation with a compile-time index (no reliance on the loop unroller for big bodies)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
 {
-    constexpr int CPR = D / 8;       // 16-byte pieces per row
-    constexpr int KST = D / 16;      // QK k-steps (32x32x16)
-    constexpr int NDB = D / 32;      // output dim blocks
-    constexpr int NKB = kBN / 32;    // key blocks per tile
-    constexpr int NPS = kBN / 16;    // PV k-steps per tile
-    constexpr int BM = 128 * NQ;
-    constexpr int KIT = kBN * CPR / 256; // K pieces per thread per tile
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+__device__ inline float dot2_ones(unsigned pk, float acc)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, acc, false);
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
+{
+    constexpr int CPR = D / 8, KST = D / 16, NDB = D / 32, NKB = kBN / 32, NPS = kBN / 16;
+    constexpr int BM = 128;
+    constexpr int NQK = NKB * KST;   // MFMAs of one S tile = K fragments of a tile
+    constexpr int NPV = NDB * NPS;   // MFMAs of one PV tile (equal to NQK)
+    static_assert(NQK == NPV, "slot schedule assumes as many QK as PV MFMAs per tile");
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
-
-    // LDS: two buffers, each holding NKB*KST key fragments and NDB*NPS V^T fragments of 64 lane
-    // slots x 16 bytes.  Inside a fragment the slot of lane l is l ^ x, where x (3 bits) depends on
-    // the fragment and on l / 32 for keys, on l / 8 and the dim block for values: with these XORs
-    // the reads (one ds_read_b128 per fragment and wave), the key-row writes and the 8-byte V^T
-    // writes were all measured free of bank conflicts on gfx950 (64 banks of 4 bytes).  The read
-    // offsets take only 4 (keys) + 2 (values) distinct per-lane values, computed once.
+    typedef const __attribute__((address_space(1))) char *gbyte_ptr;
+    typedef __attribute__((address_space(3))) char *lbyte_ptr;
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef __attribute__((address_space(3))) s16x4 *ltr_ptr;
     constexpr int FRAG = 64 * 16;
-    constexpr int KSTRIDE = FRAG, VSTRIDE = FRAG;
-    constexpr int KBUF = NKB * KST * KSTRIDE, VBUF = NDB * NPS * VSTRIDE;
-    constexpr int BUF = KBUF + VBUF;           // one buffer: keys then values
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int KBUF = NQK * FRAG, VBUF = kBN * D * 2; // 16 KB each at D = 128
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [K slot 0][K slot 1][V slot 0][V slot 1]
+    char *const ldsK = lds, *const ldsV = lds + 2 * KBUF;
 
-    // Workgroup -> (kv head, query head of the group, row block).  Consecutive workgroup ids land
-    // on consecutive XCDs (8 of them, each with its own L2), so the kv head is taken from the low
-    // bits of the id: with 8 kv heads every XCD works on ONE kv head, and the workgroups resident
-    // on it (the 4 query heads of the group x neighbouring row blocks) stream the same K/V tiles
-    // at the same time and share them through that L2.  Heaviest row blocks first.
     const int nqt = (p.n + BM - 1) / BM;
     const int wg = blockIdx.x;
     const int kvh = wg % p.Hkv;
@@ -127,17 +167,13 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_kernel(prefill_p
     const int i_last = min(i0 + BM, p.n) - 1;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n32 = lane & 31, jj = lane >> 5;
-    int kroff[4], vroff[2];                          // read offsets of this lane inside a key / value fragment
-#pragma unroll
-    for (int x = 0; x < 4; ++x) kroff[x] = 16 * (lane ^ (x | (jj << 2)));
-#pragma unroll
-    for (int x = 0; x < 2; ++x) vroff[x] = 16 * (lane ^ (((lane >> 3) & 3) | (((lane >> 5) ^ x) << 2)));
-    const int iw0 = i0 + wave * 32 * NQ;             // first row of this wave
-    const int iw_last = min(iw0 + 32 * NQ, p.n) - 1; // may be < iw0: the wave has no rows
+    const int iw0 = i0 + wave * 32;
+    const int iw_last = min(iw0 + 32, p.n) - 1;
+    const int irow = iw0 + n32;
     const bool has_shared = p.qs != nullptr;
     const int S = p.S, W = p.W;
+    const float c = p.scale_log2e;
 
-    // ---- the tile schedule of this workgroup: nD distant-phase tiles, then sink tiles, then band tiles
     int tD0 = 0, nD = 0, nP1 = 0, tB = 0;
     if (has_shared) {
         if (i_last - W >= S) { tD0 = S / kBN; nD = (i_last - W) / kBN - tD0 + 1; }
@@ -152,240 +188,307 @@ __global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void prefill_kernel(prefill_p
         kt = phaseD ? tD0 + t : (t < nD + nP1 ? t - nD : tB + (t - nD - nP1));
     };
 
-    // ---- global -> register loads of one tile.  Row addresses are a per-tile scalar base plus ONE
-    // per-thread offset (for K and for V), so a tile costs no vector address arithmetic; only the
-    // prompt's last, partly filled tile clamps rows to n-1 per thread.
-    constexpr int RS = 256 / CPR;                               // key rows covered by one K load of the workgroup
-    const int kc = tid % CPR, kr0 = tid / CPR;                  // K: piece, first row
-    const int vrest = tid / CPR;                                // V: 4-token group of this thread
-    const bool vact = vrest < 16;
-    const int vhalf = vrest & 1, vj = (vrest >> 1) & 1, vku = vrest >> 2;
-    const int vrow0 = 16 * vku + 8 * vhalf + 4 * vj;            // first of this thread's 4 V rows in the tile
-    const unsigned rowb = (unsigned)p.Hkv * D * 2;              // bytes from one token to the next
-    const unsigned koff = (unsigned)kr0 * rowb + (unsigned)(kvh * D * 2 + kc * 16);
-    const unsigned voff = (unsigned)vrow0 * rowb + (unsigned)(kvh * D * 2 + kc * 16);
-    typedef const __attribute__((address_space(1))) char *gbyte_ptr;
-    u32x4 kreg[KIT], vreg[4];
-    auto load_tile = [&](int t) {
-        int kt; bool phaseD;
-        tile_of(t, kt, phaseD);
+    // ---- global -> LDS.  Wave w moves K fragments w*NQK/4 .. and the V rows w*16 .. w*16+15.
+    constexpr int KPW = NQK / 4;                 // K fragments per wave and tile
+    constexpr int VRI = 64 / CPR;                // V rows per wave instruction (1 KB)
+    constexpr int VPW = 16 / VRI;                // V instructions per wave and tile
+    constexpr int VSWZ = 4 * ((CPR / 4 - 1) & 3); // piece-permutation mask: 12 at D = 128, 4 at D = 64
+    // A request is ONE scalar base per tile plus a per-lane offset that never changes (one register per
+    // request of the wave), so a tile costs neither vector nor scalar address arithmetic; only the
+    // prompt's last, partly filled tile takes a separate path that clamps its rows per lane.
+    const unsigned rowb = (unsigned)p.Hkv * D * 2;
+    const int v_r = lane / CPR;                                         // row inside a V instruction
+    const unsigned k_col = (unsigned)(kvh * D * 2 + jj * 16);           // + 32 s
+    const unsigned v_col = (unsigned)(kvh * D * 2 + 16 * ((lane % CPR) ^ ((4 * (v_r & 3)) & VSWZ)));
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);            // scalar copy: LDS destinations stay scalar
+    unsigned k_off[KPW], v_off[VPW];
+#pragma unroll
+    for (int x = 0; x < KPW; ++x) {
+        const int f = wave * KPW + x, fkb = f / KST, fs = f % KST;      // fragment (key block, k-step)
+        k_off[x] = (unsigned)(32 * fkb + n32) * rowb + k_col + 32 * fs;
+    }
+#pragma unroll
+    for (int x = 0; x < VPW; ++x) v_off[x] = (unsigned)(16 * wave + VRI * x + v_r) * rowb + v_col;
+    typedef const __attribute__((address_space(1))) void *gvoid_ptr;
+    typedef __attribute__((address_space(3))) void *lvoid_ptr;
+    const char *const k_dst0 = ldsK + wave_s * (KPW * FRAG);            // this wave's part of K slot 0
+    const char *const v_dst0 = ldsV + wave_s * (16 * D * 2);            // this wave's part of V slot 0
+    auto request_k = [&](int kt, bool phaseD, int slot) {
         const int j0 = kt * kBN;
-        const gbyte_ptr kb = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
-        const gbyte_ptr vb = (gbyte_ptr)p.v + (size_t)j0 * rowb;
-        if (j0 + kBN <= p.n) {
+        const gbyte_ptr base = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
+        if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
-            for (int it = 0; it < KIT; ++it) kreg[it] = *(gvec_ptr)(kb + (size_t)(it * RS) * rowb + koff);
-            if (vact) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) vreg[e] = *(gvec_ptr)(vb + (size_t)e * rowb + voff);
-            }
+            for (int x = 0; x < KPW; ++x)
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + k_off[x]), (lvoid_ptr)(k_dst0 + slot * KBUF + x * FRAG), 16, 0, 0);
         } else {
-            const unsigned colb = (unsigned)(kvh * D * 2 + kc * 16);
+            asm volatile("" ::: "memory"); // (keeps this a real branch: merged, both paths would pay for the clamping)
 #pragma unroll
-            for (int it = 0; it < KIT; ++it) {
-                const int key = min(kr0 + RS * it, p.n - 1 - j0);
-                kreg[it] = *(gvec_ptr)(kb + (size_t)key * rowb + colb);
-            }
-            if (vact) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int key = min(vrow0 + e, p.n - 1 - j0);
-                    vreg[e] = *(gvec_ptr)(vb + (size_t)key * rowb + colb);
-                }
+            for (int x = 0; x < KPW; ++x) {
+                const int f = wave * KPW + x, fkb = f / KST, fs = f % KST;
+                const unsigned off = (unsigned)min(32 * fkb + n32, p.n - 1 - j0) * rowb + k_col + 32 * fs;
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(k_dst0 + slot * KBUF + x * FRAG), 16, 0, 0);
             }
         }
     };
-    // register -> LDS: K pieces into fragment (kb, s = kc/2), slot (row % 32) + 32*(kc % 2); V pieces
-    // transposed (4 tokens x 8 dims -> 8 dims x 4 tokens) into fragment (db, ks), slot (dim % 32) + 32*vj.
-    // (the XOR only touches the low 3 slot bits, which the +16-row and +dim steps below leave alone)
-    const int kw_base = (kc >> 1) * KSTRIDE + 16 * ((kr0 + 32 * (kc & 1)) ^ (((kc >> 1) & 3) | ((kc & 1) << 2)));
-    const int vw_x = (kc & 3) | ((vj ^ ((kc >> 2) & 1)) << 2);   // XOR term of this thread's V^T slots
-    const int vw_base = KBUF + ((kc >> 2) * NPS + vku) * VSTRIDE + 16 * (8 * (kc & 3) + 32 * vj) + 8 * vhalf;
-    auto store_tile = [&](int buf) {
-        char *base = lds + buf * BUF;
+    auto request_v = [&](int kt, int slot) {
+        const int j0 = kt * kBN;
+        const gbyte_ptr base = (gbyte_ptr)p.v + (size_t)j0 * rowb;
+        if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
-        for (int it = 0; it < KIT; ++it) {
-            const int kbk = (RS * it) >> 5, radd = (RS * it) & 31;  // key block, row offset inside it (0 or 16)
-            *(u32x4 *)(base + kw_base + kbk * KST * KSTRIDE + 16 * radd) = kreg[it];
-        }
-        if (vact) {
+            for (int x = 0; x < VPW; ++x)
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + v_off[x]), (lvoid_ptr)(v_dst0 + slot * VBUF + x * (VRI * D * 2)), 16, 0, 0);
+        } else {
+            asm volatile("" ::: "memory");
 #pragma unroll
-            for (int dlt = 0; dlt < 8; ++dlt) {
-                const unsigned sel = (dlt & 1) ? 0x07060302u : 0x05040100u;
-                u32x2 pk;
-                pk.x = __builtin_amdgcn_perm(vreg[1][dlt >> 1], vreg[0][dlt >> 1], sel);
-                pk.y = __builtin_amdgcn_perm(vreg[3][dlt >> 1], vreg[2][dlt >> 1], sel);
-                *(u32x2 *)(base + vw_base + 16 * (dlt ^ vw_x)) = pk;
+            for (int x = 0; x < VPW; ++x) {
+                const unsigned off = (unsigned)min(16 * wave + VRI * x + v_r, p.n - 1 - j0) * rowb + v_col;
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(v_dst0 + slot * VBUF + x * (VRI * D * 2)), 16, 0, 0);
             }
         }
     };
+    // read offsets: K fragment lane slot; V^T transpose-read source row/piece of this lane
+    const int k_rd = 16 * lane;
+    const int v_s = lane & 15;
+    // row 4 jj + s/4 of the 16-token k-step (+8 for the second read), dims 16 ((lane/16) & 1) + 4 (s % 4) of the
+    // 32-dim block db; the piece index is XORed with 4 (row % 4) = 4 (s / 4), the dim block enters as XOR 64 db
+    const int v_rd0 = (4 * jj + (v_s >> 2)) * (D * 2) + ((64 * (v_s >> 2)) & (16 * VSWZ)) + 32 * ((lane >> 4) & 1) + 8 * (v_s & 3);
+    int v_rd[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) v_rd[db] = v_rd0 ^ (64 * db);
 
-    // ---- query operand of the current phase: lane (row n32, jj) holds dims 16s + 8jj .. +7
-    bf16x8 qf[NQ][KST];
+    bf16x8 qf[KST];
+    const int qrow = min(irow, p.n - 1);
     auto load_q = [&](const pod_bf16 *src) {
+        const gvec_ptr qr = (gvec_ptr)(src + ((size_t)qrow * p.Hq + head) * D);
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            const int row = min(iw0 + 32 * nq + n32, p.n - 1);
-            const gvec_ptr qr = (gvec_ptr)(src + ((size_t)row * p.Hq + head) * D);
-#pragma unroll
-            for (int s = 0; s < KST; ++s) qf[nq][s] = as_bf16x8(qr[2 * s + jj]);
-        }
+        for (int s = 0; s < KST; ++s) qf[s] = as_bf16x8(qr[2 * s + jj]);
     };
 
-    f32x16 oacc[NQ][NDB];
-    float m_ref[NQ], l_run[NQ]; // l_run: this lane's keys only; the two lanes of a row are added at the end
+    // -infinity on the logits of key block kb of tile (kt, phase) that are not this phase's to count
+    auto mask_block = [&](int kt, bool phaseD, int kb, f32x16 &sc) {
+        const int j0 = kt * kBN;
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        m_ref[nq] = kNegBig; l_run[nq] = 0.f;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[nq][db][r] = 0.f;
-    }
-
-    if (T > 0) {
-        load_tile(0);
-        load_q(nD > 0 ? p.qs : p.q);
-        store_tile(0);
-        if (T > 1) load_tile(1); // stays in registers while tile 0 is processed
-    }
-    __syncthreads();
-
-    for (int t = 0; t < T; ++t) {
-        const int buf = t & 1;
-        int kt; bool phaseD;
-        tile_of(t, kt, phaseD);
-        if (t == nD && nD > 0) load_q(p.q); // phase switch: own queries from here on
-
-        const int j0 = kt * kBN, j1 = j0 + kBN - 1;
-        // does this wave have anything in the tile, and is every (row, key) pair of it valid?
-        bool any, full;
-        if (phaseD) {
-            any = j0 <= iw_last - W && j1 >= S;
-            full = j0 >= S && j1 <= iw0 - W;
-        } else if (has_shared) {
-            any = j0 <= iw_last && (j0 < S || j1 > iw0 - W);
-            full = j1 <= iw0 && (j1 < S || j0 > iw_last - W);
-        } else {
-            any = j0 <= iw_last;
-            full = j1 <= iw0;
+        for (int r = 0; r < 16; ++r) {
+            const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
+            const bool okD = (j >= S) & (j <= irow - W);
+            const bool okP = (j <= irow) & ((!has_shared) | (j < S) | (j > irow - W));
+            const bool ok = phaseD ? okD : okP;
+            sc[r] = ok ? sc[r] : -__builtin_inff();
         }
-        // The arithmetic of one tile, compiled twice: FULL = every (row, key) pair of the wave is
-        // valid (no mask arithmetic at all) and the general case with the per-element predicate.
-        auto tile_body = [&](auto full_tag) {
-            constexpr bool FULL = decltype(full_tag)::value;
-            const char *lbuf = lds + buf * BUF;
-            // ---- S^T = K Q^T
-            f32x16 sc[NQ][NKB];
+    };
+    auto mask_tile = [&](int kt, bool phaseD, f32x16 (&sc)[NKB]) {
+        const int j0 = kt * kBN, j1 = j0 + kBN - 1;
+        bool full; // every (row, key) pair of the wave counts: no masking needed
+        if (phaseD) full = j0 >= S && j1 <= iw0 - W;
+        else if (has_shared) full = j1 <= iw0 && (j1 < S || j0 > iw_last - W);
+        else full = j1 <= iw0;
+        if (full && iw0 <= iw_last) return;
 #pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
+        for (int kb = 0; kb < NKB; ++kb) mask_block(kt, phaseD, kb, sc[kb]);
+    };
+
+    f32x16 oacc[NDB];
 #pragma unroll
-                for (int kb = 0; kb < NKB; ++kb)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) sc[nq][kb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+    float m_ref = kNegBig, l_run = 0.f;
+
+    auto kfrag = [&](const char *kl, int op) { // QK MFMA number op: the two key blocks alternate
+        const int s = op / NKB, kb = op % NKB;
+        return *(const u32x4 *)(kl + (kb * KST + s) * FRAG + k_rd);
+    };
+    auto vfrag = [&](const char *vl, int m) {  // PV MFMA number m = ks * NDB + db
+        const int ks = m / NDB, db = m % NDB;
+        const lbyte_ptr a = (lbyte_ptr)(vl + ks * 16 * (D * 2)) + v_rd[db];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ltr_ptr)a);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ltr_ptr)(a + 8 * (D * 2)));
+        u32x4 r;
+        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        r.x = l2.x; r.y = l2.y; r.z = h2.x; r.w = h2.y;
+        return r;
+    };
+
+    f32x16 sA[NKB], sB[NKB];
+    u32x4 pA[NPS], pB[NPS];
+    float mx_next; // scaled row maximum of the tile the next iteration exponentiates
+
+    // ---- prologue: K(0), K(1) in LDS, S(0) and its row maximum computed
+    // tiles t, t+1, t+2 of the current iteration (key tile index, phase); shifted along at its end
+    int kt_a, kt_b, kt_c;
+    bool ph_a, ph_b, ph_c;
+    tile_of(0, kt_a, ph_a);
+    tile_of(1, kt_b, ph_b);
+    tile_of(2, kt_c, ph_c);
+    request_k(kt_a, ph_a, 0);
+    if (T > 1) request_k(kt_b, ph_b, 1);
+    load_q(nD > 0 ? p.qs : p.q);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    {
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
+        for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-                for (int s = 0; s < KST; ++s) {
-                    const u32x4 a = *(const u32x4 *)(lbuf + (kb * KST + s) * KSTRIDE + kroff[s & 3]);
+            for (int r = 0; r < 16; ++r) sA[kb][r] = 0.f;
 #pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq)
-                        sc[nq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qf[nq][s], sc[nq][kb], 0, 0, 0);
-                }
-            // ---- softmax per row block
-            u32x4 pw[NQ][NPS];
+        for (int op = 0; op < NQK; ++op) {
+            const int s = op / NKB, kb = op % NKB;
+            sA[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kfrag(ldsK, op)), qf[s], sA[kb], 0, 0, 0);
+        }
+        mask_tile(kt_a, ph_a, sA);
+        float mx = -__builtin_inff();
 #pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                const int i = iw0 + 32 * nq + n32;
-                float mx = kNegBig;
-                if constexpr (FULL) {
+        for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
-                    for (int kb = 0; kb < NKB; ++kb)
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sA[kb][r]);
+        mx_next = pair_max(mx) * c;
+    }
+    __syncthreads(); // every wave is done reading K(0): iteration 0 overwrites its slot
+
+    // one iteration: FIRST has no PV slots (there is no earlier tile)
+    auto iteration = [&](auto first_tag, auto slot_tag, int t, f32x16 (&sc)[NKB], f32x16 (&sn)[NKB], const u32x4 (&pprev)[NPS], u32x4 (&pcur)[NPS]) {
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr int slot = decltype(slot_tag)::value; // = t % 2: every LDS address below is a compile-time offset
+        // K(t+2) replaces K(t) and V(t) replaces V(t-2), both last read before the previous barrier.
+        // (Spreading the requests over the slots instead of issuing them here measured 10 % slower.)
+        if (t + 2 < T) request_k(kt_c, ph_c, slot);
+        request_v(kt_a, slot);
+        if (mx_next > m_ref + kLazy) { // (rows with nothing valid so far have mx = -inf and never trigger)
+            const float alpha = __builtin_amdgcn_exp2f(m_ref - mx_next);
+            l_run *= alpha;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[nq][kb][r]);
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m_ref = mx_next;
+        }
+        if (t + 1 == nD) load_q(p.q); // the next tile is the first of the own-key phase
+        const float mr = m_ref;
+        float ps = 0.f;
+        const char *kl = ldsK + (slot ^ 1) * KBUF;   // K(t+1)
+        const char *vl = ldsV + (slot ^ 1) * VBUF;   // V(t-1)
+        // slot list: entry >= 0 is QK MFMA number entry, entry < 0 is PV MFMA number -1 - entry
+        constexpr int NS = FIRST ? NQK : NQK + NPV;
+        constexpr int NMIX = FIRST ? NQK : NQK + NQK / 2; // slots of the QK, QK, PV mix
+        auto slot_op = [](int i) constexpr { return FIRST ? i : (i < NMIX ? ((i % 3 == 2) ? -1 - i / 3 : i - i / 3) : -1 - (i - NQK)); };
+        auto frag = [&](int i) { const int op = slot_op(i); return op >= 0 ? kfrag(kl, op) : vfrag(vl, -1 - op); };
+        u32x4 fr[NS];
+        float tt[16][2], ee[16][2]; // staged softmax values (each lives for one slot)
+        float mxv[4] = {-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff()};
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kPF && i < NS; ++i) fr[i] = frag(i);
+        static_for<NS>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (!FIRST && i == NMIX) {
+                mask_tile(kt_b, ph_b, sn); // boundary tiles only; S(t+1) is complete here
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (i + kPF < NS) fr[i + kPF] = frag(i + kPF);
+            constexpr int op = slot_op(i);
+            if constexpr (op >= 0) {
+                constexpr int s = op / NKB, kb = op % NKB;
+                if constexpr (s == 0) {
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                    sn[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[i]), qf[s], z, 0, 0, 0);
                 } else {
-#pragma unroll
-                    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * jj + (r & 3);
-                            // branch-free predicate (bitwise on purpose: no short-circuit control flow)
-                            const bool okD = (j >= S) & (j <= i - W);
-                            const bool okP = (j <= i) & ((!has_shared) | (j < S) | (j > i - W));
-                            const bool ok = phaseD ? okD : okP;
-                            sc[nq][kb][r] = ok ? sc[nq][kb][r] : kNegBig;
-                            mx = fmaxf(mx, sc[nq][kb][r]);
+                    sn[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[i]), qf[s], sn[kb], 0, 0, 0);
+                }
+            } else {
+                constexpr int m = -1 - op, ks = m / NDB, db = m % NDB;
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fr[i]), as_bf16x8(pprev[ks]), oacc[db], 0, 0, 0);
+            }
+            if constexpr (i < NMIX) {
+                // this slot's share of the 16 logit pairs of tile t.  A pair takes three steps (scale and
+                // shift; exponentials; pack and row sum) in three different slots, so that no
+                // instruction of a slot waits for another one of the same slot.
+                constexpr int v_lo = (i * 18 + NMIX - 1) / NMIX; // first step v with v * NMIX / 18 == i, if any
+                static_for<(18 + NMIX - 1) / NMIX + 1>([&](auto dvc) {
+                    constexpr int v = v_lo + decltype(dvc)::value;
+                    if constexpr (v < 18 && v * NMIX / 18 == i) {
+                        if constexpr (v >= 2) {
+                            constexpr int q = v - 2;
+                            unsigned pk = pack_bf16(ee[q][0], ee[q][1]);
+                            ps = dot2_ones(pk, ps);
+                            // an empty asm statement is a use the compiler cannot move: without it, work whose
+                            // consumer sits in a later basic block is sunk out of the slot it was placed in
+                            asm volatile("" : "+v"(pk), "+v"(ps));
+                            pcur[q >> 2][q & 3] = pk;
                         }
-                }
-                mx = pair_max(mx) * p.scale_log2e; // scale > 0: max and scaling commute
-                if (mx > m_ref[nq] + kLazy) {      // (masked rows have mx = -inf-like and never trigger)
-                    const float m_new = mx;
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref[nq] - m_new);
-                    l_run[nq] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[nq][db][r] *= alpha;
-                    m_ref[nq] = m_new;
-                }
-                const float mr = m_ref[nq];
-                float ps = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float e = __builtin_amdgcn_exp2f(fmaf(sc[nq][kb][r], p.scale_log2e, -mr)); // raw v_exp_f32: tiny results flush to 0
-                        if constexpr (!FULL) e = sc[nq][kb][r] <= kNegBig ? 0.f : e;
-                        sc[nq][kb][r] = e;
-                        ps += e;
+                        if constexpr (v >= 1 && v <= 16) {
+                            constexpr int q = v - 1;
+                            float e0 = __builtin_amdgcn_exp2f(tt[q][0]), e1 = __builtin_amdgcn_exp2f(tt[q][1]);
+                            asm volatile("" : "+v"(e0), "+v"(e1));
+                            ee[q][0] = e0; ee[q][1] = e1;
+                        }
+                        if constexpr (v <= 15) {
+                            constexpr int q = v;
+                            float t0 = fmaf(sc[q >> 3][(2 * q) & 15], c, -mr), t1 = fmaf(sc[q >> 3][((2 * q) & 15) + 1], c, -mr);
+                            asm volatile("" : "+v"(t0), "+v"(t1));
+                            tt[q][0] = t0; tt[q][1] = t1;
+                        }
                     }
-                l_run[nq] += ps;
+                });
+            } else {
+                // last quarter: row maximum of S(t+1)
+                constexpr int NL = NS - NMIX, j = i - NMIX;
+                constexpr int XPS = NKB * 16 / (NL > 0 ? NL : 1); // logits per slot (FIRST has no such slots)
+                static_assert(NL == 0 || (XPS * NL == NKB * 16 && XPS % 2 == 0), "");
 #pragma unroll
-                for (int ks = 0; ks < NPS; ++ks) {
-                    const int kb = ks >> 1, u = ks & 1;
-                    pw[nq][ks].x = pack_bf16(sc[nq][kb][8 * u + 0], sc[nq][kb][8 * u + 1]);
-                    pw[nq][ks].y = pack_bf16(sc[nq][kb][8 * u + 2], sc[nq][kb][8 * u + 3]);
-                    pw[nq][ks].z = pack_bf16(sc[nq][kb][8 * u + 4], sc[nq][kb][8 * u + 5]);
-                    pw[nq][ks].w = pack_bf16(sc[nq][kb][8 * u + 6], sc[nq][kb][8 * u + 7]);
+                for (int x = j * XPS; x < (j + 1) * XPS; x += 2) {
+                    float mm = __builtin_fmaxf(__builtin_fmaxf(mxv[(x >> 1) & 3], sn[x >> 4][x & 15]), sn[x >> 4][(x & 15) + 1]);
+                    asm volatile("" : "+v"(mm));
+                    mxv[(x >> 1) & 3] = mm;
                 }
             }
-            // ---- O^T += V^T P
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (FIRST) { // no last quarter: the same housekeeping without MFMAs in between
+            mask_tile(kt_b, ph_b, sn);
 #pragma unroll
-            for (int ks = 0; ks < NPS; ++ks)
-#pragma unroll
-                for (int db = 0; db < NDB; ++db) {
-                    const u32x4 a = *(const u32x4 *)(lbuf + KBUF + (db * NPS + ks) * VSTRIDE + vroff[db & 1]);
-#pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq)
-                        oacc[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pw[nq][ks]), oacc[nq][db], 0, 0, 0);
-                }
-        };
-        if (any && iw0 <= iw_last) {
-            if (full) tile_body(std::true_type{});
-            else tile_body(std::false_type{});
+            for (int x = 0; x < NKB * 16; ++x) mxv[x & 3] = fmaxf(mxv[x & 3], sn[x >> 4][x & 15]);
         }
-        // tile t+1 (loaded one iteration ago) goes to the other buffer; the loads of tile t+2 leave
-        // before the barrier so that the wait at the barrier already overlaps their latency
-        if (t + 1 < T) store_tile(buf ^ 1);
-        if (t + 2 < T) load_tile(t + 2);
+        mx_next = pair_max(fmaxf(fmaxf(mxv[0], mxv[1]), fmaxf(mxv[2], mxv[3]))) * c;
+        l_run += ps;
+        kt_a = kt_b; ph_a = ph_b; kt_b = kt_c; ph_b = ph_c;
+        tile_of(t + 3, kt_c, ph_c);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's K(t+2), V(t) pieces are in LDS
         __syncthreads();
+    };
+
+
+    typedef std::integral_constant<int, 0> slot0;
+    typedef std::integral_constant<int, 1> slot1;
+    iteration(std::true_type{}, slot0{}, 0, sA, sB, pB, pA);
+    for (int t = 1; t < T; t += 2) {
+        iteration(std::false_type{}, slot1{}, t, sB, sA, pA, pB);
+        if (t + 1 < T) iteration(std::false_type{}, slot0{}, t + 1, sA, sB, pB, pA);
+    }
+    // ---- epilogue: O += V(T-1)^T P(T-1)
+    {
+        const char *vl = ldsV + ((T - 1) & 1) * VBUF;
+        auto pv = [&](const u32x4 (&pw)[NPS]) {
+#pragma unroll
+            for (int m = 0; m < NPV; ++m)
+                oacc[m % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vfrag(vl, m)), as_bf16x8(pw[m / NDB]), oacc[m % NDB], 0, 0, 0);
+        };
+        if ((T - 1) & 1) pv(pB);
+        else pv(pA);
     }
 
-    // ---- normalise and store: lane (row n32, jj) holds dims 32db + 8a + 4jj + {0..3}
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        const int i = iw0 + 32 * nq + n32;
-        const float l = pair_sum(l_run[nq]);
-        if (i >= p.n) continue;
+    const float l = pair_sum(l_run);
+    if (irow < p.n) {
         const float inv = 1.f / l;
-        pod_bf16 *orow = p.out + ((size_t)i * p.Hq + head) * D;
+        pod_bf16 *orow = p.out + ((size_t)irow * p.Hq + head) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 u32x2 o;
-                o.x = pack_bf16(oacc[nq][db][4 * a + 0] * inv, oacc[nq][db][4 * a + 1] * inv);
-                o.y = pack_bf16(oacc[nq][db][4 * a + 2] * inv, oacc[nq][db][4 * a + 3] * inv);
+                o.x = pack_bf16(oacc[db][4 * a + 0] * inv, oacc[db][4 * a + 1] * inv);
+                o.y = pack_bf16(oacc[db][4 * a + 2] * inv, oacc[db][4 * a + 3] * inv);
                 *(u32x2 *)(orow + 32 * db + 8 * a + 4 * jj) = o;
             }
     }
@@ -404,21 +507,19 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
-    constexpr int NQ = 1;
-    const int BM = 128 * NQ;
-    const dim3 grid((unsigned)((n + BM - 1) / BM) * (unsigned)ly.Hq);
-    // dynamic LDS: 2 buffers x (key fragments + V^T fragments), see the kernel
-    const auto lds_bytes = [](int D) { return 2 * ((kBN / 32) * (D / 16) + (D / 32) * (kBN / 16)) * 1024; };
-    static bool attr_done = false; // raising the limit past 64 KB is needed once per process
+    const dim3 grid((unsigned)((n + 127) / 128) * (unsigned)ly.Hq);
+    // dynamic LDS: two K slots and two V slots of kBN tokens x D bf16 each (64 KB at D = 128)
+    const auto lds_bytes = [](int D) { return 4 * kBN * D * 2; };
+    static bool attr_done = false; // raising the limit to 64 KB is needed once per process
     if (!attr_done) {
-        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128, NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64, NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
+        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
         attr_done = true;
     }
     if (ly.D == 128)
-        hipLaunchKernelGGL((prefill_kernel<128, NQ>), grid, dim3(256), lds_bytes(128), st, p);
+        hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(256), lds_bytes(128), st, p);
     else
-        hipLaunchKernelGGL((prefill_kernel<64, NQ>), grid, dim3(256), lds_bytes(64), st, p);
+        hipLaunchKernelGGL((prefill_kernel<64>), grid, dim3(256), lds_bytes(64), st, p);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }
