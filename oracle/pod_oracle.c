@@ -471,6 +471,92 @@ int oracle_decode_attention(pod_oracle_cache *c, int layer, int Hq, double scale
     return ORACLE_OK;
 }
 
+/*
+ * Decode attention with the gated skip of distant tokens (appendix "Computation
+ * Optimization for Distant Tokens").  At a layer that is not the lowest of its
+ * block the gate of Eq. 4 is evaluated first,
+ *     g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)),
+ * and if g >= tau the attention over distant tokens is left out: the output is
+ * o^P, the softmax over the proximal tokens alone (Eq. 3 lines 1-2).  Otherwise,
+ * and always at the lowest layer or without distant tokens, the output is the
+ * exact one, g o^P + (1 - g) o^D.  gate_out[Bcur][Hq] receives g (1 without
+ * distant tokens), skipped_out[Bcur][Hq] 1 where the distant part was left out.
+ * Same arguments and checks as oracle_decode_attention.
+ */
+int oracle_decode_attention_gated(pod_oracle_cache *c, int layer, int Hq, double scale,
+                                  const uint16_t *q, const uint16_t *q_shared, const int32_t *ctx_lens,
+                                  int Bcur, double tau, double *out, double *gate_out, int32_t *skipped_out)
+{
+    if (!c || layer < 0 || layer >= c->L || Bcur < 1 || Bcur > c->B || Hq < 1 || Hq % c->Hkv) return ORACLE_ERR_ARG;
+    if (!(tau >= 0.0 && tau <= 1.0)) return ORACLE_ERR_ARG;
+    const int lowest_layer = layer - layer % c->G;
+    const int rep = Hq / c->Hkv, d = c->d;
+    const size_t re = row_elems(c);
+    for (int b = 0; b < Bcur; ++b) {
+        seq_state *s = seq_of(c, layer, b);
+        seq_state *sa = seq_of(c, lowest_layer, b);
+        if (ctx_lens[b] < 1 || ctx_lens[b] != s->n) return ORACLE_ERR_STATE;
+        if (s->n_dist > 0 && sa->n_dist != s->n_dist) return ORACLE_ERR_STATE;
+        if (s->n_dist > 0 && layer != lowest_layer && !q_shared) return ORACLE_ERR_ARG;
+    }
+    const long work = (long)Bcur * Hq;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long w = 0; w < work; ++w) {
+        const int b = (int)(w / Hq), h = (int)(w % Hq), kv = h / rep;
+        seq_state *s = seq_of(c, layer, b);
+        seq_state *sa = seq_of(c, lowest_layer, b);
+        const long n_sink = s->n < c->S ? s->n : c->S;
+        const long nP = n_sink + s->n_recent, nD = s->n_dist;
+        double *aP = (double *)malloc((size_t)(nP > 0 ? nP : 1) * sizeof(double));
+        double *aD = (double *)malloc((size_t)(nD > 0 ? nD : 1) * sizeof(double));
+        const uint16_t *qi = q + ((size_t)b * Hq + h) * d;
+        const uint16_t *qs = (layer == lowest_layer || !q_shared) ? qi : q_shared + ((size_t)b * Hq + h) * d;
+        double *oP = (double *)calloc((size_t)d, sizeof(double));
+        double *oD = (double *)calloc((size_t)d, sizeof(double));
+        /* a^P: this layer's query against its own sink and recent keys */
+        double maxP = -INFINITY, maxD = -INFINITY;
+        for (long t = 0; t < nP; ++t) {
+            const uint16_t *krow = t < n_sink ? s->sinkK + (size_t)t * re : s->recK + (size_t)(t - n_sink) * re;
+            aP[t] = scale * dot_bf16(qi, krow + (size_t)kv * d, d);
+            if (aP[t] > maxP) maxP = aP[t];
+        }
+        /* a^D: the lowest layer's query against the block's stored distant keys */
+        for (long t = 0; t < nD; ++t) {
+            aD[t] = scale * dot_bf16(qs, sa->distK + (size_t)t * re + (size_t)kv * d, d);
+            if (aD[t] > maxD) maxD = aD[t];
+        }
+        double sumP = 0.0, sumD = 0.0;
+        for (long t = 0; t < nP; ++t) {
+            const uint16_t *vrow = t < n_sink ? s->sinkV + (size_t)t * re : s->recV + (size_t)(t - n_sink) * re;
+            const double e = exp(aP[t] - maxP);
+            sumP += e;
+            for (int x = 0; x < d; ++x) oP[x] += e * bf16_to_double(vrow[(size_t)kv * d + x]);
+        }
+        for (int x = 0; x < d; ++x) oP[x] /= sumP;
+        double g = 1.0;
+        if (nD > 0) {
+            for (long t = 0; t < nD; ++t) sumD += exp(aD[t] - maxD);
+            g = 1.0 / (1.0 + (sumD / sumP) * exp(maxD - maxP));
+        }
+        const int skip = nD > 0 && layer != lowest_layer && g >= tau;
+        double *o = out + ((size_t)b * Hq + h) * d;
+        if (nD == 0 || skip) {
+            for (int x = 0; x < d; ++x) o[x] = oP[x];
+        } else {
+            for (long t = 0; t < nD; ++t) {
+                const double e = exp(aD[t] - maxD);
+                const uint16_t *vrow = s->distV + (size_t)t * re + (size_t)kv * d;
+                for (int x = 0; x < d; ++x) oD[x] += e * bf16_to_double(vrow[x]);
+            }
+            for (int x = 0; x < d; ++x) o[x] = g * oP[x] + (1.0 - g) * (oD[x] / sumD);
+        }
+        if (gate_out) gate_out[(size_t)b * Hq + h] = g;
+        if (skipped_out) skipped_out[(size_t)b * Hq + h] = skip;
+        free(aP); free(aD); free(oP); free(oD);
+    }
+    return ORACLE_OK;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

@@ -48,6 +48,9 @@ def lib():
         L.oracle_decode_attention.restype = C.c_int
         L.oracle_decode_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, u16p, u16p,
                                               i32p, C.c_int, f64p]
+        L.oracle_decode_attention_gated.restype = C.c_int
+        L.oracle_decode_attention_gated.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, u16p, u16p,
+                                                    i32p, C.c_int, C.c_double, f64p, f64p, i32p]
         L.oracle_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -163,3 +166,18 @@ class Cache:
                                            out.ctypes.data_as(C.POINTER(C.c_double)))
         _chk(rc, "oracle_decode_attention")
         return out
+
+    def decode_attention_gated(self, layer, q, q_shared, ctx_lens, scale, tau):
+        """Decode attention with the gated skip of distant tokens; returns (out, g, skipped)."""
+        B, Hq, d = q.shape
+        ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        out = np.empty((B, Hq, d), dtype=np.float64)
+        g = np.empty((B, Hq), dtype=np.float64)
+        skipped = np.empty((B, Hq), dtype=np.int32)
+        rc = lib().oracle_decode_attention_gated(self._h, layer, Hq, float(scale), _u16(q), _u16(q_shared),
+                                                 ctx_lens.ctypes.data_as(C.POINTER(C.c_int32)), B, float(tau),
+                                                 out.ctypes.data_as(C.POINTER(C.c_double)),
+                                                 g.ctypes.data_as(C.POINTER(C.c_double)),
+                                                 skipped.ctypes.data_as(C.POINTER(C.c_int32)))
+        _chk(rc, "oracle_decode_attention_gated")
+        return out, g, skipped

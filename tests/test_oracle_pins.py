@@ -384,3 +384,88 @@ def test_decode_from_cache_equals_definition(layer, n):
     ref = po.pod_attention(q, bits(ks[layer]), bits(vs[layer]), qa if layer else None,
                            bits(ks[0]) if layer else None, [i], S, W, 0.35)
     np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- gated skip of distant tokens (appendix)
+
+def _gated_case(n, scale=0.35, boost=None):
+    """Two-layer block filled to n tokens; returns the cache model and the per-layer tensors."""
+    L, G, Hq, Hkv, d, S, W = 2, 2, 4, 2, 8, 4, 8
+    c = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    ks, vs, qs = {}, {}, {}
+    for l in range(L):
+        qs[l], ks[l], vs[l] = rand_qkv(71, n, Hq, Hkv, d, layer=l)
+        if boost is not None:  # make the proximal keys of the upper layer dominate for head pairs of kv head 0
+            ks[l] = ks[l].clone()
+            ks[l][:, 0] *= boost
+        c.fill(l, 0, bits(ks[l]), bits(vs[l]))
+    return c, qs, ks, vs, (L, G, Hq, Hkv, d, S, W)
+
+
+def test_gated_tau_one_is_exact_and_gate_matches_definition_form():
+    n = 37
+    c, qs, ks, vs, (L, G, Hq, Hkv, d, S, W) = _gated_case(n)
+    i = n - 1
+    q, qa = bits(qs[1][i:i + 1]), bits(qs[0][i:i + 1])
+    out, g, skipped = c.decode_attention_gated(1, q, qa, [n], 0.35, 1.0)
+    ref, g_ref = po.pod_attention(q, bits(ks[1]), bits(vs[1]), qa, bits(ks[0]), [i], S, W, 0.35, gate=True)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)     # tau = 1 never skips (g < 1 with distant tokens)
+    np.testing.assert_allclose(g, g_ref, rtol=1e-12)              # the gate of Eq. 4, from the full-tensor form
+    assert not skipped.any()
+
+
+def test_gated_tau_zero_is_attention_over_proximal_tokens_only():
+    """g >= 0 always: every upper-layer head leaves the distant part out, and what remains is textbook
+    softmax attention over the sink and recent tokens (checked with the library routine on those rows)."""
+    n = 37
+    c, qs, ks, vs, (L, G, Hq, Hkv, d, S, W) = _gated_case(n)
+    i = n - 1
+    q, qa = bits(qs[1][i:i + 1]), bits(qs[0][i:i + 1])
+    out, g, skipped = c.decode_attention_gated(1, q, qa, [n], 0.35, 0.0)
+    assert skipped.all()
+    prox = list(range(S)) + list(range(n - W, n))
+    kp, vp = ks[1][prox], vs[1][prox]
+    qq = qs[1][i:i + 1].double().permute(1, 0, 2)[None]
+    kk = kp.double().repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)[None]
+    vv = vp.double().repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(qq, kk, vv, scale=0.35)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+
+
+def test_gated_lowest_layer_and_short_contexts_never_skip():
+    n = 37
+    c, qs, ks, vs, (L, G, Hq, Hkv, d, S, W) = _gated_case(n)
+    q0 = bits(qs[0][n - 1:n])
+    out, g, skipped = c.decode_attention_gated(0, q0, None, [n], 0.35, 0.0)
+    np.testing.assert_allclose(out, c.decode_attention(0, q0, None, [n], 0.35), rtol=0, atol=1e-13)
+    assert not skipped.any()
+    n2 = 10                                                       # S + W = 12 > n: no distant tokens
+    c2, qs2, ks2, vs2, _ = _gated_case(n2)
+    q, qa = bits(qs2[1][n2 - 1:n2]), bits(qs2[0][n2 - 1:n2])
+    out2, g2, skipped2 = c2.decode_attention_gated(1, q, qa, [n2], 0.35, 0.0)
+    assert (g2 == 1.0).all() and not skipped2.any()
+    np.testing.assert_allclose(out2, c2.decode_attention(1, q, qa, [n2], 0.35), rtol=0, atol=1e-13)
+
+
+def test_gated_threshold_splits_heads_by_their_gate():
+    """With a threshold between the heads' gates exactly the heads at or above it skip; a skipped head
+    returns o^P, the others the exact output; the error of a skipped head is (1 - g) |o^P - o^D|."""
+    n = 37
+    c, qs, ks, vs, (L, G, Hq, Hkv, d, S, W) = _gated_case(n, boost=3.0)
+    i = n - 1
+    q, qa = bits(qs[1][i:i + 1]), bits(qs[0][i:i + 1])
+    exact, g, _ = c.decode_attention_gated(1, q, qa, [n], 0.35, 1.0)
+    gs = np.sort(g.ravel())
+    assert gs[-1] - gs[0] > 0.05                                  # the case has spread
+    tau = float((gs[1] + gs[2]) / 2)
+    out, g2, skipped = c.decode_attention_gated(1, q, qa, [n], 0.35, tau)
+    np.testing.assert_array_equal(g2, g)
+    np.testing.assert_array_equal(skipped.astype(bool), g >= tau)
+    assert skipped.sum() == 2
+    prox_only, _, _ = c.decode_attention_gated(1, q, qa, [n], 0.35, 0.0)
+    for h in range(Hq):
+        want = prox_only[0, h] if skipped[0, h] else exact[0, h]
+        np.testing.assert_allclose(out[0, h], want, rtol=0, atol=1e-13)
+        if skipped[0, h]:                                         # o = g oP + (1-g) oD  =>  oP - o = (1-g)(oP - oD)
+            oD = (exact[0, h] - g[0, h] * prox_only[0, h]) / (1 - g[0, h])
+            np.testing.assert_allclose(out[0, h] - exact[0, h], (1 - g[0, h]) * (prox_only[0, h] - oD), atol=1e-12)
