@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--context", type=int, default=32768)
     ap.add_argument("--profile-steps", type=int, default=32)
     ap.add_argument("--reuse-steps", type=int, default=32, help="steps timed through the score-reuse entry point (0 = skip)")
+    ap.add_argument("--gate-rounds", type=int, default=8, help="rounds over the blocks in the gated-skip section (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of one HIP graph replay")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -225,6 +226,77 @@ def main():
                               "bytes_per_step": step_bytes_reuse(ru[0]),
                               "value": round(rb / el / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
                               "speedup_vs_plain_step": round((elapsed / K) / (el / len(ru)), 3)}
+
+    # ---- gated skip of distant tokens (SURVEY's second "next" row): decode calls only (no appends), the
+    # R blocks round-robin, at the contexts the steps above left behind.  Three timings of the same
+    # (lowest layer, upper layer) pair: plain; gated with the generated inputs (no head's gate reaches
+    # tau = 0.7, so this is the cost of the two-launch structure); gated after the upper layers'
+    # sink and recent keys were scaled x4 (every head's gate reaches 0.7: distant rows are not read).
+    if a.gate_rounds > 0:
+        tau = 0.7
+        lens = [cache.pod_cache_seq_len(G * g, 0) for g in range(R)]
+        qs = [[gen.queries_bf16(seed, G * g + j, 0, 1, Hq, d, device=dev, pos0=lens[g] - 1) for j in range(G)] for g in range(R)]
+        ctxs = [torch.tensor([lens[g]], dtype=torch.int32, device=dev) for g in range(R)]
+        og = torch.empty((1, Hq, d), dtype=torch.bfloat16, device=dev)
+
+        def pair_plain(g):
+            cache.pod_decode_attention(G * g, qs[g][0], None, ctxs[g], scale, out=og, max_context_len=lens[g])
+            cache.pod_decode_attention(G * g + 1, qs[g][1], qs[g][0], ctxs[g], scale, out=og, max_context_len=lens[g])
+
+        def pair_gated(g):
+            cache.pod_decode_attention_gated(G * g, qs[g][0], ctxs[g], scale, tau, scores, out=og, max_context_len=lens[g])
+            cache.pod_decode_attention_gated(G * g + 1, qs[g][1], ctxs[g], scale, tau, scores, out=og, max_context_len=lens[g])
+
+        def time_pairs(fn):
+            skipped = 0
+            for g in range(R):
+                fn(g)
+            torch.cuda.synchronize()
+            gg = None
+            if not a.no_graph:
+                gg = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gg):
+                    for _ in range(a.gate_rounds):
+                        for g in range(R):
+                            fn(g)
+                torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if gg is not None:
+                gg.replay()
+            else:
+                for _ in range(a.gate_rounds):
+                    for g in range(R):
+                        fn(g)
+            torch.cuda.synchronize()
+            el = (time.perf_counter() - t0) / (a.gate_rounds * R)
+            if fn is pair_gated:
+                skipped = int(cache.skip_flags(scores)[0].sum().item())
+            return el, skipped
+
+        t_plain, _ = time_pairs(pair_plain)
+        t_none, sk_none = time_pairs(pair_gated)
+        for g in range(R):   # upper layers again, proximal keys x4 (exact in bf16)
+            layer = G * g + 1
+            n = lens[g]
+            k = gen.keys_bf16(seed, layer, 0, n, Hkv, d, device=dev, **rope)
+            v = gen.values_bf16(seed, layer, 0, n, Hkv, d, device=dev)
+            k[:S] *= 4
+            k[n - W:] *= 4
+            kl = gen.keys_bf16(seed, G * g, 0, n, Hkv, d, device=dev, **rope)
+            vl = gen.values_bf16(seed, G * g, 0, n, Hkv, d, device=dev)
+            if g == 0:
+                cache.pod_cache_reset()
+            cache_fill_pairs = ((G * g, kl, vl), (layer, k, v))
+            for (ll, kk, vv) in cache_fill_pairs:
+                cache.pod_cache_fill(ll, 0, kk, vv)
+            del k, v, kl, vl
+        t_all, sk_all = time_pairs(pair_gated)
+        cache.pod_cache_check()
+        out["tau_gating"] = {"tau": tau, "launch": mode, "unit": "ms per (lowest, upper) decode pair",
+                             "plain": round(t_plain * 1e3, 5),
+                             "gated_nothing_skips": {"ms": round(t_none * 1e3, 5), "heads_skipped": sk_none, "of": Hq},
+                             "gated_all_heads_skip": {"ms": round(t_all * 1e3, 5), "heads_skipped": sk_all, "of": Hq},
+                             "speedup_when_all_skip": round(t_plain / t_all, 3)}
 
     # ---- CPU oracle on the host cores, a bounded sample of the same steps (block 0's)
     if not a.no_cpu:

@@ -182,6 +182,25 @@ int pod_decode_attention_reuse(pod_cache *cache, int layer, const void *q, const
                                void *scores, size_t scores_bytes, void *out, void *stream);
 
 /*
+ * Decode attention with the gated skip of distant tokens (appendix "Computation Optimization for
+ * Distant Tokens").  Built on score reuse: same `scores` buffer and call order.  For the block's
+ * lowest layer the call equals pod_decode_attention_reuse (it also leaves the distant
+ * maximum and sum of every query head in the buffer).  For an upper layer the gate of Eq. 4,
+ *     g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)),
+ * is evaluated per (sequence, query head) once the proximal logits are known; heads with
+ * g >= tau leave the distant tokens out and return o^P, the softmax over their proximal tokens
+ * alone; the distant rows of a kv head are not read at all when all of its query heads skip.
+ *   tau : in [0, 1].  1 never skips (g < 1 whenever distant tokens exist); 0 always skips.
+ * The decision is taken in fp32 from bf16-input logits: a head whose g lies within rounding of
+ * tau may fall on either side.  pod_score_skip_offset gives the byte offset inside `scores` of
+ * the int32 [max_batch][num_q_heads] flags (1 = distant part left out) written by the last upper-layer call.
+ */
+int pod_decode_attention_gated(pod_cache *cache, int layer, const void *q, const int32_t *context_lens, int B,
+                               int max_context_len, float scale, float tau, void *workspace,
+                               size_t workspace_bytes, void *scores, size_t scores_bytes, void *out, void *stream);
+int pod_score_skip_offset(const pod_config *cfg, size_t *offset);
+
+/*
  * Prefill attention for one sequence (Eq. 3 with the window taken at each query's own
  * position: key j is proximal for query i if j < S or j > i - W), causal, joint softmax.
  *   q        : dev bf16 [n][Hq][d];  k, v : dev bf16 [n][Hkv][d] of `layer`

@@ -20,7 +20,7 @@ EXPORTS = [
     "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
-    "pod_score_buffer_bytes", "pod_decode_attention_reuse",
+    "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
 ]
 
 
@@ -69,6 +69,9 @@ def load():
         "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
         "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
         "pod_score_buffer_bytes": [cfgp, szp],
+        "pod_decode_attention_gated": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, C.c_float, vp, C.c_size_t,
+                                       vp, C.c_size_t, vp, vp],
+        "pod_score_skip_offset": [cfgp, szp],
         "pod_decode_attention_reuse": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp,
                                        C.c_size_t, vp, vp],
         "pod_profile_enable": [vp, C.c_int],
@@ -193,6 +196,24 @@ class PodCache:
                                                  scores.data_ptr(), scores.numel() * scores.element_size(),
                                                  _ptr(out, torch.bfloat16), _stream()))
         return out
+
+    def pod_decode_attention_gated(self, layer, q, context_lens, scale, tau, scores, out=None, max_context_len=0):
+        B = q.shape[0]
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_decode_attention_gated(self.handle, layer, _ptr(q, torch.bfloat16),
+                                                 _ptr(context_lens, torch.int32), B, max_context_len, scale, tau,
+                                                 self.workspace.data_ptr(), self.workspace.numel(),
+                                                 scores.data_ptr(), scores.numel() * scores.element_size(),
+                                                 _ptr(out, torch.bfloat16), _stream()))
+        return out
+
+    def skip_flags(self, scores):
+        """View of the int32 [max_batch][num_q_heads] flags the last gated upper-layer call left in `scores`."""
+        off = C.c_size_t()
+        _check(load().pod_score_skip_offset(C.byref(self.cfg), C.byref(off)))
+        nb = self.cfg.max_batch * self.cfg.num_q_heads * 4
+        return scores[off.value:off.value + nb].view(torch.int32).view(self.cfg.max_batch, self.cfg.num_q_heads)
 
     def new_score_buffer(self):
         """Device buffer for pod_decode_attention_reuse (one block's distant logits)."""

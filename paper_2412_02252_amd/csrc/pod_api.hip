@@ -267,14 +267,14 @@ extern "C" int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, 
 
 static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
                          const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
-                         size_t workspace_bytes, void *scores, void *out, void *stream);
+                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream);
 
 extern "C" int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void *q_shared,
                                     const int32_t *context_lens, int B, int max_context_len, float scale,
                                     void *workspace, size_t workspace_bytes, void *out, void *stream)
 {
     return decode_common(cache, layer, q, q_shared, context_lens, B, max_context_len, scale, workspace,
-                         workspace_bytes, nullptr, out, stream);
+                         workspace_bytes, nullptr, -1.f, out, stream);
 }
 
 extern "C" int pod_score_buffer_bytes(const pod_config *cfg, size_t *bytes)
@@ -287,10 +287,42 @@ extern "C" int pod_score_buffer_bytes(const pod_config *cfg, size_t *bytes)
     return POD_OK;
 }
 
+static int decode_with_scores(pod_cache *cache, int layer, const void *q, const int32_t *context_lens, int B,
+                              int max_context_len, float scale, void *workspace, size_t workspace_bytes,
+                              void *scores, size_t scores_bytes, float tau, void *out, void *stream);
+
 extern "C" int pod_decode_attention_reuse(pod_cache *cache, int layer, const void *q, const int32_t *context_lens,
                                           int B, int max_context_len, float scale, void *workspace,
                                           size_t workspace_bytes, void *scores, size_t scores_bytes, void *out,
                                           void *stream)
+{
+    return decode_with_scores(cache, layer, q, context_lens, B, max_context_len, scale, workspace, workspace_bytes,
+                              scores, scores_bytes, -1.f, out, stream);
+}
+
+extern "C" int pod_decode_attention_gated(pod_cache *cache, int layer, const void *q, const int32_t *context_lens,
+                                          int B, int max_context_len, float scale, float tau, void *workspace,
+                                          size_t workspace_bytes, void *scores, size_t scores_bytes, void *out,
+                                          void *stream)
+{
+    if (!(tau >= 0.f && tau <= 1.f)) return pod_fail(POD_ERR_INVALID_ARG, "tau = %g outside [0, 1]", (double)tau);
+    return decode_with_scores(cache, layer, q, context_lens, B, max_context_len, scale, workspace, workspace_bytes,
+                              scores, scores_bytes, tau, out, stream);
+}
+
+extern "C" int pod_score_skip_offset(const pod_config *cfg, size_t *offset)
+{
+    pod_layout ly;
+    if (!offset) return pod_fail(POD_ERR_INVALID_ARG, "offset is NULL");
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    *offset = pod_score_skip_offset_bytes(ly);
+    return POD_OK;
+}
+
+static int decode_with_scores(pod_cache *cache, int layer, const void *q, const int32_t *context_lens, int B,
+                              int max_context_len, float scale, void *workspace, size_t workspace_bytes,
+                              void *scores, size_t scores_bytes, float tau, void *out, void *stream)
 {
     if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
     if (!scores) return pod_fail(POD_ERR_INVALID_ARG, "scores is NULL");
@@ -300,12 +332,12 @@ extern "C" int pod_decode_attention_reuse(pod_cache *cache, int layer, const voi
     if (scores_bytes < need) return pod_fail(POD_ERR_CAPACITY, "score buffer has %zu bytes, needs %zu", scores_bytes, need);
     // upper layers take the distant logits from the buffer: q doubles as the (unused) shared query
     return decode_common(cache, layer, q, q, context_lens, B, max_context_len, scale, workspace, workspace_bytes,
-                         scores, out, stream);
+                         scores, tau, out, stream);
 }
 
 static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
                          const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
-                         size_t workspace_bytes, void *scores, void *out, void *stream)
+                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream)
 {
     int rc = check_cache_layer(cache, layer);
     if (rc) return rc;
@@ -326,7 +358,7 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
     if (max_context_len == 0) max_context_len = (int)longest;
     if (max_context_len == 0) max_context_len = 1;
     return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
-                             workspace, workspace_bytes, scores, out, (hipStream_t)stream);
+                             workspace, workspace_bytes, scores, tau, out, (hipStream_t)stream);
 }
 
 extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, const void *q, const void *k,

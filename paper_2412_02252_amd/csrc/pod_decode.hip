@@ -84,7 +84,11 @@ struct decode_params {
     int32_t *score_hdr;
     int32_t score_stride;
     int32_t block_id;
-    int32_t mode;    // 0 plain, 1 lowest layer writes scores, 2 upper layer reads them
+    int32_t mode;    // 0 plain, 1 lowest layer writes scores, 2 upper layer reads them, 3 upper layer reads them and gates
+    // gated skip of distant tokens (mode 1 writes gate_d, mode 3 uses it): per (sequence, query head)
+    float *gate_d;   // [B][Hq][2]: maximum and sum of the distant exponentials at the lowest layer (base-2 domain)
+    int32_t *skip;   // [B][Hq]: 1 where the upper layer left the distant part out (written by its distant pass)
+    float tau;
     int32_t hlen[kMaxHostLens];
 };
 static_assert(offsetof(decode_params, hot) == 0, "hot lines first");
@@ -142,6 +146,42 @@ __device__ inline unsigned pack_bf16(float lo, float hi)
 // and the scaled logits of distant chunks are also written to p.scores.  MODE 2 (upper layer, score
 // reuse): distant chunks take their logits from p.scores instead of reading the block's distant
 // keys (Eq. 3 line 3 says they ARE the lowest layer's logits), so such a chunk streams V only.
+// Merge of np consecutive (max, sum) partials by one wave: lane l takes entries l, l + 64, ..., then a
+// butterfly over the lanes; lane 0's result is broadcast so that every caller sees the same bits.
+// Products and sums are explicitly rounded (no contraction): the decision derived from them must
+// come out the same wherever it is evaluated.
+__device__ inline float2 merged_ml(const float *ml, int np, int lane)
+{
+    typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+    float m = kNegBig, l = 0.f;
+    for (int v = lane; v < np; v += 64) {
+        const float m2 = ((gfloat_ptr)ml)[2 * v], l2 = ((gfloat_ptr)ml)[2 * v + 1];
+        const float M = fmaxf(m, m2);
+        l = __fadd_rn(__fmul_rn(l, exp2f(m - M)), __fmul_rn(l2, exp2f(m2 - M)));
+        m = M;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
+        const float M = fmaxf(m, m2);
+        l = __fadd_rn(__fmul_rn(l, exp2f(m - M)), __fmul_rn(l2, exp2f(m2 - M)));
+        m = M;
+    }
+    return make_float2(__shfl(m, 0), __shfl(l, 0));
+}
+
+// g >= tau with g = P / (P + Dst), P = lp 2^mp, Dst = ld 2^md  <=>  (1 - tau) lp >= tau ld 2^(md - mp)
+__device__ inline bool gate_skips(float mp, float lp, float md, float ld, float tau)
+{
+    if (!(ld > 0.f)) return false;  // no distant tokens: nothing to leave out
+    return __fmul_rn(1.f - tau, lp) >= __fmul_rn(__fmul_rn(tau, ld), __builtin_amdgcn_exp2f(md - mp));
+}
+
+// MODE 3 and 4 are the two launches of a gated upper layer (appendix "Computation Optimization for Distant
+// Tokens"): MODE 3 walks the proximal chunks only; MODE 4 walks the distant chunks, and each
+// workgroup first evaluates the gate g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)) of Eq. 4 for its
+// query heads from the proximal partials of MODE 3 and the lowest layer's distant sums, records
+// which heads have g >= tau, and leaves if all of its heads do.
 template <int D, int MODE>
 __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_params p)
 {
@@ -152,9 +192,10 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     constexpr int XN = 16 / CPR;      // lanes sharing one V piece (1 for D=128, 2 for D=64)
     constexpr int NPV = 8 / XN;       // PV MFMAs per tile
 
-    const int b = blockIdx.z, h = blockIdx.y, c = blockIdx.x;
+    const int b = blockIdx.z, h = blockIdx.y;
     // The arguments the first loads depend on, in one round trip to the argument block.
     const decode_hot hot = load_hot_args();
+    const int c = MODE == 3 ? (int)blockIdx.x + hot.max_nd : (int)blockIdx.x;
     const int n_host = load_hlen_arg(b);
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
     const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, chunk = hot.chunk, max_nd = hot.max_nd;
@@ -221,7 +262,43 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     }
 
     int t0 = start + wave * kTile;
-    const bool reads_scores = MODE == 2 && distant; // such a chunk needs neither K nor Q
+    const bool reads_scores = (MODE == 2 || MODE == 4) && distant; // such a chunk needs neither K nor Q
+    if constexpr (MODE == 4) {
+        if (!distant) return;
+        // ---- the gate of this workgroup's heads: every wave computes the same values, 16 lanes per
+        // head (four heads at a time), all loads of a pass in flight together
+        typedef const __attribute__((address_space(1))) float *gfloat_ptr;
+        const int np = (n_prox + chunk - 1) / chunk;
+        const int sub = lane & 15, grp = lane >> 4;
+        bool all_skip = true;
+        for (int h0 = 0; h0 < hot.rep; h0 += 4) {
+            const int hh = min(h0 + grp, hot.rep - 1);     // (a group past the last head repeats it)
+            const int head = h * hot.rep + hh;
+            const gfloat_ptr ml = (gfloat_ptr)(hot.part_ml + ((size_t)b * hot.hq + head) * hot.nc * 2 + (size_t)max_nd * 2);
+            const gfloat_ptr gd = (gfloat_ptr)(p.gate_d + ((size_t)b * hot.hq + head) * 2);
+            const float md = gd[0], ld = gd[1];
+            float m = kNegBig, l = 0.f;
+            for (int v = sub; v < np; v += 16) {
+                const float m2 = ml[2 * v], l2 = ml[2 * v + 1];
+                const float M = fmaxf(m, m2);
+                l = __fadd_rn(__fmul_rn(l, __builtin_amdgcn_exp2f(m - M)), __fmul_rn(l2, __builtin_amdgcn_exp2f(m2 - M)));
+                m = M;
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
+                const float M = fmaxf(m, m2);
+                l = __fadd_rn(__fmul_rn(l, __builtin_amdgcn_exp2f(m - M)), __fmul_rn(l2, __builtin_amdgcn_exp2f(m2 - M)));
+                m = M;
+            }
+            m = __shfl(m, lane & 48);                      // the group's first lane decides for all
+            l = __shfl(l, lane & 48);
+            const bool sk = gate_skips(m, l, md, ld, p.tau);
+            all_skip = all_skip && __all(sk);
+            if (c == 0 && wave == 0 && sub == 0 && h0 + grp < hot.rep) p.skip[(size_t)b * hot.hq + head] = sk ? 1 : 0;
+        }
+        if (all_skip) return;
+    }
     if (!reads_scores) { POD_LOAD_TILE(t0) }
 
     // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
@@ -461,9 +538,20 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     auto chunk_slot = [&](int v) { return v < nd ? v : hot.max_nd + (v - nd); };
 
     const int g = threadIdx.x / LPR, x = threadIdx.x % LPR;
+    // gated upper layer: a head whose gate reached tau merges its proximal partials only
+    int v_begin = 0;
+    if (p.mode == 3 && nd > 0 && p.skip[(size_t)b * hot.hq + head] != 0) v_begin = nd;
+    // lowest layer of a score-reuse block: leave the distant maximum and sum for the gates of the upper layers
+    if (p.mode == 1 && xs == 0 && threadIdx.x < 64) {
+        const float2 dl = merged_ml((const float *)ml, n > 0 ? nd : 0, (int)threadIdx.x);
+        if (threadIdx.x == 0) {
+            p.gate_d[((size_t)b * hot.hq + head) * 2] = dl.x;
+            p.gate_d[((size_t)b * hot.hq + head) * 2 + 1] = dl.y;
+        }
+    }
     float m_run = kNegBig, l_run = 0.f;
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    for (int v0 = g; v0 < nvalid; v0 += NG * UN) {
+    for (int v0 = v_begin + g; v0 < nvalid; v0 += NG * UN) {
         float mk[UN], lk[UN];
         f32x4 ak[UN];
 #pragma unroll
@@ -515,7 +603,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
             n = 0;
         }
     }
-    if (p.mode == 2 && n > hot.prows) { // the distant logits must be those of this token and block
+    if (p.mode >= 2 && n > hot.prows) { // the distant logits must be those of this token and block
         if (p.score_hdr[2 * b] != n || p.score_hdr[2 * b + 1] != p.block_id) { bad = true; n = 0; }
     }
     uint2 res = make_uint2(0u, 0u);
@@ -542,10 +630,18 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
 
 size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
 
-size_t pod_score_header_bytes(const pod_layout &ly) { return ((size_t)ly.B * 2 * sizeof(int32_t) + 255) / 256 * 256; }
+// header of the score buffer: int32 [B][2] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
+static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * 2 * sizeof(int32_t) + 255) / 256 * 256; }
+static size_t score_gate_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * 2 * sizeof(float) + 255) / 256 * 256; }
+size_t pod_score_skip_offset_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly); }
+size_t pod_score_header_bytes(const pod_layout &ly)
+{
+    return score_tag_bytes(ly) + score_gate_bytes(ly) + ((size_t)ly.B * ly.Hq * sizeof(int32_t) + 255) / 256 * 256;
+}
 
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared, const int32_t *ctx, int B,
-                      int max_len, float scale, void *ws, size_t ws_bytes, void *scores, void *out, hipStream_t st)
+                      int max_len, float scale, void *ws, size_t ws_bytes, void *scores, float tau, void *out,
+                      hipStream_t st)
 {
     const pod_layout &ly = c->ly;
     const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
@@ -564,8 +660,11 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.flag = (int32_t *)(c->base + ly.off_flag);
     p.maxctx = ly.maxctx;
     p.out = (pod_bf16 *)out;
-    p.mode = scores ? (layer == lowest ? 1 : 2) : 0;
+    p.mode = scores ? (layer == lowest ? 1 : (tau >= 0.f ? 3 : 2)) : 0;
     p.score_hdr = (int32_t *)scores;
+    p.gate_d = scores ? (float *)((char *)scores + score_tag_bytes(ly)) : nullptr;
+    p.skip = scores ? (int32_t *)((char *)scores + score_tag_bytes(ly) + score_gate_bytes(ly)) : nullptr;
+    p.tau = tau;
     p.scores = scores ? (float *)((char *)scores + pod_score_header_bytes(ly)) : nullptr;
     p.score_stride = (int32_t)pod_score_stride(ly);
     p.block_id = layer / ly.G;
@@ -603,15 +702,20 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     pod_cache *mc = const_cast<pod_cache *>(c);
     const bool prof = mc->prof_ev && mc->prof_n < mc->prof_cap;
     if (prof) POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n], st));
-#define POD_LAUNCH_PARTIAL(DD, MM) hipLaunchKernelGGL((decode_partial_kernel<DD, MM>), grid, dim3(kWaves * 64), 0, st, p)
+#define POD_LAUNCH_PARTIAL(DD, MM, GRID) hipLaunchKernelGGL((decode_partial_kernel<DD, MM>), GRID, dim3(kWaves * 64), 0, st, p)
+    // gated upper layer: proximal chunks first, then the distant chunks, whose workgroups read the proximal partials
+    const dim3 grid_p((unsigned)(NC - p.hot.max_nd), (unsigned)ly.Hkv, (unsigned)B);
+    const dim3 grid_d((unsigned)(p.hot.max_nd > 0 ? p.hot.max_nd : 1), (unsigned)ly.Hkv, (unsigned)B);
     if (ly.D == 128) {
-        if (p.mode == 0) POD_LAUNCH_PARTIAL(128, 0);
-        else if (p.mode == 1) POD_LAUNCH_PARTIAL(128, 1);
-        else POD_LAUNCH_PARTIAL(128, 2);
+        if (p.mode == 0) POD_LAUNCH_PARTIAL(128, 0, grid);
+        else if (p.mode == 1) POD_LAUNCH_PARTIAL(128, 1, grid);
+        else if (p.mode == 2) POD_LAUNCH_PARTIAL(128, 2, grid);
+        else { POD_LAUNCH_PARTIAL(128, 3, grid_p); if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(128, 4, grid_d); }
     } else {
-        if (p.mode == 0) POD_LAUNCH_PARTIAL(64, 0);
-        else if (p.mode == 1) POD_LAUNCH_PARTIAL(64, 1);
-        else POD_LAUNCH_PARTIAL(64, 2);
+        if (p.mode == 0) POD_LAUNCH_PARTIAL(64, 0, grid);
+        else if (p.mode == 1) POD_LAUNCH_PARTIAL(64, 1, grid);
+        else if (p.mode == 2) POD_LAUNCH_PARTIAL(64, 2, grid);
+        else { POD_LAUNCH_PARTIAL(64, 3, grid_p); if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(64, 4, grid_d); }
     }
 #undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }

@@ -71,12 +71,14 @@ int pod_launch_fill(const pod_cache *c, int layer, int seq_slot, int n, const vo
                     hipStream_t st);
 int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, void *sinkK, void *sinkV,
                       void *recK, void *recV, void *distK, void *distV, hipStream_t st);
-// scores == NULL: plain decode; else the score-reuse buffer (lowest layer writes, upper layers read)
+// scores == NULL: plain decode; else the score-reuse buffer (lowest layer writes, upper layers read).
+// tau >= 0 (needs scores): upper layers leave the distant part out for heads whose gate reaches tau.
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
-                      void *scores, void *out, hipStream_t st);
+                      void *scores, float tau, void *out, hipStream_t st);
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
-size_t pod_score_header_bytes(const pod_layout &ly); // tag area in front of the rows
+size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
+size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
                        const void *q_shared, const void *k_shared, float scale, void *out, hipStream_t st);

@@ -193,3 +193,93 @@ def test_score_reuse_detects_stale_scores():
         c.gpu.pod_decode_attention_reuse(0, c.decode_queries(0, [n], c.dev),
                                          torch.tensor([n], dtype=torch.int32, device=c.dev), c.scale, scores[:256])
     assert e.value.code == pod.binding.ERR_CAPACITY
+
+
+# ---------------------------------------------------------------- gated skip of distant tokens (appendix)
+
+def _gated_setup(d, Hq, Hkv, S, W, lens, boost_heads, seed):
+    """One block of two layers; the sink and recent keys of the kv heads in `boost_heads` are scaled x4 at the
+    upper layer, so that those heads' gates sit near 1 while the others stay small."""
+    B = len(lens)
+    c = Case(2, 2, Hq, Hkv, d, S, W, B, max(lens) + 8, seed=seed)
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            k = c.keys(layer, b, n, "cpu").clone()
+            v = c.values(layer, b, n, "cpu")
+            if layer == 1:
+                prox = torch.zeros(n, dtype=torch.bool)
+                prox[:S] = True
+                prox[max(n - W, 0):] = True
+                for h in boost_heads:
+                    k[prox, h] = k[prox, h] * 4                       # exact in bf16
+            c.gpu.pod_cache_fill(layer, b, k.to(c.dev), v.to(c.dev))
+            c.cpu.fill(layer, b, gen.bf16_bits(k), gen.bf16_bits(v))
+    return c
+
+
+def _gated_both(c, ctx, scores, tau):
+    q1 = c.decode_queries(1, ctx, c.dev)
+    ctx_t = torch.tensor(ctx, dtype=torch.int32, device=c.dev)
+    got = c.gpu.pod_decode_attention_gated(1, q1, ctx_t, c.scale, tau, scores)
+    flags = c.gpu.skip_flags(scores)[: len(ctx)].cpu().numpy()
+    ref, g, skipped = c.cpu.decode_attention_gated(1, gen.bf16_bits(c.decode_queries(1, ctx, "cpu")),
+                                                   gen.bf16_bits(c.decode_queries(0, ctx, "cpu")), ctx, c.scale, tau)
+    return got, flags, ref, g, skipped
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 8, 2), (64, 4, 2)])
+def test_gated_decode_matches_oracle_decisions_and_outputs(d, Hq, Hkv):
+    S, W, lens = 8, 64, [700, 333, 150]
+    c = _gated_setup(d, Hq, Hkv, S, W, lens, boost_heads=[0], seed=321)
+    scores = c.gpu.new_score_buffer()
+    ctx_t = torch.tensor(lens, dtype=torch.int32, device=c.dev)
+    # lowest layer through the gated entry point: exact, and it leaves the distant sums for the gates
+    out0 = c.gpu.pod_decode_attention_gated(0, c.decode_queries(0, lens, c.dev), ctx_t, c.scale, 0.5, scores)
+    assert_close(out0, c.decode_ref(0, lens), "lowest layer")
+    _, _, _, g, _ = _gated_both(c, lens, scores, 1.0)
+    # thresholds: never, always, and one inside the widest gap between the heads' gates
+    gs = np.sort(g.ravel())
+    gaps = np.diff(gs)
+    mid = float(gs[np.argmax(gaps)] + gaps.max() / 2)
+    assert gaps.max() > 0.05, "the case must separate the heads"
+    for tau in (1.0, 0.0, mid):
+        got, flags, ref, g2, skipped = _gated_both(c, lens, scores, tau)
+        assert np.abs(g2 - tau).min() > 0.02 or tau in (0.0, 1.0)    # no head near the threshold: the decision is unique
+        np.testing.assert_array_equal(flags, skipped, err_msg=f"tau={tau}")
+        assert_close(got, ref, f"tau={tau}")
+    got, flags, ref, g2, skipped = _gated_both(c, lens, scores, mid)
+    assert 0 < skipped.sum() < skipped.size                            # the threshold case really is mixed
+    per_group = skipped.reshape(len(lens), Hkv, Hq // Hkv).sum(axis=2)
+    assert (per_group == Hq // Hkv).any()                              # a kv head whose distant rows are not read at all
+    c.gpu.pod_cache_check()
+
+
+def test_gated_decode_mixed_decisions_inside_one_kv_head():
+    """All query heads share one kv head, no boost: their gates differ by chance; a threshold inside the spread
+    makes some heads of the same workgroup skip while the others need the distant rows."""
+    S, W, lens = 8, 256, [900]
+    c = _gated_setup(128, 8, 1, S, W, lens, boost_heads=[], seed=77)
+    scores = c.gpu.new_score_buffer()
+    ctx_t = torch.tensor(lens, dtype=torch.int32, device=c.dev)
+    c.gpu.pod_decode_attention_gated(0, c.decode_queries(0, lens, c.dev), ctx_t, c.scale, 0.5, scores)
+    _, _, _, g, _ = _gated_both(c, lens, scores, 1.0)
+    gs = np.sort(g.ravel())
+    gaps = np.diff(gs)
+    i = int(np.argmax(gaps))
+    assert gaps[i] > 0.01
+    tau = float(gs[i] + gaps[i] / 2)
+    got, flags, ref, g2, skipped = _gated_both(c, lens, scores, tau)
+    assert 0 < skipped.sum() < skipped.size
+    np.testing.assert_array_equal(flags, skipped)
+    assert_close(got, ref, f"tau={tau}")
+
+
+def test_gated_decode_without_distant_tokens_and_bad_tau():
+    c = _gated_setup(64, 4, 2, 8, 64, [50], boost_heads=[], seed=5)     # 50 < S + W: nothing distant
+    scores = c.gpu.new_score_buffer()
+    ctx_t = torch.tensor([50], dtype=torch.int32, device=c.dev)
+    c.gpu.pod_decode_attention_gated(0, c.decode_queries(0, [50], c.dev), ctx_t, c.scale, 0.0, scores)
+    got = c.gpu.pod_decode_attention_gated(1, c.decode_queries(1, [50], c.dev), ctx_t, c.scale, 0.0, scores)
+    assert_close(got, c.decode_ref(1, [50]), "no distant tokens")
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_decode_attention_gated(1, c.decode_queries(1, [50], c.dev), ctx_t, c.scale, 1.5, scores)
