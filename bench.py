@@ -196,7 +196,7 @@ def main():
         "config": {"workload": "configs[1]: LLaMA3-8B-shaped PoD decode, one layer block G=2, 32q/8kv heads, d=128, "
                                f"batch 1, context {n0}+step, S=64, W=2048, RoPE keys; step = append x2 + decode x2",
                    "rotating_blocks": R, "launch": mode, "bytes_per_step": step_bytes(timed[0])},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic_from_profiles(), "bytes_per_launch": int(bytes_per_launch),
                      "avg_kernel_us": round(kernel_s * 1e6, 3), "launches": launches},
