@@ -205,6 +205,12 @@ int oracle_pod_attention_gate(long n, int Hq, int Hkv, int d, int S, int W, doub
  *   distK  : K of the same positions, kept only at the lowest layer of a block
  * A position leaving the recent list moves to the distant lists: its value
  * always, its key only if the layer is the lowest of its block.
+ *
+ * Blocks are per kv head (the paper groups layers head by head, Alg. 1): lowest[l][h]
+ * is the lowest layer of the block that layer l belongs to for kv head h.  The
+ * uniform case (blocks of G consecutive layers for every head) is lowest = l - l % G.
+ * distK of a layer holds the slices of the heads for which it is a lowest layer;
+ * the other heads' slices are never written and never read.
  */
 typedef struct {
     long n;             /* tokens seen */
@@ -214,23 +220,50 @@ typedef struct {
 } seq_state;
 
 typedef struct pod_oracle_cache {
-    int L, G, Hkv, d, S, W, B;
+    int L, Hkv, d, S, W, B;
     long max_ctx;
+    int *lowest;   /* [L][Hkv] */
     seq_state *st; /* [L][B], storage allocated on first use */
 } pod_oracle_cache;
 
 static size_t row_elems(const pod_oracle_cache *c) { return (size_t)c->Hkv * c->d; }
-static int is_lowest(const pod_oracle_cache *c, int layer) { return layer % c->G == 0; }
+static int lowest_of(const pod_oracle_cache *c, int layer, int h) { return c->lowest[(size_t)layer * c->Hkv + h]; }
+static int is_lowest(const pod_oracle_cache *c, int layer, int h) { return lowest_of(c, layer, h) == layer; }
+static int is_lowest_any(const pod_oracle_cache *c, int layer)
+{
+    for (int h = 0; h < c->Hkv; ++h) if (is_lowest(c, layer, h)) return 1;
+    return 0;
+}
+
+/*
+ * lowest: [L][Hkv] table as described above, or NULL for uniform blocks of G layers.
+ * A table must describe consecutive blocks: lowest[0][h] = 0 and lowest[l][h] is either
+ * lowest[l-1][h] (same block) or l (a new block starts).
+ */
+pod_oracle_cache *oracle_cache_create_map(int L, int G, int Hkv, int d, int S, int W, int B, long max_ctx,
+                                          const int32_t *lowest)
+{
+    if (L < 1 || Hkv < 1 || d < 1 || S < 0 || W < 1 || B < 1 || max_ctx < 1) return NULL;
+    if (!lowest && (G < 1 || L % G)) return NULL;
+    pod_oracle_cache *c = (pod_oracle_cache *)calloc(1, sizeof *c);
+    if (!c) return NULL;
+    c->L = L; c->Hkv = Hkv; c->d = d; c->S = S; c->W = W; c->B = B; c->max_ctx = max_ctx;
+    c->st = (seq_state *)calloc((size_t)L * B, sizeof(seq_state));
+    c->lowest = (int *)calloc((size_t)L * Hkv, sizeof(int));
+    if (!c->st || !c->lowest) { free(c->st); free(c->lowest); free(c); return NULL; }
+    for (int l = 0; l < L; ++l)
+        for (int h = 0; h < Hkv; ++h) {
+            const int lo = lowest ? lowest[(size_t)l * Hkv + h] : l - l % G;
+            const int prev = l > 0 ? c->lowest[(size_t)(l - 1) * Hkv + h] : 0;
+            if ((l == 0 && lo != 0) || (l > 0 && lo != prev && lo != l)) { free(c->st); free(c->lowest); free(c); return NULL; }
+            c->lowest[(size_t)l * Hkv + h] = lo;
+        }
+    return c;
+}
 
 pod_oracle_cache *oracle_cache_create(int L, int G, int Hkv, int d, int S, int W, int B, long max_ctx)
 {
-    if (L < 1 || G < 1 || L % G || Hkv < 1 || d < 1 || S < 0 || W < 1 || B < 1 || max_ctx < 1) return NULL;
-    pod_oracle_cache *c = (pod_oracle_cache *)calloc(1, sizeof *c);
-    if (!c) return NULL;
-    c->L = L; c->G = G; c->Hkv = Hkv; c->d = d; c->S = S; c->W = W; c->B = B; c->max_ctx = max_ctx;
-    c->st = (seq_state *)calloc((size_t)L * B, sizeof(seq_state));
-    if (!c->st) { free(c); return NULL; }
-    return c;
+    return oracle_cache_create_map(L, G, Hkv, d, S, W, B, max_ctx, NULL);
 }
 
 static void seq_free(seq_state *s)
@@ -244,6 +277,7 @@ void oracle_cache_destroy(pod_oracle_cache *c)
     if (!c) return;
     for (long x = 0; x < (long)c->L * c->B; ++x) seq_free(&c->st[x]);
     free(c->st);
+    free(c->lowest);
     free(c);
 }
 
@@ -258,7 +292,7 @@ static int seq_alloc(const pod_oracle_cache *c, seq_state *s, int lowest)
     s->recK = (uint16_t *)malloc(re * (size_t)c->W);
     s->recV = (uint16_t *)malloc(re * (size_t)c->W);
     s->distV = (uint16_t *)malloc(re * (size_t)(cap_dist + 1));
-    s->distK = lowest ? (uint16_t *)malloc(re * (size_t)(cap_dist + 1)) : NULL;
+    s->distK = lowest ? (uint16_t *)calloc((size_t)(cap_dist + 1), re) : NULL; /* slices of non-lowest heads stay zero */
     if (!s->sinkK || !s->sinkV || !s->recK || !s->recV || !s->distV || (lowest && !s->distK))
         return ORACLE_ERR_CAPACITY;
     return ORACLE_OK;
@@ -275,11 +309,21 @@ long oracle_cache_len(pod_oracle_cache *c, int layer, int seq)
     return seq_of(c, layer, seq)->n;
 }
 
+/* rows of distant keys: only the slices of the heads for which `layer` is a lowest layer */
+static void copy_lowest_heads(const pod_oracle_cache *c, int layer, uint16_t *dst, const uint16_t *src, long rows)
+{
+    const size_t re = row_elems(c);
+    for (long r = 0; r < rows; ++r)
+        for (int h = 0; h < c->Hkv; ++h)
+            if (is_lowest(c, layer, h))
+                memcpy(dst + (size_t)r * re + (size_t)h * c->d, src + (size_t)r * re + (size_t)h * c->d, (size_t)c->d * sizeof(uint16_t));
+}
+
 /* One token (position p = number of tokens already stored) enters the cache. */
 static int seq_push(pod_oracle_cache *c, int layer, seq_state *s, const uint16_t *krow, const uint16_t *vrow)
 {
     const size_t re = row_elems(c), rb = re * sizeof(uint16_t);
-    int rc = seq_alloc(c, s, is_lowest(c, layer));
+    int rc = seq_alloc(c, s, is_lowest_any(c, layer));
     if (rc) return rc;
     if (s->n >= c->max_ctx) return ORACLE_ERR_CAPACITY;
     const long p = s->n;
@@ -290,8 +334,8 @@ static int seq_push(pod_oracle_cache *c, int layer, seq_state *s, const uint16_t
         if (s->n_recent == c->W) {
             /* the oldest recent token stops being proximal: demote it */
             memcpy(s->distV + (size_t)s->n_dist * re, s->recV, rb);
-            if (is_lowest(c, layer))
-                memcpy(s->distK + (size_t)s->n_dist * re, s->recK, rb);
+            if (is_lowest_any(c, layer))
+                copy_lowest_heads(c, layer, s->distK + (size_t)s->n_dist * re, s->recK, 1);
             s->n_dist += 1;
             memmove(s->recK, s->recK + re, rb * (size_t)(c->W - 1));
             memmove(s->recV, s->recV + re, rb * (size_t)(c->W - 1));
@@ -337,7 +381,7 @@ int oracle_cache_fill(pod_oracle_cache *c, int layer, int seq, long n, const uin
     if (n > c->max_ctx) return ORACLE_ERR_CAPACITY;
     seq_state *s = seq_of(c, layer, seq);
     if (s->n != 0) return ORACLE_ERR_STATE;
-    int rc = seq_alloc(c, s, is_lowest(c, layer));
+    int rc = seq_alloc(c, s, is_lowest_any(c, layer));
     if (rc) return rc;
     const size_t re = row_elems(c), rb = re * sizeof(uint16_t);
     const long n_sink = n < c->S ? n : c->S;
@@ -349,7 +393,7 @@ int oracle_cache_fill(pod_oracle_cache *c, int layer, int seq, long n, const uin
     memcpy(s->recK, k + (size_t)rec_lo * re, rb * (size_t)n_rec);
     memcpy(s->recV, v + (size_t)rec_lo * re, rb * (size_t)n_rec);
     memcpy(s->distV, v + (size_t)c->S * re, rb * (size_t)n_dist);
-    if (is_lowest(c, layer)) memcpy(s->distK, k + (size_t)c->S * re, rb * (size_t)n_dist);
+    if (is_lowest_any(c, layer)) copy_lowest_heads(c, layer, s->distK, k + (size_t)c->S * re, n_dist);
     s->n = n; s->n_recent = n_rec; s->n_dist = n_dist;
     return ORACLE_OK;
 }
@@ -371,8 +415,8 @@ int oracle_cache_export(pod_oracle_cache *c, int layer, int seq, long *counts,
     if (recV) memcpy(recV, s->recV, rb * (size_t)s->n_recent);
     if (distV) memcpy(distV, s->distV, rb * (size_t)s->n_dist);
     if (distK) {
-        if (!is_lowest(c, layer)) return ORACLE_ERR_ARG; /* that layer keeps no distant keys */
-        memcpy(distK, s->distK, rb * (size_t)s->n_dist);
+        if (!is_lowest_any(c, layer)) return ORACLE_ERR_ARG; /* that layer keeps no distant keys */
+        memcpy(distK, s->distK, rb * (size_t)s->n_dist);   /* heads that are not lowest here: zeros */
     }
     return ORACLE_OK;
 }
@@ -385,8 +429,10 @@ long oracle_cache_stored_elems(pod_oracle_cache *c)
         for (int b = 0; b < c->B; ++b) {
             seq_state *s = seq_of(c, l, b);
             const long n_sink = s->n < c->S ? s->n : c->S;
-            long rows = 2 * n_sink + 2 * s->n_recent + s->n_dist + (is_lowest(c, l) ? s->n_dist : 0);
-            total += rows * (long)row_elems(c);
+            for (int h = 0; h < c->Hkv; ++h) {
+                long rows = 2 * n_sink + 2 * s->n_recent + s->n_dist + (is_lowest(c, l, h) ? s->n_dist : 0);
+                total += rows * (long)c->d;
+            }
         }
     return total;
 }
@@ -407,6 +453,23 @@ void oracle_cache_bytes_formula(int L, int G, int Hkv, int d, int S, int W, long
     *dense_bytes = 2.0 * row * (double)L * (double)n;
 }
 
+/* The same for head-wise blocks: kv head h keeps distant keys once per block of ITS partition. */
+void oracle_cache_bytes_formula_map(int L, int Hkv, int d, int S, int W, long n, int elem_bytes,
+                                    const int32_t *lowest, double *pod_bytes, double *dense_bytes)
+{
+    const double row = (double)d * elem_bytes; /* one head */
+    const double n_prox = (double)(n < (long)S + W ? n : (long)S + W);
+    const double n_dist = (double)(n - S - W > 0 ? n - S - W : 0);
+    double total = 0.0;
+    for (int h = 0; h < Hkv; ++h) {
+        int blocks = 0;
+        for (int l = 0; l < L; ++l) blocks += lowest[(size_t)l * Hkv + h] == l;
+        total += row * ((double)L * (2.0 * n_prox + n_dist) + (double)blocks * n_dist);
+    }
+    *pod_bytes = total;
+    *dense_bytes = 2.0 * row * Hkv * (double)L * (double)n;
+}
+
 /*
  * Decode attention from the cache model: one query token per sequence, at
  * position n-1 where n = ctx_lens[b] must equal the stored length.
@@ -421,21 +484,23 @@ int oracle_decode_attention(pod_oracle_cache *c, int layer, int Hq, double scale
                             int Bcur, double *out)
 {
     if (!c || layer < 0 || layer >= c->L || Bcur < 1 || Bcur > c->B || Hq < 1 || Hq % c->Hkv) return ORACLE_ERR_ARG;
-    const int lowest_layer = layer - layer % c->G;
     const int rep = Hq / c->Hkv, d = c->d;
     const size_t re = row_elems(c);
     for (int b = 0; b < Bcur; ++b) {
         seq_state *s = seq_of(c, layer, b);
-        seq_state *sa = seq_of(c, lowest_layer, b);
         if (ctx_lens[b] < 1 || ctx_lens[b] != s->n) return ORACLE_ERR_STATE;
-        if (s->n_dist > 0 && sa->n_dist != s->n_dist) return ORACLE_ERR_STATE;
-        if (s->n_dist > 0 && layer != lowest_layer && !q_shared) return ORACLE_ERR_ARG;
+        for (int h = 0; h < c->Hkv; ++h) {
+            seq_state *sa = seq_of(c, lowest_of(c, layer, h), b);
+            if (s->n_dist > 0 && sa->n_dist != s->n_dist) return ORACLE_ERR_STATE;
+            if (s->n_dist > 0 && !is_lowest(c, layer, h) && !q_shared) return ORACLE_ERR_ARG;
+        }
     }
     const long work = (long)Bcur * Hq;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long w = 0; w < work; ++w) {
         const int b = (int)(w / Hq), h = (int)(w % Hq), kv = h / rep;
         seq_state *s = seq_of(c, layer, b);
+        const int lowest_layer = lowest_of(c, layer, kv);   /* of this head's block */
         seq_state *sa = seq_of(c, lowest_layer, b);
         const long n_sink = s->n < c->S ? s->n : c->S;
         const long total = n_sink + s->n_recent + s->n_dist;
@@ -489,21 +554,23 @@ int oracle_decode_attention_gated(pod_oracle_cache *c, int layer, int Hq, double
 {
     if (!c || layer < 0 || layer >= c->L || Bcur < 1 || Bcur > c->B || Hq < 1 || Hq % c->Hkv) return ORACLE_ERR_ARG;
     if (!(tau >= 0.0 && tau <= 1.0)) return ORACLE_ERR_ARG;
-    const int lowest_layer = layer - layer % c->G;
     const int rep = Hq / c->Hkv, d = c->d;
     const size_t re = row_elems(c);
     for (int b = 0; b < Bcur; ++b) {
         seq_state *s = seq_of(c, layer, b);
-        seq_state *sa = seq_of(c, lowest_layer, b);
         if (ctx_lens[b] < 1 || ctx_lens[b] != s->n) return ORACLE_ERR_STATE;
-        if (s->n_dist > 0 && sa->n_dist != s->n_dist) return ORACLE_ERR_STATE;
-        if (s->n_dist > 0 && layer != lowest_layer && !q_shared) return ORACLE_ERR_ARG;
+        for (int h = 0; h < c->Hkv; ++h) {
+            seq_state *sa = seq_of(c, lowest_of(c, layer, h), b);
+            if (s->n_dist > 0 && sa->n_dist != s->n_dist) return ORACLE_ERR_STATE;
+            if (s->n_dist > 0 && !is_lowest(c, layer, h) && !q_shared) return ORACLE_ERR_ARG;
+        }
     }
     const long work = (long)Bcur * Hq;
 #pragma omp parallel for schedule(dynamic, 1)
     for (long w = 0; w < work; ++w) {
         const int b = (int)(w / Hq), h = (int)(w % Hq), kv = h / rep;
         seq_state *s = seq_of(c, layer, b);
+        const int lowest_layer = lowest_of(c, layer, kv);   /* of this head's block */
         seq_state *sa = seq_of(c, lowest_layer, b);
         const long n_sink = s->n < c->S ? s->n : c->S;
         const long nP = n_sink + s->n_recent, nD = s->n_dist;

@@ -31,6 +31,10 @@ def lib():
         L.oracle_pod_attention_gate.argtypes = L.oracle_pod_attention.argtypes + [f64p]
         L.oracle_cache_create.restype = C.c_void_p
         L.oracle_cache_create.argtypes = [C.c_int] * 7 + [C.c_long]
+        L.oracle_cache_create_map.restype = C.c_void_p
+        L.oracle_cache_create_map.argtypes = [C.c_int] * 7 + [C.c_long, i32p]
+        L.oracle_cache_bytes_formula_map.restype = None
+        L.oracle_cache_bytes_formula_map.argtypes = [C.c_int] * 5 + [C.c_long, C.c_int, i32p, f64p, f64p]
         L.oracle_cache_destroy.restype = None
         L.oracle_cache_destroy.argtypes = [C.c_void_p]
         L.oracle_cache_len.restype = C.c_long
@@ -107,12 +111,31 @@ def cache_bytes_formula(L, G, Hkv, d, S, W, n, elem_bytes=2):
     return p.value, dn.value
 
 
-class Cache:
-    """Logical model of the split cache (lists per layer and sequence)."""
+def cache_bytes_formula_map(lowest, d, S, W, n, elem_bytes=2):
+    """Closed-form bytes for head-wise blocks; lowest: int [L][Hkv] (lowest layer of each layer's block per kv head)."""
+    lowest = np.ascontiguousarray(lowest, dtype=np.int32)
+    L, Hkv = lowest.shape
+    p, dn = C.c_double(), C.c_double()
+    lib().oracle_cache_bytes_formula_map(L, Hkv, d, S, W, n, elem_bytes, lowest.ctypes.data_as(C.POINTER(C.c_int32)),
+                                         C.byref(p), C.byref(dn))
+    return p.value, dn.value
 
-    def __init__(self, L, G, Hkv, d, S, W, B, max_ctx):
+
+class Cache:
+    """Logical model of the split cache (lists per layer and sequence).  block_lowest: optional int [L][Hkv]
+    table of head-wise blocks (lowest layer of the block each layer belongs to, per kv head); default: uniform
+    blocks of G layers."""
+
+    def __init__(self, L, G, Hkv, d, S, W, B, max_ctx, block_lowest=None):
         self.L, self.G, self.Hkv, self.d, self.S, self.W, self.B, self.max_ctx = L, G, Hkv, d, S, W, B, max_ctx
-        self._h = lib().oracle_cache_create(L, G, Hkv, d, S, W, B, max_ctx)
+        if block_lowest is None:
+            self.lowest = np.array([[l - l % G] * Hkv for l in range(L)], dtype=np.int32)
+            self._h = lib().oracle_cache_create(L, G, Hkv, d, S, W, B, max_ctx)
+        else:
+            self.lowest = np.ascontiguousarray(block_lowest, dtype=np.int32)
+            assert self.lowest.shape == (L, Hkv)
+            self._h = lib().oracle_cache_create_map(L, G, Hkv, d, S, W, B, max_ctx,
+                                                    self.lowest.ctypes.data_as(C.POINTER(C.c_int32)))
         if not self._h:
             raise OracleError(ERR_ARG, "oracle_cache_create")
 
@@ -139,13 +162,13 @@ class Cache:
 
     def export(self, layer, seq):
         """dict of uint16 arrays [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV and,
-        at a block's lowest layer, distK."""
+        at a layer that is the lowest of a block for some kv head, distK (zeros in the other heads' slices)."""
         counts = (C.c_long * 3)()
         _chk(lib().oracle_cache_export(self._h, layer, seq, counts, *([None] * 6)), "oracle_cache_export")
         ns, nr, nd = counts[0], counts[1], counts[2]
         mk = lambda t: np.zeros((t, self.Hkv, self.d), dtype=np.uint16)
         out = dict(sinkK=mk(ns), sinkV=mk(ns), recentK=mk(nr), recentV=mk(nr), distV=mk(nd))
-        lowest = layer % self.G == 0
+        lowest = bool((self.lowest[layer] == layer).any())   # a lowest layer for at least one kv head
         if lowest:
             out["distK"] = mk(nd)
         rc = lib().oracle_cache_export(self._h, layer, seq, counts, _u16(out["sinkK"]), _u16(out["sinkV"]),

@@ -469,3 +469,130 @@ def test_gated_threshold_splits_heads_by_their_gate():
         if skipped[0, h]:                                         # o = g oP + (1-g) oD  =>  oP - o = (1-g)(oP - oD)
             oD = (exact[0, h] - g[0, h] * prox_only[0, h]) / (1 - g[0, h])
             np.testing.assert_allclose(out[0, h] - exact[0, h], (1 - g[0, h]) * (prox_only[0, h] - oD), atol=1e-12)
+
+
+# ---------------------------------------------------------------- head-wise blocks and offline grouping
+
+from oracle import pod_grouping as pg
+
+MAP4 = np.array([[0, 0, 0],     # kv head 0: one block {0,1,2,3}; head 1: {0,1},{2,3}; head 2: every layer alone
+                 [0, 0, 1],
+                 [0, 2, 2],
+                 [0, 2, 3]], dtype=np.int32)
+
+
+def _filled_map_cache(n, block_lowest, L=4, Hq=6, Hkv=3, d=8, S=4, W=8, seed=83):
+    c = po.Cache(L, 1, Hkv, d, S, W, 1, 64, block_lowest=block_lowest)
+    qs, ks, vs = {}, {}, {}
+    for l in range(L):
+        qs[l], ks[l], vs[l] = rand_qkv(seed, n, Hq, Hkv, d, layer=l)
+        c.fill(l, 0, bits(ks[l]), bits(vs[l]))
+    return c, qs, ks, vs
+
+
+def test_explicit_uniform_map_equals_group_size():
+    n, L, G, Hq, Hkv, d, S, W = 37, 4, 2, 4, 2, 8, 4, 8
+    uni = np.array([[l - l % G] * Hkv for l in range(L)], dtype=np.int32)
+    a = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    b = po.Cache(L, 1, Hkv, d, S, W, 1, 64, block_lowest=uni)
+    for l in range(L):
+        q, k, v = rand_qkv(91, n, Hq, Hkv, d, layer=l)
+        for c in (a, b):
+            c.fill(l, 0, bits(k), bits(v))
+    assert a.stored_elems() == b.stored_elems()
+    for l in range(L):
+        q = bits(rand_qkv(91, n, Hq, Hkv, d, layer=l)[0][n - 1:])
+        qa = bits(rand_qkv(91, n, Hq, Hkv, d, layer=l - l % G)[0][n - 1:])
+        np.testing.assert_array_equal(a.decode_attention(l, q, qa, [n], 0.3), b.decode_attention(l, q, qa, [n], 0.3))
+        ea, eb = a.export(l, 0), b.export(l, 0)
+        assert set(ea) == set(eb)
+        for key in ea:
+            np.testing.assert_array_equal(ea[key], eb[key])
+
+
+def test_headwise_map_decode_equals_definition_with_per_head_sources():
+    """Each kv head takes its distant logits from the lowest layer of ITS block: the definition, fed with
+    k_shared / q_shared gathered head by head from those layers, must give the cache model's result."""
+    n, L, Hq, Hkv, d, S, W = 37, 4, 6, 3, 8, 4, 8
+    c, qs, ks, vs = _filled_map_cache(n, MAP4)
+    rep, i = Hq // Hkv, n - 1
+    for layer in range(L):
+        k_sh = torch.stack([ks[int(MAP4[layer, h])][:, h] for h in range(Hkv)], dim=1)          # [n][Hkv][d]
+        q_sh = torch.stack([qs[int(MAP4[layer, h // rep])][i, h] for h in range(Hq)], dim=0)[None]  # [1][Hq][d]
+        q = bits(qs[layer][i:i + 1])
+        got = c.decode_attention(layer, q, bits(q_sh), [n], 0.35)
+        ref = po.pod_attention(q, bits(ks[layer]), bits(vs[layer]), bits(q_sh), bits(k_sh), [i], S, W, 0.35)
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13)
+    # kv head 2 is alone in every block: textbook attention for its query heads at every layer
+    for layer in range(L):
+        q_sh = torch.stack([qs[int(MAP4[layer, h // rep])][i, h] for h in range(Hq)], dim=0)[None]
+        got = c.decode_attention(layer, bits(qs[layer][i:i + 1]), bits(q_sh), [n], 0.35)
+        ref = sdpa_causal(qs[layer], ks[layer], vs[layer], 0.35)[i]
+        np.testing.assert_allclose(got[0, 2 * rep:], ref[2 * rep:], rtol=0, atol=1e-12)
+
+
+def test_headwise_map_keeps_distant_keys_only_where_lowest_and_counts_match_closed_form():
+    n, L, Hq, Hkv, d, S, W = 37, 4, 6, 3, 8, 4, 8
+    c, qs, ks, vs = _filled_map_cache(n, MAP4)
+    n_dist = n - S - W
+    for layer in range(L):
+        e = c.export(layer, 0)
+        assert e["distV"].shape[0] == n_dist
+        for h in range(Hkv):
+            want = bits(ks[layer][S:n - W, h]) if MAP4[layer, h] == layer else np.zeros((n_dist, d), np.uint16)
+            np.testing.assert_array_equal(e["distK"][:, h], want)
+    pod_b, dense_b = po.cache_bytes_formula_map(MAP4, d, S, W, n)
+    assert c.stored_elems() * 2 == pod_b
+    blocks = [1, 2, 4]                                    # per kv head
+    by_hand = sum(d * 2 * (L * (2 * (S + W) + n_dist) + nb * n_dist) for nb in blocks)
+    assert pod_b == by_hand and dense_b == 2 * L * n * Hkv * d * 2
+    uni = np.array([[l - l % 2] * Hkv for l in range(L)], dtype=np.int32)
+    assert po.cache_bytes_formula_map(uni, d, S, W, n) == po.cache_bytes_formula(L, 2, Hkv, d, S, W, n)
+
+
+def test_headwise_map_must_describe_consecutive_blocks():
+    bad = MAP4.copy()
+    bad[3, 1] = 1                                         # layer 3 cannot join block {0,1} across block {2}
+    with pytest.raises(po.OracleError):
+        po.Cache(4, 1, 3, 8, 4, 8, 1, 64, block_lowest=bad)
+
+
+def test_greedy_grouping_by_hand():
+    L = 5
+    sim = np.zeros((2, L, L))
+    # head 0: 0~1, 1~2 but 0 and 2 dissimilar -> layer 2 must be similar to ALL of {0,1}: new block; 2~3~4 all similar
+    for a, b, v in [(0, 1, .9), (1, 2, .9), (0, 2, .2), (2, 3, .6), (2, 4, .5), (3, 4, .7), (1, 3, .9), (0, 3, .9)]:
+        sim[0, a, b] = sim[0, b, a] = v
+    # head 1: nothing similar
+    lowest = pg.group_layers(sim, 0.5)
+    assert lowest[:, 0].tolist() == [0, 0, 2, 2, 2]       # 0.5 counts as similar (>=)
+    assert lowest[:, 1].tolist() == [0, 1, 2, 3, 4]
+    assert pg.group_layers(np.ones((3, L, L)), 0.5).tolist() == [[0, 0, 0]] * L
+
+
+def test_gqa_grouping_is_a_strict_majority_vote():
+    L, Hq, Hkv = 3, 4, 1
+    sim = np.zeros((Hq, L, L))
+    sim[:3, 0, 1] = sim[:3, 1, 0] = 0.8                   # 3 of 4 heads: similar
+    sim[:2, 1, 2] = sim[:2, 2, 1] = 0.8                   # 2 of 4 heads: a tie, not a majority
+    sim[:, 0, 2] = sim[:, 2, 0] = 0.9
+    assert pg.group_layers_gqa(sim, Hkv, 0.5)[:, 0].tolist() == [0, 0, 2]
+    sim[2, 1, 2] = sim[2, 2, 1] = 0.8                     # now 3 of 4
+    assert pg.group_layers_gqa(sim, Hkv, 0.5)[:, 0].tolist() == [0, 0, 0]
+
+
+def test_js_similarity_special_cases():
+    assert pg.js_divergence_base2([1, 0], [0, 1]) == pytest.approx(1.0)           # disjoint support
+    assert pg.js_divergence_base2([.2, .3, .5], [.2, .3, .5]) == 0.0
+    p, q = np.array([.7, .2, .1]), np.array([.1, .1, .8])
+    assert pg.js_divergence_base2(p, q) == pytest.approx(pg.js_divergence_base2(q, p))
+    # closed form for p = (1, 0), q = (1/2, 1/2): 1/2 log2(4/3) + 1/2 (1/2 log2(2/3) + 1/2 log2 2)
+    want = 0.5 * math.log2(4 / 3) + 0.5 * (0.5 * math.log2(2 / 3) + 0.5)
+    assert pg.js_divergence_base2([1, 0], [.5, .5]) == pytest.approx(want)
+    from scipy.spatial.distance import jensenshannon                                # library routine: sqrt of JS
+    assert pg.js_divergence_base2(p, q) == pytest.approx(jensenshannon(p, q, base=2) ** 2)
+    a = np.random.default_rng(0).dirichlet(np.ones(16), size=(2, 3))
+    assert pg.layer_similarity(a, a) == pytest.approx(1.0)
+    b = np.roll(a, 5, axis=2)
+    manual = 1 - np.mean([pg.js_divergence_base2(a[i, j], b[i, j]) for i in range(2) for j in range(3)])
+    assert pg.layer_similarity(a, b) == pytest.approx(manual) and 0 < manual < 1
