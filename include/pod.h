@@ -62,12 +62,22 @@ typedef struct pod_config {
     int32_t num_layers;   /* L, a multiple of group_size */
     int32_t group_size;   /* G: layers per block; G = 1 is ordinary attention */
     int32_t num_q_heads;  /* Hq */
-    int32_t num_kv_heads; /* Hkv, divides Hq */
+    int32_t num_kv_heads; /* Hkv, divides Hq, at most 64 */
     int32_t head_dim;     /* d: 64 or 128 */
     int32_t sink;         /* S = n_s >= 0 */
     int32_t window;       /* W = n_r >= 1; counts the query's own token */
     int32_t max_batch;    /* sequence slots */
     int32_t max_context;  /* tokens per sequence the buffers are sized for */
+    /*
+     * Optional head-wise blocks (the paper groups layers head by head, "Greedy Layer Grouping
+     * Algorithm"; per kv head under GQA): host array int32 [num_layers][num_kv_heads], entry
+     * (l, h) = lowest layer of the block layer l belongs to for kv head h.  Blocks are runs of
+     * consecutive layers: entry (0, h) = 0 and entry (l, h) is entry (l-1, h) or l.  NULL: uniform
+     * blocks of group_size layers.  Read during the call only (the cache keeps a copy).  With a table, group_size is ignored, and for a layer that is not the lowest
+     * of every head's block the callers of decode / prefill pass q_shared (and k_shared)
+     * gathered head by head: the slice of head h comes from layer entry (l, h).
+     */
+    const int32_t *block_lowest;
 } pod_config;
 
 typedef struct pod_cache pod_cache; /* host-side handle; holds no device allocation of its own */
@@ -199,6 +209,19 @@ int pod_decode_attention_gated(pod_cache *cache, int layer, const void *q, const
                                int max_context_len, float scale, float tau, void *workspace,
                                size_t workspace_bytes, void *scores, size_t scores_bytes, void *out, void *stream);
 int pod_score_skip_offset(const pod_config *cfg, size_t *offset);
+
+/*
+ * Offline grouping of layers into head-wise blocks ("Greedy Layer Grouping Algorithm"; host
+ * arrays, no GPU work).  sim: float [num_q_heads][num_layers][num_layers], sim[h][a][b] the
+ * attention similarity of layers a and b for query head h.  For each kv head, bottom-up: layer
+ * l joins the current block if it is similar to ALL layers already in it, else it starts a new
+ * block; two layers are similar for a kv head if sim >= threshold for more than half of its
+ * query heads (the paper's majority vote under GQA; a tie is not a majority; with one query
+ * head per kv head this is the plain test).  lowest_out: int32 [num_layers][num_kv_heads], in
+ * the form pod_config.block_lowest takes.
+ */
+int pod_group_layers(const float *sim, int num_layers, int num_q_heads, int num_kv_heads, float threshold,
+                     int32_t *lowest_out);
 
 /*
  * Prefill attention for one sequence (Eq. 3 with the window taken at each query's own

@@ -21,12 +21,14 @@ EXPORTS = [
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
+    "pod_group_layers",
 ]
 
 
 class PodConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("num_layers", "group_size", "num_q_heads", "num_kv_heads", "head_dim",
-                                          "sink", "window", "max_batch", "max_context")]
+                                          "sink", "window", "max_batch", "max_context")] + \
+               [("block_lowest", C.POINTER(C.c_int32))]
 
 
 class PodError(RuntimeError):
@@ -72,6 +74,7 @@ def load():
         "pod_decode_attention_gated": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, C.c_float, vp, C.c_size_t,
                                        vp, C.c_size_t, vp, vp],
         "pod_score_skip_offset": [cfgp, szp],
+        "pod_group_layers": [vp, C.c_int, C.c_int, C.c_int, C.c_float, vp],
         "pod_decode_attention_reuse": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp,
                                        C.c_size_t, vp, vp],
         "pod_profile_enable": [vp, C.c_int],
@@ -105,9 +108,30 @@ def _stream():
 
 
 def make_config(num_layers, group_size, num_q_heads, num_kv_heads, head_dim, sink, window, max_batch,
-                max_context) -> PodConfig:
-    return PodConfig(num_layers, group_size, num_q_heads, num_kv_heads, head_dim, sink, window, max_batch,
-                     max_context)
+                max_context, block_lowest=None) -> PodConfig:
+    """block_lowest: optional int [num_layers][num_kv_heads] table of head-wise blocks (see pod.h)."""
+    cfg = PodConfig(num_layers, group_size, num_q_heads, num_kv_heads, head_dim, sink, window, max_batch,
+                    max_context, None)
+    if block_lowest is not None:
+        import numpy as np
+        tab = np.ascontiguousarray(block_lowest, dtype=np.int32)
+        if tab.shape != (num_layers, num_kv_heads):
+            raise ValueError(f"block_lowest must have shape ({num_layers}, {num_kv_heads})")
+        cfg._block_lowest_keepalive = tab           # the struct only holds the pointer
+        cfg.block_lowest = tab.ctypes.data_as(C.POINTER(C.c_int32))
+    return cfg
+
+
+def pod_group_layers(sim, num_kv_heads, threshold=0.5):
+    """Greedy grouping of layers into head-wise blocks; sim: float [num_q_heads][L][L]; returns int32 [L][num_kv_heads]."""
+    import numpy as np
+    sim = np.ascontiguousarray(sim, dtype=np.float32)
+    Hq, L, L2 = sim.shape
+    assert L == L2
+    out = np.zeros((L, num_kv_heads), dtype=np.int32)
+    _check(load().pod_group_layers(sim.ctypes.data_as(C.c_void_p), L, Hq, num_kv_heads, float(threshold),
+                                   out.ctypes.data_as(C.c_void_p)))
+    return out
 
 
 def pod_cache_bytes(cfg: PodConfig) -> int:
@@ -249,9 +273,10 @@ class PodCache:
         nd = max(0, n - c.sink - c.window)
         mk = lambda t: torch.zeros((t, c.num_kv_heads, c.head_dim), dtype=torch.bfloat16, device=self.device)
         out = dict(sinkK=mk(ns), sinkV=mk(ns), recentK=mk(nr), recentV=mk(nr), distV=mk(nd))
-        lowest = layer % c.group_size == 0
+        tab = getattr(c, "_block_lowest_keepalive", None)   # head-wise table, if the config has one
+        lowest = bool((tab[layer] == layer).any()) if tab is not None else layer % c.group_size == 0
         if lowest:
-            out["distK"] = mk(nd)
+            out["distK"] = mk(nd)                              # (heads that are not lowest at this layer: zeros)
         _check(load().pod_cache_export_logical(self.handle, layer, seq_slot, _ptr(out["sinkK"]), _ptr(out["sinkV"]),
                                                _ptr(out["recentK"]), _ptr(out["recentV"]),
                                                _ptr(out["distK"]) if lowest else None, _ptr(out["distV"]), _stream()))

@@ -27,10 +27,39 @@ int pod_hip_fail(hipError_t e, const char *what)
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// The block table of cfg as two arrays [L][Hkv] (caller frees with free()): lowest layer of each (layer, head)'s
+// block and the distant-key slot it reads; slots are numbered in (layer, head) order of the lowest layers.
+static int make_tables(const pod_config *cfg, int32_t **lowest_out, int32_t **kslot_out, int *nslots, bool *uniform)
+{
+    const int L = cfg->num_layers, H = cfg->num_kv_heads;
+    int32_t *lowest = (int32_t *)malloc((size_t)L * H * sizeof(int32_t));
+    int32_t *kslot = (int32_t *)malloc((size_t)L * H * sizeof(int32_t));
+    if (!lowest || !kslot) { free(lowest); free(kslot); return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
+    int slots = 0;
+    bool uni = true;
+    for (int l = 0; l < L; ++l)
+        for (int h = 0; h < H; ++h) {
+            const int lo = cfg->block_lowest ? cfg->block_lowest[(size_t)l * H + h] : l - l % cfg->group_size;
+            const int prev = l > 0 ? lowest[(size_t)(l - 1) * H + h] : 0;
+            if ((l == 0 && lo != 0) || (l > 0 && lo != prev && lo != l)) {
+                free(lowest); free(kslot);
+                return pod_fail(POD_ERR_INVALID_ARG, "block_lowest[%d][%d] = %d: blocks must be runs of consecutive layers", l, h, lo);
+            }
+            lowest[(size_t)l * H + h] = lo;
+            kslot[(size_t)l * H + h] = lo == l ? slots++ : kslot[(size_t)lo * H + h];
+            if (lo != lowest[(size_t)l * H]) uni = false;
+        }
+    *nslots = slots;
+    if (uniform) *uniform = uni;
+    if (lowest_out) *lowest_out = lowest; else free(lowest);
+    if (kslot_out) *kslot_out = kslot; else free(kslot);
+    return POD_OK;
+}
+
 static int make_layout(const pod_config *cfg, pod_layout *ly)
 {
     if (!cfg) return pod_fail(POD_ERR_INVALID_ARG, "config is NULL");
-    if (cfg->num_layers < 1 || cfg->group_size < 1 || cfg->num_layers % cfg->group_size)
+    if (cfg->num_layers < 1 || (!cfg->block_lowest && (cfg->group_size < 1 || cfg->num_layers % cfg->group_size)))
         return pod_fail(POD_ERR_INVALID_ARG, "num_layers (%d) must be a positive multiple of group_size (%d)",
                         cfg->num_layers, cfg->group_size);
     if (cfg->num_kv_heads < 1 || cfg->num_q_heads < 1 || cfg->num_q_heads % cfg->num_kv_heads)
@@ -38,6 +67,8 @@ static int make_layout(const pod_config *cfg, pod_layout *ly)
                         cfg->num_q_heads, cfg->num_kv_heads);
     if (cfg->num_q_heads / cfg->num_kv_heads > 16)
         return pod_fail(POD_ERR_INVALID_ARG, "more than 16 query heads per KV head is not supported");
+    if (cfg->num_kv_heads > kMaxKvHeads)
+        return pod_fail(POD_ERR_INVALID_ARG, "at most %d kv heads are supported", kMaxKvHeads);
     if (cfg->head_dim != 64 && cfg->head_dim != 128)
         return pod_fail(POD_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", cfg->head_dim);
     if (cfg->sink < 0 || cfg->window < 1)
@@ -46,8 +77,14 @@ static int make_layout(const pod_config *cfg, pod_layout *ly)
         return pod_fail(POD_ERR_INVALID_ARG, "need 1 <= max_batch <= 65535 and max_context >= 1");
     if ((int64_t)cfg->sink + cfg->window > (int64_t)INT32_MAX / 2)
         return pod_fail(POD_ERR_INVALID_ARG, "sink + window too large");
+    int nslots = 0;
+    {
+        const int rc = make_tables(cfg, nullptr, nullptr, &nslots, nullptr);
+        if (rc) return rc;
+    }
     memset(ly, 0, sizeof *ly);
-    ly->L = cfg->num_layers; ly->G = cfg->group_size; ly->Hq = cfg->num_q_heads; ly->Hkv = cfg->num_kv_heads;
+    ly->nslots = nslots;
+    ly->L = cfg->num_layers; ly->G = cfg->block_lowest ? 1 : cfg->group_size; ly->Hq = cfg->num_q_heads; ly->Hkv = cfg->num_kv_heads;
     ly->D = cfg->head_dim; ly->S = cfg->sink; ly->W = cfg->window; ly->B = cfg->max_batch;
     ly->maxctx = cfg->max_context;
     ly->P = ly->S + ly->W;
@@ -63,9 +100,35 @@ static int make_layout(const pod_config *cfg, pod_layout *ly)
     ly->off_proxK = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
     ly->off_proxV = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
     ly->off_distV = off; off = align_up(off + per_layer_heads * ly->Cd * row, 256);
-    ly->off_distK = off; off = align_up(off + (per_layer_heads / ly->G) * ly->Cd * row, 256);
+    ly->off_distK = off; off = align_up(off + (size_t)ly->nslots * ly->B * ly->Cd * row, 256);
     ly->total_bytes = off;
     return POD_OK;
+}
+
+pod_headmap pod_make_headmap(const pod_cache *c, int layer)
+{
+    pod_headmap hm;
+    memset(&hm, 0, sizeof hm);
+    const int H = c->ly.Hkv;
+    for (int h = 0; h < H; ++h) {
+        hm.kslot_row[h] = c->kslot[(size_t)layer * H + h] * c->ly.B;
+        if (c->lowest[(size_t)layer * H + h] == layer) hm.lowest_mask |= (uint64_t)1 << h;
+    }
+    // uniform blocks: the slots of one block are consecutive over the heads
+    hm.uniform_row0 = c->uniform ? hm.kslot_row[0] : -1;
+    return hm;
+}
+
+// is `layer` the lowest of its block for every / for some kv head?
+static bool layer_lowest_all(const pod_cache *c, int layer)
+{
+    for (int h = 0; h < c->ly.Hkv; ++h) if (c->lowest[(size_t)layer * c->ly.Hkv + h] != layer) return false;
+    return true;
+}
+static bool layer_lowest_any(const pod_cache *c, int layer)
+{
+    for (int h = 0; h < c->ly.Hkv; ++h) if (c->lowest[(size_t)layer * c->ly.Hkv + h] == layer) return true;
+    return false;
 }
 
 extern "C" const char *pod_last_error(void) { return g_err; }
@@ -86,11 +149,12 @@ extern "C" int pod_cache_live_bytes(const pod_config *cfg, int64_t n, size_t *po
     int rc = make_layout(cfg, &ly);
     if (rc) return rc;
     if (n < 0) return pod_fail(POD_ERR_INVALID_ARG, "n must be >= 0");
-    const size_t row = (size_t)ly.D * 2 * ly.Hkv;
+    const size_t row = (size_t)ly.D * 2; // one head
     const size_t n_prox = (size_t)(n < ly.P ? n : ly.P);
     const size_t n_dist = (size_t)(n > ly.P ? n - ly.P : 0);
-    if (pod_bytes) *pod_bytes = row * ((size_t)ly.L * (2 * n_prox + n_dist) + (size_t)(ly.L / ly.G) * n_dist);
-    if (dense_bytes) *dense_bytes = row * 2 * (size_t)ly.L * (size_t)n;
+    // per kv head: K and V of the proximal tokens and V of the distant ones at every layer; distant K once per block
+    if (pod_bytes) *pod_bytes = row * ((size_t)ly.L * ly.Hkv * (2 * n_prox + n_dist) + (size_t)ly.nslots * n_dist);
+    if (dense_bytes) *dense_bytes = row * ly.Hkv * 2 * (size_t)ly.L * (size_t)n;
     return POD_OK;
 }
 
@@ -120,13 +184,19 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
     c->ly = ly;
     c->base = (char *)dev_buf;
     c->host_len = (int64_t *)calloc((size_t)ly.L * ly.B, sizeof(int64_t));
+    c->lowest = nullptr; c->kslot = nullptr; c->uniform = true;
+    {
+        int nslots = 0;
+        rc = make_tables(cfg, &c->lowest, &c->kslot, &nslots, &c->uniform);
+        if (rc) { free(c->host_len); delete c; return rc; }
+    }
     c->device = -1;
     c->prof_ev = nullptr; c->prof_cap = 0; c->prof_n = 0;
-    if (!c->host_len) { delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
+    if (!c->host_len) { free(c->lowest); free(c->kslot); delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
     hipError_t e = hipGetDevice(&c->device);
-    if (e != hipSuccess) { free(c->host_len); delete c; return pod_hip_fail(e, "hipGetDevice"); }
+    if (e != hipSuccess) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return pod_hip_fail(e, "hipGetDevice"); }
     rc = pod_launch_clear_header(c, (hipStream_t)stream);
-    if (rc) { free(c->host_len); delete c; return rc; }
+    if (rc) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return rc; }
     *out = c;
     return POD_OK;
 }
@@ -136,6 +206,8 @@ extern "C" int pod_cache_destroy(pod_cache *cache)
     if (!cache) return POD_OK;
     pod_profile_disable(cache);
     free(cache->host_len);
+    free(cache->lowest);
+    free(cache->kslot);
     delete cache;
     return POD_OK;
 }
@@ -326,6 +398,7 @@ static int decode_with_scores(pod_cache *cache, int layer, const void *q, const 
 {
     if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
     if (!scores) return pod_fail(POD_ERR_INVALID_ARG, "scores is NULL");
+    if (!cache->uniform) return pod_fail(POD_ERR_INVALID_ARG, "score reuse and the gated skip need the same blocks for every kv head");
     if ((uintptr_t)scores % 256) return pod_fail(POD_ERR_INVALID_ARG, "scores must be 256-byte aligned");
     const pod_layout &ly = cache->ly;
     const size_t need = pod_score_header_bytes(ly) + (size_t)ly.B * ly.Hq * pod_score_stride(ly) * sizeof(float);
@@ -352,13 +425,47 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
     const int64_t *len = cache->host_len + (size_t)layer * ly.B;
     int64_t longest = 0;
     for (int b = 0; b < B; ++b) longest = len[b] > longest ? len[b] : longest;
-    const bool lowest = layer % ly.G == 0;
+    const bool lowest = layer_lowest_all(cache, layer);
     if (!lowest && !q_shared && longest > ly.P)
         return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and holds distant tokens: q_shared is required", layer);
+    // every head's lowest layer must hold the same tokens as this layer (the device checks this layer's own lengths)
+    for (int h = 0; h < ly.Hkv; ++h) {
+        const int64_t *low = cache->host_len + (size_t)cache->lowest[(size_t)layer * ly.Hkv + h] * ly.B;
+        for (int b = 0; b < B; ++b)
+            if (len[b] > ly.P && low[b] != len[b])
+                return pod_fail(POD_ERR_STATE, "slot %d: layer %d holds %lld tokens but layer %d, the lowest of kv head %d's block, holds %lld",
+                                b, layer, (long long)len[b], cache->lowest[(size_t)layer * ly.Hkv + h], h, (long long)low[b]);
+    }
     if (max_context_len == 0) max_context_len = (int)longest;
     if (max_context_len == 0) max_context_len = 1;
     return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
                              workspace, workspace_bytes, scores, tau, out, (hipStream_t)stream);
+}
+
+extern "C" int pod_group_layers(const float *sim, int num_layers, int num_q_heads, int num_kv_heads, float threshold,
+                                int32_t *lowest_out)
+{
+    if (!sim || !lowest_out) return pod_fail(POD_ERR_INVALID_ARG, "sim and lowest_out must not be NULL");
+    if (num_layers < 1 || num_kv_heads < 1 || num_q_heads < 1 || num_q_heads % num_kv_heads)
+        return pod_fail(POD_ERR_INVALID_ARG, "need num_layers >= 1 and num_q_heads a positive multiple of num_kv_heads");
+    const int L = num_layers, rep = num_q_heads / num_kv_heads;
+    // similar(a, b) for kv head g: more than half of its query heads have sim >= threshold
+    auto similar = [&](int g, int a, int b) {
+        int votes = 0;
+        for (int h = g * rep; h < (g + 1) * rep; ++h) votes += sim[((size_t)h * L + a) * L + b] >= threshold;
+        return 2 * votes > rep;
+    };
+    for (int g = 0; g < num_kv_heads; ++g) {
+        int block_start = 0; // the current block is [block_start, l)
+        lowest_out[g] = 0;
+        for (int l = 1; l < L; ++l) {
+            bool joins = true;
+            for (int m = block_start; m < l && joins; ++m) joins = similar(g, l, m);
+            if (!joins) block_start = l;
+            lowest_out[(size_t)l * num_kv_heads + g] = block_start;
+        }
+    }
+    return POD_OK;
 }
 
 extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, const void *q, const void *k,
@@ -370,7 +477,7 @@ extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, 
     const pod_layout &ly = cache->ly;
     if (!q || !k || !v || !out) return pod_fail(POD_ERR_INVALID_ARG, "q, k, v and out must not be NULL");
     if (n < 1) return pod_fail(POD_ERR_INVALID_ARG, "n must be >= 1");
-    const bool lowest = layer % ly.G == 0;
+    const bool lowest = layer_lowest_all(cache, layer);
     if ((q_shared == nullptr) != (k_shared == nullptr))
         return pod_fail(POD_ERR_INVALID_ARG, "q_shared and k_shared must be given together");
     if (!lowest && !q_shared && n > ly.P)
@@ -382,7 +489,8 @@ extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, 
             return pod_fail(POD_ERR_STATE, "slot %d at layer %d is not empty", seq_slot, layer);
     }
     if (lowest) { q_shared = nullptr; k_shared = nullptr; }
-    rc = pod_launch_prefill(ly, layer, n, q, k, v, q_shared, k_shared, scale, out, (hipStream_t)stream);
+    rc = pod_launch_prefill(ly, layer, n, q, k, v, q_shared, k_shared, pod_make_headmap(cache, layer).lowest_mask, scale, out,
+                            (hipStream_t)stream);
     if (rc) return rc;
     if (write_cache) return pod_cache_fill(cache, layer, seq_slot, n, k, v, stream);
     return POD_OK;
@@ -395,8 +503,8 @@ extern "C" int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slo
     if (rc) return rc;
     const pod_layout &ly = cache->ly;
     if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
-    if (distK && layer % ly.G != 0)
-        return pod_fail(POD_ERR_INVALID_ARG, "layer %d keeps no distant keys (not the lowest layer of its block)", layer);
+    if (distK && !layer_lowest_any(cache, layer))
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d keeps no distant keys (not the lowest layer of any head's block)", layer);
     const int64_t n = cache->host_len[(size_t)layer * ly.B + seq_slot];
     if (n == 0) return POD_OK;
     return pod_launch_export(cache, layer, seq_slot, n, sinkK, sinkV, recentK, recentV, distK, distV, (hipStream_t)stream);

@@ -22,7 +22,7 @@ __global__ void clear_header_kernel(char *base, pod_layout ly, int seq_slot)
 }
 
 // One block per sequence.  Each thread moves 16-byte pieces of the (kv head, dim) row.
-__global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 *__restrict__ k_new,
+__global__ void append_kernel(char *base, pod_layout ly, pod_headmap hm, int layer, const uint4 *__restrict__ k_new,
                               const uint4 *__restrict__ v_new, const int32_t *__restrict__ positions)
 {
     const int b = blockIdx.x;
@@ -40,8 +40,6 @@ __global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 
     }
     const int slot = p < ly.S ? p : ly.S + (p - ly.S) % ly.W;
     const bool demote = p >= ly.P;          // the ring slot holds position p - W
-    const bool lowest = layer % ly.G == 0;
-    const int group = layer / ly.G;
     uint4 *proxK = (uint4 *)(base + ly.off_proxK);
     uint4 *proxV = (uint4 *)(base + ly.off_proxV);
     uint4 *distK = (uint4 *)(base + ly.off_distK);
@@ -56,7 +54,7 @@ __global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 
         if (demote) {
             const size_t t = (size_t)(p - ly.P); // distant row of position p - W
             distV[(pod_dist_row0(ly, layer, b, h) + t) * cpr + c] = proxV[pr];
-            if (lowest) distK[(pod_dist_row0(ly, group, b, h) + t) * cpr + c] = proxK[pr];
+            if ((hm.lowest_mask >> h) & 1) distK[(pod_distk_row0(ly, hm, b, h) + t) * cpr + c] = proxK[pr];
         }
         proxK[pr] = kn;
         proxV[pr] = vn;
@@ -66,12 +64,10 @@ __global__ void append_kernel(char *base, pod_layout ly, int layer, const uint4 
 }
 
 // Grid-stride over 16-byte pieces of the prompt's K/V [n][Hkv][D].
-__global__ void fill_kernel(char *base, pod_layout ly, int layer, int b, int n, const uint4 *__restrict__ k,
-                            const uint4 *__restrict__ v)
+__global__ void fill_kernel(char *base, pod_layout ly, pod_headmap hm, int layer, int b, int n,
+                            const uint4 *__restrict__ k, const uint4 *__restrict__ v)
 {
     const int cpr = ly.D / 8;
-    const bool lowest = layer % ly.G == 0;
-    const int group = layer / ly.G;
     const int rec_lo = n - ly.W > ly.S ? n - ly.W : ly.S; // first position of the recent window
     uint4 *proxK = (uint4 *)(base + ly.off_proxK);
     uint4 *proxV = (uint4 *)(base + ly.off_proxV);
@@ -90,18 +86,17 @@ __global__ void fill_kernel(char *base, pod_layout ly, int layer, int b, int n, 
         } else {
             const size_t t = (size_t)(p - ly.S);
             distV[(pod_dist_row0(ly, layer, b, h) + t) * cpr + c] = v[idx];
-            if (lowest) distK[(pod_dist_row0(ly, group, b, h) + t) * cpr + c] = k[idx];
+            if ((hm.lowest_mask >> h) & 1) distK[(pod_distk_row0(ly, hm, b, h) + t) * cpr + c] = k[idx];
         }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) lens_ptr(base, ly)[(size_t)layer * ly.B + b] = n;
 }
 
 // Gather the logical views [tokens][Hkv][D] in position order.
-__global__ void export_kernel(const char *base, pod_layout ly, int layer, int b, int n, uint4 *sinkK, uint4 *sinkV,
-                              uint4 *recK, uint4 *recV, uint4 *dK, uint4 *dV)
+__global__ void export_kernel(const char *base, pod_layout ly, pod_headmap hm, int layer, int b, int n, uint4 *sinkK,
+                              uint4 *sinkV, uint4 *recK, uint4 *recV, uint4 *dK, uint4 *dV)
 {
     const int cpr = ly.D / 8;
-    const int group = layer / ly.G;
     const int n_sink = n < ly.S ? n : ly.S;
     const int rec_lo = n - ly.W > ly.S ? n - ly.W : ly.S;
     const uint4 *proxK = (const uint4 *)(base + ly.off_proxK);
@@ -128,7 +123,8 @@ __global__ void export_kernel(const char *base, pod_layout ly, int layer, int b,
             const size_t t = (size_t)(p - ly.S);
             const size_t o = (t * ly.Hkv + h) * cpr + c;
             if (dV) dV[o] = distV[(pod_dist_row0(ly, layer, b, h) + t) * cpr + c];
-            if (dK) dK[o] = distK[(pod_dist_row0(ly, group, b, h) + t) * cpr + c];
+            // (heads for which this layer is not a lowest layer keep no keys here: zeros)
+            if (dK) dK[o] = ((hm.lowest_mask >> h) & 1) ? distK[(pod_distk_row0(ly, hm, b, h) + t) * cpr + c] : make_uint4(0, 0, 0, 0);
         }
     }
 }
@@ -164,7 +160,7 @@ int pod_launch_append(const pod_cache *c, int layer, const void *k_new, const vo
 {
     int threads = c->ly.Hkv * (c->ly.D / 8);
     threads = threads < 64 ? 64 : (threads > 1024 ? 1024 : (threads + 63) / 64 * 64);
-    hipLaunchKernelGGL(append_kernel, dim3(B), dim3(threads), 0, st, c->base, c->ly, layer, (const uint4 *)k_new,
+    hipLaunchKernelGGL(append_kernel, dim3(B), dim3(threads), 0, st, c->base, c->ly, pod_make_headmap(c, layer), layer, (const uint4 *)k_new,
                        (const uint4 *)v_new, positions);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
@@ -173,7 +169,7 @@ int pod_launch_append(const pod_cache *c, int layer, const void *k_new, const vo
 int pod_launch_fill(const pod_cache *c, int layer, int seq_slot, int n, const void *k, const void *v, hipStream_t st)
 {
     const size_t items = (size_t)n * c->ly.Hkv * (c->ly.D / 8);
-    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, c->base, c->ly, layer, seq_slot, n,
+    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, c->base, c->ly, pod_make_headmap(c, layer), layer, seq_slot, n,
                        (const uint4 *)k, (const uint4 *)v);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
@@ -184,7 +180,7 @@ int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, vo
 {
     const size_t items = (size_t)n * c->ly.Hkv * (c->ly.D / 8);
     hipLaunchKernelGGL(export_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, (const char *)c->base, c->ly,
-                       layer, seq_slot, (int)n, (uint4 *)sinkK, (uint4 *)sinkV, (uint4 *)recK, (uint4 *)recV,
+                       pod_make_headmap(c, layer), layer, seq_slot, (int)n, (uint4 *)sinkK, (uint4 *)sinkV, (uint4 *)recK, (uint4 *)recV,
                        (uint4 *)distK, (uint4 *)distV);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;

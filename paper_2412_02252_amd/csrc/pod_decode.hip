@@ -90,6 +90,9 @@ struct decode_params {
     int32_t *skip;   // [B][Hq]: 1 where the upper layer left the distant part out (written by its distant pass)
     float tau;
     int32_t hlen[kMaxHostLens];
+    // per kv head: (slot * max_batch of the distant-key store the head reads at this layer) | sign bit if this
+    // layer is the lowest of the head's block (then every logit of the head uses q, not q_shared)
+    int32_t head_arg[kMaxKvHeads];
 };
 static_assert(offsetof(decode_params, hot) == 0, "hot lines first");
 
@@ -107,6 +110,12 @@ __device__ inline decode_hot load_hot_args()
     const i32x32 raw = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19,
                                                20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
     return __builtin_bit_cast(decode_hot, raw);
+}
+__device__ inline int load_head_arg(int h)
+{
+    const volatile __attribute__((address_space(4))) int32_t *ka =
+        (const volatile __attribute__((address_space(4))) int32_t *)__builtin_amdgcn_kernarg_segment_ptr();
+    return ka[offsetof(decode_params, head_arg) / 4 + (h < kMaxKvHeads ? h : 0)];
 }
 __device__ inline int load_hlen_arg(int b)
 {
@@ -197,6 +206,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const decode_hot hot = load_hot_args();
     const int c = MODE == 3 ? (int)blockIdx.x + hot.max_nd : (int)blockIdx.x;
     const int n_host = load_hlen_arg(b);
+    const int head_arg = load_head_arg(h);
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
     const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, chunk = hot.chunk, max_nd = hot.max_nd;
     const bool use_hlen = hot.use_hlen != 0;
@@ -224,9 +234,10 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
     const size_t pair = (size_t)b * hkv + h;
-    const gvec_ptr Kb = (gvec_ptr)(distant ? kdist + pair * cd * CPR : kprox + pair * prows * CPR);
+    const size_t kslot_row = (size_t)(head_arg & 0x7fffffff) + b; // distant keys live per (kv head, block): [slot][B][cd]
+    const gvec_ptr Kb = (gvec_ptr)(distant ? kdist + kslot_row * cd * CPR : kprox + pair * prows * CPR);
     const gvec_ptr Vb = (gvec_ptr)(distant ? vdist + pair * cd * CPR : vprox + pair * prows * CPR);
-    const pod_bf16 *qsrc = (distant && hot.q_shared) ? hot.q_shared : hot.q;
+    const pod_bf16 *qsrc = (distant && hot.q_shared && head_arg >= 0) ? hot.q_shared : hot.q;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m16 = lane & 15, j = lane >> 4;
@@ -645,9 +656,16 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 {
     const pod_layout &ly = c->ly;
     const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
-    const int lowest = layer - layer % ly.G;
+    const int H = ly.Hkv;
+    bool lowest_all = true;
+    for (int h = 0; h < H; ++h) lowest_all = lowest_all && c->lowest[(size_t)layer * H + h] == layer;
+    // the layer whose lengths the device compares with this layer's: the block's lowest layer when all kv heads
+    // share it (the host has already compared every head's lowest layer through its mirror)
+    const int lowest = c->uniform ? c->lowest[(size_t)layer * H] : layer;
     decode_params p;
-    p.hot.kdist = (const u32x4 *)(c->base + ly.off_distK) + pod_dist_row0(ly, layer / ly.G, 0, 0) * row16;
+    const pod_headmap hm = pod_make_headmap(c, layer);
+    for (int h = 0; h < H; ++h) p.head_arg[h] = hm.kslot_row[h] | (((hm.lowest_mask >> h) & 1) ? (int32_t)0x80000000 : 0);
+    p.hot.kdist = (const u32x4 *)(c->base + ly.off_distK);
     p.hot.vdist = (const u32x4 *)(c->base + ly.off_distV) + pod_dist_row0(ly, layer, 0, 0) * row16;
     p.hot.kprox = (const u32x4 *)(c->base + ly.off_proxK) + pod_prox_row0(ly, layer, 0, 0) * row16;
     p.hot.vprox = (const u32x4 *)(c->base + ly.off_proxV) + pod_prox_row0(ly, layer, 0, 0) * row16;
@@ -660,14 +678,14 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.flag = (int32_t *)(c->base + ly.off_flag);
     p.maxctx = ly.maxctx;
     p.out = (pod_bf16 *)out;
-    p.mode = scores ? (layer == lowest ? 1 : (tau >= 0.f ? 3 : 2)) : 0;
+    p.mode = scores ? (lowest_all ? 1 : (tau >= 0.f ? 3 : 2)) : 0;
     p.score_hdr = (int32_t *)scores;
     p.gate_d = scores ? (float *)((char *)scores + score_tag_bytes(ly)) : nullptr;
     p.skip = scores ? (int32_t *)((char *)scores + score_tag_bytes(ly) + score_gate_bytes(ly)) : nullptr;
     p.tau = tau;
     p.scores = scores ? (float *)((char *)scores + pod_score_header_bytes(ly)) : nullptr;
     p.score_stride = (int32_t)pod_score_stride(ly);
-    p.block_id = layer / ly.G;
+    p.block_id = c->kslot[(size_t)layer * H] / H; // uniform tables only (score reuse): number of the block
     p.hot.use_hlen = B <= kMaxHostLens;
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];

@@ -17,7 +17,9 @@
 //            the ring fills from its first slot, so the live proximal rows are
 //            always the contiguous slots [0, min(n, P)).
 // distV    : [L][B][Hkv][Cd][D]  Cd = max_context - P; row t = position S + t
-// distK    : [L/G][B][Hkv][Cd][D] keys of the block's lowest layer only
+// distK    : [slots][B][Cd][D]    keys of a block's lowest layer only: one slot per
+//            (kv head, block of that head), numbered in (layer, head) order of the lowest
+//            layers; uniform blocks of G layers give slot (l / G) * Hkv + h
 //
 // Head-major on purpose: the rows one (sequence, kv head) pair streams at decode
 // time are one contiguous run, so a split-K chunk is a single linear read.
@@ -28,6 +30,7 @@ struct pod_layout {
     int32_t P;   // S + W
     int32_t Cd;  // distant rows per (layer, slot, head)
     int32_t rep; // Hq / Hkv
+    int32_t nslots; // distant-key stores: (kv head, block) pairs
     size_t off_lens, off_flag, off_proxK, off_proxV, off_distV, off_distK, total_bytes;
 };
 
@@ -37,15 +40,33 @@ __host__ __device__ inline size_t pod_prox_row0(const pod_layout &ly, int layer,
 {
     return (((size_t)layer * ly.B + b) * ly.Hkv + h) * (size_t)ly.P;
 }
-__host__ __device__ inline size_t pod_dist_row0(const pod_layout &ly, int layer_or_group, int b, int h)
+__host__ __device__ inline size_t pod_dist_row0(const pod_layout &ly, int layer, int b, int h) // distant values
 {
-    return (((size_t)layer_or_group * ly.B + b) * ly.Hkv + h) * (size_t)ly.Cd;
+    return (((size_t)layer * ly.B + b) * ly.Hkv + h) * (size_t)ly.Cd;
+}
+
+// One layer's view of the block table, passed to kernels by value.
+constexpr int kMaxKvHeads = 64;
+struct pod_headmap {
+    uint64_t lowest_mask;           // bit h: this layer is the lowest of head h's block (it owns that store)
+    int32_t uniform_row0;           // >= 0: every head h reads slot row uniform_row0 + h * B (uniform blocks); the
+                                    // table below is then not consulted (a per-thread index into kernel arguments
+                                    // is a memory load, which the cache-update kernels avoid in the common case)
+    int32_t kslot_row[kMaxKvHeads]; // slot * B of the distant-key store head h reads at this layer
+};
+__host__ __device__ inline size_t pod_distk_row0(const pod_layout &ly, const pod_headmap &hm, int b, int h) // distant keys
+{
+    const size_t row = hm.uniform_row0 >= 0 ? (size_t)hm.uniform_row0 + (size_t)h * ly.B : (size_t)hm.kslot_row[h];
+    return (row + b) * (size_t)ly.Cd;
 }
 
 struct pod_cache {
     pod_layout ly;
     char *base;        // device buffer (caller's)
     int64_t *host_len; // [L][B] mirror
+    int32_t *lowest;   // [L][Hkv] lowest layer of the block of (layer, kv head)
+    int32_t *kslot;    // [L][Hkv] distant-key slot that (layer, kv head) reads
+    bool uniform;      // every kv head has the same blocks
     int device;
     // optional event pairs around the decode partial kernel (pod_profile_*)
     hipEvent_t *prof_ev; // [2 * prof_cap]
@@ -61,6 +82,8 @@ int pod_hip_fail(hipError_t e, const char *what);
         hipError_t e__ = (expr);                                 \
         if (e__ != hipSuccess) return pod_hip_fail(e__, #expr);  \
     } while (0)
+
+pod_headmap pod_make_headmap(const pod_cache *c, int layer);
 
 // launchers (each validates nothing: the API layer did)
 int pod_launch_clear_header(const pod_cache *c, hipStream_t st);
@@ -80,5 +103,7 @@ size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (seque
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
+// lowest_mask: bit h set = kv head h takes every logit from (q, k); clear = distant logits from (q_shared, k_shared)
 int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
-                       const void *q_shared, const void *k_shared, float scale, void *out, hipStream_t st);
+                       const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
+                       hipStream_t st);

@@ -50,6 +50,7 @@ struct prefill_params {
     const pod_bf16 *q, *k, *v, *qs, *ks; // qs/ks NULL: own q,k serve every key
     pod_bf16 *out;
     float scale_log2e;
+    unsigned long long lowest_mask; // bit h: kv head h takes every logit from (q, k) even if qs/ks are given
 };
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     const int iw0 = i0 + wave * 32;
     const int iw_last = min(iw0 + 32, p.n) - 1;
     const int irow = iw0 + n32;
-    const bool has_shared = p.qs != nullptr;
+    const bool has_shared = p.qs != nullptr && !((p.lowest_mask >> kvh) & 1);
     const int S = p.S, W = p.W;
     const float c = p.scale_log2e;
 
@@ -497,7 +498,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 } // namespace
 
 int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
-                       const void *q_shared, const void *k_shared, float scale, void *out, hipStream_t st)
+                       const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
+                       hipStream_t st)
 {
     (void)layer;
     prefill_params p;
@@ -506,6 +508,7 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, co
     p.qs = (const pod_bf16 *)q_shared; p.ks = (const pod_bf16 *)k_shared;
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
+    p.lowest_mask = lowest_mask;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
     const dim3 grid((unsigned)((n + 127) / 128) * (unsigned)ly.Hq);
     // dynamic LDS: two K slots and two V slots of kBN tokens x D bf16 each (64 KB at D = 128)

@@ -22,12 +22,16 @@ def assert_close(got_bf16: torch.Tensor, ref_f64: np.ndarray, what=""):
 
 
 class Case:
-    def __init__(self, L, G, Hq, Hkv, d, S, W, B, max_ctx, seed=1, device="cuda:0", with_oracle_cache=True, **kgen):
+    def __init__(self, L, G, Hq, Hkv, d, S, W, B, max_ctx, seed=1, device="cuda:0", with_oracle_cache=True,
+                 block_lowest=None, **kgen):
         self.L, self.G, self.Hq, self.Hkv, self.d, self.S, self.W, self.B = L, G, Hq, Hkv, d, S, W, B
         self.max_ctx, self.seed, self.dev, self.kgen = max_ctx, seed, device, kgen
-        self.cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx)
+        # lowest[l][h]: lowest layer of the block of (layer l, kv head h); uniform blocks of G layers by default
+        self.lowest = (np.array([[l - l % G] * Hkv for l in range(L)], dtype=np.int32) if block_lowest is None
+                       else np.ascontiguousarray(block_lowest, dtype=np.int32))
+        self.cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx, block_lowest=block_lowest)
         self.gpu = pod.PodCache(self.cfg, device)
-        self.cpu = po.Cache(L, G, Hkv, d, S, W, B, max_ctx) if with_oracle_cache else None
+        self.cpu = po.Cache(L, G, Hkv, d, S, W, B, max_ctx, block_lowest=block_lowest) if with_oracle_cache else None
         self.scale = 1.0 / math.sqrt(d)
 
     # ---- inputs (device = "cpu" or the GPU) -------------------------------------------
@@ -64,10 +68,19 @@ class Case:
         """Query of the token at position ctx[b]-1 of each sequence: [B][Hq][d]."""
         return torch.cat([self.queries(layer, b, 1, device, pos0=max(n, 1) - 1) for b, n in enumerate(ctx)]).contiguous()
 
+    def shared_queries(self, layer, ctx, device):
+        """q_shared for `layer`: head by head the query of the lowest layer of that head's block; None if the
+        layer is the lowest for every head."""
+        src = self.lowest[layer]
+        if (src == layer).all():
+            return None
+        rep = self.Hq // self.Hkv
+        per_layer = {int(l): self.decode_queries(int(l), ctx, device) for l in set(src.tolist())}
+        return torch.stack([per_layer[int(src[h // rep])][:, h] for h in range(self.Hq)], dim=1).contiguous()
+
     def decode(self, layer, ctx, max_context_len=0):
-        lowest = layer - layer % self.G
         q = self.decode_queries(layer, ctx, self.dev)
-        qs = self.decode_queries(lowest, ctx, self.dev) if lowest != layer else None
+        qs = self.shared_queries(layer, ctx, self.dev)
         ctx_t = torch.tensor(ctx, dtype=torch.int32, device=self.dev)
         return self.gpu.pod_decode_attention(layer, q, qs, ctx_t, self.scale, max_context_len=max_context_len)
 
@@ -78,9 +91,9 @@ class Case:
         return self.gpu.pod_decode_attention_reuse(layer, q, ctx_t, self.scale, scores, max_context_len=max_context_len)
 
     def decode_ref(self, layer, ctx):
-        lowest = layer - layer % self.G
         q = gen.bf16_bits(self.decode_queries(layer, ctx, "cpu"))
-        qs = gen.bf16_bits(self.decode_queries(lowest, ctx, "cpu")) if lowest != layer else None
+        qs = self.shared_queries(layer, ctx, "cpu")
+        qs = gen.bf16_bits(qs) if qs is not None else None
         return self.cpu.decode_attention(layer, q, qs, ctx, self.scale)
 
     def assert_cache_equal(self, layer, seq):

@@ -101,11 +101,11 @@ def test_wrong_context_length_is_flagged_not_faulted():
     with pytest.raises(pod.PodError) as e:
         c.gpu.pod_cache_check()
     assert e.value.code == pod.binding.ERR_STATE
-    # lowest layer out of step with the upper layer
+    # lowest layer out of step with the upper layer: the host mirror knows, the call is refused
     c.append(1, [100, 50])
-    c.decode(1, [101, 51])
-    with pytest.raises(pod.PodError):
-        c.gpu.pod_cache_check()
+    with pytest.raises(pod.PodError) as e:
+        c.decode(1, [101, 51])
+    assert e.value.code == pod.binding.ERR_STATE
 
 
 def test_decode_steps_with_demotion_match_oracle_every_step():

@@ -1,0 +1,105 @@
+"""GPU: head-wise blocks (a table lowest[layer][kv head] instead of uniform blocks) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_02252_amd as pod
+from oracle import pod_oracle as po
+from pod_inputs import gen
+from podcase import Case, assert_close
+
+pytestmark = pytest.mark.gpu
+
+# kv head 0: one block of all four layers; head 1: {0,1},{2,3}; head 2: every layer alone
+MAP4 = np.array([[0, 0, 0], [0, 0, 1], [0, 2, 2], [0, 2, 3]], dtype=np.int32)
+
+
+def gathered(c, layer, what, seq, n, device):
+    """k_shared [n][Hkv][d] or q_shared [n][Hq][d] for a prompt: head by head from the lowest layer of its block."""
+    src = c.lowest[layer]
+    rep = c.Hq // c.Hkv
+    if what == "k":
+        per = {int(l): c.keys(int(l), seq, n, device) for l in set(src.tolist())}
+        return torch.stack([per[int(src[h])][:, h] for h in range(c.Hkv)], dim=1).contiguous()
+    per = {int(l): c.queries(int(l), seq, n, device) for l in set(src.tolist())}
+    return torch.stack([per[int(src[h // rep])][:, h] for h in range(c.Hq)], dim=1).contiguous()
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_cache_and_decode_with_a_headwise_table(d):
+    L, Hq, Hkv, S, W = 4, 6, 3, 8, 32
+    lens = [150, 41, 300]
+    c = Case(L, 1, Hq, Hkv, d, S, W, len(lens), 400, seed=700 + d, block_lowest=MAP4)
+    for layer in range(L):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    for step in range(3):                                   # appends with demotion, every layer in step
+        pos = [n + step for n in lens]
+        for layer in range(L):
+            c.append(layer, pos)
+        ctx = [p + 1 for p in pos]
+        for layer in range(L):
+            assert_close(c.decode(layer, ctx), c.decode_ref(layer, ctx), f"step {step} layer {layer}")
+    for layer in range(L):
+        for b in range(len(lens)):
+            c.assert_cache_equal(layer, b)                  # incl. distant keys only where the layer is a head's lowest
+    c.gpu.pod_cache_check()
+    live, _ = pod.pod_cache_live_bytes(c.cfg, 1)            # (sizes are per sequence)
+    assert c.cpu.stored_elems() * 2 == sum(pod.pod_cache_live_bytes(c.cfg, n + 3)[0] for n in lens)
+
+
+def test_prefill_with_a_headwise_table():
+    L, Hq, Hkv, d, S, W, n = 4, 6, 3, 128, 8, 40, 333
+    c = Case(L, 1, Hq, Hkv, d, S, W, 1, 600, seed=711, block_lowest=MAP4)
+    rows = np.arange(n)
+    for layer in range(L):
+        q, k, v = c.queries(layer, 0, n, c.dev), c.keys(layer, 0, n, c.dev), c.values(layer, 0, n, c.dev)
+        all_lowest = bool((c.lowest[layer] == layer).all())
+        qs = None if all_lowest else gathered(c, layer, "q", 0, n, c.dev)
+        ks = None if all_lowest else gathered(c, layer, "k", 0, n, c.dev)
+        out = c.gpu.pod_prefill_attention(layer, 0, q, k, v, qs, ks, c.scale, write_cache=True)
+        qc = gen.bf16_bits(c.queries(layer, 0, n, "cpu"))
+        kc, vc = gen.bf16_bits(c.keys(layer, 0, n, "cpu")), gen.bf16_bits(c.values(layer, 0, n, "cpu"))
+        qsc = None if all_lowest else gen.bf16_bits(gathered(c, layer, "q", 0, n, "cpu"))
+        ksc = None if all_lowest else gen.bf16_bits(gathered(c, layer, "k", 0, n, "cpu"))
+        assert_close(out, po.pod_attention(qc, kc, vc, qsc, ksc, rows, S, W, c.scale), f"layer {layer}")
+        c.cpu.fill(layer, 0, kc, vc)
+        c.assert_cache_equal(layer, 0)
+    # the cache prefill built serves decode
+    for layer in range(L):
+        c.append(layer, [n])
+    for layer in range(L):
+        assert_close(c.decode(layer, [n + 1]), c.decode_ref(layer, [n + 1]), f"decode layer {layer}")
+    c.gpu.pod_cache_check()
+
+
+def test_explicit_uniform_table_behaves_like_group_size():
+    L, G, Hq, Hkv, d, S, W, n = 4, 2, 8, 2, 128, 8, 32, 200
+    uni = np.array([[l - l % G] * Hkv for l in range(L)], dtype=np.int32)
+    a = Case(L, G, Hq, Hkv, d, S, W, 1, 300, seed=720)
+    b = Case(L, 1, Hq, Hkv, d, S, W, 1, 300, seed=720, block_lowest=uni)
+    for layer in range(L):
+        a.fill(layer, 0, n)
+        b.fill(layer, 0, n)
+    for layer in range(L):
+        assert torch.equal(a.decode(layer, [n]), b.decode(layer, [n]))
+    scores = b.gpu.new_score_buffer()                       # a uniform table also allows score reuse
+    for layer in range(L):
+        assert_close(b.decode_reuse(layer, [n], scores), b.decode_ref(layer, [n]), f"reuse layer {layer}")
+
+
+def test_score_reuse_and_gating_refuse_headwise_tables_and_lagging_lowest_layers_are_caught():
+    c = Case(4, 1, 6, 3, 64, 8, 32, 1, 300, seed=730, block_lowest=MAP4)
+    for layer in range(4):
+        c.fill(layer, 0, 100)
+    scores = c.gpu.new_score_buffer()
+    ctx = torch.tensor([100], dtype=torch.int32, device=c.dev)
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_decode_attention_reuse(0, c.decode_queries(0, [100], c.dev), ctx, c.scale, scores)
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_decode_attention_gated(0, c.decode_queries(0, [100], c.dev), ctx, c.scale, 0.5, scores)
+    # layer 3 moves ahead of layer 2, the lowest layer of kv head 1's block: refused on the host
+    c.append(3, [100])
+    with pytest.raises(pod.PodError) as e:
+        c.decode(3, [101])
+    assert e.value.code == pod.binding.ERR_STATE
