@@ -190,7 +190,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     };
 
     // ---- global -> LDS.  Wave w moves K fragments w*NQK/4 .. and the V rows w*16 .. w*16+15.
-    constexpr int KPW = NQK / 4;                 // K fragments per wave and tile
     constexpr int VRI = 64 / CPR;                // V rows per wave instruction (1 KB)
     constexpr int VPW = 16 / VRI;                // V instructions per wave and tile
     constexpr int VSWZ = 4 * ((CPR / 4 - 1) & 3); // piece-permutation mask: 12 at D = 128, 4 at D = 64
@@ -199,35 +198,40 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     // prompt's last, partly filled tile takes a separate path that clamps its rows per lane.
     const unsigned rowb = (unsigned)p.Hkv * D * 2;
     const int v_r = lane / CPR;                                         // row inside a V instruction
-    const unsigned k_col = (unsigned)(kvh * D * 2 + jj * 16);           // + 32 s
+    // K rows: a lane of a request fetches piece (slot piece ^ krot(row)) of its row, krot(row) = row * CPR / 16 mod CPR
+    // (16 consecutive rows then put the same piece into 16 different 16-byte bank groups)
+    auto k_col = [&](int x) { // x-th request of the wave: LDS rows 16 wave + VRI x + v_r
+        const int rot = (((VRI * x + v_r) * CPR) / 16) & (CPR - 1);
+        return (unsigned)(kvh * D * 2 + 16 * ((lane % CPR) ^ rot));
+    };
     const unsigned v_col = (unsigned)(kvh * D * 2 + 16 * ((lane % CPR) ^ ((4 * (v_r & 3)) & VSWZ)));
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);            // scalar copy: LDS destinations stay scalar
-    unsigned k_off[KPW], v_off[VPW];
+    unsigned k_off[VPW], v_off[VPW];
 #pragma unroll
-    for (int x = 0; x < KPW; ++x) {
-        const int f = wave * KPW + x, fkb = f / KST, fs = f % KST;      // fragment (key block, k-step)
-        k_off[x] = (unsigned)(32 * fkb + n32) * rowb + k_col + 32 * fs;
+    for (int x = 0; x < VPW; ++x) {
+        v_off[x] = (unsigned)(16 * wave + VRI * x + v_r) * rowb + v_col;
+        k_off[x] = (unsigned)(16 * wave + VRI * x + v_r) * rowb + k_col(x);
     }
-#pragma unroll
-    for (int x = 0; x < VPW; ++x) v_off[x] = (unsigned)(16 * wave + VRI * x + v_r) * rowb + v_col;
     typedef const __attribute__((address_space(1))) void *gvoid_ptr;
     typedef __attribute__((address_space(3))) void *lvoid_ptr;
-    const char *const k_dst0 = ldsK + wave_s * (KPW * FRAG);            // this wave's part of K slot 0
+    const char *const k_dst0 = ldsK + wave_s * (16 * D * 2);            // this wave's part of K slot 0
     const char *const v_dst0 = ldsV + wave_s * (16 * D * 2);            // this wave's part of V slot 0
     auto request_k = [&](int kt, bool phaseD, int slot) {
         const int j0 = kt * kBN;
         const gbyte_ptr base = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
         if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
-            for (int x = 0; x < KPW; ++x)
-                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + k_off[x]), (lvoid_ptr)(k_dst0 + slot * KBUF + x * FRAG), 16, 0, 0);
+            for (int x = 0; x < VPW; ++x) {
+                unsigned off = k_off[x];
+                asm volatile("" : "+v"(off)); // (else the compiler keeps 64-bit copies of all offsets live: 8 more registers)
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(k_dst0 + slot * KBUF + x * (VRI * D * 2)), 16, 0, 0);
+            }
         } else {
             asm volatile("" ::: "memory"); // (keeps this a real branch: merged, both paths would pay for the clamping)
 #pragma unroll
-            for (int x = 0; x < KPW; ++x) {
-                const int f = wave * KPW + x, fkb = f / KST, fs = f % KST;
-                const unsigned off = (unsigned)min(32 * fkb + n32, p.n - 1 - j0) * rowb + k_col + 32 * fs;
-                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(k_dst0 + slot * KBUF + x * FRAG), 16, 0, 0);
+            for (int x = 0; x < VPW; ++x) {
+                const unsigned off = (unsigned)min(16 * wave + VRI * x + v_r, p.n - 1 - j0) * rowb + k_col(x);
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(k_dst0 + slot * KBUF + x * (VRI * D * 2)), 16, 0, 0);
             }
         }
     };
@@ -236,8 +240,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         const gbyte_ptr base = (gbyte_ptr)p.v + (size_t)j0 * rowb;
         if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
-            for (int x = 0; x < VPW; ++x)
-                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + v_off[x]), (lvoid_ptr)(v_dst0 + slot * VBUF + x * (VRI * D * 2)), 16, 0, 0);
+            for (int x = 0; x < VPW; ++x) {
+                unsigned off = v_off[x];
+                asm volatile("" : "+v"(off));
+                __builtin_amdgcn_global_load_lds((gvoid_ptr)(base + off), (lvoid_ptr)(v_dst0 + slot * VBUF + x * (VRI * D * 2)), 16, 0, 0);
+            }
         } else {
             asm volatile("" ::: "memory");
 #pragma unroll
@@ -248,7 +255,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         }
     };
     // read offsets: K fragment lane slot; V^T transpose-read source row/piece of this lane
-    const int k_rd = 16 * lane;
+    // K fragment (key block kb, k-step s): lane (row n32, jj) reads piece 2 s + jj of row 32 kb + n32, stored at
+    // piece (2 s + jj) ^ krot(row) = (jj ^ krot) ^ 2 s; krot(32 kb + n32) = krot(n32)
+    const int k_rot = ((n32 * CPR) / 16) & (CPR - 1);
+    const int k_rd0 = n32 * (D * 2) + 16 * (jj ^ k_rot);
     const int v_s = lane & 15;
     // row 4 jj + s/4 of the 16-token k-step (+8 for the second read), dims 16 ((lane/16) & 1) + 4 (s % 4) of the
     // 32-dim block db; the piece index is XORed with 4 (row % 4) = 4 (s / 4), the dim block enters as XOR 64 db
@@ -297,7 +307,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 
     auto kfrag = [&](const char *kl, int op) { // QK MFMA number op: the two key blocks alternate
         const int s = op / NKB, kb = op % NKB;
-        return *(const u32x4 *)(kl + (kb * KST + s) * FRAG + k_rd);
+        return *(const u32x4 *)(kl + kb * 32 * (D * 2) + (k_rd0 ^ (32 * s)));
     };
     auto vfrag = [&](const char *vl, int m) {  // PV MFMA number m = ks * NDB + db
         const int ks = m / NDB, db = m % NDB;
