@@ -211,6 +211,19 @@ int pod_decode_attention_gated(pod_cache *cache, int layer, const void *q, const
 int pod_score_skip_offset(const pod_config *cfg, size_t *offset);
 
 /*
+ * Inter-layer attention similarity for the offline grouping ("Attention Similarity Measurement"):
+ * sim[h][a][b] = 1 - mean over the sampled rows of the Jensen-Shannon divergence (base-2
+ * logarithms, so in [0, 1]) between the attention rows of layers a and b for head h; 1 on the
+ * diagonal.  One GPU pass over the rows per layer pair.
+ *   att : dev float [num_layers][num_heads][rows][n], every row a probability vector (the last
+ *         `q` tokens of `N` samples flattened into rows = N * q); 16-byte aligned, rows * n a
+ *         multiple of 4
+ *   sim : dev float [num_heads][num_layers][num_layers], fully written
+ * Feed sim (copied to the host) to pod_group_layers.
+ */
+int pod_layer_similarity(const float *att, int num_layers, int num_heads, int rows, int n, float *sim, void *stream);
+
+/*
  * Offline grouping of layers into head-wise blocks ("Greedy Layer Grouping Algorithm"; host
  * arrays, no GPU work).  sim: float [num_q_heads][num_layers][num_layers], sim[h][a][b] the
  * attention similarity of layers a and b for query head h.  For each kv head, bottom-up: layer

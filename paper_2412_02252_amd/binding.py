@@ -21,7 +21,7 @@ EXPORTS = [
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
-    "pod_group_layers",
+    "pod_group_layers", "pod_layer_similarity",
 ]
 
 
@@ -75,6 +75,7 @@ def load():
                                        vp, C.c_size_t, vp, vp],
         "pod_score_skip_offset": [cfgp, szp],
         "pod_group_layers": [vp, C.c_int, C.c_int, C.c_int, C.c_float, vp],
+        "pod_layer_similarity": [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp],
         "pod_decode_attention_reuse": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp,
                                        C.c_size_t, vp, vp],
         "pod_profile_enable": [vp, C.c_int],
@@ -132,6 +133,14 @@ def pod_group_layers(sim, num_kv_heads, threshold=0.5):
     _check(load().pod_group_layers(sim.ctypes.data_as(C.c_void_p), L, Hq, num_kv_heads, float(threshold),
                                    out.ctypes.data_as(C.c_void_p)))
     return out
+
+
+def pod_layer_similarity(att: torch.Tensor) -> torch.Tensor:
+    """att: CUDA float32 [L][H][rows][n] attention rows; returns CUDA float32 sim [H][L][L]."""
+    L, H, R, n = att.shape
+    sim = torch.empty((H, L, L), dtype=torch.float32, device=att.device)
+    _check(load().pod_layer_similarity(_ptr(att, torch.float32), L, H, R, n, _ptr(sim, torch.float32), _stream()))
+    return sim
 
 
 def pod_cache_bytes(cfg: PodConfig) -> int:

@@ -442,6 +442,19 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
                              workspace, workspace_bytes, scores, tau, out, (hipStream_t)stream);
 }
 
+extern "C" int pod_layer_similarity(const float *att, int num_layers, int num_heads, int rows, int n, float *sim,
+                                    void *stream)
+{
+    if (!att || !sim) return pod_fail(POD_ERR_INVALID_ARG, "att and sim must not be NULL");
+    if (num_layers < 1 || num_heads < 1 || rows < 1 || n < 1)
+        return pod_fail(POD_ERR_INVALID_ARG, "num_layers, num_heads, rows and n must be >= 1");
+    if (num_heads > 65535 || (int64_t)num_layers * (num_layers - 1) / 2 > INT32_MAX)
+        return pod_fail(POD_ERR_INVALID_ARG, "too many heads or layer pairs for one launch");
+    if (((uintptr_t)att % 16) || ((size_t)rows * n) % 4)
+        return pod_fail(POD_ERR_INVALID_ARG, "att must be 16-byte aligned and rows * n a multiple of 4");
+    return pod_launch_similarity(att, num_layers, num_heads, rows, n, sim, (hipStream_t)stream);
+}
+
 extern "C" int pod_group_layers(const float *sim, int num_layers, int num_q_heads, int num_kv_heads, float threshold,
                                 int32_t *lowest_out)
 {

@@ -99,6 +99,7 @@ int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, vo
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
                       void *scores, float tau, void *out, hipStream_t st);
+int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *sim, hipStream_t st);
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start

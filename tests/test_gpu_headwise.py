@@ -103,3 +103,57 @@ def test_score_reuse_and_gating_refuse_headwise_tables_and_lagging_lowest_layers
     with pytest.raises(pod.PodError) as e:
         c.decode(3, [101])
     assert e.value.code == pod.binding.ERR_STATE
+
+
+# ---------------------------------------------------------------- attention similarity -> grouping -> table
+
+from oracle import pod_grouping as pg
+
+
+@pytest.mark.parametrize("L,H,R,n", [(3, 2, 4, 64), (5, 4, 6, 1000), (2, 1, 1, 4), (4, 3, 3, 4100)])
+def test_layer_similarity_matches_the_oracle(L, H, R, n):
+    rng = np.random.default_rng(L * 1000 + n)
+    att = rng.dirichlet(np.full(n, 0.3), size=(L, H, R)).astype(np.float32)
+    att[0, 0, 0, : n // 2] = 0                               # exact zeros: 0 log 0 = 0
+    att[0, 0, 0, n // 2] = 1e-41                             # and a subnormal entry
+    att[0, 0, 0] /= att[0, 0, 0].sum()
+    if L > 1:
+        att[1] = att[0]                                      # two identical layers: similarity exactly 1
+    got = pod.pod_layer_similarity(torch.from_numpy(att).cuda()).cpu().numpy()
+    ref = np.ones((H, L, L))
+    for h in range(H):
+        for a in range(L):
+            for b in range(a + 1, L):
+                ref[h, a, b] = ref[h, b, a] = pg.layer_similarity(att[a, h][None], att[b, h][None])
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-5)  # fp32 sums of up to 25000 terms of size <= 1
+    if L > 1:
+        assert np.abs(got[:, 0, 1] - 1).max() < 1e-6
+    assert (got >= -1e-6).all() and (got <= 1 + 1e-6).all()
+
+
+def test_similarity_to_grouping_to_cache_table():
+    """Layers 0-2 share one attention pattern, layers 3-4 another (plus noise), per head differently:
+    the GPU similarity, the host grouping and a cache built from the table agree with the oracle chain."""
+    rng = np.random.default_rng(99)
+    L, Hq, Hkv, R, n = 5, 4, 2, 8, 256
+    base = rng.dirichlet(np.full(n, 0.1), size=(2, Hq, R))
+    att = np.empty((L, Hq, R, n), np.float32)
+    for l in range(L):
+        for h in range(Hq):
+            pattern = 0 if (l < 3 if h < 2 else l < 2) else 1   # heads 0,1 split after layer 2; heads 2,3 after layer 1
+            noisy = base[pattern, h] * rng.uniform(0.9, 1.1, size=(R, n))
+            att[l, h] = noisy / noisy.sum(axis=1, keepdims=True)
+    sim = pod.pod_layer_similarity(torch.from_numpy(att).cuda()).cpu().numpy()
+    table = pod.pod_group_layers(sim, Hkv, 0.5)
+    sim_ref = np.ones((Hq, L, L))
+    for h in range(Hq):
+        for a in range(L):
+            for b in range(a + 1, L):
+                sim_ref[h, a, b] = sim_ref[h, b, a] = pg.layer_similarity(att[a, h][None], att[b, h][None])
+    np.testing.assert_array_equal(table, pg.group_layers_gqa(sim_ref, Hkv, 0.5))
+    assert table[:, 0].tolist() == [0, 0, 0, 3, 3] and table[:, 1].tolist() == [0, 0, 2, 2, 2]
+    c = Case(L, 1, Hq, Hkv, 64, 8, 32, 1, 200, seed=750, block_lowest=table)
+    for layer in range(L):
+        c.fill(layer, 0, 150)
+    for layer in range(L):
+        assert_close(c.decode(layer, [150]), c.decode_ref(layer, [150]), f"layer {layer}")
