@@ -111,10 +111,13 @@ __device__ inline float pair_sum(float x)
 // Data movement uses no registers: K and V tiles go from global memory straight into LDS
 // (global_load_lds_dwordx4: each wave instruction fills 1 KB of consecutive LDS, lane l its 16
 // bytes; which 16 bytes of the tile a lane fetches is free to choose).
-//   K slot: MFMA fragment order, fragment (key block kb, k-step s) = 64 lanes x 16 bytes, lane
-//           (key row l % 32, l / 32) holds dims 16 s + 8 (l / 32) .. + 7: a lane fetches exactly the
-//           piece it will later read with one ds_read_b128.
-//   V slot: row-major [64 tokens][D] as in global memory, 16-byte pieces of a row XOR-permuted by
+// Both slots are row-major [64 tokens][D] as in global memory, so a wave instruction fetches whole
+// rows (256 consecutive bytes per row at D = 128: fully coalesced requests); only the order of the
+// 16-byte pieces inside a row is permuted, differently for the two readers:
+//   K slot: piece c of row r sits at piece c ^ krot(r), krot(r) = (r D / 128) mod (D / 8).  The B
+//           operand of the QK product (one key row, 8 dims per lane) is one ds_read_b128; the 16 rows
+//           that such a read touches at once hit 16 different 16-byte bank groups.
+//   V slot: 16-byte pieces of a row XOR-permuted by
 //           4 (token % 4).  The A operand of the PV product (V^T: one dim, 8 tokens per lane) comes
 //           out of two ds_read_b64_tr_b16 (the LDS transpose read: inside 16 lanes, lane L receives
 //           element L % 4 of the four 8-byte rows addressed by lanes L / 4 + {0, 4, 8, 12}).
