@@ -371,6 +371,36 @@ int oracle_cache_append(pod_oracle_cache *c, int layer, const uint16_t *k_new, c
 }
 
 /*
+ * Several tokens per sequence in one call (a chunk of a prompt, or tokens accepted
+ * together).  By definition the same as appending them one at a time in position
+ * order.  k_new, v_new: [Bcur][T][Hkv][d]; sequence b takes its first counts[b]
+ * rows (counts == NULL: all T), the first of them at positions[b], which must be
+ * its current length.  Nothing is stored if any sequence fails the checks.
+ */
+int oracle_cache_append_many(pod_oracle_cache *c, int layer, const uint16_t *k_new, const uint16_t *v_new,
+                             const int32_t *positions, const int32_t *counts, int T, int Bcur)
+{
+    if (!c || layer < 0 || layer >= c->L || Bcur < 1 || Bcur > c->B || T < 1) return ORACLE_ERR_ARG;
+    const size_t re = row_elems(c);
+    for (int b = 0; b < Bcur; ++b) {
+        seq_state *s = seq_of(c, layer, b);
+        const int cnt = counts ? counts[b] : T;
+        if (cnt < 0 || cnt > T) return ORACLE_ERR_ARG;
+        if (cnt > 0 && positions[b] != s->n) return ORACLE_ERR_STATE;
+        if (s->n + cnt > c->max_ctx) return ORACLE_ERR_CAPACITY;
+    }
+    for (int b = 0; b < Bcur; ++b) {
+        const int cnt = counts ? counts[b] : T;
+        for (int t = 0; t < cnt; ++t) {
+            const size_t row = ((size_t)b * T + t) * re;
+            int rc = seq_push(c, layer, seq_of(c, layer, b), k_new + row, v_new + row);
+            if (rc) return rc;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Prompt-time construction, stated directly as slices of the prompt's K/V
  * [n][Hkv][d] (not as n appends; the tests check that the two agree):
  *   sink = [0, min(n,S)),  recent = [max(S, n-W), n),  distant = [S, n-W).
@@ -622,6 +652,101 @@ int oracle_decode_attention_gated(pod_oracle_cache *c, int layer, int Hq, double
         free(aP); free(aD); free(oP); free(oD);
     }
     return ORACLE_OK;
+}
+
+/*
+ * Where the cache model keeps position j of a sequence: key and value rows of kv
+ * head kv, or NULL for what it does not keep (the key of a distant position at a
+ * layer that is not the lowest of that head's block).
+ */
+static const uint16_t *stored_key(const pod_oracle_cache *c, int layer, const seq_state *s, long j, int kv)
+{
+    const size_t re = row_elems(c);
+    if (j < 0 || j >= s->n) return NULL;
+    if (j < c->S) return s->sinkK + (size_t)j * re + (size_t)kv * c->d;
+    const long rec_lo = s->n - s->n_recent;
+    if (j >= rec_lo) return s->recK + (size_t)(j - rec_lo) * re + (size_t)kv * c->d;
+    if (!is_lowest(c, layer, kv)) return NULL;
+    return s->distK + (size_t)(j - c->S) * re + (size_t)kv * c->d;
+}
+static const uint16_t *stored_value(const pod_oracle_cache *c, const seq_state *s, long j, int kv)
+{
+    const size_t re = row_elems(c);
+    if (j < 0 || j >= s->n) return NULL;
+    if (j < c->S) return s->sinkV + (size_t)j * re + (size_t)kv * c->d;
+    const long rec_lo = s->n - s->n_recent;
+    if (j >= rec_lo) return s->recV + (size_t)(j - rec_lo) * re + (size_t)kv * c->d;
+    return s->distV + (size_t)(j - c->S) * re + (size_t)kv * c->d;
+}
+
+/*
+ * Attention of a chunk of T new tokens of one sequence against the cache model
+ * and the chunk itself (a prompt processed in pieces).  The chunk is not stored
+ * yet at `layer`: with p0 its stored length, chunk token t has position p0 + t
+ * and sees positions j <= p0 + t, each by Eq. 3 taken at the query's own
+ * position i (proximal: j < S or j > i - W):
+ *   proximal j : this layer's q and key    (stored lists for j < p0, else k row j - p0)
+ *   distant j  : q_shared row and the key of the lowest layer of the head's block
+ *                (that layer's stored lists for j < p0, else k_shared row j - p0)
+ *   value      : always this layer's       (stored lists for j < p0, else v row j - p0)
+ * The lowest layer's lists may hold p0 tokens or may have taken the chunk already
+ * (p0 + T).  q, q_shared: [T][Hq][d]; k, v, k_shared: [T][Hkv][d]; q_shared and
+ * k_shared may be NULL when this layer is the lowest for every kv head.
+ * out: [T][Hq][d] double.  One joint softmax per row (Eq. 4 / appendix).
+ */
+int oracle_chunk_attention(pod_oracle_cache *c, int layer, int seq, int Hq, double scale, int T,
+                           const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                           const uint16_t *q_shared, const uint16_t *k_shared, double *out)
+{
+    if (!c || layer < 0 || layer >= c->L || seq < 0 || seq >= c->B || Hq < 1 || Hq % c->Hkv || T < 1) return ORACLE_ERR_ARG;
+    const int rep = Hq / c->Hkv, d = c->d, Hkv = c->Hkv;
+    seq_state *s = seq_of(c, layer, seq);
+    const long p0 = s->n;
+    if (p0 + T > c->max_ctx) return ORACLE_ERR_CAPACITY;
+    for (int h = 0; h < Hkv; ++h) {
+        if (is_lowest(c, layer, h)) continue;
+        if (!q_shared || !k_shared) return ORACLE_ERR_ARG;
+        const long nl = seq_of(c, lowest_of(c, layer, h), seq)->n;
+        if (nl != p0 && nl != p0 + T) return ORACLE_ERR_STATE;
+    }
+    const long work = (long)T * Hq;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long w = 0; w < work; ++w) {
+        const int t = (int)(w / Hq), h = (int)(w % Hq), kv = h / rep;
+        const long i = p0 + t;
+        const int la = lowest_of(c, layer, kv);
+        const seq_state *sa = seq_of(c, la, seq);
+        const uint16_t *qi = q + ((size_t)t * Hq + h) * d;
+        const uint16_t *qs = la == layer ? qi : q_shared + ((size_t)t * Hq + h) * d;
+        double *a = (double *)malloc((size_t)(i + 1) * sizeof(double));
+        if (!a) { bad = 1; continue; }
+        double amax = -INFINITY;
+        for (long j = 0; j <= i; ++j) {
+            const uint16_t *key;
+            if (is_proximal(j, i, c->S, c->W)) {
+                key = j < p0 ? stored_key(c, layer, s, j, kv) : k + ((size_t)(j - p0) * Hkv + kv) * d;
+                a[j] = key ? scale * dot_bf16(qi, key, d) : NAN;      /* Eq. 3, line 1 */
+            } else {
+                if (la == layer) key = j < p0 ? stored_key(c, layer, s, j, kv) : k + ((size_t)(j - p0) * Hkv + kv) * d;
+                else key = j < p0 ? stored_key(c, la, sa, j, kv) : k_shared + ((size_t)(j - p0) * Hkv + kv) * d;
+                a[j] = key ? scale * dot_bf16(qs, key, d) : NAN;      /* Eq. 3, line 3 */
+            }
+            if (!key) bad = 2;   /* the model does not hold what Eq. 3 asks for: cannot happen if the cache rule is right */
+            if (a[j] > amax) amax = a[j];
+        }
+        double denom = 0.0;
+        for (long j = 0; j <= i; ++j) { a[j] = exp(a[j] - amax); denom += a[j]; }
+        double *o = out + ((size_t)t * Hq + h) * d;
+        for (int x = 0; x < d; ++x) o[x] = 0.0;
+        for (long j = 0; j <= i; ++j) {
+            const double p = a[j] / denom;
+            const uint16_t *vj = j < p0 ? stored_value(c, s, j, kv) : v + ((size_t)(j - p0) * Hkv + kv) * d;
+            for (int x = 0; x < d; ++x) o[x] += p * bf16_to_double(vj[x]);
+        }
+        free(a);
+    }
+    return bad == 1 ? ORACLE_ERR_CAPACITY : (bad == 2 ? ORACLE_ERR_STATE : ORACLE_OK);
 }
 
 int oracle_num_threads(void)

@@ -41,6 +41,11 @@ def lib():
         L.oracle_cache_len.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.oracle_cache_append.restype = C.c_int
         L.oracle_cache_append.argtypes = [C.c_void_p, C.c_int, u16p, u16p, i32p, C.c_int]
+        L.oracle_cache_append_many.restype = C.c_int
+        L.oracle_cache_append_many.argtypes = [C.c_void_p, C.c_int, u16p, u16p, i32p, i32p, C.c_int, C.c_int]
+        L.oracle_chunk_attention.restype = C.c_int
+        L.oracle_chunk_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int,
+                                             u16p, u16p, u16p, u16p, u16p, f64p]
         L.oracle_cache_fill.restype = C.c_int
         L.oracle_cache_fill.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, u16p, u16p]
         L.oracle_cache_export.restype = C.c_int
@@ -154,6 +159,31 @@ class Cache:
         rc = lib().oracle_cache_append(self._h, layer, _u16(k_new), _u16(v_new),
                                        positions.ctypes.data_as(C.POINTER(C.c_int32)), B)
         _chk(rc, "oracle_cache_append")
+
+    def append_many(self, layer, k_new, v_new, positions, counts=None):
+        """T tokens per sequence at once: k_new, v_new uint16 [B][T][Hkv][d]; counts: rows taken per sequence."""
+        positions = np.ascontiguousarray(positions, dtype=np.int32)
+        B, T = k_new.shape[0], k_new.shape[1]
+        assert positions.shape == (B,) and k_new.shape == (B, T, self.Hkv, self.d) and v_new.shape == k_new.shape
+        cp = None
+        if counts is not None:
+            counts = np.ascontiguousarray(counts, dtype=np.int32)
+            assert counts.shape == (B,)
+            cp = counts.ctypes.data_as(C.POINTER(C.c_int32))
+        rc = lib().oracle_cache_append_many(self._h, layer, _u16(k_new), _u16(v_new),
+                                            positions.ctypes.data_as(C.POINTER(C.c_int32)), cp, T, B)
+        _chk(rc, "oracle_cache_append_many")
+
+    def chunk_attention(self, layer, seq, q, k, v, q_shared, k_shared, scale):
+        """Attention of a chunk of new tokens (not stored yet at this layer) over the cache and the chunk.
+        q, q_shared: uint16 [T][Hq][d]; k, v, k_shared: uint16 [T][Hkv][d].  Returns float64 [T][Hq][d]."""
+        T, Hq, d = q.shape
+        assert k.shape == (T, self.Hkv, d) and v.shape == k.shape
+        out = np.empty((T, Hq, d), dtype=np.float64)
+        rc = lib().oracle_chunk_attention(self._h, layer, seq, Hq, float(scale), T, _u16(q), _u16(k), _u16(v),
+                                          _u16(q_shared), _u16(k_shared), out.ctypes.data_as(C.POINTER(C.c_double)))
+        _chk(rc, "oracle_chunk_attention")
+        return out
 
     def fill(self, layer, seq, k, v):
         n = k.shape[0]

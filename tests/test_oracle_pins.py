@@ -596,3 +596,92 @@ def test_js_similarity_special_cases():
     b = np.roll(a, 5, axis=2)
     manual = 1 - np.mean([pg.js_divergence_base2(a[i, j], b[i, j]) for i in range(2) for j in range(3)])
     assert pg.layer_similarity(a, b) == pytest.approx(manual) and 0 < manual < 1
+
+
+# ---------------------------------------------------------------- several tokens at once; a prompt in chunks
+
+@pytest.mark.parametrize("chunks", [[40], [1, 39], [3, 1, 8, 9, 19], [12, 12, 16], [5, 30, 5], [13, 27]])
+def test_append_many_equals_single_appends_and_the_slice_rule(chunks):
+    """A chunk of tokens is by definition the tokens one at a time; the end state is again the slice
+    rule of Eq. 3's index ranges, whatever the chunk boundaries (shorter, equal, longer than S, W, S + W)."""
+    L, G, Hkv, d, S, W = 2, 2, 2, 4, 4, 8
+    n = sum(chunks)
+    a = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    b = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    for layer in range(L):
+        k, v = _tagged_kv(n, Hkv, d, layer)
+        p = 0
+        for t in chunks:
+            a.append_many(layer, k[None, p:p + t], v[None, p:p + t], [p])
+            p += t
+        for p in range(n):
+            b.append(layer, k[p:p + 1], v[p:p + 1], [p])
+        ea, eb = a.export(layer, 0), b.export(layer, 0)
+        lo = max(S, n - W)
+        want = dict(sinkK=k[:min(n, S)], sinkV=v[:min(n, S)], recentK=k[lo:n], recentV=v[lo:n], distV=v[S:lo])
+        if layer % G == 0:
+            want["distK"] = k[S:lo]
+        assert set(ea) == set(eb) == set(want)
+        for name in want:
+            assert np.array_equal(ea[name], want[name]), name
+            assert np.array_equal(eb[name], want[name]), name
+
+
+def test_append_many_ragged_counts_and_checks():
+    L, G, Hkv, d, S, W, B, T = 1, 1, 1, 2, 2, 3, 3, 6
+    c = po.Cache(L, G, Hkv, d, S, W, B, 16)
+    k, v = _tagged_kv(B * T, Hkv, d, 0)
+    k, v = k.reshape(B, T, Hkv, d), v.reshape(B, T, Hkv, d)
+    c.append_many(0, k, v, [0, 0, 0], counts=[6, 0, 2])
+    assert [c.length(0, b) for b in range(B)] == [6, 0, 2]
+    e0, e2 = c.export(0, 0), c.export(0, 2)
+    assert np.array_equal(e0["recentK"], k[0, 3:6]) and np.array_equal(e0["distV"], v[0, 2:3])
+    assert np.array_equal(e2["sinkK"], k[2, :2]) and len(e2["recentK"]) == 0
+    with pytest.raises(po.OracleError):                      # wrong start position: nothing is stored, for any sequence
+        c.append_many(0, k, v, [6, 0, 3], counts=[1, 1, 1])
+    assert [c.length(0, b) for b in range(B)] == [6, 0, 2]
+    with pytest.raises(po.OracleError):                      # over the capacity of 16
+        c.append_many(0, np.concatenate([k, k], axis=1), np.concatenate([v, v], axis=1), [6, 0, 2], counts=[11, 0, 0])
+    with pytest.raises(po.OracleError):
+        c.append_many(0, k, v, [6, 0, 2], counts=[7, 0, 0])  # more rows than the call carries
+
+
+@pytest.mark.parametrize("layer", [0, 1])
+@pytest.mark.parametrize("chunks,lowest_first", [([37], True), ([5, 32], True), ([12, 1, 24], True), ([13, 9, 15], False),
+                                                 ([3, 20, 14], True), ([30, 7], False)])
+def test_chunk_attention_from_cache_equals_rows_of_the_definition(layer, chunks, lowest_first):
+    """Rows p0 .. p0+T-1 of Eq. 3 on the whole sequence, computed from what the cache model holds plus the
+    chunk: fails if the model drops a key some later query still needs (e.g. the lowest layer's key of a
+    token that is in the window for early rows of the chunk and distant for late ones), or takes a key
+    from the wrong layer.  lowest_first: the lowest layer has stored the chunk already when the upper layer runs."""
+    L, G, Hq, Hkv, d, S, W = 2, 2, 4, 2, 8, 4, 8
+    n = sum(chunks)
+    c = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    qs, ks, vs = {}, {}, {}
+    for l in range(L):
+        qs[l], ks[l], vs[l] = rand_qkv(81, n, Hq, Hkv, d, layer=l)
+    full = po.pod_attention(bits(qs[layer]), bits(ks[layer]), bits(vs[layer]), bits(qs[0]) if layer else None,
+                            bits(ks[0]) if layer else None, np.arange(n), S, W, 0.35)
+    p = 0
+    for t in chunks:
+        sl = slice(p, p + t)
+        if lowest_first:
+            c.append_many(0, bits(ks[0][sl])[None], bits(vs[0][sl])[None], [p])
+        if layer == 1 or not lowest_first:
+            got = c.chunk_attention(layer, 0, bits(qs[layer][sl]), bits(ks[layer][sl]), bits(vs[layer][sl]),
+                                    bits(qs[0][sl]) if layer else None, bits(ks[0][sl]) if layer else None, 0.35)
+            np.testing.assert_allclose(got, full[sl], rtol=0, atol=1e-13)
+        if not lowest_first:
+            c.append_many(0, bits(ks[0][sl])[None], bits(vs[0][sl])[None], [p])
+        c.append_many(1, bits(ks[1][sl])[None], bits(vs[1][sl])[None], [p])
+        p += t
+
+
+def test_chunk_attention_rejects_a_lowest_layer_out_of_step():
+    L, G, Hq, Hkv, d, S, W = 2, 2, 2, 1, 4, 2, 4
+    c = po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    q, k, v = rand_qkv(82, 12, Hq, Hkv, d)
+    c.append_many(0, bits(k[:7])[None], bits(v[:7])[None], [0])
+    c.append_many(1, bits(k[:6])[None], bits(v[:6])[None], [0])
+    with pytest.raises(po.OracleError):   # chunk of 3 at p0 = 6: the lowest layer must hold 6 or 9 tokens, not 7
+        c.chunk_attention(1, 0, bits(q[6:9]), bits(k[6:9]), bits(v[6:9]), bits(q[6:9]), bits(k[6:9]), 0.5)
