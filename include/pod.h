@@ -252,6 +252,49 @@ int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, cons
                           void *out, int write_cache, void *stream);
 
 /*
+ * Cache update with several tokens per sequence in one call (a chunk of a prompt, or tokens
+ * accepted together; the state the index ranges of Eq. 3 give after all of them, i.e. the
+ * state after appending them one at a time).
+ *   k_new, v_new : dev bf16 [B][T][Hkv][d]
+ *   positions    : dev int32 [B], position of each sequence's first new token; must equal the
+ *                  number of tokens the slot holds at this layer (checked in the kernel;
+ *                  ignored for sequences that take no token)
+ *   counts       : HOST int32 [B] or NULL: sequence b takes its first counts[b] rows
+ *                  (0 <= counts[b] <= T; NULL = T for all)
+ * New tokens that are outside the window of W recent tokens by the end of the call go to the
+ * distant stores directly (key only where `layer` is the lowest of the head's block); the
+ * others enter the ring, whose displaced tokens become distant as in pod_cache_append.
+ * POD_ERR_CAPACITY if the host mirror shows a slot would exceed max_context.
+ */
+int pod_cache_append_many(pod_cache *cache, int layer, const void *k_new, const void *v_new,
+                          const int32_t *positions, const int32_t *counts, int T, int B, void *stream);
+
+/* Bytes of device scratch pod_prefill_attention_chunk needs for a sequence that holds n_total
+ * tokens after the chunk (contiguous copies of its keys and values). host out. */
+int pod_prefill_chunk_workspace_bytes(const pod_config *cfg, int64_t n_total, size_t *bytes);
+
+/*
+ * Prefill attention for a chunk of T new tokens of a sequence whose first p0 tokens are in
+ * the cache already (a prompt processed in pieces; p0 = tokens (layer, seq_slot) holds, p0 = 0
+ * is pod_prefill_attention).  Chunk token t has position p0 + t and attends positions
+ * j <= p0 + t by Eq. 3 taken at its own position: proximal keys (j < S or j > p0 + t - W) from
+ * this layer, distant keys from the lowest layer of the head's block with that layer's query;
+ * values from this layer; one joint softmax.
+ *   q        : dev bf16 [T][Hq][d];  k, v : dev bf16 [T][Hkv][d] of `layer` for the chunk
+ *   q_shared, k_shared : the lowest layer's q and k for the chunk (same shapes); both NULL when
+ *              `layer` is the lowest of its block for every kv head
+ *   workspace: dev scratch of pod_prefill_chunk_workspace_bytes(cfg, p0 + T) bytes, 256-byte aligned
+ *   out      : dev bf16 [T][Hq][d]
+ *   write_cache : nonzero = afterwards store the chunk at (layer, seq_slot) as pod_cache_append_many does
+ * Keys of earlier positions come from the cache: this layer's sink and recent window, and the
+ * stores of the lowest layer of each head's block, which must hold either p0 tokens or
+ * p0 + T (it has stored this chunk already): otherwise POD_ERR_STATE.
+ */
+int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T, const void *q, const void *k,
+                                const void *v, const void *q_shared, const void *k_shared, float scale,
+                                void *workspace, size_t workspace_bytes, void *out, int write_cache, void *stream);
+
+/*
  * Test hook: copy the cache's logical content for (layer, seq_slot) out in position
  * order, each as dev bf16 [tokens][Hkv][d]:
  *   sink   : positions [0, min(n,S))           recent : [max(S, n-W), n), oldest first

@@ -22,6 +22,7 @@ EXPORTS = [
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
+    "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
 ]
 
 
@@ -78,6 +79,10 @@ def load():
         "pod_layer_similarity": [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp],
         "pod_decode_attention_reuse": [vp, C.c_int, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp,
                                        C.c_size_t, vp, vp],
+        "pod_cache_append_many": [vp, C.c_int, vp, vp, i32p, i32p, C.c_int, C.c_int, vp],
+        "pod_prefill_chunk_workspace_bytes": [cfgp, C.c_int64, szp],
+        "pod_prefill_attention_chunk": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_size_t, vp,
+                                        C.c_int, vp],
         "pod_profile_enable": [vp, C.c_int],
         "pod_profile_disable": [vp],
         "pod_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)],
@@ -161,6 +166,12 @@ def pod_score_buffer_bytes(cfg: PodConfig) -> int:
     return out.value
 
 
+def pod_prefill_chunk_workspace_bytes(cfg: PodConfig, n_total: int) -> int:
+    b = C.c_size_t()
+    _check(load().pod_prefill_chunk_workspace_bytes(C.byref(cfg), n_total, C.byref(b)))
+    return b.value
+
+
 def pod_workspace_bytes(cfg: PodConfig) -> int:
     out = C.c_size_t()
     _check(load().pod_workspace_bytes(C.byref(cfg), C.byref(out)))
@@ -203,6 +214,16 @@ class PodCache:
         B = positions.shape[0]
         _check(load().pod_cache_append(self.handle, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
                                        _ptr(positions, torch.int32), B, _stream()))
+
+    def pod_cache_append_many(self, layer, k_new, v_new, positions, counts=None):
+        """k_new, v_new: [B][T][Hkv][d]; positions: device int32 [B]; counts: host sequence of B ints or None."""
+        B, T = k_new.shape[0], k_new.shape[1]
+        cp = None
+        if counts is not None:
+            assert len(counts) == B
+            cp = (C.c_int32 * B)(*[int(x) for x in counts])
+        _check(load().pod_cache_append_many(self.handle, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+                                            _ptr(positions, torch.int32), cp, T, B, _stream()))
 
     def pod_cache_fill(self, layer, seq_slot, k, v):
         n = k.shape[0]
@@ -260,6 +281,20 @@ class PodCache:
                                             _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16),
                                             _ptr(q_shared, torch.bfloat16), _ptr(k_shared, torch.bfloat16), scale,
                                             _ptr(out, torch.bfloat16), int(bool(write_cache)), _stream()))
+        return out
+
+    def pod_prefill_attention_chunk(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, workspace, out=None,
+                                    write_cache=False):
+        """Chunk of T new tokens of a sequence whose earlier tokens are in the cache; workspace: device uint8 tensor of
+        pod_prefill_chunk_workspace_bytes(cfg, tokens after the chunk) bytes."""
+        T = q.shape[0]
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_prefill_attention_chunk(self.handle, layer, seq_slot, T, _ptr(q, torch.bfloat16),
+                                                  _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16),
+                                                  _ptr(q_shared, torch.bfloat16), _ptr(k_shared, torch.bfloat16), scale,
+                                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                  _ptr(out, torch.bfloat16), int(bool(write_cache)), _stream()))
         return out
 
     def pod_profile_enable(self, max_records):

@@ -502,10 +502,94 @@ extern "C" int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, 
             return pod_fail(POD_ERR_STATE, "slot %d at layer %d is not empty", seq_slot, layer);
     }
     if (lowest) { q_shared = nullptr; k_shared = nullptr; }
-    rc = pod_launch_prefill(ly, layer, n, q, k, v, q_shared, k_shared, pod_make_headmap(cache, layer).lowest_mask, scale, out,
+    rc = pod_launch_prefill(ly, layer, n, 0, q, k, v, q_shared, k_shared, pod_make_headmap(cache, layer).lowest_mask, scale, out,
                             (hipStream_t)stream);
     if (rc) return rc;
     if (write_cache) return pod_cache_fill(cache, layer, seq_slot, n, k, v, stream);
+    return POD_OK;
+}
+
+extern "C" int pod_cache_append_many(pod_cache *cache, int layer, const void *k_new, const void *v_new,
+                                     const int32_t *positions, const int32_t *counts, int T, int B, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!k_new || !v_new || !positions) return pod_fail(POD_ERR_INVALID_ARG, "k_new, v_new and positions must not be NULL");
+    if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
+    if (T < 1) return pod_fail(POD_ERR_INVALID_ARG, "T must be >= 1");
+    int64_t *len = cache->host_len + (size_t)layer * ly.B;
+    int32_t *cnt = (int32_t *)malloc((size_t)B * sizeof(int32_t));
+    if (!cnt) return pod_fail(POD_ERR_CAPACITY, "out of host memory");
+    for (int b = 0; b < B; ++b) {
+        cnt[b] = counts ? counts[b] : T;
+        if (cnt[b] < 0 || cnt[b] > T) { free(cnt); return pod_fail(POD_ERR_INVALID_ARG, "counts[%d] = %d outside [0, T = %d]", b, counts[b], T); }
+        if (len[b] + cnt[b] > ly.maxctx) {
+            free(cnt);
+            return pod_fail(POD_ERR_CAPACITY, "slot %d at layer %d would exceed max_context = %d", b, layer, ly.maxctx);
+        }
+    }
+    rc = pod_launch_append_many(cache, layer, k_new, v_new, positions, cnt, T, 0, B, (hipStream_t)stream);
+    if (rc == POD_OK)
+        for (int b = 0; b < B; ++b) len[b] += cnt[b];
+    free(cnt);
+    return rc;
+}
+
+static size_t chunk_rows_bytes(const pod_layout &ly, int64_t n) { return align_up((size_t)n * ly.Hkv * ly.D * 2, 256); }
+
+extern "C" int pod_prefill_chunk_workspace_bytes(const pod_config *cfg, int64_t n_total, size_t *bytes)
+{
+    pod_layout ly;
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    if (!bytes || n_total < 1) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL or n_total < 1");
+    if (n_total > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n_total = %lld exceeds max_context = %d", (long long)n_total, ly.maxctx);
+    *bytes = 3 * chunk_rows_bytes(ly, n_total);
+    return POD_OK;
+}
+
+extern "C" int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T, const void *q, const void *k,
+                                           const void *v, const void *q_shared, const void *k_shared, float scale,
+                                           void *workspace, size_t workspace_bytes, void *out, int write_cache, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!q || !k || !v || !out || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "q, k, v, out and workspace must not be NULL");
+    if (T < 1) return pod_fail(POD_ERR_INVALID_ARG, "T must be >= 1");
+    if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
+    if ((q_shared == nullptr) != (k_shared == nullptr))
+        return pod_fail(POD_ERR_INVALID_ARG, "q_shared and k_shared must be given together");
+    const int64_t p0 = cache->host_len[(size_t)layer * ly.B + seq_slot];
+    const int64_t n = p0 + T;
+    if (n > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "slot %d at layer %d would exceed max_context = %d", seq_slot, layer, ly.maxctx);
+    const bool lowest = layer_lowest_all(cache, layer);
+    if (!lowest && !q_shared && n > ly.P)
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and there are distant tokens: q_shared and k_shared are required", layer);
+    for (int h = 0; h < ly.Hkv; ++h) {
+        const int la = cache->lowest[(size_t)layer * ly.Hkv + h];
+        const int64_t na = cache->host_len[(size_t)la * ly.B + seq_slot];
+        if (la != layer && na != p0 && na != n)
+            return pod_fail(POD_ERR_STATE, "layer %d (lowest of kv head %d's block) holds %lld tokens of slot %d; layer %d holds %lld and the chunk has %d",
+                            la, h, (long long)na, seq_slot, layer, (long long)p0, T);
+    }
+    const size_t part = chunk_rows_bytes(ly, n);
+    if (workspace_bytes < 3 * part) return pod_fail(POD_ERR_CAPACITY, "chunk workspace too small: %zu < %zu", workspace_bytes, 3 * part);
+    if (lowest) { q_shared = nullptr; k_shared = nullptr; }
+    char *k_all = (char *)workspace, *v_all = k_all + part, *ks_all = q_shared ? v_all + part : nullptr;
+    hipStream_t st = (hipStream_t)stream;
+    rc = pod_launch_gather(cache, layer, seq_slot, (int)p0, T, k, v, k_shared, k_all, v_all, ks_all, st);
+    if (rc) return rc;
+    rc = pod_launch_prefill(ly, layer, (int)n, (int)p0, q, k_all, v_all, q_shared, ks_all, pod_make_headmap(cache, layer).lowest_mask,
+                            scale, out, st);
+    if (rc) return rc;
+    if (write_cache) {
+        const int32_t cnt = T;
+        rc = pod_launch_append_many(cache, layer, k, v, nullptr, &cnt, T, seq_slot, 1, st);
+        if (rc) return rc;
+        cache->host_len[(size_t)layer * ly.B + seq_slot] = n;
+    }
     return POD_OK;
 }
 

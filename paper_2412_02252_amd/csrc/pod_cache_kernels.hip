@@ -9,6 +9,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kCountsPerLaunch = 256; // sequences one append_many launch covers (their counts travel as kernel arguments)
 
 __device__ inline int32_t *lens_ptr(char *base, const pod_layout &ly) { return (int32_t *)(base + ly.off_lens); }
 __device__ inline int32_t *flag_ptr(char *base, const pod_layout &ly) { return (int32_t *)(base + ly.off_flag); }
@@ -61,6 +62,143 @@ __global__ void append_kernel(char *base, pod_layout ly, pod_headmap hm, int lay
     }
     __syncthreads(); // every thread has read *lens (through cur) before it changes
     if (threadIdx.x == 0) *lens = p + 1;
+}
+
+// Several tokens per sequence in one launch: the state after the call is the state after appending
+// them one at a time.  blockIdx.y = sequence, grid-stride over 16-byte pieces of its new rows
+// [cnt][Hkv][D].  With n0 tokens stored and n1 = n0 + cnt afterwards, new position p goes to
+//   its sink slot                          if p < S,
+//   distant row p - S directly             if p < n1 - W   (it has left the window by the end of the call),
+//   ring slot S + (p - S) % W              otherwise; what that slot held (the last stored position below n0
+//                                          that maps to it, if any) is first moved to its distant row.
+// The positions of the last case are fewer than W + 1 consecutive ones, so each ring slot is touched by one
+// thread per piece: no ordering between threads is needed.  The lengths are left alone (every workgroup
+// reads them); commit_lens_kernel stores the new ones afterwards.
+struct pod_counts { int32_t cnt[kCountsPerLaunch]; };
+
+__global__ void append_many_kernel(char *base, pod_layout ly, pod_headmap hm, int layer, int b_first, int b0, int T, pod_counts counts,
+                                   const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                                   const int32_t *__restrict__ positions)
+{
+    const int b = b0 + blockIdx.y;
+    const int cnt = counts.cnt[blockIdx.y];
+    if (cnt <= 0) return;
+    const int n0 = lens_ptr(base, ly)[(size_t)layer * ly.B + b];
+    if ((positions && positions[b] != n0) || n0 < 0 || n0 + cnt > ly.maxctx) return; // commit_lens_kernel raises the flag
+    const int n1 = n0 + cnt;
+    const int cpr = ly.D / 8;
+    uint4 *proxK = (uint4 *)(base + ly.off_proxK);
+    uint4 *proxV = (uint4 *)(base + ly.off_proxV);
+    uint4 *distK = (uint4 *)(base + ly.off_distK);
+    uint4 *distV = (uint4 *)(base + ly.off_distV);
+    const size_t total = (size_t)cnt * ly.Hkv * cpr;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % cpr);
+        const int h = (int)((idx / cpr) % ly.Hkv);
+        const int t = (int)(idx / ((size_t)cpr * ly.Hkv));
+        const int p = n0 + t;
+        const size_t src = ((size_t)(b - b_first) * T + t) * ly.Hkv * cpr + (size_t)h * cpr + c; // rows start at sequence b_first
+        const uint4 kn = k_new[src], vn = v_new[src];
+        const bool low = (hm.lowest_mask >> h) & 1;
+        if (p >= ly.S && p < n1 - ly.W) {
+            const size_t r = (size_t)(p - ly.S);
+            distV[(pod_dist_row0(ly, layer, b, h) + r) * cpr + c] = vn;
+            if (low) distK[(pod_distk_row0(ly, hm, b, h) + r) * cpr + c] = kn;
+            continue;
+        }
+        const int slot = p < ly.S ? p : ly.S + (p - ly.S) % ly.W;
+        const size_t pr = (pod_prox_row0(ly, layer, b, h) + slot) * cpr + c;
+        if (p >= ly.S) {
+            const int held = p - ((p - n0) / ly.W + 1) * ly.W; // the stored position in this ring slot
+            if (held >= ly.S) {
+                const size_t r = (size_t)(held - ly.S);
+                distV[(pod_dist_row0(ly, layer, b, h) + r) * cpr + c] = proxV[pr];
+                if (low) distK[(pod_distk_row0(ly, hm, b, h) + r) * cpr + c] = proxK[pr];
+            }
+        }
+        proxK[pr] = kn;
+        proxV[pr] = vn;
+    }
+}
+
+// One thread per sequence of the launch above: store the new length, or raise the flag if the
+// start position was not the stored length.
+__global__ void commit_lens_kernel(char *base, pod_layout ly, int layer, int b0, int nb, pod_counts counts,
+                                   const int32_t *__restrict__ positions)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nb || counts.cnt[i] <= 0) return;
+    int32_t *len = lens_ptr(base, ly) + (size_t)layer * ly.B + b0 + i;
+    const int n0 = *len;
+    if ((positions && positions[b0 + i] != n0) || n0 < 0 || n0 + counts.cnt[i] > ly.maxctx) atomicOr(flag_ptr(base, ly), 1);
+    else *len = n0 + counts.cnt[i];
+}
+
+// Contiguous K/V [n][Hkv][D] of one sequence for the chunk attention: positions below p0 (the stored
+// length) come out of the cache, positions p0 .. p0 + T - 1 from the chunk's own rows.
+//   v_all : this layer's values (every position is stored)
+//   k_all : this layer's keys where it keeps them (sink, recent window, and distant positions of the heads
+//           for which the layer is the lowest of the block); zeros elsewhere (never counted by Eq. 3 for a
+//           query at or after p0)
+//   ks_all: for the other heads, the keys of the lowest layer of the head's block, wherever that layer holds
+//           them at ITS current length (it may have stored the chunk already); heads that are lowest here
+//           are skipped
+struct pod_gather_args {
+    int32_t low_layer[kMaxKvHeads]; // lowest layer of head h's block
+    int32_t low_row[kMaxKvHeads];   // slot * B of the distant-key store of that block
+};
+
+__global__ void gather_kernel(const char *base, pod_layout ly, pod_gather_args ga, uint64_t lowest_mask, int layer, int b,
+                              int p0, int T, const uint4 *__restrict__ k_chunk, const uint4 *__restrict__ v_chunk,
+                              const uint4 *__restrict__ ks_chunk, uint4 *k_all, uint4 *v_all, uint4 *ks_all)
+{
+    const int cpr = ly.D / 8;
+    const uint4 *proxK = (const uint4 *)(base + ly.off_proxK);
+    const uint4 *proxV = (const uint4 *)(base + ly.off_proxV);
+    const uint4 *distK = (const uint4 *)(base + ly.off_distK);
+    const uint4 *distV = (const uint4 *)(base + ly.off_distV);
+    const int32_t *lens = (const int32_t *)(base + ly.off_lens);
+    const int rec_lo = p0 - ly.W > ly.S ? p0 - ly.W : ly.S;   // first position of this layer's recent window
+    const size_t total = (size_t)(p0 + T) * ly.Hkv * cpr;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % cpr);
+        const int h = (int)((idx / cpr) % ly.Hkv);
+        const int j = (int)(idx / ((size_t)cpr * ly.Hkv));
+        const bool low = (lowest_mask >> h) & 1;
+        if (j >= p0) {
+            const size_t src = ((size_t)(j - p0) * ly.Hkv + h) * cpr + c;
+            k_all[idx] = k_chunk[src];
+            v_all[idx] = v_chunk[src];
+            if (!low && ks_all) ks_all[idx] = ks_chunk[src];
+            continue;
+        }
+        uint4 kk = make_uint4(0, 0, 0, 0), vv;
+        if (j < ly.S || j >= rec_lo) {
+            const int slot = j < ly.S ? j : ly.S + (j - ly.S) % ly.W;
+            const size_t pr = (pod_prox_row0(ly, layer, b, h) + slot) * cpr + c;
+            kk = proxK[pr];
+            vv = proxV[pr];
+        } else {
+            const size_t r = (size_t)(j - ly.S);
+            vv = distV[(pod_dist_row0(ly, layer, b, h) + r) * cpr + c];
+            if (low) kk = distK[((size_t)(ga.low_row[h] + b) * ly.Cd + r) * cpr + c];
+        }
+        k_all[idx] = kk;
+        v_all[idx] = vv;
+        if (!low && ks_all) {
+            const int la = ga.low_layer[h];
+            const int na = lens[(size_t)la * ly.B + b];       // p0, or p0 + T if that layer took the chunk already
+            const int rec_a = na - ly.W > ly.S ? na - ly.W : ly.S;
+            uint4 ka;
+            if (j < ly.S || j >= rec_a) {
+                const int slot = j < ly.S ? j : ly.S + (j - ly.S) % ly.W;
+                ka = proxK[(pod_prox_row0(ly, la, b, h) + slot) * cpr + c];
+            } else {
+                ka = distK[((size_t)(ga.low_row[h] + b) * ly.Cd + (size_t)(j - ly.S)) * cpr + c];
+            }
+            ks_all[idx] = ka;
+        }
+    }
 }
 
 // Grid-stride over 16-byte pieces of the prompt's K/V [n][Hkv][D].
@@ -182,6 +320,48 @@ int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, vo
     hipLaunchKernelGGL(export_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, (const char *)c->base, c->ly,
                        pod_make_headmap(c, layer), layer, seq_slot, (int)n, (uint4 *)sinkK, (uint4 *)sinkV, (uint4 *)recK, (uint4 *)recV,
                        (uint4 *)distK, (uint4 *)distV);
+    POD_HIP_TRY(hipGetLastError());
+    return POD_OK;
+}
+
+int pod_launch_append_many(const pod_cache *c, int layer, const void *k_new, const void *v_new, const int32_t *positions,
+                           const int32_t *counts, int T, int b_first, int B, hipStream_t st)
+{
+    const pod_headmap hm = pod_make_headmap(c, layer);
+    for (int g0 = 0; g0 < B; g0 += kCountsPerLaunch) {
+        const int nb = B - g0 < kCountsPerLaunch ? B - g0 : kCountsPerLaunch;
+        const int b0 = b_first + g0;
+        pod_counts pc;
+        int most = 0;
+        for (int i = 0; i < kCountsPerLaunch; ++i) {
+            pc.cnt[i] = i < nb ? counts[g0 + i] : 0;
+            if (pc.cnt[i] > most) most = pc.cnt[i];
+        }
+        if (most == 0) continue;
+        const size_t items = (size_t)most * c->ly.Hkv * (c->ly.D / 8);
+        int gx = grid_for(items);
+        if (gx > 2048) gx = 2048;
+        hipLaunchKernelGGL(append_many_kernel, dim3(gx, nb), dim3(kThreads), 0, st, c->base, c->ly, hm, layer, b_first, b0, T, pc,
+                           (const uint4 *)k_new, (const uint4 *)v_new, positions);
+        hipLaunchKernelGGL(commit_lens_kernel, dim3((nb + 63) / 64), dim3(64), 0, st, c->base, c->ly, layer, b0, nb, pc, positions);
+    }
+    POD_HIP_TRY(hipGetLastError());
+    return POD_OK;
+}
+
+int pod_launch_gather(const pod_cache *c, int layer, int seq_slot, int p0, int T, const void *k_chunk, const void *v_chunk,
+                      const void *ks_chunk, void *k_all, void *v_all, void *ks_all, hipStream_t st)
+{
+    pod_gather_args ga;
+    const int H = c->ly.Hkv;
+    for (int h = 0; h < kMaxKvHeads; ++h) {
+        ga.low_layer[h] = h < H ? c->lowest[(size_t)layer * H + h] : 0;
+        ga.low_row[h] = h < H ? c->kslot[(size_t)layer * H + h] * c->ly.B : 0;
+    }
+    const size_t items = (size_t)(p0 + T) * H * (c->ly.D / 8);
+    hipLaunchKernelGGL(gather_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, (const char *)c->base, c->ly, ga,
+                       pod_make_headmap(c, layer).lowest_mask, layer, seq_slot, p0, T, (const uint4 *)k_chunk,
+                       (const uint4 *)v_chunk, (const uint4 *)ks_chunk, (uint4 *)k_all, (uint4 *)v_all, (uint4 *)ks_all);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }

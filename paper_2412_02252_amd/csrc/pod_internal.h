@@ -92,6 +92,13 @@ int pod_launch_append(const pod_cache *c, int layer, const void *k_new, const vo
                       const int32_t *positions, int B, hipStream_t st);
 int pod_launch_fill(const pod_cache *c, int layer, int seq_slot, int n, const void *k, const void *v,
                     hipStream_t st);
+// sequences b_first .. b_first + B - 1; k_new, v_new: [B][T][Hkv][D] and counts: host array [B], both starting at
+// sequence b_first; positions: device array indexed by sequence, or NULL (the stored lengths are the start positions)
+int pod_launch_append_many(const pod_cache *c, int layer, const void *k_new, const void *v_new, const int32_t *positions,
+                           const int32_t *counts, int T, int b_first, int B, hipStream_t st);
+// contiguous [p0 + T][Hkv][D] keys / values / lowest layers' keys of one sequence (ks_all may be NULL)
+int pod_launch_gather(const pod_cache *c, int layer, int seq_slot, int p0, int T, const void *k_chunk, const void *v_chunk,
+                      const void *ks_chunk, void *k_all, void *v_all, void *ks_all, hipStream_t st);
 int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, void *sinkK, void *sinkV,
                       void *recK, void *recV, void *distK, void *distV, hipStream_t st);
 // scores == NULL: plain decode; else the score-reuse buffer (lowest layer writes, upper layers read).
@@ -105,6 +112,7 @@ size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and s
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 // lowest_mask: bit h set = kv head h takes every logit from (q, k); clear = distant logits from (q_shared, k_shared)
-int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
+// k, v, k_shared: rows for positions 0 .. n-1; q, q_shared, out: rows for positions q0 .. n-1
+int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,
                        const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
                        hipStream_t st);

@@ -47,6 +47,7 @@ constexpr float kLazy = 8.0f; // how far (log2) a tile's maximum may exceed the 
 
 struct prefill_params {
     int n, Hq, Hkv, rep, S, W;
+    int q0; // position of the first query row: q, qs and out hold rows q0 .. n-1 (k, v, ks hold 0 .. n-1)
     const pod_bf16 *q, *k, *v, *qs, *ks; // qs/ks NULL: own q,k serve every key
     pod_bf16 *out;
     float scale_log2e;
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     for (int db = 0; db < NDB; ++db) v_rd[db] = v_rd0 ^ (64 * db);
 
     bf16x8 qf[KST];
-    const int qrow = min(irow, p.n - 1);
+    const int qrow = max(min(irow, p.n - 1), p.q0) - p.q0;
     auto load_q = [&](const pod_bf16 *src) {
         const gvec_ptr qr = (gvec_ptr)(src + ((size_t)qrow * p.Hq + head) * D);
 #pragma unroll
@@ -493,9 +494,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     }
 
     const float l = pair_sum(l_run);
-    if (irow < p.n) {
+    if (irow < p.n && irow >= p.q0) {
         const float inv = 1.f / l;
-        pod_bf16 *orow = p.out + ((size_t)irow * p.Hq + head) * D;
+        pod_bf16 *orow = p.out + ((size_t)(irow - p.q0) * p.Hq + head) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -510,20 +511,21 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 
 } // namespace
 
-int pod_launch_prefill(const pod_layout &ly, int layer, int n, const void *q, const void *k, const void *v,
+int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,
                        const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
                        hipStream_t st)
 {
     (void)layer;
     prefill_params p;
-    p.n = n; p.Hq = ly.Hq; p.Hkv = ly.Hkv; p.rep = ly.rep; p.S = ly.S; p.W = ly.W;
+    p.n = n; p.q0 = q0; p.Hq = ly.Hq; p.Hkv = ly.Hkv; p.rep = ly.rep; p.S = ly.S; p.W = ly.W;
     p.q = (const pod_bf16 *)q; p.k = (const pod_bf16 *)k; p.v = (const pod_bf16 *)v;
     p.qs = (const pod_bf16 *)q_shared; p.ks = (const pod_bf16 *)k_shared;
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.lowest_mask = lowest_mask;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
-    const dim3 grid((unsigned)((n + 127) / 128) * (unsigned)ly.Hq);
+    // query tiles of 128 positions, counted from the end: the kernel takes tile (n + 127) / 128 - 1 - blockIdx.x / Hq
+    const dim3 grid((unsigned)((n + 127) / 128 - q0 / 128) * (unsigned)ly.Hq);
     // dynamic LDS: two K slots and two V slots of kBN tokens x D bf16 each (64 KB at D = 128)
     const auto lds_bytes = [](int D) { return 4 * kBN * D * 2; };
     static bool attr_done = false; // raising the limit to 64 KB is needed once per process

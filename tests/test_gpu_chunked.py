@@ -1,0 +1,227 @@
+"""GPU: several tokens per cache update (pod_cache_append_many) and a prompt processed in chunks
+(pod_prefill_attention_chunk), against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_02252_amd as pod
+from oracle import pod_oracle as po
+from pod_inputs import gen
+from podcase import Case, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def kv_rows(c, layer, seq, p0, t, device):
+    return c.keys(layer, seq, t, device, pos0=p0), c.values(layer, seq, t, device, pos0=p0)
+
+
+def append_many_both(c, layer, starts, counts, T):
+    """Sequences 0..B-1 take counts[b] tokens from position starts[b]; rows beyond counts[b] are filler."""
+    B = len(starts)
+    kd = torch.stack([kv_rows(c, layer, b, starts[b], T, c.dev)[0] for b in range(B)]).contiguous()
+    vd = torch.stack([kv_rows(c, layer, b, starts[b], T, c.dev)[1] for b in range(B)]).contiguous()
+    pos = torch.tensor(starts, dtype=torch.int32, device=c.dev)
+    c.gpu.pod_cache_append_many(layer, kd, vd, pos, counts)
+    kc = torch.stack([kv_rows(c, layer, b, starts[b], T, "cpu")[0] for b in range(B)])
+    vc = torch.stack([kv_rows(c, layer, b, starts[b], T, "cpu")[1] for b in range(B)])
+    c.cpu.append_many(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), starts, counts)
+
+
+@pytest.mark.parametrize("d,Hkv", [(128, 2), (64, 3)])
+@pytest.mark.parametrize("chunks", [[1, 1, 1], [7, 40, 9], [48], [49, 1], [3, 120, 2, 60], [100, 100, 100], [8, 40, 40, 40]])
+def test_append_many_matches_the_oracle_bit_for_bit(d, Hkv, chunks):
+    """S = 8, W = 40: chunks shorter than, equal to and longer than the sink, the window and both; after every
+    call all regions of every layer equal the oracle's lists, and lengths agree."""
+    c = Case(2, 2, 2 * Hkv, Hkv, d, 8, 40, 2, 400, seed=300 + len(chunks))
+    p = [0, 0]
+    for t in chunks:
+        counts = [t, max(t - 3, 0)]            # the second sequence lags: ragged counts
+        for layer in range(2):
+            append_many_both(c, layer, p, counts, t)
+        p = [p[0] + counts[0], p[1] + counts[1]]
+        for layer in range(2):
+            for b in range(2):
+                assert c.gpu.pod_cache_seq_len(layer, b) == p[b] == c.cpu.length(layer, b)
+                if p[b]:
+                    c.assert_cache_equal(layer, b)
+    c.gpu.pod_cache_check()
+
+
+def test_append_many_then_single_appends_and_decode():
+    """Mixed use: chunk, single tokens, chunk; then decode attention on both layers agrees with the oracle."""
+    c = Case(2, 2, 8, 2, 128, 8, 40, 1, 400, seed=311)
+    p = 0
+    for step in ([57], 1, 1, [44], 1, [130], 1):
+        for layer in range(2):
+            if isinstance(step, list):
+                append_many_both(c, layer, [p], [step[0]], step[0])
+            else:
+                c.append(layer, [p])
+        p += step[0] if isinstance(step, list) else 1
+    for layer in range(2):
+        c.assert_cache_equal(layer, 0)
+        assert_close(c.decode(layer, [p]), c.decode_ref(layer, [p]), f"layer {layer}")
+
+
+def test_append_many_head_wise_blocks():
+    """Keys of demoted and directly stored distant tokens go to the store of each head's own block."""
+    table = [[0, 0], [0, 1], [0, 1], [3, 1]]
+    c = Case(4, 1, 4, 2, 128, 8, 40, 1, 300, seed=312, block_lowest=table)
+    p = 0
+    for t in (30, 100, 5, 77):
+        for layer in range(4):
+            append_many_both(c, layer, [p], [t], t)
+        p += t
+    for layer in range(4):
+        c.assert_cache_equal(layer, 0)
+    for layer in range(4):
+        assert_close(c.decode(layer, [p]), c.decode_ref(layer, [p]), f"layer {layer}")
+
+
+def test_append_many_contract_violations():
+    c = Case(1, 1, 2, 1, 64, 4, 8, 2, 32, seed=313)
+    k = torch.zeros(2, 6, 1, 64, dtype=torch.bfloat16, device=c.dev)
+    pos = torch.zeros(2, dtype=torch.int32, device=c.dev)
+    with pytest.raises(pod.PodError) as e:
+        c.gpu.pod_cache_append_many(0, k, k, pos, [7, 0])             # more rows than the call carries
+    assert e.value.code == pod.binding.ERR_INVALID_ARG
+    c.gpu.pod_cache_append_many(0, k, k, pos, [6, 2])
+    with pytest.raises(pod.PodError) as e:
+        big = torch.zeros(2, 30, 1, 64, dtype=torch.bfloat16, device=c.dev)
+        c.gpu.pod_cache_append_many(0, big, big, pos, [27, 0])        # 6 + 27 > 32
+    assert e.value.code == pod.binding.ERR_CAPACITY
+    # wrong start position for sequence 0: the kernel skips it and raises the flag; sequence 1 is stored
+    c.gpu.pod_cache_append_many(0, k, k, torch.tensor([5, 2], dtype=torch.int32, device=c.dev), [3, 1])
+    with pytest.raises(pod.PodError) as e:
+        c.gpu.pod_cache_check()
+    assert e.value.code == pod.binding.ERR_STATE
+
+
+# ---------------------------------------------------------------------------------------------- chunked prefill
+
+def chunk_inputs(c, layer, seq, p0, t, device):
+    src = c.lowest[layer]
+    q, (k, v) = c.queries(layer, seq, t, device, pos0=p0), kv_rows(c, layer, seq, p0, t, device)
+    if (src == layer).all():
+        return q, k, v, None, None
+    rep = c.Hq // c.Hkv
+    qs = torch.stack([c.queries(int(src[h // rep]), seq, t, device, pos0=p0)[:, h] for h in range(c.Hq)], dim=1).contiguous()
+    ks = torch.stack([c.keys(int(src[h]), seq, t, device, pos0=p0)[:, h] for h in range(c.Hkv)], dim=1).contiguous()
+    return q, k, v, qs, ks
+
+
+def run_chunks(c, chunks, seq=0, check_rows=None):
+    """Every layer processes the prompt chunk by chunk (attention, then the chunk enters the cache) on the GPU
+    and in the oracle's cache model; outputs are compared chunk by chunk."""
+    n_total = sum(chunks)
+    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, n_total), dtype=torch.uint8, device=c.dev)
+    p = 0
+    for t in chunks:
+        for layer in range(c.L):
+            q, k, v, qs, ks = chunk_inputs(c, layer, seq, p, t, c.dev)
+            out = c.gpu.pod_prefill_attention_chunk(layer, seq, q, k, v, qs, ks, c.scale, ws, write_cache=True)
+            qc, kc, vc, qsc, ksc = [gen.bf16_bits(x) if x is not None else None for x in chunk_inputs(c, layer, seq, p, t, "cpu")]
+            ref = c.cpu.chunk_attention(layer, seq, qc, kc, vc, qsc, ksc, c.scale)
+            assert_close(out, ref, f"chunk at {p} (+{t}) layer {layer}")
+            counts = [0] * c.B
+            counts[seq] = t
+            c.cpu.append_many(layer, np.broadcast_to(kc, (c.B, *kc.shape)).copy(), np.broadcast_to(vc, (c.B, *vc.shape)).copy(),
+                              [c.cpu.length(layer, b) for b in range(c.B)], counts)
+        p += t
+    for layer in range(c.L):
+        c.assert_cache_equal(layer, seq)
+    c.gpu.pod_cache_check()
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 2), (64, 4, 1)])
+@pytest.mark.parametrize("chunks", [[300], [1, 1, 1], [5, 59, 1, 63], [64, 64, 64], [127, 2, 128, 43], [40, 200, 17], [129, 300]])
+def test_chunked_prefill_matches_the_oracle(d, Hq, Hkv, chunks):
+    """S = 8, W = 40, 64-key tiles and 128-row query tiles: chunk starts inside tiles, chunks shorter and longer
+    than the window, a first chunk that is the whole prompt."""
+    c = Case(2, 2, Hq, Hkv, d, 8, 40, 2, 600, seed=320 + len(chunks))
+    run_chunks(c, chunks, seq=1)
+
+
+def test_chunked_prefill_equals_one_shot_prefill_rows():
+    """Same prompt in one call and in chunks: the oracle's rows are the same by definition; the two GPU paths
+    agree with each other to bf16 rounding of the same sums taken in a different tile order."""
+    c = Case(2, 2, 8, 2, 128, 64, 512, 2, 1600, seed=331, with_oracle_cache=False)
+    n, cuts = 1500, [0, 700, 701, 1100, 1500]
+    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, n), dtype=torch.uint8, device=c.dev)
+    t = {}
+    for layer in range(2):
+        t[layer] = (c.queries(layer, 0, n, c.dev), c.keys(layer, 0, n, c.dev), c.values(layer, 0, n, c.dev))
+    whole = {}
+    for layer in range(2):
+        q, k, v = t[layer]
+        whole[layer] = c.gpu.pod_prefill_attention(layer, 0, q, k, v, t[0][0] if layer else None, t[0][1] if layer else None, c.scale)
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        for layer in range(2):
+            q, k, v = (x[a:b].contiguous() for x in t[layer])
+            qs = t[0][0][a:b].contiguous() if layer else None
+            ks = t[0][1][a:b].contiguous() if layer else None
+            part = c.gpu.pod_prefill_attention_chunk(layer, 1, q, k, v, qs, ks, c.scale, ws, write_cache=True)
+            diff = (part.float() - whole[layer][a:b].float()).abs()
+            assert diff.max().item() <= 2e-2 and diff.mean().item() <= 1e-3, (layer, a, b, diff.max().item())
+    c.gpu.pod_cache_check()
+
+
+def test_chunked_prefill_head_wise_blocks_and_deferred_cache_writes():
+    """Head-wise table; the lowest layers store the chunk before (write_cache) or after the upper layers run."""
+    table = [[0, 0], [0, 1], [0, 1], [3, 1]]
+    for defer in (False, True):
+        c = Case(4, 1, 4, 2, 128, 8, 40, 1, 400, seed=332, block_lowest=table)
+        ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, 330), dtype=torch.uint8, device=c.dev)
+        p = 0
+        for t in (100, 30, 200):
+            held = []
+            for layer in range(4):
+                q, k, v, qs, ks = chunk_inputs(c, layer, 0, p, t, c.dev)
+                out = c.gpu.pod_prefill_attention_chunk(layer, 0, q, k, v, qs, ks, c.scale, ws, write_cache=not defer)
+                qc, kc, vc, qsc, ksc = [gen.bf16_bits(x) if x is not None else None for x in chunk_inputs(c, layer, 0, p, t, "cpu")]
+                assert_close(out, c.cpu.chunk_attention(layer, 0, qc, kc, vc, qsc, ksc, c.scale), f"defer={defer} p={p} layer {layer}")
+                if defer:
+                    held.append((layer, k, v, kc, vc))
+                else:
+                    c.cpu.append_many(layer, kc[None], vc[None], [p])
+            for layer, k, v, kc, vc in held:
+                c.gpu.pod_cache_append_many(layer, k[None].contiguous(), v[None].contiguous(),
+                                            torch.tensor([p], dtype=torch.int32, device=c.dev))
+                c.cpu.append_many(layer, kc[None], vc[None], [p])
+            p += t
+        for layer in range(4):
+            c.assert_cache_equal(layer, 0)
+        c.gpu.pod_cache_check()
+
+
+def test_chunked_prefill_then_decode():
+    c = Case(2, 2, 8, 2, 128, 8, 40, 1, 600, seed=333)
+    run_chunks(c, [150, 90, 61])
+    n = 302   # one more token after the 301 of the prompt
+    for layer in range(2):
+        c.append(layer, [n - 1])
+    for layer in range(2):
+        assert_close(c.decode(layer, [n]), c.decode_ref(layer, [n]), f"layer {layer}")
+
+
+def test_chunked_prefill_contract_violations():
+    c = Case(2, 2, 4, 2, 128, 8, 40, 1, 200, seed=334, with_oracle_cache=False)
+    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, 200), dtype=torch.uint8, device=c.dev)
+    q, k, v, qs, ks = chunk_inputs(c, 1, 0, 0, 100, c.dev)
+    with pytest.raises(pod.PodError) as e:        # upper layer, distant tokens, no shared tensors
+        c.gpu.pod_prefill_attention_chunk(1, 0, q, k, v, None, None, c.scale, ws)
+    assert e.value.code == pod.binding.ERR_INVALID_ARG
+    with pytest.raises(pod.PodError) as e:        # workspace too small
+        c.gpu.pod_prefill_attention_chunk(1, 0, q, k, v, qs, ks, c.scale, ws[:1024])
+    assert e.value.code == pod.binding.ERR_CAPACITY
+    c.gpu.pod_cache_fill(0, 0, c.keys(0, 0, 50, c.dev), c.values(0, 0, 50, c.dev))
+    with pytest.raises(pod.PodError) as e:        # lowest layer holds 50 tokens, this layer 0, chunk 100: out of step
+        c.gpu.pod_prefill_attention_chunk(1, 0, q, k, v, qs, ks, c.scale, ws)
+    assert e.value.code == pod.binding.ERR_STATE
+    q2, k2, v2, _, _ = chunk_inputs(c, 0, 0, 50, 160, c.dev)
+    with pytest.raises(pod.PodError) as e:        # 50 + 160 > max_context
+        c.gpu.pod_prefill_attention_chunk(0, 0, q2, k2, v2, None, None, c.scale, ws)
+    assert e.value.code == pod.binding.ERR_CAPACITY
+    with pytest.raises(pod.PodError):
+        pod.pod_prefill_chunk_workspace_bytes(c.cfg, 201)
