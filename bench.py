@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--prefill-n", type=int, default=16384)
+    ap.add_argument("--chunk", type=int, default=2048, help="chunk length of the chunked-prefill figure (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain copy kernels of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -356,6 +357,30 @@ def main():
             t = min(times[1:])
             res[name] = {"ms": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 2),
                          "frac_of_bf16_mfma_peak": round(flops / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        # the same prompt in chunks (every layer takes a chunk, stores it, then the next chunk)
+        if a.chunk > 0:
+            ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(pcfg, n), dtype=torch.uint8, device=dev)
+            cuts = list(range(0, n, a.chunk)) + [n]
+            best = None
+            for it in range(3):
+                pc.pod_cache_reset(-1)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in cuts]
+                ev[0].record()
+                for ci, (c0, c1) in enumerate(zip(cuts[:-1], cuts[1:])):
+                    for layer in range(G):
+                        pc.pod_prefill_attention_chunk(layer, 0, q[layer][c0:c1], k[layer][c0:c1], v[layer][c0:c1],
+                                                       q[0][c0:c1] if layer else None, k[0][c0:c1] if layer else None,
+                                                       scale, ws, out=o[c0:c1], write_cache=True)
+                    ev[ci + 1].record()
+                torch.cuda.synchronize()
+                per = [ev[i].elapsed_time(ev[i + 1]) for i in range(len(cuts) - 1)]
+                if best is None or sum(per) < sum(best):
+                    best = per
+            tot = sum(best) / 1e3
+            res["chunked"] = {"chunk": a.chunk, "chunks": len(best), "ms_both_layers": round(tot * 1e3, 4),
+                              "ms_first_chunk": round(best[0], 4), "ms_last_chunk": round(best[-1], 4),
+                              "tflops": round(G * flops / tot / 1e12, 2),
+                              "vs_one_call": round((res["lowest_layer"]["ms"] + res["upper_layer"]["ms"]) / (tot * 1e3), 3)}
         pc.pod_cache_check()
         out["prefill"] = {"workload": f"configs[3]: one block G=2, 32q/8kv, d=128, prompt {n}, S=64, W=2048, "
                                       "attention + cache construction", "flops_per_layer": flops,
