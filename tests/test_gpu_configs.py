@@ -196,3 +196,47 @@ def test_config4_prefill_16384_sampled_rows_and_cache():
         for name in c:
             assert np.array_equal(host_bits(g[name]), c[name]), (l, name)
     cache.pod_cache_check()
+
+
+def test_config4_prompt_in_chunks_sampled_rows_and_cache():
+    """Config 4's prompt processed in chunks (the bench's 2048-token chunks, plus an uneven split): sampled rows
+    of every chunk against the whole-sequence definition, and the cache after the last chunk against the
+    oracle's slice definition, every element."""
+    L, G, Hq, Hkv, d, S, W, n = 2, 2, 32, 8, 128, 64, 2048, 16384
+    seed = SEED0 + 4
+    cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, 2, n)
+    cache = pod.PodCache(cfg, DEV)
+    scale = 1.0 / math.sqrt(d)
+    Q = [gen.queries_bf16(seed, l, 0, n, Hq, d, device=DEV) for l in range(L)]
+    K = [gen.keys_bf16(seed, l, 0, n, Hkv, d, device=DEV) for l in range(L)]
+    V = [gen.values_bf16(seed, l, 0, n, Hkv, d, device=DEV) for l in range(L)]
+    Kh, Vh = [host_bits(t) for t in K], [host_bits(t) for t in V]
+    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(cfg, n), dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(seed + 1)
+    for slot, cuts in ((0, list(range(0, n + 1, 2048))), (1, [0, 100, 2211, 2212, 9000, n])):
+        out = [torch.empty_like(Q[0]) for _ in range(L)]
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            for l in range(L):
+                cache.pod_prefill_attention_chunk(l, slot, Q[l][a:b], K[l][a:b], V[l][a:b], Q[0][a:b] if l else None,
+                                                  K[0][a:b] if l else None, scale, ws, out=out[l][a:b], write_cache=True)
+        rows = set()
+        for a, b in zip(cuts[:-1], cuts[1:]):   # first and last rows of every chunk, and a few inside
+            rows.update(range(a, min(a + 3, b)))
+            rows.update(range(max(b - 3, a), b))
+            rows.update(int(x) for x in rng.integers(a, b, 6))
+        rows = np.array(sorted(rows))
+        for l in range(L):
+            q = host_bits(Q[l][rows].contiguous())
+            qa = host_bits(Q[0][rows].contiguous()) if l else None
+            ref = po.pod_attention(q, Kh[l], Vh[l], qa, Kh[0] if l else None, rows, S, W, scale)
+            assert_close(out[l][rows], ref, f"slot {slot} layer {l}")
+    oc = po.Cache(L, G, Hkv, d, S, W, 1, n)
+    for l in range(L):
+        oc.fill(l, 0, Kh[l], Vh[l])
+        c = oc.export(l, 0)
+        for slot in (0, 1):
+            g = cache.pod_cache_export_logical(l, slot)
+            assert set(g) == set(c)
+            for name in c:
+                assert np.array_equal(host_bits(g[name]), c[name]), (l, slot, name)
+    cache.pod_cache_check()
