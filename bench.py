@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--prefill-n", type=int, default=16384)
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg5"], default="cfg2",
+                    help="cfg2 (default): the headline workload; cfg3 / cfg5: the large-batch decode configurations "
+                         "(32 layers, 30-44 GB of cache), one line of the same shape, decode figures only")
     ap.add_argument("--chunk", type=int, default=2048, help="chunk length of the chunked-prefill figure (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -62,11 +65,85 @@ def traffic_from_profiles():
     return None
 
 
+def main_large(a):
+    """configs[2] (16 ragged sequences of 4K-32K tokens, G=2) or configs[4] (4 sequences of 128K, G=4, 1 % of the
+    distant key rows x8): a step = one new token per sequence through all 32 layers (append, then decode attention)."""
+    import torch
+
+    import paper_2412_02252_amd as pod
+    from pod_inputs import gen
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Hq, Hkv, d, L = 32, 8, 128, 32
+    if a.workload == "cfg3":
+        G, B, S, W, seed = 2, 16, 64, 2048, 20241202 + 3
+        lens = gen.ragged_lengths(seed, B, 4096, 32768)
+        kgen = {}
+        name = "configs[2]: 32 layers G=2, 32q/8kv heads, d=128, 16 sequences of 4096..32768 tokens (seeded), S=64, W=2048"
+    else:
+        G, B, S, W, seed = 4, 4, 128, 4096, 20241202 + 5
+        lens = [131072] * B
+        kgen = dict(outlier_rate=0.01, outlier_scale=8.0, outlier_lo=S, outlier_hi=lens[0] - W)
+        name = "configs[4]: 32 layers G=4, 32q/8kv heads, d=128, 4 sequences of 131072 tokens, S=128, W=4096, 1 % of distant key rows x8"
+    K, Wm = a.steps, a.warmup
+    total = K + Wm
+    max_ctx = max(lens) + total + 1
+    cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx), dev)
+    scale = 1.0 / math.sqrt(d)
+    row = Hkv * d * 2
+    for layer in range(L):
+        for b in range(B):
+            k = gen.keys_bf16(seed, layer, b, lens[b], Hkv, d, device=dev, **kgen)
+            v = gen.values_bf16(seed, layer, b, lens[b], Hkv, d, device=dev)
+            cache.pod_cache_fill(layer, b, k, v)
+            del k, v
+    kn = [torch.stack([gen.keys_bf16(seed, l, b, 1, Hkv, d, device=dev, pos0=lens[b] + s)[0] for b in range(B)]) for s in range(total) for l in range(L)]
+    vn = [torch.stack([gen.values_bf16(seed, l, b, 1, Hkv, d, device=dev, pos0=lens[b] + s)[0] for b in range(B)]) for s in range(total) for l in range(L)]
+    q = [torch.stack([gen.queries_bf16(seed, l, b, 1, Hq, d, device=dev, pos0=lens[b])[0] for b in range(B)]) for l in range(L)]
+    out = torch.empty_like(q[0])
+    pos = [torch.tensor([n + s for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
+    ctx = [torch.tensor([n + s + 1 for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
+
+    def run_step(s):
+        for l in range(L):
+            cache.pod_cache_append(l, kn[s * L + l], vn[s * L + l], pos[s])
+            cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out,
+                                       max_context_len=max(lens) + s + 1)
+
+    for s in range(Wm):
+        run_step(s)
+    cache.pod_cache_check()
+    cache.pod_profile_enable(K * L)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(Wm, total):
+        run_step(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms, launches = cache.pod_profile_read()
+    cache.pod_profile_disable()
+    cache.pod_cache_check()
+    nbytes = sum(sum(2 * (n + s + 1) * row for n in lens) * L for s in range(Wm, total))
+    per_launch = nbytes / (K * L)
+    print(json.dumps({
+        "metric": "decode attn HBM GB/s", "value": round(nbytes / dt / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
+        "warmup": Wm, "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name + "; step = (append + decode) x 32 layers", "launch": "eager", "bytes_per_step": nbytes // K},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0>", "achieved": round(per_launch / (kernel_ms / launches * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(per_launch / (kernel_ms / launches * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": int(per_launch), "avg_kernel_us": round(kernel_ms / launches * 1e3, 3),
+                     "launches": launches}}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here shards across GPUs)", file=sys.stderr)
         sys.exit(2)
+    if a.workload != "cfg2":
+        return main_large(a)
     import numpy as np
     import torch
 
