@@ -225,3 +225,19 @@ def test_chunked_prefill_contract_violations():
     assert e.value.code == pod.binding.ERR_CAPACITY
     with pytest.raises(pod.PodError):
         pod.pod_prefill_chunk_workspace_bytes(c.cfg, 201)
+
+
+def test_append_many_more_sequences_than_one_launch_covers():
+    """Counts travel as kernel arguments, 256 sequences per launch: 300 sequences take two launches."""
+    B, T = 300, 5
+    c = Case(1, 1, 2, 1, 64, 4, 8, B, 40, seed=340)
+    starts = [0] * B
+    for rnd in range(3):
+        counts = [(b + rnd) % (T + 1) for b in range(B)]
+        append_many_both(c, 0, starts, counts, T)
+        starts = [s + k for s, k in zip(starts, counts)]
+    for b in (0, 1, 255, 256, 257, 299):
+        assert c.gpu.pod_cache_seq_len(0, b) == starts[b] == c.cpu.length(0, b)
+        if starts[b]:
+            c.assert_cache_equal(0, b)
+    c.gpu.pod_cache_check()

@@ -283,3 +283,31 @@ def test_gated_decode_without_distant_tokens_and_bad_tau():
     assert_close(got, c.decode_ref(1, [50]), "no distant tokens")
     with pytest.raises(pod.PodError):
         c.gpu.pod_decode_attention_gated(1, c.decode_queries(1, [50], c.dev), ctx_t, c.scale, 1.5, scores)
+
+
+def test_more_than_256_sequences_use_the_device_side_lengths():
+    """Up to 256 sequences the host mirror's lengths travel as kernel arguments; beyond that both kernels read
+    and validate the lengths on the device.  300 ragged sequences (some without, some with distant tokens),
+    one token appended to all of them, both layers; then one wrong context length is caught on the device."""
+    B, S, W = 300, 4, 16
+    c = Case(2, 2, 4, 2, 64, S, W, B, 100, seed=61)
+    lens = [1 + (37 * b) % 90 for b in range(B)]
+    for layer in range(2):
+        for b in range(B):
+            c.fill(layer, b, lens[b])
+        c.append(layer, lens)
+    ctx = [n + 1 for n in lens]
+    for layer in range(2):
+        assert_close(c.decode(layer, ctx), c.decode_ref(layer, ctx), f"layer {layer}")
+    for b in (0, 17, 299):
+        c.assert_cache_equal(1, b)
+    c.gpu.pod_cache_check()
+    wrong = list(ctx)
+    wrong[123] += 1
+    out = c.decode(1, wrong)
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_cache_check()
+    ref = c.decode_ref(1, ctx)
+    keep = [b for b in range(B) if b != 123]
+    assert_close(out[keep], ref[keep], "the other sequences")
+    assert float(out[123].float().abs().max()) == 0.0
