@@ -179,11 +179,14 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
  * also writes them (scaled, fp32) to `scores`; called for an upper layer it reads them from
  * there instead of streaming the block's distant keys again, which cuts the bytes such a call
  * has to read from 2*n rows to about n rows + 4 bytes per (query head, distant token).
- *   scores : dev buffer of >= pod_score_buffer_bytes(cfg), 256-byte aligned, holding the logits
- *            of ONE block at a time: call the block's lowest layer first, then its upper layers,
- *            for the same token, batch and scale, before moving to the next block.  A tag in the
- *            buffer (token count and block per sequence) is checked on the device; a mismatch
- *            zeroes the output row and raises the flag pod_cache_check reports.
+ *   scores : dev buffer of >= pod_score_buffer_bytes(cfg), 256-byte aligned, holding for every
+ *            kv head the logits of ONE block at a time: call the layers in ascending order for
+ *            the same token, batch and scale (a block's lowest layer first, then its upper
+ *            layers, before the next block).  A tag in the buffer (token count and block, per
+ *            sequence and kv head) is checked on the device; a mismatch zeroes the output row
+ *            and raises the flag pod_cache_check reports.
+ * With head-wise blocks (pod_config.block_lowest) a layer can be the lowest for some kv heads
+ * and an upper layer for others: each kv head writes or reads its own part of the buffer.
  * Other arguments as in pod_decode_attention; no q_shared is needed.
  */
 int pod_score_buffer_bytes(const pod_config *cfg, size_t *bytes);
@@ -195,7 +198,8 @@ int pod_decode_attention_reuse(pod_cache *cache, int layer, const void *q, const
  * Decode attention with the gated skip of distant tokens (appendix "Computation Optimization for
  * Distant Tokens").  Built on score reuse: same `scores` buffer and call order.  For the block's
  * lowest layer the call equals pod_decode_attention_reuse (it also leaves the distant
- * maximum and sum of every query head in the buffer).  For an upper layer the gate of Eq. 4,
+ * maximum and sum of every query head in the buffer).  For an upper layer (head by head with
+ * head-wise blocks) the gate of Eq. 4,
  *     g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)),
  * is evaluated per (sequence, query head) once the proximal logits are known; heads with
  * g >= tau leave the distant tokens out and return o^P, the softmax over their proximal tokens

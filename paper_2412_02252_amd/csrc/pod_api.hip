@@ -398,7 +398,6 @@ static int decode_with_scores(pod_cache *cache, int layer, const void *q, const 
 {
     if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
     if (!scores) return pod_fail(POD_ERR_INVALID_ARG, "scores is NULL");
-    if (!cache->uniform) return pod_fail(POD_ERR_INVALID_ARG, "score reuse and the gated skip need the same blocks for every kv head");
     if ((uintptr_t)scores % 256) return pod_fail(POD_ERR_INVALID_ARG, "scores must be 256-byte aligned");
     const pod_layout &ly = cache->ly;
     const size_t need = pod_score_header_bytes(ly) + (size_t)ly.B * ly.Hq * pod_score_stride(ly) * sizeof(float);

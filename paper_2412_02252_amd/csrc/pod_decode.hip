@@ -79,12 +79,12 @@ struct decode_params {
     // lowest layer, fp32, stored tile by tile in the register order of the S^T accumulators:
     // [B][Hkv][score_stride / (32 * rep) tiles][4 (lane / 16)][rep heads][8 tokens of the lane],
     // so that a wave writes (and later reads) 32 contiguous bytes per lane and 128 contiguous bytes
-    // per 4 neighbouring lanes; preceded by a header int32 [B][2] = (n, block)
+    // per 4 neighbouring lanes; preceded by a header int32 [B][Hkv][2] = (n, distant-key store of the head's block)
     float *scores;
     int32_t *score_hdr;
     int32_t score_stride;
-    int32_t block_id;
-    int32_t mode;    // 0 plain, 1 lowest layer writes scores, 2 upper layer reads them, 3 upper layer reads them and gates
+    int32_t mode;    // 0 plain; 2 score reuse; 3 score reuse with the gated skip.  With 2 and 3 a kv head for which this
+                     // layer is the lowest of its block writes the logits, every other head reads them
     // gated skip of distant tokens (mode 1 writes gate_d, mode 3 uses it): per (sequence, query head)
     float *gate_d;   // [B][Hq][2]: maximum and sum of the distant exponentials at the lowest layer (base-2 domain)
     int32_t *skip;   // [B][Hq]: 1 where the upper layer left the distant part out (written by its distant pass)
@@ -227,9 +227,14 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     if (start >= region_len) return;
     const int end = min(start + chunk, region_len);
 
-    if (MODE == 1 && c == 0 && h == 0 && threadIdx.x == 0) { // tag the score buffer: which token, which block
-        p.score_hdr[2 * b] = n;
-        p.score_hdr[2 * b + 1] = p.block_id;
+    // Score reuse with head-wise blocks: the writing launch (MODE 1) serves the kv heads for which this layer is
+    // the lowest of the block, the reading launches (MODE 2, 3, 4) the others; with uniform blocks one of the
+    // two kinds is empty and is not launched.
+    if (MODE == 1 && head_arg >= 0) return;
+    if (MODE >= 2 && head_arg < 0) return;
+    if (MODE == 1 && c == 0 && threadIdx.x == 0) { // tag this head's logits: which token, which block's keys
+        p.score_hdr[2 * ((size_t)b * hkv + h)] = n;
+        p.score_hdr[2 * ((size_t)b * hkv + h) + 1] = head_arg & 0x7fffffff;
     }
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
@@ -549,11 +554,13 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     auto chunk_slot = [&](int v) { return v < nd ? v : hot.max_nd + (v - nd); };
 
     const int g = threadIdx.x / LPR, x = threadIdx.x % LPR;
+    const int head_arg = load_head_arg(head / hot.rep);
+    const bool low = head_arg < 0;   // this layer is the lowest of the head's block
     // gated upper layer: a head whose gate reached tau merges its proximal partials only
     int v_begin = 0;
-    if (p.mode == 3 && nd > 0 && p.skip[(size_t)b * hot.hq + head] != 0) v_begin = nd;
+    if (p.mode == 3 && !low && nd > 0 && p.skip[(size_t)b * hot.hq + head] != 0) v_begin = nd;
     // lowest layer of a score-reuse block: leave the distant maximum and sum for the gates of the upper layers
-    if (p.mode == 1 && xs == 0 && threadIdx.x < 64) {
+    if (p.mode != 0 && low && xs == 0 && threadIdx.x < 64) {
         const float2 dl = merged_ml((const float *)ml, n > 0 ? nd : 0, (int)threadIdx.x);
         if (threadIdx.x == 0) {
             p.gate_d[((size_t)b * hot.hq + head) * 2] = dl.x;
@@ -614,8 +621,9 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
             n = 0;
         }
     }
-    if (p.mode >= 2 && n > hot.prows) { // the distant logits must be those of this token and block
-        if (p.score_hdr[2 * b] != n || p.score_hdr[2 * b + 1] != p.block_id) { bad = true; n = 0; }
+    if (p.mode != 0 && !low && n > hot.prows) { // the distant logits must be those of this token and of the head's block
+        const size_t tag = 2 * ((size_t)b * hot.hkv + head / hot.rep);
+        if (p.score_hdr[tag] != n || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff)) { bad = true; n = 0; }
     }
     uint2 res = make_uint2(0u, 0u);
     if (n > 0) {
@@ -641,8 +649,8 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
 
 size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
 
-// header of the score buffer: int32 [B][2] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
-static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * 2 * sizeof(int32_t) + 255) / 256 * 256; }
+// header of the score buffer: int32 [B][Hkv][2] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
+static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hkv * 2 * sizeof(int32_t) + 255) / 256 * 256; }
 static size_t score_gate_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * 2 * sizeof(float) + 255) / 256 * 256; }
 size_t pod_score_skip_offset_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly); }
 size_t pod_score_header_bytes(const pod_layout &ly)
@@ -657,8 +665,12 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     const pod_layout &ly = c->ly;
     const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
     const int H = ly.Hkv;
-    bool lowest_all = true;
-    for (int h = 0; h < H; ++h) lowest_all = lowest_all && c->lowest[(size_t)layer * H + h] == layer;
+    bool lowest_all = true, lowest_any = false;
+    for (int h = 0; h < H; ++h) {
+        const bool low = c->lowest[(size_t)layer * H + h] == layer;
+        lowest_all = lowest_all && low;
+        lowest_any = lowest_any || low;
+    }
     // the layer whose lengths the device compares with this layer's: the block's lowest layer when all kv heads
     // share it (the host has already compared every head's lowest layer through its mirror)
     const int lowest = c->uniform ? c->lowest[(size_t)layer * H] : layer;
@@ -678,14 +690,13 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.flag = (int32_t *)(c->base + ly.off_flag);
     p.maxctx = ly.maxctx;
     p.out = (pod_bf16 *)out;
-    p.mode = scores ? (lowest_all ? 1 : (tau >= 0.f ? 3 : 2)) : 0;
+    p.mode = scores ? (tau >= 0.f ? 3 : 2) : 0;
     p.score_hdr = (int32_t *)scores;
     p.gate_d = scores ? (float *)((char *)scores + score_tag_bytes(ly)) : nullptr;
     p.skip = scores ? (int32_t *)((char *)scores + score_tag_bytes(ly) + score_gate_bytes(ly)) : nullptr;
     p.tau = tau;
     p.scores = scores ? (float *)((char *)scores + pod_score_header_bytes(ly)) : nullptr;
     p.score_stride = (int32_t)pod_score_stride(ly);
-    p.block_id = c->kslot[(size_t)layer * H] / H; // uniform tables only (score reuse): number of the block
     p.hot.use_hlen = B <= kMaxHostLens;
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
@@ -724,17 +735,20 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // gated upper layer: proximal chunks first, then the distant chunks, whose workgroups read the proximal partials
     const dim3 grid_p((unsigned)(NC - p.hot.max_nd), (unsigned)ly.Hkv, (unsigned)B);
     const dim3 grid_d((unsigned)(p.hot.max_nd > 0 ? p.hot.max_nd : 1), (unsigned)ly.Hkv, (unsigned)B);
-    if (ly.D == 128) {
-        if (p.mode == 0) POD_LAUNCH_PARTIAL(128, 0, grid);
-        else if (p.mode == 1) POD_LAUNCH_PARTIAL(128, 1, grid);
-        else if (p.mode == 2) POD_LAUNCH_PARTIAL(128, 2, grid);
-        else { POD_LAUNCH_PARTIAL(128, 3, grid_p); if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(128, 4, grid_d); }
-    } else {
-        if (p.mode == 0) POD_LAUNCH_PARTIAL(64, 0, grid);
-        else if (p.mode == 1) POD_LAUNCH_PARTIAL(64, 1, grid);
-        else if (p.mode == 2) POD_LAUNCH_PARTIAL(64, 2, grid);
-        else { POD_LAUNCH_PARTIAL(64, 3, grid_p); if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(64, 4, grid_d); }
+    // score reuse: the writing launch for the kv heads whose block starts at this layer, the reading launch(es) for
+    // the others (workgroups of the other kind leave at once); a gated read is two launches, proximal chunks first
+#define POD_LAUNCH_ALL(DD)                                                                   \
+    if (p.mode == 0) POD_LAUNCH_PARTIAL(DD, 0, grid);                                        \
+    else {                                                                                   \
+        if (lowest_any) POD_LAUNCH_PARTIAL(DD, 1, grid);                                     \
+        if (!lowest_all && p.mode == 2) POD_LAUNCH_PARTIAL(DD, 2, grid);                     \
+        if (!lowest_all && p.mode == 3) {                                                    \
+            POD_LAUNCH_PARTIAL(DD, 3, grid_p);                                               \
+            if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(DD, 4, grid_d);                         \
+        }                                                                                    \
     }
+    if (ly.D == 128) { POD_LAUNCH_ALL(128) } else { POD_LAUNCH_ALL(64) }
+#undef POD_LAUNCH_ALL
 #undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }
     if (ly.D == 128)

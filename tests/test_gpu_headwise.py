@@ -88,21 +88,91 @@ def test_explicit_uniform_table_behaves_like_group_size():
         assert_close(b.decode_reuse(layer, [n], scores), b.decode_ref(layer, [n]), f"reuse layer {layer}")
 
 
-def test_score_reuse_and_gating_refuse_headwise_tables_and_lagging_lowest_layers_are_caught():
+def test_lagging_lowest_layer_of_one_head_is_caught_on_the_host():
     c = Case(4, 1, 6, 3, 64, 8, 32, 1, 300, seed=730, block_lowest=MAP4)
     for layer in range(4):
         c.fill(layer, 0, 100)
-    scores = c.gpu.new_score_buffer()
-    ctx = torch.tensor([100], dtype=torch.int32, device=c.dev)
-    with pytest.raises(pod.PodError):
-        c.gpu.pod_decode_attention_reuse(0, c.decode_queries(0, [100], c.dev), ctx, c.scale, scores)
-    with pytest.raises(pod.PodError):
-        c.gpu.pod_decode_attention_gated(0, c.decode_queries(0, [100], c.dev), ctx, c.scale, 0.5, scores)
     # layer 3 moves ahead of layer 2, the lowest layer of kv head 1's block: refused on the host
     c.append(3, [100])
     with pytest.raises(pod.PodError) as e:
         c.decode(3, [101])
     assert e.value.code == pod.binding.ERR_STATE
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_score_reuse_with_a_headwise_table(d):
+    """Layers in ascending order through the score-reuse entry point: at each layer the kv heads whose block
+    starts there write their logits, the others read theirs (MAP4 has layers that do both at once)."""
+    L, Hq, Hkv, S, W = 4, 6, 3, 8, 32
+    lens = [150, 41, 300]
+    c = Case(L, 1, Hq, Hkv, d, S, W, len(lens), 400, seed=740 + d, block_lowest=MAP4)
+    for layer in range(L):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    scores = c.gpu.new_score_buffer()
+    for step in range(2):
+        pos = [n + step for n in lens]
+        for layer in range(L):
+            c.append(layer, pos)
+        ctx = [p + 1 for p in pos]
+        for layer in range(L):
+            assert_close(c.decode_reuse(layer, ctx, scores), c.decode_ref(layer, ctx), f"step {step} layer {layer}")
+    c.gpu.pod_cache_check()
+    # a stale buffer: layer 3 reads head 1's logits of the previous token -> rows zeroed, flag raised
+    pos = [n + 2 for n in lens]
+    for layer in range(L):
+        c.append(layer, pos)
+    ctx = [p + 1 for p in pos]
+    out = c.decode_reuse(3, ctx, scores)
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_cache_check()
+    rep = Hq // Hkv                                         # (sequence 1 has no distant tokens: nothing to check there)
+    assert float(out[0, : 2 * rep].float().abs().max()) == 0.0     # kv heads 0 and 1 read stale logits at layer 3
+    assert_close(out[0, 2 * rep:], c.decode_ref(3, ctx)[0, 2 * rep:], "kv head 2 starts a block at layer 3: exact")
+
+
+def test_gated_skip_with_a_headwise_table():
+    """Per head: no gate where the layer is the lowest of the head's block, the gate of Eq. 4 elsewhere;
+    decisions and outputs against the oracle for tau = 1 (never), 0 (always) and a value between the gates."""
+    L, Hq, Hkv, d, S, W = 4, 6, 3, 128, 8, 64
+    lens = [500, 260]
+    c = Case(L, 1, Hq, Hkv, d, S, W, len(lens), 600, seed=750, block_lowest=MAP4)
+    for layer in range(L):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    scores = c.gpu.new_score_buffer()
+    ctx_t = torch.tensor(lens, dtype=torch.int32, device=c.dev)
+
+    def both(layer, tau):
+        got = c.gpu.pod_decode_attention_gated(layer, c.decode_queries(layer, lens, c.dev), ctx_t, c.scale, tau, scores)
+        flags = c.gpu.skip_flags(scores)[: len(lens)].cpu().numpy().copy()
+        qs = c.shared_queries(layer, lens, "cpu")
+        ref, g, skipped = c.cpu.decode_attention_gated(layer, gen.bf16_bits(c.decode_queries(layer, lens, "cpu")),
+                                                       gen.bf16_bits(qs) if qs is not None else None, lens, c.scale, tau)
+        return got, flags, ref, g, skipped
+
+    rep = Hq // Hkv
+    for tau in (1.0, 0.0, None):
+        for layer in range(L):
+            if tau is None:                                  # a threshold inside the widest gap of this layer's gates
+                _, _, _, g, _ = both(layer, 1.0)
+                upper = np.repeat(c.lowest[layer] != layer, rep)
+                gs = np.sort(g[:, upper].ravel())
+                if len(gs) < 2:
+                    t = 0.5
+                else:
+                    gaps = np.diff(gs)
+                    t = float(gs[np.argmax(gaps)] + gaps.max() / 2)
+                    if gaps.max() < 0.04:
+                        t = 0.0
+            else:
+                t = tau
+            got, flags, ref, g, skipped = both(layer, t)
+            upper = np.repeat(c.lowest[layer] != layer, rep)
+            np.testing.assert_array_equal(flags[:, upper], skipped[:, upper], err_msg=f"tau={t} layer {layer}")
+            assert not skipped[:, ~upper].any()              # heads for which the layer is the lowest never skip
+            assert_close(got, ref, f"tau={t} layer {layer}")
+    c.gpu.pod_cache_check()
 
 
 # ---------------------------------------------------------------- attention similarity -> grouping -> table
