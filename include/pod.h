@@ -123,6 +123,15 @@ int pod_cache_seq_len(const pod_cache *cache, int layer, int seq_slot, int64_t *
  */
 int pod_cache_check(pod_cache *cache, void *stream);
 
+/*
+ * Wait for stream, then copy the device-side lengths of every (layer, slot) into the host
+ * mirror.  Only needed after work the host did not see call by call: a replay of a captured
+ * HIP graph advances the device-side lengths but not the mirror (a captured call fixes its
+ * host-side arguments, the mirror's lengths among them, so a graph must be replayed from the
+ * cache state it was captured at).
+ */
+int pod_cache_sync_lengths(pod_cache *cache, void *stream);
+
 /* Bytes of device scratch pod_decode_attention needs for cfg (split-K partial results). host out. */
 int pod_workspace_bytes(const pod_config *cfg, size_t *bytes);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
-    "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
+    "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
 ]
 
 
@@ -65,6 +65,7 @@ def load():
         "pod_cache_reset": [vp, C.c_int, vp],
         "pod_cache_seq_len": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64)],
         "pod_cache_check": [vp, vp],
+        "pod_cache_sync_lengths": [vp, vp],
         "pod_workspace_bytes": [cfgp, szp],
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
@@ -209,6 +210,9 @@ class PodCache:
 
     def pod_cache_check(self):
         _check(load().pod_cache_check(self.handle, _stream()))
+
+    def pod_cache_sync_lengths(self):
+        _check(load().pod_cache_sync_lengths(self.handle, _stream()))
 
     def pod_cache_append(self, layer, k_new, v_new, positions):
         B = positions.shape[0]

@@ -301,6 +301,21 @@ extern "C" int pod_cache_check(pod_cache *cache, void *stream)
     return POD_OK;
 }
 
+extern "C" int pod_cache_sync_lengths(pod_cache *cache, void *stream)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    const size_t count = (size_t)cache->ly.L * cache->ly.B;
+    int32_t *tmp = (int32_t *)malloc(count * sizeof(int32_t));
+    if (!tmp) return pod_fail(POD_ERR_CAPACITY, "out of host memory");
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(tmp, cache->base + cache->ly.off_lens, count * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { free(tmp); return pod_hip_fail(e, "copying the lengths to the host"); }
+    for (size_t i = 0; i < count; ++i) cache->host_len[i] = tmp[i];
+    free(tmp);
+    return POD_OK;
+}
+
 extern "C" int pod_cache_append(pod_cache *cache, int layer, const void *k_new, const void *v_new,
                                 const int32_t *positions, int B, void *stream)
 {
