@@ -152,52 +152,49 @@ __global__ void gather_kernel(const char *base, pod_layout ly, pod_gather_args g
                               int p0, int T, const uint4 *__restrict__ k_chunk, const uint4 *__restrict__ v_chunk,
                               const uint4 *__restrict__ ks_chunk, uint4 *k_all, uint4 *v_all, uint4 *ks_all)
 {
-    const int cpr = ly.D / 8;
+    // blockIdx.y = kv head: everything that depends on the head is uniform over the block, and the index
+    // arithmetic per piece is a shift and a mask (D / 8 is 8 or 16)
+    const int h = blockIdx.y;
+    const int cpr = ly.D / 8, cshift = ly.D == 128 ? 4 : 3;
     const uint4 *proxK = (const uint4 *)(base + ly.off_proxK);
     const uint4 *proxV = (const uint4 *)(base + ly.off_proxV);
     const uint4 *distK = (const uint4 *)(base + ly.off_distK);
     const uint4 *distV = (const uint4 *)(base + ly.off_distV);
     const int32_t *lens = (const int32_t *)(base + ly.off_lens);
     const int rec_lo = p0 - ly.W > ly.S ? p0 - ly.W : ly.S;   // first position of this layer's recent window
-    const size_t total = (size_t)(p0 + T) * ly.Hkv * cpr;
+    const bool low = (lowest_mask >> h) & 1;
+    const bool want_ks = !low && ks_all;
+    const int la = ga.low_layer[h];
+    const int na = want_ks ? lens[(size_t)la * ly.B + b] : 0;  // p0, or p0 + T if that layer took the chunk already
+    const int rec_a = na - ly.W > ly.S ? na - ly.W : ly.S;
+    const size_t own_prox = pod_prox_row0(ly, layer, b, h), low_prox = pod_prox_row0(ly, la, b, h);
+    const size_t own_dist = pod_dist_row0(ly, layer, b, h), key_dist = (size_t)(ga.low_row[h] + b) * ly.Cd;
+    const size_t total = (size_t)(p0 + T) << cshift;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
-        const int c = (int)(idx % cpr);
-        const int h = (int)((idx / cpr) % ly.Hkv);
-        const int j = (int)(idx / ((size_t)cpr * ly.Hkv));
-        const bool low = (lowest_mask >> h) & 1;
+        const int c = (int)(idx & (cpr - 1));
+        const int j = (int)(idx >> cshift);
+        const size_t dst = (((size_t)j * ly.Hkv + h) << cshift) + c;
         if (j >= p0) {
-            const size_t src = ((size_t)(j - p0) * ly.Hkv + h) * cpr + c;
-            k_all[idx] = k_chunk[src];
-            v_all[idx] = v_chunk[src];
-            if (!low && ks_all) ks_all[idx] = ks_chunk[src];
+            const size_t src = (((size_t)(j - p0) * ly.Hkv + h) << cshift) + c;
+            k_all[dst] = k_chunk[src];
+            v_all[dst] = v_chunk[src];
+            if (want_ks) ks_all[dst] = ks_chunk[src];
             continue;
         }
+        const int slot = j < ly.S ? j : ly.S + (j - ly.S) % ly.W;
+        const size_t r = (size_t)(j - ly.S);
         uint4 kk = make_uint4(0, 0, 0, 0), vv;
         if (j < ly.S || j >= rec_lo) {
-            const int slot = j < ly.S ? j : ly.S + (j - ly.S) % ly.W;
-            const size_t pr = (pod_prox_row0(ly, layer, b, h) + slot) * cpr + c;
-            kk = proxK[pr];
-            vv = proxV[pr];
+            kk = proxK[((own_prox + slot) << cshift) + c];
+            vv = proxV[((own_prox + slot) << cshift) + c];
         } else {
-            const size_t r = (size_t)(j - ly.S);
-            vv = distV[(pod_dist_row0(ly, layer, b, h) + r) * cpr + c];
-            if (low) kk = distK[((size_t)(ga.low_row[h] + b) * ly.Cd + r) * cpr + c];
+            vv = distV[((own_dist + r) << cshift) + c];
+            if (low) kk = distK[((key_dist + r) << cshift) + c];
         }
-        k_all[idx] = kk;
-        v_all[idx] = vv;
-        if (!low && ks_all) {
-            const int la = ga.low_layer[h];
-            const int na = lens[(size_t)la * ly.B + b];       // p0, or p0 + T if that layer took the chunk already
-            const int rec_a = na - ly.W > ly.S ? na - ly.W : ly.S;
-            uint4 ka;
-            if (j < ly.S || j >= rec_a) {
-                const int slot = j < ly.S ? j : ly.S + (j - ly.S) % ly.W;
-                ka = proxK[(pod_prox_row0(ly, la, b, h) + slot) * cpr + c];
-            } else {
-                ka = distK[((size_t)(ga.low_row[h] + b) * ly.Cd + (size_t)(j - ly.S)) * cpr + c];
-            }
-            ks_all[idx] = ka;
-        }
+        k_all[dst] = kk;
+        v_all[dst] = vv;
+        if (want_ks)
+            ks_all[dst] = (j < ly.S || j >= rec_a) ? proxK[((low_prox + slot) << cshift) + c] : distK[((key_dist + r) << cshift) + c];
     }
 }
 
@@ -358,8 +355,10 @@ int pod_launch_gather(const pod_cache *c, int layer, int seq_slot, int p0, int T
         ga.low_layer[h] = h < H ? c->lowest[(size_t)layer * H + h] : 0;
         ga.low_row[h] = h < H ? c->kslot[(size_t)layer * H + h] * c->ly.B : 0;
     }
-    const size_t items = (size_t)(p0 + T) * H * (c->ly.D / 8);
-    hipLaunchKernelGGL(gather_kernel, dim3(grid_for(items)), dim3(kThreads), 0, st, (const char *)c->base, c->ly, ga,
+    const size_t items = (size_t)(p0 + T) * (c->ly.D / 8);      // per kv head (blockIdx.y)
+    int gx = grid_for(items);
+    if (gx > 4096 / H + 1) gx = 4096 / H + 1;
+    hipLaunchKernelGGL(gather_kernel, dim3(gx, H), dim3(kThreads), 0, st, (const char *)c->base, c->ly, ga,
                        pod_make_headmap(c, layer).lowest_mask, layer, seq_slot, p0, T, (const uint4 *)k_chunk,
                        (const uint4 *)v_chunk, (const uint4 *)ks_chunk, (uint4 *)k_all, (uint4 *)v_all, (uint4 *)ks_all);
     POD_HIP_TRY(hipGetLastError());
