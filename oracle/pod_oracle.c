@@ -281,6 +281,16 @@ void oracle_cache_destroy(pod_oracle_cache *c)
     free(c);
 }
 
+/* Forget one sequence slot (seq >= 0) or all of them (seq < 0), at every layer. */
+int oracle_cache_reset(pod_oracle_cache *c, int seq)
+{
+    if (!c || seq >= c->B) return ORACLE_ERR_ARG;
+    for (int l = 0; l < c->L; ++l)
+        for (int b = 0; b < c->B; ++b)
+            if (seq < 0 || b == seq) seq_free(&c->st[(size_t)l * c->B + b]);
+    return ORACLE_OK;
+}
+
 static int seq_alloc(const pod_oracle_cache *c, seq_state *s, int lowest)
 {
     if (s->sinkV) return ORACLE_OK;

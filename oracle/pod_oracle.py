@@ -38,6 +38,8 @@ def lib():
         L.oracle_cache_bytes_formula_map.argtypes = [C.c_int] * 5 + [C.c_long, C.c_int, i32p, f64p, f64p]
         L.oracle_cache_destroy.restype = None
         L.oracle_cache_destroy.argtypes = [C.c_void_p]
+        L.oracle_cache_reset.restype = C.c_int
+        L.oracle_cache_reset.argtypes = [C.c_void_p, C.c_int]
         L.oracle_cache_len.restype = C.c_long
         L.oracle_cache_len.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.oracle_cache_append.restype = C.c_int
@@ -149,6 +151,9 @@ class Cache:
         if getattr(self, "_h", None):
             lib().oracle_cache_destroy(self._h)
             self._h = None
+
+    def reset(self, seq=-1):
+        _chk(lib().oracle_cache_reset(self._h, seq), "oracle_cache_reset")
 
     def length(self, layer, seq):
         return lib().oracle_cache_len(self._h, layer, seq)

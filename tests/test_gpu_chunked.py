@@ -241,3 +241,50 @@ def test_append_many_more_sequences_than_one_launch_covers():
         if starts[b]:
             c.assert_cache_equal(0, b)
     c.gpu.pod_cache_check()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_sequences_of_cache_updates(seed):
+    """Random mixes of single appends, ragged multi-token appends, resets of one slot and prompt fills, every
+    layer kept in step: after each operation lengths agree, and at intervals every region of every slot is
+    compared bit for bit and decode attention is compared on all sequences."""
+    rng = np.random.default_rng(seed)
+    L, G, Hq, Hkv, d, S, W, B, cap = 2, 2, 4, 2, 64, 6, 24, 3, 160
+    c = Case(L, G, Hq, Hkv, d, S, W, B, cap, seed=350 + seed)
+    n = [0] * B
+    for step in range(60):
+        op = rng.choice(["append", "many", "many", "reset", "fill"], p=[0.3, 0.25, 0.2, 0.1, 0.15])
+        if op == "append" and max(n) < cap:
+            for layer in range(L):
+                c.append(layer, list(n))
+            n = [x + 1 for x in n]
+        elif op == "many":
+            T = int(rng.integers(1, 40))
+            counts = [int(min(rng.integers(0, T + 1), cap - n[b])) for b in range(B)]
+            for layer in range(L):
+                append_many_both(c, layer, list(n), counts, T)
+            n = [x + k for x, k in zip(n, counts)]
+        elif op == "reset":
+            b = int(rng.integers(0, B))
+            c.gpu.pod_cache_reset(b)
+            c.cpu.reset(b)
+            n[b] = 0
+        elif op == "fill":
+            empty = [b for b in range(B) if n[b] == 0]
+            if empty:
+                b, m = empty[0], int(rng.integers(1, 100))
+                for layer in range(L):
+                    c.fill(layer, b, m)
+                n[b] = m
+        for layer in range(L):
+            for b in range(B):
+                assert c.gpu.pod_cache_seq_len(layer, b) == n[b] == c.cpu.length(layer, b), (step, op)
+        if step % 6 == 5 or step == 59:
+            for layer in range(L):
+                for b in range(B):
+                    if n[b]:
+                        c.assert_cache_equal(layer, b)
+            if min(n) >= 1:
+                for layer in range(L):
+                    assert_close(c.decode(layer, list(n)), c.decode_ref(layer, list(n)), f"step {step} layer {layer}")
+    c.gpu.pod_cache_check()

@@ -685,3 +685,17 @@ def test_chunk_attention_rejects_a_lowest_layer_out_of_step():
     c.append_many(1, bits(k[:6])[None], bits(v[:6])[None], [0])
     with pytest.raises(po.OracleError):   # chunk of 3 at p0 = 6: the lowest layer must hold 6 or 9 tokens, not 7
         c.chunk_attention(1, 0, bits(q[6:9]), bits(k[6:9]), bits(v[6:9]), bits(q[6:9]), bits(k[6:9]), 0.5)
+
+
+def test_reset_forgets_one_slot_or_all():
+    c = po.Cache(2, 2, 1, 2, 1, 2, 2, 16)
+    k, v = _tagged_kv(6, 1, 2, 0)
+    for layer in range(2):
+        for b in range(2):
+            c.fill(layer, b, k, v)
+    c.reset(1)
+    assert [c.length(l, b) for l in range(2) for b in range(2)] == [6, 0, 6, 0]
+    c.fill(0, 1, k[:3], v[:3])                               # an emptied slot takes a new prompt
+    assert np.array_equal(c.export(0, 1)["recentK"], k[1:3])
+    c.reset()
+    assert [c.length(l, b) for l in range(2) for b in range(2)] == [0, 0, 0, 0]
