@@ -62,3 +62,39 @@ def test_prefill_in_one_call_and_in_chunks(L, G, Hq, Hkv, d, S, W, max_ctx, n):
     c2 = Case(L, G, Hq, Hkv, d, S, W, 1, max_ctx, seed=1100 + n)
     cuts = [n // 3, 1, n - n // 3 - 1]
     run_chunks(c2, [t for t in cuts if t > 0])
+
+
+@pytest.mark.parametrize("seed", list(range(1, 9)))
+def test_random_geometries_and_lengths(seed):
+    """Geometry, batch and lengths drawn at random (seeded): cache updates, decode (plain and with score reuse),
+    prefill in one call and in chunks, all against the oracle."""
+    rng = np.random.default_rng(seed)
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 4, 8]))
+    S, W = int(rng.integers(0, 21)), int(rng.integers(1, 71))
+    G = int(rng.choice([1, 2, 3]))
+    L = G * int(rng.choice([1, 2]))
+    B = int(rng.integers(1, 4))
+    lens = [int(rng.integers(1, 400)) for _ in range(B)]
+    max_ctx = max(lens) + 2
+    c = Case(L, G, Hq, Hkv, d, S, W, B, max_ctx, seed=1200 + seed)
+    for layer in range(L):
+        for b in range(B):
+            c.fill(layer, b, lens[b])
+        c.append(layer, lens)
+    ctx = [n + 1 for n in lens]
+    scores = c.gpu.new_score_buffer()
+    for layer in range(L):
+        ref = c.decode_ref(layer, ctx)
+        assert_close(c.decode(layer, ctx), ref, f"decode layer {layer}")
+        assert_close(c.decode_reuse(layer, ctx, scores), ref, f"reuse layer {layer}")
+        c.assert_cache_equal(layer, int(rng.integers(0, B)))
+    c.gpu.pod_cache_check()
+    n = int(rng.integers(1, 380))
+    p = Case(L, G, Hq, Hkv, d, S, W, 1, n, seed=1300 + seed, with_oracle_cache=False)
+    for layer in (0, L - 1):
+        assert_close(run_prefill(p, layer, n), ref_prefill(p, layer, n, np.arange(n)), f"prefill layer {layer}")
+    cuts = sorted(set(int(x) for x in rng.integers(1, n, size=3)) | {n}) if n > 1 else [n]
+    chunks = [b - a for a, b in zip([0] + cuts[:-1], cuts)]
+    run_chunks(Case(L, G, Hq, Hkv, d, S, W, 1, n, seed=1300 + seed), chunks)
