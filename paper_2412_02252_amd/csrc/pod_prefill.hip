@@ -361,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     __syncthreads(); // every wave is done reading K(0): iteration 0 overwrites its slot
 
     // one iteration: FIRST has no PV slots (there is no earlier tile)
-    auto iteration = [&](auto first_tag, auto slot_tag, int t, f32x16 (&sc)[NKB], f32x16 (&sn)[NKB], const u32x4 (&pprev)[NPS], u32x4 (&pcur)[NPS]) {
+    auto iteration = [&](auto first_tag, auto slot_tag, int t, f32x16 (&sc)[NKB], f32x16 (&sn)[NKB], u32x4 (&pprev)[NPS], u32x4 (&pcur)[NPS]) {
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr int slot = decltype(slot_tag)::value; // = t % 2: every LDS address below is a compile-time offset
         // K(t+2) replaces K(t) and V(t) replaces V(t-2), both last read before the previous barrier.
@@ -369,12 +369,25 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         if (t + 2 < T) request_k(kt_c, ph_c, slot);
         request_v(kt_a, slot);
         if (mx_next > m_ref + kLazy) { // (rows with nothing valid so far have mx = -inf and never trigger)
+            // The reference moves before tile t is exponentiated: everything computed with the old one is brought
+            // to the new one.  That is the row sum, the output accumulators (tiles <= t-2), and P(t-1), whose
+            // product with V(t-1) is still to come in this iteration's PV slots.
             const float alpha = __builtin_amdgcn_exp2f(m_ref - mx_next);
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            if constexpr (!FIRST) {
+#pragma unroll
+                for (int ks = 0; ks < NPS; ++ks)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const unsigned pk = pprev[ks][w];
+                        const float lo = __builtin_bit_cast(float, pk << 16), hi = __builtin_bit_cast(float, pk & 0xffff0000u);
+                        pprev[ks][w] = pack_bf16(lo * alpha, hi * alpha);
+                    }
+            }
             m_ref = mx_next;
         }
         if (t + 1 == nD) load_q(p.q); // the next tile is the first of the own-key phase

@@ -96,3 +96,37 @@ def test_prefill_argument_errors():
         c.gpu.pod_prefill_attention(0, 0, big, c.keys(0, 0, 65, c.dev), c.values(0, 0, 65, c.dev), None, None, c.scale,
                                     write_cache=True)
     assert e.value.code == pod.binding.ERR_CAPACITY
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 8, 2), (64, 4, 2)])
+@pytest.mark.parametrize("rate,scale", [(0.02, 8.0), (0.3, 16.0)])
+def test_outlier_keys_move_the_reference_maximum(d, Hq, Hkv, rate, scale):
+    """Rows of keys scaled by 8 or 16 give logits tens of units above the rest, arriving at random tiles: the
+    running reference of the softmax has to move (and the accumulated sums to be rescaled) many times per row,
+    which unit-variance inputs never ask for.  With 30 % outliers at x16 most probabilities underflow to zero."""
+    n = 700
+    c = Case(2, 2, Hq, Hkv, d, 8, 40, 1, n, seed=260, with_oracle_cache=False, outlier_rate=rate, outlier_scale=scale)
+    for layer in range(2):
+        assert_close(run_prefill(c, layer, n), ref_prefill(c, layer, n, np.arange(n)), f"layer {layer}")
+
+
+def test_logits_growing_along_the_prompt():
+    """Keys whose norm grows with the position: every tile raises the maximum of the rows that see it."""
+    n, Hq, Hkv, d = 600, 4, 2, 128
+    c = Case(2, 2, Hq, Hkv, d, 8, 40, 1, n, seed=261, with_oracle_cache=False)
+    ramp = (1.0 + torch.arange(n, dtype=torch.float32) / 20.0).view(n, 1, 1)
+    for layer in range(2):
+        q = c.queries(layer, 0, n, c.dev)
+        k = (c.keys(layer, 0, n, c.dev).float() * ramp.to(c.dev)).to(torch.bfloat16)
+        v = c.values(layer, 0, n, c.dev)
+        qs = c.queries(0, 0, n, c.dev) if layer else None
+        ks = (c.keys(0, 0, n, c.dev).float() * ramp.to(c.dev)).to(torch.bfloat16) if layer else None
+        out = c.gpu.pod_prefill_attention(layer, 0, q, k, v, qs, ks, c.scale)
+        rows = np.arange(n)
+        kc = (c.keys(layer, 0, n, "cpu").float() * ramp).to(torch.bfloat16)
+        ksc = (c.keys(0, 0, n, "cpu").float() * ramp).to(torch.bfloat16) if layer else None
+        ref = po.pod_attention(gen.bf16_bits(c.queries(layer, 0, n, "cpu")), gen.bf16_bits(kc),
+                               gen.bf16_bits(c.values(layer, 0, n, "cpu")),
+                               gen.bf16_bits(c.queries(0, 0, n, "cpu")) if layer else None,
+                               gen.bf16_bits(ksc) if layer else None, rows, c.S, c.W, c.scale)
+        assert_close(out, ref, f"layer {layer}")
