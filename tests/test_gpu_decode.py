@@ -126,13 +126,25 @@ def test_decode_steps_with_demotion_match_oracle_every_step():
     c.gpu.pod_cache_check()
 
 
-def test_outlier_keys_do_not_break_the_softmax():
-    c = Case(4, 4, 8, 2, 128, 8, 64, 1, 3000, seed=38, outlier_rate=0.01, outlier_scale=8.0)
+@pytest.mark.parametrize("rate,scale", [(0.01, 8.0), (0.3, 16.0)])
+def test_outlier_keys_do_not_break_the_softmax(rate, scale):
+    """Rows of keys scaled by 8 or 16: logits tens of units above the rest, so the running maximum moves inside
+    the tiles of a wave, between the waves of a workgroup and between the chunks the combine kernel merges;
+    through the plain path, score reuse and the gate at tau = 1."""
+    c = Case(4, 4, 8, 2, 128, 8, 64, 1, 3000, seed=38, outlier_rate=rate, outlier_scale=scale)
     n = 2900
     for layer in range(4):
         c.fill(layer, 0, n)
-    for layer in (0, 3):
-        assert_close(c.decode(layer, [n]), c.decode_ref(layer, [n]), f"layer {layer}")
+    scores = c.gpu.new_score_buffer()
+    ctx_t = torch.tensor([n], dtype=torch.int32, device=c.dev)
+    for layer in range(4):
+        ref = c.decode_ref(layer, [n])
+        assert_close(c.decode(layer, [n]), ref, f"layer {layer}")
+        assert_close(c.decode_reuse(layer, [n], scores), ref, f"reuse layer {layer}")
+    for layer in range(4):
+        got = c.gpu.pod_decode_attention_gated(layer, c.decode_queries(layer, [n], c.dev), ctx_t, c.scale, 1.0, scores)
+        assert_close(got, c.decode_ref(layer, [n]), f"gated layer {layer}")
+    c.gpu.pod_cache_check()
 
 
 # ---------------------------------------------------------------- score reuse (distant logits computed once per block)
