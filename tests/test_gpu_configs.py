@@ -240,3 +240,31 @@ def test_config4_prompt_in_chunks_sampled_rows_and_cache():
             for name in c:
                 assert np.array_equal(host_bits(g[name]), c[name]), (l, slot, name)
     cache.pod_cache_check()
+
+
+def test_long_prompt_100k_sampled_rows():
+    """A prompt of 100003 tokens (config 5's geometry: S=128, W=4096, 32/8 heads): index arithmetic far beyond the
+    benchmark's 16384; sampled rows of the upper layer against the definition, and the distant stores it fills."""
+    L, G, Hq, Hkv, d, S, W, n = 2, 2, 32, 8, 128, 128, 4096, 100003
+    seed = SEED0 + 6
+    cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, 1, n), DEV)
+    scale = 1.0 / math.sqrt(d)
+    Q = [gen.queries_bf16(seed, l, 0, n, Hq, d, device=DEV) for l in range(L)]
+    K = [gen.keys_bf16(seed, l, 0, n, Hkv, d, device=DEV) for l in range(L)]
+    V = [gen.values_bf16(seed, l, 0, n, Hkv, d, device=DEV) for l in range(L)]
+    rng = np.random.default_rng(seed)
+    rows = np.array(sorted(set([0, 1, S, S + W - 1, S + W, 65535, 65536, 65537, n - 2, n - 1] +
+                               [int(x) for x in rng.integers(S + W, n, 12)])))
+    Kh, Vh = [host_bits(t) for t in K], [host_bits(t) for t in V]
+    for l in range(L):
+        out = cache.pod_prefill_attention(l, 0, Q[l], K[l], V[l], Q[0] if l else None, K[0] if l else None, scale,
+                                          write_cache=True)
+        if l == 1:
+            ref = po.pod_attention(host_bits(Q[1][rows].contiguous()), Kh[1], Vh[1], host_bits(Q[0][rows].contiguous()),
+                                   Kh[0], rows, S, W, scale)
+            assert_close(out[rows], ref, "upper layer")
+    g = cache.pod_cache_export_logical(0, 0)
+    assert np.array_equal(host_bits(g["distK"]), Kh[0][S:n - W]) and np.array_equal(host_bits(g["distV"]), Vh[0][S:n - W])
+    g = cache.pod_cache_export_logical(1, 0)
+    assert np.array_equal(host_bits(g["distV"]), Vh[1][S:n - W]) and np.array_equal(host_bits(g["recentK"]), Kh[1][n - W:])
+    cache.pod_cache_check()
