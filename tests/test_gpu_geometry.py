@@ -98,3 +98,27 @@ def test_random_geometries_and_lengths(seed):
     cuts = sorted(set(int(x) for x in rng.integers(1, n, size=3)) | {n}) if n > 1 else [n]
     chunks = [b - a for a, b in zip([0] + cuts[:-1], cuts)]
     run_chunks(Case(L, G, Hq, Hkv, d, S, W, 1, n, seed=1300 + seed), chunks)
+
+
+@pytest.mark.parametrize("scale", [0.01, 1.0, 3.0])
+def test_other_scales(scale):
+    """scale is an argument: 0.01 gives an almost uniform softmax, 1 and 3 give logits with a standard deviation of
+    11 and 34 (a few keys take all the weight, and the running maxima move all the time)."""
+    lens = [900, 77]
+    c = Case(2, 2, 8, 2, 128, 8, 64, 2, 1000, seed=1400)
+    c.scale = scale
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    scores = c.gpu.new_score_buffer()
+    for layer in range(2):
+        ref = c.decode_ref(layer, lens)
+        assert_close(c.decode(layer, lens), ref, f"decode layer {layer}")
+        assert_close(c.decode_reuse(layer, lens, scores), ref, f"reuse layer {layer}")
+    p = Case(2, 2, 8, 2, 128, 8, 64, 1, 700, seed=1401, with_oracle_cache=False)
+    p.scale = scale
+    for layer in range(2):
+        assert_close(run_prefill(p, layer, 700), ref_prefill(p, layer, 700, np.arange(700)), f"prefill layer {layer}")
+    q = Case(2, 2, 8, 2, 128, 8, 64, 1, 700, seed=1401)
+    q.scale = scale
+    run_chunks(q, [300, 250, 150])
