@@ -280,7 +280,7 @@ def main():
                      "avg_kernel_us": round(kernel_s * 1e6, 3), "launches": launches},
     }
 
-    # ---- the same steps through the score-reuse entry point (SURVEY's first "next" row)
+    # ---- the same steps through the score-reuse entry point
     if RU > 0:
         ru = steps[Wm + K + P:]
         g2 = None
@@ -305,7 +305,7 @@ def main():
                               "value": round(rb / el / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
                               "speedup_vs_plain_step": round((elapsed / K) / (el / len(ru)), 3)}
 
-    # ---- gated skip of distant tokens (SURVEY's second "next" row): decode calls only (no appends), the
+    # ---- gated skip of distant tokens: decode calls only (no appends), the
     # R blocks round-robin, at the contexts the steps above left behind.  Three timings of the same
     # (lowest layer, upper layer) pair: plain; gated with the generated inputs (no head's gate reaches
     # tau = 0.7, so this is the cost of the two-launch structure); gated after the upper layers'
