@@ -54,7 +54,7 @@ struct decode_hot { // exactly two 64-byte lines, read in one go at kernel entry
     const u32x4 *kdist, *vdist, *kprox, *vprox; // row 0 of (slot 0, head 0) in this layer's / block's regions
     int32_t cd, prows;   // rows per (slot, head) in the distant / proximal regions (Cd, P = S + W)
     int32_t hkv, rep;
-    int32_t chunk;       // tokens per workgroup
+    int32_t chunk;       // tokens per workgroup: distant chunks in the low 16 bits, proximal chunks in the high 16 bits
     int32_t max_nd;      // distant chunk slots per (sequence, head)
     int32_t nc;          // all chunk slots per (sequence, head): max_nd + proximal slots
     int32_t use_hlen;    // 1: hlen[] holds the host mirror's length of every slot < B
@@ -208,7 +208,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int n_host = load_hlen_arg(b);
     const int head_arg = load_head_arg(h);
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
-    const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, chunk = hot.chunk, max_nd = hot.max_nd;
+    const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, max_nd = hot.max_nd;
+    const int chunk_p = (int)((unsigned)hot.chunk >> 16);
     const bool use_hlen = hot.use_hlen != 0;
     // The host mirror's length is always within the buffers; whether it agrees with context_lens
     // and the device-side lengths is checked by the combine kernel, which zeroes the output and
@@ -223,6 +224,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int n_dist = n - n_prox;
     const bool distant = c < max_nd;
     const int region_len = distant ? n_dist : n_prox;
+    const int chunk = distant ? (hot.chunk & 0xffff) : chunk_p;
     const int start = (distant ? c : c - max_nd) * chunk;
     if (start >= region_len) return;
     const int end = min(start + chunk, region_len);
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         // ---- the gate of this workgroup's heads: every wave computes the same values, 16 lanes per
         // head (four heads at a time), all loads of a pass in flight together
         typedef const __attribute__((address_space(1))) float *gfloat_ptr;
-        const int np = (n_prox + chunk - 1) / chunk;
+        const int np = (n_prox + chunk_p - 1) / chunk_p;
         const int sub = lane & 15, grp = lane >> 4;
         bool all_skip = true;
         for (int h0 = 0; h0 < hot.rep; h0 += 4) {
@@ -545,8 +547,9 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
 
     const int n_prox = n < hot.prows ? n : hot.prows;
     const int n_dist = n - n_prox;
-    const int nd = (n_dist + hot.chunk - 1) / hot.chunk;
-    const int np = (n_prox + hot.chunk - 1) / hot.chunk;
+    const int chunk_d = hot.chunk & 0xffff, chunk_p = (int)((unsigned)hot.chunk >> 16);
+    const int nd = (n_dist + chunk_d - 1) / chunk_d;
+    const int np = (n_prox + chunk_p - 1) / chunk_p;
     const int NC = hot.nc;
     const int nvalid = n > 0 ? nd + np : 0;
     const gfloat_ptr ml = (gfloat_ptr)hot.part_ml + ((size_t)b * hot.hq + head) * NC * 2;
@@ -714,11 +717,19 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     if (chunk < kMinChunk) chunk = kMinChunk;
     if (chunk > 1024 && env_chunk <= 0) chunk = 1024;
     if (chunk > 8192) chunk = 8192;
-    p.hot.chunk = (int)chunk;
+    // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time of
+    // one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
+    // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
+    const char *envp = getenv("POD_DECODE_CHUNK_PROX"); // tuning / test override
+    long chunk_p = envp && atoi(envp) > 0 ? atoi(envp) : ((scores && !lowest_all && tau >= 0.f) ? kMinChunk : chunk);
+    chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
+    if (chunk_p < kMinChunk) chunk_p = kMinChunk;
+    if (chunk_p > 8192) chunk_p = 8192;
+    p.hot.chunk = (int)(chunk | (chunk_p << 16));
     const int max_prox = max_len < ly.P ? max_len : ly.P;
     const int max_dist = max_len - max_prox;
-    p.hot.max_nd = chunk_slots(max_dist, p.hot.chunk);
-    p.hot.nc = p.hot.max_nd + chunk_slots(max_prox, p.hot.chunk);
+    p.hot.max_nd = chunk_slots(max_dist, (int)chunk);
+    p.hot.nc = p.hot.max_nd + chunk_slots(max_prox, (int)chunk_p);
     const size_t NC = (size_t)p.hot.nc;
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
