@@ -170,7 +170,9 @@ int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, const void 
  *                  0 skips the entry (output row zeroed); any other value must equal the
  *                  cache's length for (layer, slot b) (checked in the kernel)
  *   max_context_len : host upper bound on context_lens (sizes the launch); 0 = use the
- *                  host mirror's maximum over the B slots
+ *                  host mirror's maximum over the B slots.  An entry with a larger
+ *                  context_lens is skipped like any other contract violation (output row
+ *                  zeroed, flag raised)
  *   scale        : logits multiplier, 1/sqrt(d) in the paper
  *   workspace    : dev scratch of >= pod_workspace_bytes(cfg); contents undefined afterwards
  *   out          : dev bf16 [B][Hq][d]

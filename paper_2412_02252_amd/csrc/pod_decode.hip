@@ -74,6 +74,7 @@ struct decode_params {
     decode_hot hot;
     int32_t *flag;
     int32_t maxctx;
+    int32_t max_len; // the launch covers contexts up to this many tokens (host argument)
     pod_bf16 *out;   // [B][Hq][D]
     // score reuse (modes 1 and 2 of the partial kernel): scaled distant logits of the block's
     // lowest layer, fp32, stored tile by tile in the register order of the S^T accumulators:
@@ -135,7 +136,7 @@ __device__ inline int decode_seq_len(const decode_params &p, int b, bool *bad)
     const int low = p.hot.lens_lowest[b];
     *bad = false;
     if (n == 0) return 0;
-    if (n < 0 || n > p.maxctx || n != dev || (n > p.hot.prows && low != n) || (p.hot.use_hlen && n != p.hlen[b])) {
+    if (n < 0 || n > p.maxctx || n > p.max_len || n != dev || (n > p.hot.prows && low != n) || (p.hot.use_hlen && n != p.hlen[b])) {
         *bad = true;
         return 0;
     }
@@ -619,7 +620,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     // validation: the same rule as decode_seq_len, on the values loaded at the top
     if (hot.use_hlen) {
         if (v_ctx == 0) n = 0;
-        else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx != v_dev || (v_ctx > hot.prows && v_low != v_ctx) || v_ctx != n_host) {
+        else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx > p.max_len || v_ctx != v_dev || (v_ctx > hot.prows && v_low != v_ctx) || v_ctx != n_host) {
             bad = true;
             n = 0;
         }
@@ -692,6 +693,7 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.hot.lens_lowest = (const int32_t *)(c->base + ly.off_lens) + (size_t)lowest * ly.B;
     p.flag = (int32_t *)(c->base + ly.off_flag);
     p.maxctx = ly.maxctx;
+    p.max_len = max_len;
     p.out = (pod_bf16 *)out;
     p.mode = scores ? (tau >= 0.f ? 3 : 2) : 0;
     p.score_hdr = (int32_t *)scores;

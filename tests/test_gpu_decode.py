@@ -323,3 +323,24 @@ def test_more_than_256_sequences_use_the_device_side_lengths():
     keep = [b for b in range(B) if b != 123]
     assert_close(out[keep], ref[keep], "the other sequences")
     assert float(out[123].float().abs().max()) == 0.0
+
+
+def test_launch_bound_below_a_context_is_caught_on_the_device():
+    """max_context_len sizes the launch; a sequence longer than it cannot be served by that launch: its row is
+    zeroed and the flag raised, the sequences within the bound are exact.  An inactive long sequence is fine."""
+    lens = [300, 90, 500]
+    c = Case(2, 2, 4, 2, 64, 8, 32, 3, 600, seed=62)
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    ref = c.decode_ref(1, lens)
+    out = c.decode(1, lens, max_context_len=320)            # sequence 2 holds 500 tokens
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_cache_check()
+    assert_close(out[:2], ref[:2], "sequences within the bound")
+    assert float(out[2].float().abs().max()) == 0.0
+    q = c.decode_queries(1, lens, c.dev)
+    ctx = torch.tensor([300, 90, 0], dtype=torch.int32, device=c.dev)   # the long one sits this step out
+    out = c.gpu.pod_decode_attention(1, q, c.shared_queries(1, lens, c.dev), ctx, c.scale, max_context_len=320)
+    c.gpu.pod_cache_check()
+    assert_close(out[:2], ref[:2], "with the long sequence inactive")
