@@ -193,9 +193,9 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
  *   scores : dev buffer of >= pod_score_buffer_bytes(cfg), 256-byte aligned, holding for every
  *            kv head the logits of ONE block at a time: call the layers in ascending order for
  *            the same token, batch and scale (a block's lowest layer first, then its upper
- *            layers, before the next block).  A tag in the buffer (token count and block, per
- *            sequence and kv head) is checked on the device; a mismatch zeroes the output row
- *            and raises the flag pod_cache_check reports.
+ *            layers, before the next block).  A tag in the buffer (token count, block and
+ *            scale, per sequence and kv head) is checked on the device; a mismatch zeroes the
+ *            output row and raises the flag pod_cache_check reports.
  * With head-wise blocks (pod_config.block_lowest) a layer can be the lowest for some kv heads
  * and an upper layer for others: each kv head writes or reads its own part of the buffer.
  * Other arguments as in pod_decode_attention; no q_shared is needed.

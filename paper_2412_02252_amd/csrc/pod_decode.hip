@@ -80,7 +80,8 @@ struct decode_params {
     // lowest layer, fp32, stored tile by tile in the register order of the S^T accumulators:
     // [B][Hkv][score_stride / (32 * rep) tiles][4 (lane / 16)][rep heads][8 tokens of the lane],
     // so that a wave writes (and later reads) 32 contiguous bytes per lane and 128 contiguous bytes
-    // per 4 neighbouring lanes; preceded by a header int32 [B][Hkv][2] = (n, distant-key store of the head's block)
+    // per 4 neighbouring lanes; preceded by a header int32 [B][Hkv][4] = (n, distant-key store of the head's block,
+    // bits of the logit scale, unused)
     float *scores;
     int32_t *score_hdr;
     int32_t score_stride;
@@ -236,8 +237,9 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     if (MODE == 1 && head_arg >= 0) return;
     if (MODE >= 2 && head_arg < 0) return;
     if (MODE == 1 && c == 0 && threadIdx.x == 0) { // tag this head's logits: which token, which block's keys
-        p.score_hdr[2 * ((size_t)b * hkv + h)] = n;
-        p.score_hdr[2 * ((size_t)b * hkv + h) + 1] = head_arg & 0x7fffffff;
+        p.score_hdr[4 * ((size_t)b * hkv + h)] = n;
+        p.score_hdr[4 * ((size_t)b * hkv + h) + 1] = head_arg & 0x7fffffff;
+        p.score_hdr[4 * ((size_t)b * hkv + h) + 2] = __float_as_int(hot.scale_log2e);
     }
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
@@ -626,8 +628,9 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
         }
     }
     if (p.mode != 0 && !low && n > hot.prows) { // the distant logits must be those of this token and of the head's block
-        const size_t tag = 2 * ((size_t)b * hot.hkv + head / hot.rep);
-        if (p.score_hdr[tag] != n || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff)) { bad = true; n = 0; }
+        const size_t tag = 4 * ((size_t)b * hot.hkv + head / hot.rep);
+        if (p.score_hdr[tag] != n || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff) ||
+            p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e)) { bad = true; n = 0; }
     }
     uint2 res = make_uint2(0u, 0u);
     if (n > 0) {
@@ -653,8 +656,8 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
 
 size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
 
-// header of the score buffer: int32 [B][Hkv][2] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
-static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hkv * 2 * sizeof(int32_t) + 255) / 256 * 256; }
+// header of the score buffer: int32 [B][Hkv][4] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
+static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hkv * 4 * sizeof(int32_t) + 255) / 256 * 256; }
 static size_t score_gate_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * 2 * sizeof(float) + 255) / 256 * 256; }
 size_t pod_score_skip_offset_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly); }
 size_t pod_score_header_bytes(const pod_layout &ly)

@@ -201,6 +201,11 @@ def test_score_reuse_detects_stale_scores():
     c.decode_reuse(2, [n], scores)
     assert_close(c.decode_reuse(3, [n], scores), c.decode_ref(3, [n]), "after the right lowest layer")
     c.gpu.pod_cache_check()
+    ctx_t = torch.tensor([n], dtype=torch.int32, device=c.dev)
+    out = c.gpu.pod_decode_attention_reuse(3, c.decode_queries(3, [n], c.dev), ctx_t, c.scale * 2, scores)
+    assert torch.all(out == 0)                        # logits written with another scale are not this call's
+    with pytest.raises(pod.PodError):
+        c.gpu.pod_cache_check()
     with pytest.raises(pod.PodError) as e:            # undersized buffer
         c.gpu.pod_decode_attention_reuse(0, c.decode_queries(0, [n], c.dev),
                                          torch.tensor([n], dtype=torch.int32, device=c.dev), c.scale, scores[:256])
