@@ -14,9 +14,10 @@
  * layer's own values (Eq. 3, lines 2 and 4).  Consequence for storage: distant
  * keys are kept once per block, everything else per layer.
  *
- * Here blocks are uniform: layer l belongs to block l / group_size, whose lowest
- * layer is l - l % group_size.  GQA: query head h reads KV head
- * h / (num_q_heads / num_kv_heads).
+ * By default blocks are uniform: layer l belongs to block l / group_size, whose
+ * lowest layer is l - l % group_size; pod_config.block_lowest gives every kv head
+ * its own blocks instead (the paper groups layers head by head).  GQA: query
+ * head h reads KV head h / (num_q_heads / num_kv_heads).
  *
  * Conventions
  *  - Every call returns POD_OK (0) or a negative pod_status; pod_last_error()
@@ -24,7 +25,12 @@
  *  - "dev" pointers are device memory of the current HIP device, "host" pointers
  *    are ordinary host memory.  The caller owns every buffer it passes; the
  *    library never allocates or frees device memory and never synchronises the
- *    device, except pod_cache_check (which waits on the given stream).
+ *    device, except pod_cache_check and pod_cache_sync_lengths (which wait on the
+ *    given stream).  Every other call can be captured into a HIP graph; a captured
+ *    call fixes its host-side arguments, the mirror's lengths (below) among them,
+ *    so a graph is replayed from the cache state it was captured at.
+ *  - A cache handle keeps host-side state (the mirror): use it from one host thread
+ *    at a time.
  *  - All device work is enqueued on the stream argument (a hipStream_t passed as
  *    void*; NULL = the default stream).  Calls that touch one cache must be
  *    issued in program order on one stream (or be ordered by the caller).
