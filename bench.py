@@ -46,6 +46,7 @@ def parse():
     ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg5"], default="cfg2",
                     help="cfg2 (default): the headline workload; cfg3 / cfg5: the large-batch decode configurations "
                          "(32 layers, 30-44 GB of cache), one line of the same shape, decode figures only")
+    ap.add_argument("--reuse", action="store_true", help="with --workload cfg3|cfg5: the step through the score-reuse entry point")
     ap.add_argument("--chunk", type=int, default=2048, help="chunk length of the chunked-prefill figure (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -105,11 +106,16 @@ def main_large(a):
     pos = [torch.tensor([n + s for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
     ctx = [torch.tensor([n + s + 1 for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
 
+    scores = cache.new_score_buffer() if a.reuse else None
+
     def run_step(s):
         for l in range(L):
             cache.pod_cache_append(l, kn[s * L + l], vn[s * L + l], pos[s])
-            cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out,
-                                       max_context_len=max(lens) + s + 1)
+            if a.reuse:     # upper layers of a block take the lowest layer's distant logits instead of its keys
+                cache.pod_decode_attention_reuse(l, q[l], ctx[s], scale, scores, out=out, max_context_len=max(lens) + s + 1)
+            else:
+                cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out,
+                                           max_context_len=max(lens) + s + 1)
 
     for s in range(Wm):
         run_step(s)
@@ -125,6 +131,21 @@ def main_large(a):
     cache.pod_profile_disable()
     cache.pod_cache_check()
     nbytes = sum(sum(2 * (n + s + 1) * row for n in lens) * L for s in range(Wm, total))
+    if a.reuse:
+        # its own, smaller byte count: an upper layer reads V rows, proximal K rows and 4 B per (query head, distant
+        # token); a lowest layer reads K and V rows and writes those 4 B
+        def layer_bytes(n, upper):
+            n_prox = min(n, S + W)
+            logits = (n - n_prox) * Hq * 4
+            return (n * row + n_prox * row + logits) if upper else (2 * n * row + logits)
+        reuse_bytes = sum(sum(layer_bytes(n + s + 1, l % G != 0) for n in lens) for l in range(L) for s in range(Wm, total))
+        print(json.dumps({
+            "metric": "decode step with score reuse", "ms_per_step": round(dt / K * 1e3, 4), "steps": K, "warmup": Wm,
+            "config": {"workload": name + "; step = (append + decode through pod_decode_attention_reuse) x 32 layers", "launch": "eager"},
+            "bytes_per_step_plain": nbytes // K, "bytes_per_step_reuse": reuse_bytes // K,
+            "value": round(reuse_bytes / dt / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
+            "plain_equivalent_GBs": round(nbytes / dt / 1e9, 1)}))
+        return
     per_launch = nbytes / (K * L)
     print(json.dumps({
         "metric": "decode attn HBM GB/s", "value": round(nbytes / dt / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
