@@ -229,7 +229,9 @@ extern "C" int pod_profile_enable(pod_cache *cache, int max_records)
     cache->prof_ev = (hipEvent_t *)calloc((size_t)2 * max_records, sizeof(hipEvent_t));
     if (!cache->prof_ev) return pod_fail(POD_ERR_CAPACITY, "out of host memory");
     for (int i = 0; i < 2 * max_records; ++i) {
-        hipError_t e = hipEventCreate(&cache->prof_ev[i]);
+        // timing only: no system-scope fence when the event is reached (that fence is part of what an event pair
+        // around a short kernel otherwise measures)
+        hipError_t e = hipEventCreateWithFlags(&cache->prof_ev[i], hipEventDisableSystemFence);
         if (e != hipSuccess) {
             for (int k = 0; k < i; ++k) (void)hipEventDestroy(cache->prof_ev[k]);
             free(cache->prof_ev); cache->prof_ev = nullptr;
