@@ -288,3 +288,11 @@ def test_random_sequences_of_cache_updates(seed):
                 for layer in range(L):
                     assert_close(c.decode(layer, list(n)), c.decode_ref(layer, list(n)), f"step {step} layer {layer}")
     c.gpu.pod_cache_check()
+
+
+@pytest.mark.parametrize("d,Hq,Hkv", [(128, 8, 2), (64, 4, 2)])
+def test_chunked_prefill_with_outlier_keys(d, Hq, Hkv):
+    """Outlier keys (x16, 30 % of the rows) in the cache and in the chunks: the softmax reference moves inside
+    chunk calls whose keys come from the gathered copies."""
+    c = Case(2, 2, Hq, Hkv, d, 8, 40, 1, 700, seed=360, outlier_rate=0.3, outlier_scale=16.0)
+    run_chunks(c, [130, 257, 1, 200])
