@@ -190,6 +190,26 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
                          void *workspace, size_t workspace_bytes, void *out, void *stream);
 
 /*
+ * pod_decode_attention for callers that cannot allocate device memory or take a workspace from
+ * an allocator: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as pod_decode_attention, except that the
+ * split-K partial results go to a fixed 16 MiB array inside the library's code object (one copy per
+ * GPU, held until the process ends; its device address is looked up in pod_cache_init) instead of
+ * a caller's workspace.  The call allocates and frees nothing.
+ *  - POD_ERR_CAPACITY if this call's launch needs more than the 16 MiB: it needs
+ *    4 * B * num_q_heads * chunks * (head_dim + 2) bytes, chunks = the split-K pieces of the longest
+ *    sequence (128 to 1024 tokens each).  With 32 query heads x 128: batch 1 at 32K tokens takes
+ *    1.1 MB, 16 sequences of up to 32K tokens 8.8 MB, 4 sequences of 128K tokens 8.6 MB.  Larger
+ *    launches go through pod_decode_attention.
+ *  - Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (other
+ *    streams, other caches, other host threads) race; issue them in order on one stream.
+ *  - The current device must be the cache's.
+ */
+int pod_decode_attention_static(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                                const int32_t *context_lens, int B, int max_context_len, float scale,
+                                void *out, void *stream);
+
+/*
  * Decode attention with score reuse: same result as pod_decode_attention, but the distant
  * logits are computed once per block.  Eq. 3 line 3 defines the distant logits of every layer of
  * a block as those of the block's lowest layer; called for the lowest layer, this entry point

@@ -22,6 +22,7 @@ EXPORTS = [
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
+    "pod_decode_attention_static",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
 ]
 
@@ -70,6 +71,7 @@ def load():
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
+        "pod_decode_attention_static": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, vp],
         "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
         "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
         "pod_score_buffer_bytes": [cfgp, szp],
@@ -242,6 +244,13 @@ class PodCache:
                                            _ptr(context_lens, torch.int32), B, max_context_len, scale,
                                            self.workspace.data_ptr(), self.workspace.numel(), _ptr(out, torch.bfloat16),
                                            _stream()))
+        return out
+
+    def pod_decode_attention_static(self, layer, q, q_shared, context_lens, scale, out, max_context_len=0):
+        """pod_decode_attention on the library's own fixed scratch array; `out` is the caller's (nothing is allocated)."""
+        _check(load().pod_decode_attention_static(self.handle, layer, _ptr(q, torch.bfloat16), _ptr(q_shared, torch.bfloat16),
+                                                  _ptr(context_lens, torch.int32), q.shape[0], max_context_len, scale,
+                                                  _ptr(out, torch.bfloat16), _stream()))
         return out
 
     def pod_decode_attention_reuse(self, layer, q, context_lens, scale, scores, out=None, max_context_len=0):

@@ -195,7 +195,8 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
     if (!c->host_len) { free(c->lowest); free(c->kslot); delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return pod_hip_fail(e, "hipGetDevice"); }
-    rc = pod_launch_clear_header(c, (hipStream_t)stream);
+    rc = pod_decode_static_scratch(&c->static_scratch, &c->static_scratch_bytes); // this device's copy of the array
+    if (rc == POD_OK) rc = pod_launch_clear_header(c, (hipStream_t)stream);
     if (rc) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return rc; }
     *out = c;
     return POD_OK;
@@ -356,7 +357,20 @@ extern "C" int pod_cache_fill(pod_cache *cache, int layer, int seq_slot, int n, 
 
 static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
                          const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
-                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream);
+                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream, bool own_scratch = false);
+
+extern "C" int pod_decode_attention_static(pod_cache *cache, int layer, const void *q, const void *q_shared,
+                                           const int32_t *context_lens, int B, int max_context_len, float scale,
+                                           void *out, void *stream)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    int dev = -1;
+    POD_HIP_TRY(hipGetDevice(&dev));
+    if (dev != cache->device)
+        return pod_fail(POD_ERR_INVALID_ARG, "current device %d is not the cache's device %d", dev, cache->device);
+    return decode_common(cache, layer, q, q_shared, context_lens, B, max_context_len, scale, cache->static_scratch,
+                         cache->static_scratch_bytes, nullptr, -1.f, out, stream, true);
+}
 
 extern "C" int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void *q_shared,
                                     const int32_t *context_lens, int B, int max_context_len, float scale,
@@ -426,7 +440,7 @@ static int decode_with_scores(pod_cache *cache, int layer, const void *q, const 
 
 static int decode_common(pod_cache *cache, int layer, const void *q, const void *q_shared,
                          const int32_t *context_lens, int B, int max_context_len, float scale, void *workspace,
-                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream)
+                         size_t workspace_bytes, void *scores, float tau, void *out, void *stream, bool own_scratch)
 {
     int rc = check_cache_layer(cache, layer);
     if (rc) return rc;
@@ -434,7 +448,9 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
     if (!q || !context_lens || !out || !workspace)
         return pod_fail(POD_ERR_INVALID_ARG, "q, context_lens, workspace and out must not be NULL");
     if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
-    if (workspace_bytes < pod_decode_workspace_bytes(ly))
+    // (a caller's workspace is held to the configuration's worst case; the library's own fixed array to what this
+    // call's launch really needs, checked by the launcher)
+    if (!own_scratch && workspace_bytes < pod_decode_workspace_bytes(ly))
         return pod_fail(POD_ERR_CAPACITY, "workspace has %zu bytes, needs %zu", workspace_bytes, pod_decode_workspace_bytes(ly));
     if (max_context_len < 0 || max_context_len > ly.maxctx)
         return pod_fail(POD_ERR_INVALID_ARG, "max_context_len %d outside [0, %d]", max_context_len, ly.maxctx);

@@ -30,6 +30,8 @@
 //    16-token MFMA tiles: tokens {4j..4j+3} of tile 0 and of tile 1.
 #include <stddef.h>
 
+#include <mutex>
+
 #include "pod_internal.h"
 
 namespace {
@@ -647,6 +649,38 @@ int chunk_slots(int rows, int chunk) { return (rows + chunk - 1) / chunk; }
 
 } // namespace
 
+// ---------------------------------------------------------------------------------------------
+// Split-K partials in library-owned memory, for callers that may not allocate (code under HIP
+// graph capture, serving loops, harnesses that forbid hipMalloc): a fixed array in the code
+// object's device data, one copy per GPU, held until the process ends.  In host code the array's
+// name is only a stand-in for the symbol; its device address is looked up once per device and
+// that pointer is what kernels, copies and clears receive.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on device i (NULL: not looked up yet)
+std::mutex g_scratch_mutex;
+} // namespace
+
+int pod_decode_static_scratch(void **ptr, size_t *bytes)
+{
+    int dev = -1;
+    POD_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return pod_fail(POD_ERR_INVALID_ARG, "device %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        POD_HIP_TRY(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));   // of the current device's copy
+        if (!p) return pod_fail(POD_ERR_HIP, "hipGetSymbolAddress returned a NULL address");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    *bytes = kStaticScratchBytes;
+    return POD_OK;
+}
+
 size_t pod_decode_workspace_bytes(const pod_layout &ly)
 {
     const size_t nc = (size_t)chunk_slots(ly.Cd, kMinChunk) + chunk_slots(ly.P, kMinChunk) + 2;
@@ -738,7 +772,9 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     const size_t NC = (size_t)p.hot.nc;
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
-    if (acc_bytes + ml_bytes > ws_bytes) return pod_fail(POD_ERR_CAPACITY, "decode workspace too small");
+    if (acc_bytes + ml_bytes > ws_bytes)
+        return pod_fail(POD_ERR_CAPACITY, "decode scratch too small: %d sequences x %d query heads x %zu chunks of up to %d tokens need %zu bytes, %zu are there",
+                        B, ly.Hq, NC, max_len, acc_bytes + ml_bytes, ws_bytes);
     p.hot.part_acc = (float *)ws;
     p.hot.part_ml = (float *)((char *)ws + acc_bytes);
 

@@ -68,6 +68,9 @@ struct pod_cache {
     int32_t *kslot;    // [L][Hkv] distant-key slot that (layer, kv head) reads
     bool uniform;      // every kv head has the same blocks
     int device;
+    // the library's own split-K scratch on `device` (pod_decode_attention_static): device address and size
+    void *static_scratch;
+    size_t static_scratch_bytes;
     // optional event pairs around the decode partial kernel (pod_profile_*)
     hipEvent_t *prof_ev; // [2 * prof_cap]
     int prof_cap, prof_n;
@@ -111,6 +114,8 @@ size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (seque
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
+// device address and size of the library's own split-K scratch array on the current device (looked up once per device)
+int pod_decode_static_scratch(void **ptr, size_t *bytes);
 // lowest_mask: bit h set = kv head h takes every logit from (q, k); clear = distant logits from (q_shared, k_shared)
 // k, v, k_shared: rows for positions 0 .. n-1; q, q_shared, out: rows for positions q0 .. n-1
 int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,
