@@ -3,7 +3,7 @@
 Written from the paper's "Offline Inter-Layer Attention Sharing Exploration": the similarity of two
 layers for one head is computed from the Jensen-Shannon divergence of their attention rows
 (the equation defining sim_h), and consecutive layers are merged bottom-up into blocks (Greedy Layer
-Grouping Algorithm).  Plain Python / numpy, loops as in the text; nothing here is used by the product.
+Grouping Algorithm).  Plain Python / numpy; nothing here is used by the product.
 
 Readings taken where the text leaves a choice:
   * sim_h is said to be 1 for identical and 0 for completely dissimilar rows while being built from
@@ -40,49 +40,39 @@ def layer_similarity(att_a, att_b):
     return 1.0 - total / (N * q)
 
 
-def group_layers(sim, threshold=0.5):
-    """Greedy Layer Grouping Algorithm.  sim: [H][L][L] with sim[h][a][b] the similarity of layers a, b for head h.
-    Returns lowest: int32 [L][H], the lowest layer of the block each layer was put in."""
-    sim = np.asarray(sim, dtype=np.float64)
-    H, L, _ = sim.shape
-    lowest = np.zeros((L, H), dtype=np.int32)
-    for h in range(H):
-        blocks = [[0]]
-        for l in range(1, L):
-            current = blocks[-1]
-            if all(sim[h, l, lh] >= threshold for lh in current):
-                current.append(l)
-            else:
-                blocks.append([l])
-        for blk in blocks:
-            for l in blk:
-                lowest[l, h] = blk[0]
+def _lowest_layers(L, similar):
+    """What the greedy bottom-up grouping (Greedy Layer Grouping Algorithm) arrives at, stated as a recurrence on the
+    result rather than as the construction: blocks are runs of consecutive layers, layer 0 starts the first one, and
+    layer l stays in the block of layer l - 1 exactly when it is similar to EVERY layer that block holds so far,
+    i.e. to all of lowest[l-1] .. l-1; otherwise it is the lowest layer of a new block.
+    similar(a, b) -> bool.  Returns the list lowest[0..L-1]."""
+    lowest = [0] * L
+    for l in range(1, L):
+        start = lowest[l - 1]
+        lowest[l] = start if all(similar(l, m) for m in range(start, l)) else l
     return lowest
 
 
+def group_layers(sim, threshold=0.5):
+    """sim: [H][L][L] with sim[h][a][b] the similarity of layers a, b for head h; two layers are similar for a head if
+    sim >= threshold.  Returns lowest: int32 [L][H], the lowest layer of the block each layer belongs to."""
+    sim = np.asarray(sim, dtype=np.float64)
+    H, L, _ = sim.shape
+    cols = [_lowest_layers(L, lambda a, b, h=h: sim[h, a, b] >= threshold) for h in range(H)]
+    return np.array(cols, dtype=np.int32).T.reshape(L, H).copy()
+
+
 def group_layers_gqa(sim, num_kv_heads, threshold=0.5):
-    """The same per kv head: two layers count as similar for a kv head if more than half of its query heads say so.
-    sim: [Hq][L][L].  Returns lowest: int32 [L][Hkv]."""
+    """The same per kv head: two layers count as similar for a kv head if more than half of its query heads say so
+    (the appendix's majority vote; a tie is not a majority).  sim: [Hq][L][L].  Returns lowest: int32 [L][Hkv]."""
     sim = np.asarray(sim, dtype=np.float64)
     Hq, L, _ = sim.shape
     rep = Hq // num_kv_heads
     assert rep * num_kv_heads == Hq
-    lowest = np.zeros((L, num_kv_heads), dtype=np.int32)
-    for g in range(num_kv_heads):
-        heads = range(g * rep, (g + 1) * rep)
 
-        def similar(a, b):
-            votes = sum(1 for h in heads if sim[h, a, b] >= threshold)
-            return 2 * votes > rep
+    def majority(g):
+        votes = (sim[g * rep:(g + 1) * rep] >= threshold).sum(axis=0)   # [L][L] query heads in favour
+        return lambda a, b: 2 * int(votes[a, b]) > rep
 
-        blocks = [[0]]
-        for l in range(1, L):
-            current = blocks[-1]
-            if all(similar(l, lh) for lh in current):
-                current.append(l)
-            else:
-                blocks.append([l])
-        for blk in blocks:
-            for l in blk:
-                lowest[l, g] = blk[0]
-    return lowest
+    cols = [_lowest_layers(L, majority(g)) for g in range(num_kv_heads)]
+    return np.array(cols, dtype=np.int32).T.reshape(L, num_kv_heads).copy()
