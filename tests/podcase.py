@@ -10,15 +10,44 @@ import paper_2412_02252_amd as pod
 from oracle import pod_oracle as po
 from pod_inputs import gen
 
-MAX_ABS, MEAN_ABS = 2e-2, 2e-3   # bf16 inputs, fp32 accumulation, bf16 output
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3   # bf16 inputs, fp32 accumulation, bf16 output: the stated bounds, absolute
+# Relative bounds, which keep their meaning where the outputs are small (at 32K tokens of unit-variance values an
+# output element is ~0.01, so the absolute bounds alone would let a 20 % error through).  Per element the GPU result
+# differs from the exact one by (a) the round-to-nearest of the output to bf16, at most 2^-8 of the element (half an
+# ulp of an 8-bit significand), about 2^-9.5 of it on average; (b) the bf16 rounding of the probabilities that enter
+# the PV product: sum_j p_j e_j v_j with independent |e_j| <= 2^-8, whose standard deviation is at most
+# 2^-8 / sqrt(3) of sqrt(sum_j p_j^2 v_j^2), i.e. of the size of the output itself when the weights are spread over
+# many tokens; (c) fp32 summation order, 2^-24 per operation, negligible.  Together about 2^-9 of the output's rms
+# per element on average.  The bounds below leave a factor of about two to four over that and over the largest
+# error measured on the GPU at the large configurations:
+#   max |err| <= 2^-7 max |ref|        mean |err| <= 2^-8 rms(ref)
+REL_MAX, REL_MEAN = 2.0 ** -7, 2.0 ** -8
+
+
+def closeness_failures(got: np.ndarray, ref: np.ndarray):
+    """The bounds a result must keep against the oracle's: a list of the violated ones (empty = close enough)."""
+    err = np.abs(got - ref)
+    peak, rms = float(np.abs(ref).max(initial=0.0)), float(np.sqrt(np.mean(np.square(ref)))) if ref.size else 0.0
+    bad = []
+    if err.size == 0:
+        return bad
+    if err.max() > MAX_ABS:
+        bad.append(f"max abs err {err.max():.3e} > {MAX_ABS:g}")
+    if err.mean() > MEAN_ABS:
+        bad.append(f"mean abs err {err.mean():.3e} > {MEAN_ABS:g}")
+    if err.max() > REL_MAX * peak:
+        bad.append(f"max abs err {err.max():.3e} > 2^-7 of the largest reference value {peak:.3e}")
+    if err.mean() > REL_MEAN * rms:
+        bad.append(f"mean abs err {err.mean():.3e} > 2^-8 of the reference rms {rms:.3e}")
+    return bad
 
 
 def assert_close(got_bf16: torch.Tensor, ref_f64: np.ndarray, what=""):
     got = got_bf16.float().cpu().numpy().astype(np.float64)
     assert got.shape == ref_f64.shape, (got.shape, ref_f64.shape)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    err = np.abs(got - ref_f64)
-    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, f"{what}: max {err.max():.3e} mean {err.mean():.3e}"
+    bad = closeness_failures(got, ref_f64)
+    assert not bad, f"{what}: " + "; ".join(bad)
 
 
 class Case:
