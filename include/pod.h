@@ -123,9 +123,20 @@ int pod_cache_reset(pod_cache *cache, int seq_slot, void *stream);
 int pod_cache_seq_len(const pod_cache *cache, int layer, int seq_slot, int64_t *n);
 
 /*
+ * Sizes of the three regions (layer, seq_slot) holds by the host mirror's length n, in tokens:
+ * counts[0] sink tokens (positions below S), counts[1] tokens in the recent window (the last
+ * min(W, n - S) positions), counts[2] distant tokens (everything between); *has_distant_keys
+ * (may be NULL) = 1 if `layer` is the lowest layer of some kv head's block, i.e. keeps distant keys.
+ * These are the row counts pod_cache_export_logical writes.  host outs.
+ */
+int pod_cache_region_counts(const pod_cache *cache, int layer, int seq_slot, int64_t counts[3], int *has_distant_keys);
+
+/*
  * Wait for stream, then report whether any kernel since the last check skipped an
  * entry because a device-side contract was violated (wrong position, wrong
  * context length, overflow): POD_ERR_STATE if so (the flag is cleared), else POD_OK.
+ * The host mirror counts every entry of every accepted call, skipped ones included, so after a
+ * POD_ERR_STATE from here it may be ahead of the device: call pod_cache_sync_lengths before going on.
  */
 int pod_cache_check(pod_cache *cache, void *stream);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
-    "pod_decode_attention_static",
+    "pod_decode_attention_static", "pod_cache_region_counts",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
 ]
 
@@ -66,6 +66,7 @@ def load():
         "pod_cache_reset": [vp, C.c_int, vp],
         "pod_cache_seq_len": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64)],
         "pod_cache_check": [vp, vp],
+        "pod_cache_region_counts": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int)],
         "pod_cache_sync_lengths": [vp, vp],
         "pod_workspace_bytes": [cfgp, szp],
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
@@ -210,6 +211,12 @@ class PodCache:
         _check(load().pod_cache_seq_len(self.handle, layer, seq_slot, C.byref(n)))
         return n.value
 
+    def pod_cache_region_counts(self, layer, seq_slot):
+        """((sink, recent, distant) token counts, keeps_distant_keys) of (layer, seq_slot)."""
+        cnt, low = (C.c_int64 * 3)(), C.c_int()
+        _check(load().pod_cache_region_counts(self.handle, layer, seq_slot, cnt, C.byref(low)))
+        return (cnt[0], cnt[1], cnt[2]), bool(low.value)
+
     def pod_cache_check(self):
         _check(load().pod_cache_check(self.handle, _stream()))
 
@@ -324,14 +331,9 @@ class PodCache:
     def pod_cache_export_logical(self, layer, seq_slot):
         """dict of bf16 tensors [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV (+ distK at a lowest layer)."""
         c = self.cfg
-        n = self.pod_cache_seq_len(layer, seq_slot)
-        ns = min(n, c.sink)
-        nr = min(c.window, max(0, n - c.sink))
-        nd = max(0, n - c.sink - c.window)
+        (ns, nr, nd), lowest = self.pod_cache_region_counts(layer, seq_slot)
         mk = lambda t: torch.zeros((t, c.num_kv_heads, c.head_dim), dtype=torch.bfloat16, device=self.device)
         out = dict(sinkK=mk(ns), sinkV=mk(ns), recentK=mk(nr), recentV=mk(nr), distV=mk(nd))
-        tab = getattr(c, "_block_lowest_keepalive", None)   # head-wise table, if the config has one
-        lowest = bool((tab[layer] == layer).any()) if tab is not None else layer % c.group_size == 0
         if lowest:
             out["distK"] = mk(nd)                              # (heads that are not lowest at this layer: zeros)
         _check(load().pod_cache_export_logical(self.handle, layer, seq_slot, _ptr(out["sinkK"]), _ptr(out["sinkV"]),

@@ -191,6 +191,11 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
         if (rc) { free(c->host_len); delete c; return rc; }
     }
     c->device = -1;
+    {   // tuning overrides: read here, once, so that the environment cannot change launch geometry between calls
+        const char *e1 = getenv("POD_DECODE_CHUNK"), *e2 = getenv("POD_DECODE_CHUNK_PROX");
+        c->tune_chunk = e1 && atoi(e1) > 0 ? atoi(e1) : 0;
+        c->tune_chunk_prox = e2 && atoi(e2) > 0 ? atoi(e2) : 0;
+    }
     c->prof_ev = nullptr; c->prof_cap = 0; c->prof_n = 0;
     if (!c->host_len) { free(c->lowest); free(c->kslot); delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
     hipError_t e = hipGetDevice(&c->device);
@@ -285,6 +290,21 @@ extern "C" int pod_cache_seq_len(const pod_cache *cache, int layer, int seq_slot
     if (seq_slot < 0 || seq_slot >= cache->ly.B || !n)
         return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d) or n is NULL", seq_slot, cache->ly.B);
     *n = cache->host_len[(size_t)layer * cache->ly.B + seq_slot];
+    return POD_OK;
+}
+
+extern "C" int pod_cache_region_counts(const pod_cache *cache, int layer, int seq_slot, int64_t counts[3], int *has_distant_keys)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (seq_slot < 0 || seq_slot >= ly.B || !counts)
+        return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d) or counts is NULL", seq_slot, ly.B);
+    const int64_t n = cache->host_len[(size_t)layer * ly.B + seq_slot];
+    counts[0] = n < ly.S ? n : ly.S;                         // sink
+    counts[1] = n - counts[0] < ly.W ? n - counts[0] : ly.W; // recent window
+    counts[2] = n - counts[0] - counts[1];                   // distant
+    if (has_distant_keys) *has_distant_keys = layer_lowest_any(cache, layer) ? 1 : 0;
     return POD_OK;
 }
 

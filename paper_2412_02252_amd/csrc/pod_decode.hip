@@ -748,8 +748,7 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // moderately sized chunks so that the tail stays short: measured best near 1024 tokens for
     // 16 ragged sequences of 4K-32K tokens and within 2 % of best for 4 sequences of 128K.
     // Never below kMinChunk tokens, so the partials stay a small fraction of the K/V bytes.
-    const char *env = getenv("POD_DECODE_CHUNK"); // tuning / test override
-    const int env_chunk = env ? atoi(env) : 0;
+    const int env_chunk = c->tune_chunk; // tuning / test override
     const long rows = (long)max_len * ly.Hkv * B;
     long chunk = env_chunk > 0 ? env_chunk : rows / 512;
     chunk = (chunk + kTile - 1) / kTile * kTile;
@@ -759,8 +758,7 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time of
     // one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
     // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
-    const char *envp = getenv("POD_DECODE_CHUNK_PROX"); // tuning / test override
-    long chunk_p = envp && atoi(envp) > 0 ? atoi(envp) : ((scores && !lowest_all && tau >= 0.f) ? kMinChunk : chunk);
+    long chunk_p = c->tune_chunk_prox > 0 ? c->tune_chunk_prox : ((scores && !lowest_all && tau >= 0.f) ? kMinChunk : chunk);
     chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
     if (chunk_p < kMinChunk) chunk_p = kMinChunk;
     if (chunk_p > 8192) chunk_p = 8192;

@@ -68,6 +68,9 @@ struct pod_cache {
     int32_t *kslot;    // [L][Hkv] distant-key slot that (layer, kv head) reads
     bool uniform;      // every kv head has the same blocks
     int device;
+    // tuning overrides read once from the environment in pod_cache_init (0 = none): tokens per split-K piece of the
+    // distant / proximal region (POD_DECODE_CHUNK, POD_DECODE_CHUNK_PROX)
+    int tune_chunk, tune_chunk_prox;
     // the library's own split-K scratch on `device` (pod_decode_attention_static): device address and size
     void *static_scratch;
     size_t static_scratch_bytes;

@@ -28,6 +28,7 @@
 // moved when a tile exceeds it by more than 2^8 (probabilities then stay below 256, harmless in
 // fp32 sums and in bf16), which removes most rescaling passes over the output accumulators.
 #include <stdlib.h>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -541,11 +542,19 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const voi
     const dim3 grid((unsigned)((n + 127) / 128 - q0 / 128) * (unsigned)ly.Hq);
     // dynamic LDS: two K slots and two V slots of kBN tokens x D bf16 each (64 KB at D = 128)
     const auto lds_bytes = [](int D) { return 4 * kBN * D * 2; };
-    static bool attr_done = false; // raising the limit to 64 KB is needed once per process
-    if (!attr_done) {
-        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-        POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
-        attr_done = true;
+    // raising the dynamic-LDS limit to 64 KB is needed once per device; any host thread may get here first
+    {
+        static std::mutex attr_mutex;
+        static bool attr_done[64] = {};
+        int dev = -1;
+        POD_HIP_TRY(hipGetDevice(&dev));
+        if (dev < 0 || dev >= 64) return pod_fail(POD_ERR_INVALID_ARG, "device %d outside [0, 64)", dev);
+        std::lock_guard<std::mutex> lock(attr_mutex);
+        if (!attr_done[dev]) {
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
+            attr_done[dev] = true;
+        }
     }
     if (ly.D == 128)
         hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(256), lds_bytes(128), st, p);
