@@ -4,21 +4,26 @@
 Workload (benchmark configs[1]): LLaMA3-8B-shaped decode, one layer block of G=2 layers,
 32 query / 8 KV heads, head_dim 128, batch 1, context 32768 (+1 per step), S=64, W=2048, bf16,
 RoPE-rotated keys (base 500000).  A *step* is one pass of the whole path for one new token:
-append its K/V to both layers (with window-to-distant demotion), decode attention on the
-block's lowest layer, decode attention on the upper layer (shared distant logits).
+the block's lowest layer takes the token (cache update with window-to-distant demotion +
+decode attention), then the upper layer does (shared distant logits).  Each layer's part is
+one pod_decode_step launch.
 
 The chip has a 256 MB last-level cache and one block's cache is only 206 MB, so the bench
 keeps `--rotate` independent blocks (same shape, different data) and visits them round-robin:
 each step streams K/V that left the cache long ago, as a 32-layer model would.
 
-Prints ONE JSON line: whole-step throughput (`value`, algorithmic K/V bytes per second), the
-roofline of the dominant kernel (split-K partial kernel, timed with HIP events through
-pod_profile_*), the CPU oracle timed on the host cores, and the prefill figures (configs[3]).
+Prints ONE JSON line: whole-step throughput (`value`, algorithmic K/V bytes per second; median
+of `--segments` independently captured HIP-graph segments of `--steps` steps each), the roofline
+of the dominant kernel (the fused streaming kernel, timed launch by launch with HIP events
+through pod_profile_*; lowest-layer launches, whose K/V is all cold, apart from upper-layer ones,
+and a plain streaming read of the same size beside them), the CPU oracle timed on the host
+cores, the prefill figures (configs[3]) and the large-batch decode configurations (configs[2], [4]).
 """
 import argparse
 import json
 import math
 import os
+import statistics
 import sys
 import time
 
@@ -27,6 +32,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X datasheet
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+T_START = time.perf_counter()
 
 
 def parse():
@@ -34,19 +40,24 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--segments", type=int, default=5, help="independently captured graph segments of --steps steps (median and min reported)")
     ap.add_argument("--rotate", type=int, default=4, help="independent layer blocks visited round-robin")
     ap.add_argument("--context", type=int, default=32768)
     ap.add_argument("--profile-steps", type=int, default=32)
     ap.add_argument("--reuse-steps", type=int, default=32, help="steps timed through the score-reuse entry point (0 = skip)")
     ap.add_argument("--gate-rounds", type=int, default=8, help="rounds over the blocks in the gated-skip section (0 = skip)")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of one HIP graph replay")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-large", action="store_true", help="skip the large-batch configurations in the default line")
+    ap.add_argument("--large-steps", type=int, default=6)
+    ap.add_argument("--time-guard", type=float, default=240.0, help="seconds after which optional sections are skipped")
     ap.add_argument("--prefill-n", type=int, default=16384)
     ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg5"], default="cfg2",
-                    help="cfg2 (default): the headline workload; cfg3 / cfg5: the large-batch decode configurations "
+                    help="cfg2 (default): the headline workload; cfg3 / cfg5: only that large-batch decode configuration "
                          "(32 layers, 30-44 GB of cache), one line of the same shape, decode figures only")
     ap.add_argument("--reuse", action="store_true", help="with --workload cfg3|cfg5: the step through the score-reuse entry point")
+    ap.add_argument("--separate-calls", action="store_true", help="with --workload cfg3|cfg5: pod_cache_append + pod_decode_attention instead of pod_decode_step")
     ap.add_argument("--chunk", type=int, default=2048, help="chunk length of the chunked-prefill figure (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -54,30 +65,24 @@ def parse():
     return ap.parse_args()
 
 
-def traffic_from_profiles():
-    """HBM bytes per launch of the decode partial kernel from the committed rocprofv3 --pmc summary."""
-    path = os.path.join(ROOT, "profiles", "decode_partial_kernel_cfg2_pmc.txt")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1].split()[0])
-    except OSError:
-        pass
-    return None
+def stats(ms_list):
+    return {"median": round(statistics.median(ms_list), 5), "min": round(min(ms_list), 5), "max": round(max(ms_list), 5),
+            "n": len(ms_list)}
 
 
-def main_large(a):
+def run_large(workload, K, Wm, variant):
     """configs[2] (16 ragged sequences of 4K-32K tokens, G=2) or configs[4] (4 sequences of 128K, G=4, 1 % of the
-    distant key rows x8): a step = one new token per sequence through all 32 layers (append, then decode attention)."""
+    distant key rows x8): a step = one new token per sequence through all 32 layers.  variant: "step" (one
+    pod_decode_step launch per layer), "separate" (pod_cache_append + pod_decode_attention), "reuse" (append +
+    pod_decode_attention_reuse)."""
     import torch
 
     import paper_2412_02252_amd as pod
     from pod_inputs import gen
 
     dev = "cuda:0"
-    torch.cuda.set_device(0)
     Hq, Hkv, d, L = 32, 8, 128, 32
-    if a.workload == "cfg3":
+    if workload == "cfg3":
         G, B, S, W, seed = 2, 16, 64, 2048, 20241202 + 3
         lens = gen.ragged_lengths(seed, B, 4096, 32768)
         kgen = {}
@@ -87,7 +92,6 @@ def main_large(a):
         lens = [131072] * B
         kgen = dict(outlier_rate=0.01, outlier_scale=8.0, outlier_lo=S, outlier_hi=lens[0] - W)
         name = "configs[4]: 32 layers G=4, 32q/8kv heads, d=128, 4 sequences of 131072 tokens, S=128, W=4096, 1 % of distant key rows x8"
-    K, Wm = a.steps, a.warmup
     total = K + Wm
     max_ctx = max(lens) + total + 1
     cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx), dev)
@@ -105,33 +109,42 @@ def main_large(a):
     out = torch.empty_like(q[0])
     pos = [torch.tensor([n + s for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
     ctx = [torch.tensor([n + s + 1 for n in lens], dtype=torch.int32, device=dev) for s in range(total)]
-
-    scores = cache.new_score_buffer() if a.reuse else None
+    scores = cache.new_score_buffer() if variant == "reuse" else None
 
     def run_step(s):
+        bound = max(lens) + s + 1
         for l in range(L):
+            if variant == "step":
+                cache.pod_decode_step(l, kn[s * L + l], vn[s * L + l], q[l], q[l - l % G] if l % G else None, pos[s], scale,
+                                      out=out, max_context_len=bound)
+                continue
             cache.pod_cache_append(l, kn[s * L + l], vn[s * L + l], pos[s])
-            if a.reuse:     # upper layers of a block take the lowest layer's distant logits instead of its keys
-                cache.pod_decode_attention_reuse(l, q[l], ctx[s], scale, scores, out=out, max_context_len=max(lens) + s + 1)
+            if variant == "reuse":  # upper layers of a block take the lowest layer's distant logits instead of its keys
+                cache.pod_decode_attention_reuse(l, q[l], ctx[s], scale, scores, out=out, max_context_len=bound)
             else:
-                cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out,
-                                           max_context_len=max(lens) + s + 1)
+                cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out, max_context_len=bound)
 
     for s in range(Wm):
         run_step(s)
     cache.pod_cache_check()
     cache.pod_profile_enable(K * L)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    per_step = []
     for s in range(Wm, total):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         run_step(s)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    kernel_ms, launches = cache.pod_profile_read()
+        torch.cuda.synchronize()
+        per_step.append((time.perf_counter() - t0) * 1e3)
+    each = cache.pod_profile_read_each(K * L)
     cache.pod_profile_disable()
     cache.pod_cache_check()
+    dt = sum(per_step) / 1e3
     nbytes = sum(sum(2 * (n + s + 1) * row for n in lens) * L for s in range(Wm, total))
-    if a.reuse:
+    res = {"workload": name + "; step = one new token per sequence through 32 layers, " +
+                       {"step": "one pod_decode_step launch per layer", "separate": "pod_cache_append + pod_decode_attention per layer",
+                        "reuse": "pod_cache_append + pod_decode_attention_reuse per layer"}[variant],
+           "launch": "eager", "steps": K, "warmup": Wm, "ms_per_step": stats(per_step), "bytes_per_step": nbytes // K}
+    if variant == "reuse":
         # its own, smaller byte count: an upper layer reads V rows, proximal K rows and 4 B per (query head, distant
         # token); a lowest layer reads K and V rows and writes those 4 B
         def layer_bytes(n, upper):
@@ -139,23 +152,37 @@ def main_large(a):
             logits = (n - n_prox) * Hq * 4
             return (n * row + n_prox * row + logits) if upper else (2 * n * row + logits)
         reuse_bytes = sum(sum(layer_bytes(n + s + 1, l % G != 0) for n in lens) for l in range(L) for s in range(Wm, total))
-        print(json.dumps({
-            "metric": "decode step with score reuse", "ms_per_step": round(dt / K * 1e3, 4), "steps": K, "warmup": Wm,
-            "config": {"workload": name + "; step = (append + decode through pod_decode_attention_reuse) x 32 layers", "launch": "eager"},
-            "bytes_per_step_plain": nbytes // K, "bytes_per_step_reuse": reuse_bytes // K,
-            "value": round(reuse_bytes / dt / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
-            "plain_equivalent_GBs": round(nbytes / dt / 1e9, 1)}))
-        return
-    per_launch = nbytes / (K * L)
-    print(json.dumps({
-        "metric": "decode attn HBM GB/s", "value": round(nbytes / dt / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
-        "warmup": Wm, "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name + "; step = (append + decode) x 32 layers", "launch": "eager", "bytes_per_step": nbytes // K},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0>", "achieved": round(per_launch / (kernel_ms / launches * 1e-3) / 1e9, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(per_launch / (kernel_ms / launches * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": int(per_launch), "avg_kernel_us": round(kernel_ms / launches * 1e3, 3),
-                     "launches": launches}}))
+        res.update({"bytes_per_step_reuse": reuse_bytes // K, "GBs_of_its_own_bytes": round(reuse_bytes / dt / 1e9, 1),
+                    "plain_equivalent_GBs": round(nbytes / dt / 1e9, 1)})
+    else:
+        per_launch = nbytes / (K * L)
+        kus = statistics.median(each) * 1e3 if each else float("nan")
+        res.update({"GBs": round(nbytes / dt / 1e9, 1), "frac_of_hbm_peak": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4),
+                    "kernel": {"name": "decode_partial_kernel<128, 0, %d>" % (2 if variant == "step" else 1),
+                               "bytes_per_launch": int(per_launch), "median_us": round(kus, 3),
+                               "GBs": round(per_launch / (kus * 1e-6) / 1e9, 1),
+                               "frac_of_hbm_peak": round(per_launch / (kus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "launches": len(each)}})
+    del cache, kn, vn, q, out, scores
+    torch.cuda.empty_cache()
+    return res
+
+
+def main_large(a):
+    import torch
+    torch.cuda.set_device(0)
+    variant = "reuse" if a.reuse else ("separate" if a.separate_calls else "step")
+    r = run_large(a.workload, a.steps, a.warmup, variant)
+    ms = r["ms_per_step"]["median"]
+    line = {"metric": "decode attn HBM GB/s", "value": r.get("GBs", r.get("GBs_of_its_own_bytes")), "unit": "GB/s", "n_gpus": 1,
+            "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": r["workload"], "launch": "eager", "bytes_per_step": r["bytes_per_step"]}, "detail": r}
+    if "kernel" in r:
+        k = r["kernel"]
+        line["roofline"] = {"bound": "hbm", "kernel": k["name"], "achieved": k["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": k["frac_of_hbm_peak"], "traffic": None, "bytes_per_launch": k["bytes_per_launch"],
+                            "avg_kernel_us": k["median_us"], "launches": k["launches"]}
+    print(json.dumps(line))
 
 
 def main():
@@ -174,11 +201,12 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     G, Hq, Hkv, d, S, W = 2, 32, 8, 128, 64, 2048
-    R, n0, K, Wm, P = a.rotate, a.context, a.steps, a.warmup, a.profile_steps
+    R, n0, K, Wm, P, NSEG = a.rotate, a.context, a.steps, a.warmup, a.profile_steps, max(1, a.segments)
     RU = a.reuse_steps
+    GR = K          # replays of the token-reusable step graph (each replay = R steps)
     seed = 20241202 + 2
-    total_steps = Wm + K + P + RU
-    per_block = (total_steps + R - 1) // R
+    total_steps = Wm + NSEG * K + K + P + RU
+    per_block = (total_steps + R - 1) // R + GR + 2
     max_ctx = n0 + per_block + 1
     L = G * R
     cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, 1, max_ctx)
@@ -207,7 +235,12 @@ def main():
             ent[f"o{j}"] = torch.empty((1, Hq, d), dtype=torch.bfloat16, device=dev)
         steps.append(ent)
 
-    def run_step(e):
+    def run_step(e):                    # the hot path: one launch per layer
+        l0, l1 = e["layers"]
+        cache.pod_decode_step(l0, e["k0"], e["v0"], e["q0"], None, e["pos"], scale, out=e["o0"], max_context_len=e["n"])
+        cache.pod_decode_step(l1, e["k1"], e["v1"], e["q1"], e["q0"], e["pos"], scale, out=e["o1"], max_context_len=e["n"])
+
+    def run_step_separate(e):           # the same step through the separate calls (two launches per layer)
         l0, l1 = e["layers"]
         cache.pod_cache_append(l0, e["k0"], e["v0"], e["pos"])
         cache.pod_cache_append(l1, e["k1"], e["v1"], e["pos"])
@@ -231,6 +264,30 @@ def main():
         n_prox = min(n, S + W)
         return 2 * n * row + (n * row + n_prox * row + (n - n_prox) * Hq * 4) + (n - n_prox) * Hq * 4
 
+    def time_segments(fn, segs):
+        """Each segment (a list of consecutive steps) is captured into its own HIP graph, then the graphs are
+        replayed in order, each bracketed by a device synchronisation.  Returns seconds per segment."""
+        graphs = []
+        if not a.no_graph:
+            for seg in segs:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for e in seg:
+                        fn(e)
+                graphs.append(g)
+        out = []
+        for i, seg in enumerate(segs):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if graphs:
+                graphs[i].replay()
+            else:
+                for e in seg:
+                    fn(e)
+            torch.cuda.synchronize()
+            out.append(time.perf_counter() - t0)
+        return out
+
     if a.pmc_calibration:   # a plain copy kernel of known size: reads 1 GiB, writes 1 GiB per launch
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -245,86 +302,119 @@ def main():
     torch.cuda.synchronize()
     cache.pod_cache_check()
 
-    # ---- timed region: exactly K steps
-    timed = steps[Wm:Wm + K]
-    mode = "eager"
-    graph = None
-    if not a.no_graph:
-        try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for e in timed:
-                    run_step(e)
-            mode = "hipgraph"
-        except Exception as ex:  # capture unsupported: fall back to eager launches of the same kernels
-            print(f"bench.py: graph capture failed ({ex}); timing eager launches", file=sys.stderr)
-            graph = None
-            a.no_graph = True
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if graph is not None:
-        graph.replay()
-    else:
-        for e in timed:
-            run_step(e)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    # ---- timed region: NSEG segments of exactly K steps each; the headline is the median segment
+    mode = "eager" if a.no_graph else "hipgraph"
+    segs = [steps[Wm + i * K:Wm + (i + 1) * K] for i in range(NSEG)]
+    seg_s = time_segments(run_step, segs)
     cache.pod_cache_check()
-    elapsed = t1 - t0
-    nbytes = sum(step_bytes(e) for e in timed)
-    value = nbytes / elapsed / 1e9
+    seg_ms_per_step = [t / K * 1e3 for t in seg_s]
+    med = statistics.median(seg_s)
+    nbytes = sum(step_bytes(e) for e in segs[seg_s.index(med) if med in seg_s else 0])
+    value = nbytes / med / 1e9
+    cursor = Wm + NSEG * K
 
-    # ---- dominant kernel (decode partial kernel) with HIP events, eager launches
-    prof = steps[Wm + K:Wm + K + P]
+    # ---- the same step through the separate calls (append, append, attention, attention), one segment
+    sep = steps[cursor:cursor + K]
+    cursor += K
+    sep_s = time_segments(run_step_separate, [sep])[0]
+    cache.pod_cache_check()
+
+    # ---- dominant kernel (the fused streaming kernel of pod_decode_step) with HIP events, eager launches
+    prof = steps[cursor:cursor + P]
+    cursor += P
     cache.pod_profile_enable(2 * len(prof) + 4)
     for e in prof:
         run_step(e)
     torch.cuda.synchronize()
-    ms, launches = cache.pod_profile_read()
+    each = cache.pod_profile_read_each(2 * len(prof) + 4)
     cache.pod_profile_disable()
     cache.pod_cache_check()
-    kernel_s = ms / 1e3 / max(launches, 1)
-    bytes_per_launch = sum(step_bytes(e) for e in prof) / max(launches, 1)
-    achieved = bytes_per_launch / kernel_s / 1e9
+    low_us = [t * 1e3 for t in each[0::2]]      # lowest-layer launches: every K/V byte comes from HBM
+    up_us = [t * 1e3 for t in each[1::2]]       # upper-layer launches: the block's distant keys were read a launch earlier
+    bytes_per_launch = sum(step_bytes(e) for e in prof) / max(len(each), 1)
+    cold_us = statistics.median(low_us)
+    achieved = bytes_per_launch / (cold_us * 1e-6) / 1e9
+    # a plain streaming read of the same number of bytes from memory that left the caches long ago
+    sweep = torch.empty(8 * int(bytes_per_launch) // 16 * 16 + 4096, dtype=torch.uint8, device=dev).fill_(1)
+    part = int(bytes_per_launch) // 256 * 256
+    cache.pod_profile_enable(48)
+    for i in range(40):
+        pod.pod_profile_stream_read(sweep[(i % 8) * part:], part, cache)
+    torch.cuda.synchronize()
+    ceil_us = [t * 1e3 for t in cache.pod_profile_read_each(48)][8:]
+    cache.pod_profile_disable()
+    del sweep
+    ceil_med = statistics.median(ceil_us)
 
     out = {
         "metric": "decode attn HBM GB/s @32K ctx",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": round(elapsed / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(med / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: LLaMA3-8B-shaped PoD decode, one layer block G=2, 32q/8kv heads, d=128, "
-                               f"batch 1, context {n0}+step, S=64, W=2048, RoPE keys; step = append x2 + decode x2",
-                   "rotating_blocks": R, "launch": mode, "bytes_per_step": step_bytes(timed[0])},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0>", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic_from_profiles(), "bytes_per_launch": int(bytes_per_launch),
-                     "avg_kernel_us": round(kernel_s * 1e6, 3), "launches": launches},
+                               f"batch 1, context {n0}+step, S=64, W=2048, RoPE keys; step = pod_decode_step (cache update + "
+                               "attention in one launch) on the lowest layer, then on the upper layer",
+                   "rotating_blocks": R, "launch": mode, "launch_info": cache.pod_cache_launch_info(), "bytes_per_step": step_bytes(segs[0][0]),
+                   "segments": NSEG, "ms_per_step_segments": stats(seg_ms_per_step),
+                   "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0, 2> (streams K/V, updates the cache, merges the partials)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": int(bytes_per_launch),
+                     "avg_kernel_us": round(cold_us, 3), "launches": len(each),
+                     "timed": "HIP event pair per launch (reads 1-2 us more than the kernel's own begin-to-end time); "
+                              "achieved/frac are the lowest-layer launches, whose bytes all come from HBM",
+                     "lowest_layer_launch_us": stats(low_us), "upper_layer_launch_us": stats(up_us),
+                     "upper_layer_frac": round(bytes_per_launch / (statistics.median(up_us) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "streaming_ceiling": {"what": "plain read-only kernel over the same number of cold bytes, same event timing",
+                                           "us": stats(ceil_us), "GBs": round(part / (ceil_med * 1e-6) / 1e9, 1),
+                                           "frac_of_peak": round(part / (ceil_med * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                           "kernel_vs_ceiling": round(ceil_med / cold_us * bytes_per_launch / part, 4)}},
+        "separate_calls": {"what": "the same step as pod_cache_append x2 + pod_decode_attention x2 (4 launches)",
+                           "ms_per_step": round(sep_s / K * 1e3, 5), "step_speedup_from_fusing": round((sep_s / K) / (med / K), 3)},
     }
 
     # ---- the same steps through the score-reuse entry point
     if RU > 0:
-        ru = steps[Wm + K + P:]
-        g2 = None
-        if not a.no_graph:
-            g2 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g2):
-                for e in ru:
-                    run_step_reuse(e)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if g2 is not None:
-            g2.replay()
-        else:
-            for e in ru:
-                run_step_reuse(e)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
+        ru = steps[cursor:cursor + RU]
+        cursor += RU
+        el = time_segments(run_step_reuse, [ru])[0]
         cache.pod_cache_check()
         rb = sum(step_bytes_reuse(e) for e in ru)
         out["score_reuse"] = {"steps": len(ru), "ms_per_step": round(el / len(ru) * 1e3, 5),
                               "bytes_per_step": step_bytes_reuse(ru[0]),
                               "value": round(rb / el / 1e9, 1), "unit": "GB/s (of its own, smaller byte count)",
-                              "speedup_vs_plain_step": round((elapsed / K) / (el / len(ru)), 3)}
+                              "speedup_vs_separate_calls": round((sep_s / K) / (el / len(ru)), 3)}
+
+    # ---- one step graph replayed for successive tokens (lengths taken from device arrays only): every replay is one
+    # step on each of the R blocks; the graph advances its own position arrays
+    if not a.no_graph and GR > 0:
+        lens0 = [cache.pod_cache_seq_len(G * g, 0) for g in range(R)]
+        cache.pod_cache_set_length_source(1)
+        gpos = [torch.tensor([lens0[g]], dtype=torch.int32, device=dev) for g in range(R)]
+        fixed = [dict(steps[g]) for g in range(R)]      # any token's k, v, q: the values do not change the time
+        for e in fixed:
+            e["o0"], e["o1"] = torch.empty_like(e["o0"]), torch.empty_like(e["o1"])
+        bound = max(lens0) + GR + 1
+        gg = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gg):
+            for g in range(R):
+                e = fixed[g]
+                cache.pod_decode_step(G * g, e["k0"], e["v0"], e["q0"], None, gpos[g], scale, out=e["o0"], max_context_len=bound)
+                cache.pod_decode_step(G * g + 1, e["k1"], e["v1"], e["q1"], e["q0"], gpos[g], scale, out=e["o1"], max_context_len=bound)
+                gpos[g].add_(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(GR):
+            gg.replay()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        cache.pod_cache_check()
+        cache.pod_cache_sync_lengths()
+        cache.pod_cache_set_length_source(0)
+        ok = all(cache.pod_cache_seq_len(G * g + j, 0) == lens0[g] + GR for g in range(R) for j in range(G))
+        out["reusable_step_graph"] = {"what": f"one captured graph = one step on each of the {R} blocks, replayed {GR} times for successive "
+                                              "tokens; lengths from device arrays, launch sized for the last token",
+                                      "ms_per_step": round(el / (GR * R) * 1e3, 5), "lengths_advanced_as_expected": ok}
 
     # ---- gated skip of distant tokens: decode calls only (no appends), the
     # R blocks round-robin, at the contexts the steps above left behind.  Three timings of the same
@@ -427,12 +517,13 @@ def main():
                                "kind": "oracle", "sample": f"{done} of the same decode steps (one block, both layers)",
                                "ms_per_step": round(cpu_t / done * 1e3, 2), "gpu_vs_oracle_max_abs_err": worst}
 
+    del cache, steps, scores
+    torch.cuda.empty_cache()
+
     # ---- prefill (configs[3]): one block, n tokens, causal, attention + cache construction
     if not a.no_prefill:
         n = a.prefill_n
         pcfg = pod.make_config(G, G, Hq, Hkv, d, S, W, 1, n)
-        del cache
-        torch.cuda.empty_cache()
         pc = pod.PodCache(pcfg, dev)
         pseed = 20241202 + 4
         q = [gen.queries_bf16(pseed, l, 0, n, Hq, d, device=dev) for l in range(G)]
@@ -443,7 +534,7 @@ def main():
         res = {}
         for layer, name in ((0, "lowest_layer"), (1, "upper_layer")):
             times = []
-            for it in range(4):
+            for it in range(8):
                 pc.pod_cache_reset(-1)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -451,9 +542,9 @@ def main():
                                          k[0] if layer else None, scale, out=o, write_cache=True)
                 e1.record()
                 torch.cuda.synchronize()
-                times.append(e0.elapsed_time(e1) / 1e3)
-            t = min(times[1:])
-            res[name] = {"ms": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 2),
+                times.append(e0.elapsed_time(e1))
+            t = statistics.median(times[1:]) / 1e3
+            res[name] = {"ms": round(t * 1e3, 4), "ms_min": round(min(times[1:]), 4), "tflops": round(flops / t / 1e12, 2),
                          "frac_of_bf16_mfma_peak": round(flops / t / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
         # the same prompt in chunks (every layer takes a chunk, stores it, then the next chunk)
         if a.chunk > 0:
@@ -479,10 +570,26 @@ def main():
                               "ms_first_chunk": round(best[0], 4), "ms_last_chunk": round(best[-1], 4),
                               "tflops": round(G * flops / tot / 1e12, 2),
                               "vs_one_call": round((res["lowest_layer"]["ms"] + res["upper_layer"]["ms"]) / (tot * 1e3), 3)}
+            del ws
         pc.pod_cache_check()
         out["prefill"] = {"workload": f"configs[3]: one block G=2, 32q/8kv, d=128, prompt {n}, S=64, W=2048, "
                                       "attention + cache construction", "flops_per_layer": flops,
                           "peak_tflops": MFMA_BF16_PEAK_TFLOPS, **res}
+        del pc, q, k, v, o
+        torch.cuda.empty_cache()
+
+    # ---- the large-batch decode configurations (configs[2] and configs[4]); skipped once the run is past the time guard
+    if not a.no_large:
+        large = {}
+        for wl in ("cfg3", "cfg5"):
+            for variant in ("step", "reuse"):
+                key = f"{wl}_{variant}"
+                if time.perf_counter() - T_START > a.time_guard:
+                    large[key] = {"skipped": f"past the time guard of {a.time_guard:.0f} s"}
+                    continue
+                large[key] = run_large(wl, a.large_steps, 2, variant)
+        out["large_batch"] = large
+    out["bench_seconds"] = round(time.perf_counter() - T_START, 1)
     print(json.dumps(out))
 
 

@@ -201,6 +201,47 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
                          void *workspace, size_t workspace_bytes, void *out, void *stream);
 
 /*
+ * One decode step of a layer in one launch: pod_cache_append(layer, k_new, v_new, positions) followed by
+ * pod_decode_attention(layer, q, q_shared, context_lens = positions + 1): same cache contents afterwards
+ * (bit for bit) and the same attention (Eq. 3 + Eq. 4 over the tokens including the new one).  The kernel
+ * walks the rows held before the call; one more workgroup per (sequence, kv head) takes the new token
+ * (proximal: this layer's query and the new key) and the token it displaces from the recent window
+ * (distant from now on: the key the block's lowest layer holds for it, with that layer's query),
+ * performs the cache update, and the last workgroup to finish merges the partial results.
+ *   k_new, v_new : dev bf16 [B][Hkv][d];  positions : dev int32 [B], as in pod_cache_append
+ *   q, q_shared, scale, workspace, out : as in pod_decode_attention
+ *   max_context_len : host upper bound on positions + 1; 0 = the host mirror's maximum + 1
+ * Every entry takes a token (no inactive entries).  A wrong position skips the entry: nothing
+ * stored, output row zeroed, flag raised (pod_cache_check).  The block's lowest layer must take the
+ * token before the block's upper layers.
+ */
+int pod_decode_step(pod_cache *cache, int layer, const void *k_new, const void *v_new, const void *q,
+                    const void *q_shared, const int32_t *positions, int B, int max_context_len, float scale,
+                    void *workspace, size_t workspace_bytes, void *out, void *stream);
+
+/*
+ * Where the decode kernels take sequence lengths from.  0 (default): batches of up to 256
+ * sequences pass the host mirror's lengths as kernel arguments (the shortest way to the first
+ * load; the device-side arrays are still compared with them).  1: only from the device arrays the
+ * calls name (context_lens, positions) and the cache's own header; nothing a call enqueues then
+ * depends on the mirror, so a HIP graph captured over pod_cache_append / pod_decode_attention /
+ * pod_decode_step calls can be replayed for successive tokens: refresh the device arrays between
+ * replays, pass max_context_len >= every length the replays will see (it sizes the launch and must
+ * be given), always pass q_shared for an upper layer, and call pod_cache_sync_lengths once the
+ * replays are done.  Checks the host can no longer make are made on the device (flag).
+ */
+int pod_cache_set_length_source(pod_cache *cache, int from_device);
+
+/*
+ * How this cache's decode launches are shaped on the current device (host out, for reports and tests):
+ * info[0] = number of XCDs a one-dimensional launch was seen to spread over round-robin (0 = no such
+ * pattern); info[1] = 1 if split-K partials are handed over inside one XCD's L2 where the batch allows;
+ * info[2] = 1 if plain decode merges its partials inside the streaming kernel; info[3] = the length source
+ * (pod_cache_set_length_source).
+ */
+int pod_cache_launch_info(const pod_cache *cache, int32_t info[4]);
+
+/*
  * pod_decode_attention for callers that cannot allocate device memory or take a workspace from
  * an allocator: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, kernels and results as pod_decode_attention, except that the
@@ -368,6 +409,28 @@ int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slot, void *si
 int pod_profile_enable(pod_cache *cache, int max_records);
 int pod_profile_disable(pod_cache *cache);
 int pod_profile_read(pod_cache *cache, double *total_ms, int *launches);
+/* The same, launch by launch: ms_each (host float [capacity]) receives the kernel time of each recorded launch in
+ * call order, *launches how many were written; the records are then forgotten. */
+int pod_profile_read_each(pod_cache *cache, float *ms_each, int capacity, int *launches);
+/*
+ * Measurement aid: while dev_buf is set (NULL = off), every workgroup of a pod_decode_step / fused
+ * pod_decode_attention launch that stores a partial result leaves 8 uint64 words in it, at index (workgroup number
+ * in the launch) * 8: (sequence * num_kv_heads + kv head) << 32 | piece (bit 31 set: this workgroup merged), the id of
+ * the XCD it ran on, and the device's 100 MHz clock at its start, at the end of its tile loop, when its partial was
+ * stored, when its arrival was counted, and at its end.  bytes / 64 workgroups are recorded; later launches overwrite
+ * earlier ones.  The caller owns dev_buf.
+ */
+int pod_profile_set_trace(pod_cache *cache, void *dev_buf, size_t bytes);
+
+/*
+ * Measurement aid: enqueue the plainest possible kernel that reads `bytes` of device memory once (16-byte loads,
+ * one resident round of workgroups, nothing stored).  Timed by the caller on memory that is not in any cache, it
+ * gives the rate a streaming launch of that size can reach on this device: the ceiling the decode kernel's
+ * launches are compared with.  dev_buf 16-byte aligned, bytes a positive multiple of 16.  With a cache whose
+ * profiling is enabled (cache may be NULL) the launch is recorded like a decode launch: same events, read back
+ * through pod_profile_read / pod_profile_read_each.
+ */
+int pod_profile_stream_read(pod_cache *cache, const void *dev_buf, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,10 +19,10 @@ EXPORTS = [
     "pod_last_error", "pod_cache_bytes", "pod_cache_live_bytes", "pod_cache_init", "pod_cache_destroy",
     "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
-    "pod_profile_enable", "pod_profile_disable", "pod_profile_read",
+    "pod_profile_enable", "pod_profile_disable", "pod_profile_read", "pod_profile_read_each", "pod_profile_stream_read", "pod_profile_set_trace",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
-    "pod_decode_attention_static", "pod_cache_region_counts",
+    "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
 ]
 
@@ -72,6 +72,9 @@ def load():
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
+        "pod_decode_step": [vp, C.c_int, vp, vp, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
+        "pod_cache_set_length_source": [vp, C.c_int],
+        "pod_cache_launch_info": [vp, C.POINTER(C.c_int32)],
         "pod_decode_attention_static": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, vp],
         "pod_prefill_attention": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_int, vp],
         "pod_cache_export_logical": [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp],
@@ -90,6 +93,9 @@ def load():
         "pod_profile_enable": [vp, C.c_int],
         "pod_profile_disable": [vp],
         "pod_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)],
+        "pod_profile_read_each": [vp, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)],
+        "pod_profile_stream_read": [vp, vp, C.c_size_t, vp],
+        "pod_profile_set_trace": [vp, vp, C.c_size_t],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -182,6 +188,12 @@ def pod_workspace_bytes(cfg: PodConfig) -> int:
     return out.value
 
 
+def pod_profile_stream_read(buf: torch.Tensor, nbytes: int, cache=None):
+    """Enqueue one plain streaming read of the first nbytes of a CUDA tensor on the current stream; with a PodCache
+    whose profiling is enabled the launch is recorded like a decode launch."""
+    _check(load().pod_profile_stream_read(cache.handle if cache is not None else None, buf.data_ptr(), nbytes, _stream()))
+
+
 class PodCache:
     """Owns the torch buffers (cache + decode workspace) and the libpod handle."""
 
@@ -252,6 +264,23 @@ class PodCache:
                                            self.workspace.data_ptr(), self.workspace.numel(), _ptr(out, torch.bfloat16),
                                            _stream()))
         return out
+
+    def pod_decode_step(self, layer, k_new, v_new, q, q_shared, positions, scale, out=None, max_context_len=0):
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_decode_step(self.handle, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+                                      _ptr(q, torch.bfloat16), _ptr(q_shared, torch.bfloat16), _ptr(positions, torch.int32),
+                                      q.shape[0], max_context_len, scale, self.workspace.data_ptr(), self.workspace.numel(),
+                                      _ptr(out, torch.bfloat16), _stream()))
+        return out
+
+    def pod_cache_launch_info(self):
+        info = (C.c_int32 * 4)()
+        _check(load().pod_cache_launch_info(self.handle, info))
+        return dict(xcds=info[0], xcd_local=bool(info[1]), fused_merge=bool(info[2]), device_lengths=bool(info[3]))
+
+    def pod_cache_set_length_source(self, from_device):
+        _check(load().pod_cache_set_length_source(self.handle, int(bool(from_device))))
 
     def pod_decode_attention_static(self, layer, q, q_shared, context_lens, scale, out, max_context_len=0):
         """pod_decode_attention on the library's own fixed scratch array; `out` is the caller's (nothing is allocated)."""
@@ -327,6 +356,17 @@ class PodCache:
         ms, cnt = C.c_double(), C.c_int()
         _check(load().pod_profile_read(self.handle, C.byref(ms), C.byref(cnt)))
         return ms.value, cnt.value
+
+    def pod_profile_set_trace(self, buf):
+        """buf: CUDA int64 tensor (8 words per workgroup) or None."""
+        _check(load().pod_profile_set_trace(self.handle, buf.data_ptr() if buf is not None else None,
+                                            buf.numel() * buf.element_size() if buf is not None else 0))
+
+    def pod_profile_read_each(self, capacity):
+        """Kernel time in ms of each recorded launch, in call order."""
+        buf, cnt = (C.c_float * capacity)(), C.c_int()
+        _check(load().pod_profile_read_each(self.handle, buf, capacity, C.byref(cnt)))
+        return [buf[i] for i in range(cnt.value)]
 
     def pod_cache_export_logical(self, layer, seq_slot):
         """dict of bf16 tensors [tokens][Hkv][d]: sinkK, sinkV, recentK, recentV, distV (+ distK at a lowest layer)."""

@@ -96,6 +96,8 @@ static int make_layout(const pod_config *cfg, pod_layout *ly)
     ly->off_lens = off; off += (size_t)ly->L * ly->B * sizeof(int32_t);
     off = align_up(off, 16);
     ly->off_flag = off; off += 16;
+    ly->off_tickets = off; off += (size_t)ly->B * ly->Hkv * sizeof(uint64_t);
+    ly->off_stepdone = off; off += (size_t)ly->B * sizeof(int32_t);
     off = align_up(off, 256);
     ly->off_proxK = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
     ly->off_proxV = off; off = align_up(off + per_layer_heads * ly->P * row, 256);
@@ -195,12 +197,20 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
         const char *e1 = getenv("POD_DECODE_CHUNK"), *e2 = getenv("POD_DECODE_CHUNK_PROX");
         c->tune_chunk = e1 && atoi(e1) > 0 ? atoi(e1) : 0;
         c->tune_chunk_prox = e2 && atoi(e2) > 0 ? atoi(e2) : 0;
+        const char *e3 = getenv("POD_DECODE_FUSED");
+        c->fused_merge = !(e3 && atoi(e3) == 0);
+        const char *e4 = getenv("POD_DECODE_XCD_LOCAL");
+        c->xcd_local = !(e4 && atoi(e4) == 0);
+        c->nxcd = 0;
+        c->device_lengths = false;
     }
     c->prof_ev = nullptr; c->prof_cap = 0; c->prof_n = 0;
+    c->trace = nullptr; c->trace_cap = 0;
     if (!c->host_len) { free(c->lowest); free(c->kslot); delete c; return pod_fail(POD_ERR_CAPACITY, "out of host memory"); }
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return pod_hip_fail(e, "hipGetDevice"); }
     rc = pod_decode_static_scratch(&c->static_scratch, &c->static_scratch_bytes); // this device's copy of the array
+    if (rc == POD_OK) rc = pod_probe_xcds(&c->nxcd);
     if (rc == POD_OK) rc = pod_launch_clear_header(c, (hipStream_t)stream);
     if (rc) { free(c->host_len); free(c->lowest); free(c->kslot); delete c; return rc; }
     *out = c;
@@ -261,6 +271,35 @@ extern "C" int pod_profile_read(pod_cache *cache, double *total_ms, int *launche
     *total_ms = sum; *launches = cache->prof_n;
     cache->prof_n = 0;
     return POD_OK;
+}
+
+extern "C" int pod_profile_read_each(pod_cache *cache, float *ms_each, int capacity, int *launches)
+{
+    if (!cache || !ms_each || !launches || capacity < 0) return pod_fail(POD_ERR_INVALID_ARG, "NULL argument or negative capacity");
+    const int n = cache->prof_n < capacity ? cache->prof_n : capacity;
+    for (int i = 0; i < n; ++i) {
+        POD_HIP_TRY(hipEventSynchronize(cache->prof_ev[2 * i + 1]));
+        POD_HIP_TRY(hipEventElapsedTime(&ms_each[i], cache->prof_ev[2 * i], cache->prof_ev[2 * i + 1]));
+    }
+    *launches = n;
+    cache->prof_n = 0;
+    return POD_OK;
+}
+
+extern "C" int pod_profile_set_trace(pod_cache *cache, void *dev_buf, size_t bytes)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    if (dev_buf && ((uintptr_t)dev_buf % 8)) return pod_fail(POD_ERR_INVALID_ARG, "dev_buf must be 8-byte aligned");
+    cache->trace = dev_buf;
+    cache->trace_cap = dev_buf ? (int)(bytes / 64 > 0x7fffffff ? 0x7fffffff : bytes / 64) : 0;
+    return POD_OK;
+}
+
+extern "C" int pod_profile_stream_read(pod_cache *cache, const void *dev_buf, size_t bytes, void *stream)
+{
+    if (!dev_buf || ((uintptr_t)dev_buf % 16) || bytes < 16 || bytes % 16)
+        return pod_fail(POD_ERR_INVALID_ARG, "dev_buf must be 16-byte aligned and bytes a positive multiple of 16");
+    return pod_launch_stream_read(cache, dev_buf, bytes, (hipStream_t)stream);
 }
 
 static int check_cache_layer(const pod_cache *c, int layer)
@@ -478,6 +517,13 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
     int64_t longest = 0;
     for (int b = 0; b < B; ++b) longest = len[b] > longest ? len[b] : longest;
     const bool lowest = layer_lowest_all(cache, layer);
+    if (cache->device_lengths) {
+        // the mirror is not consulted: the launch bound must come from the caller, and an upper layer always names its shared query
+        if (max_context_len < 1) return pod_fail(POD_ERR_INVALID_ARG, "with lengths taken from the device, max_context_len must be given");
+        if (!lowest && !q_shared) return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block: q_shared is required", layer);
+        return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
+                                 workspace, workspace_bytes, scores, tau, out, (hipStream_t)stream);
+    }
     if (!lowest && !q_shared && longest > ly.P)
         return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and holds distant tokens: q_shared is required", layer);
     // every head's lowest layer must hold the same tokens as this layer (the device checks this layer's own lengths)
@@ -492,6 +538,70 @@ static int decode_common(pod_cache *cache, int layer, const void *q, const void 
     if (max_context_len == 0) max_context_len = 1;
     return pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, context_lens, B, max_context_len, scale,
                              workspace, workspace_bytes, scores, tau, out, (hipStream_t)stream);
+}
+
+extern "C" int pod_cache_launch_info(const pod_cache *cache, int32_t info[4])
+{
+    if (!cache || !info) return pod_fail(POD_ERR_INVALID_ARG, "NULL argument");
+    info[0] = cache->nxcd;
+    info[1] = cache->xcd_local && cache->nxcd >= 1;
+    info[2] = cache->fused_merge;
+    info[3] = cache->device_lengths;
+    return POD_OK;
+}
+
+extern "C" int pod_cache_set_length_source(pod_cache *cache, int from_device)
+{
+    if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");
+    cache->device_lengths = from_device != 0;
+    return POD_OK;
+}
+
+extern "C" int pod_decode_step(pod_cache *cache, int layer, const void *k_new, const void *v_new, const void *q,
+                               const void *q_shared, const int32_t *positions, int B, int max_context_len, float scale,
+                               void *workspace, size_t workspace_bytes, void *out, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!k_new || !v_new || !q || !positions || !out || !workspace)
+        return pod_fail(POD_ERR_INVALID_ARG, "k_new, v_new, q, positions, workspace and out must not be NULL");
+    if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
+    if (workspace_bytes < pod_decode_workspace_bytes(ly))
+        return pod_fail(POD_ERR_CAPACITY, "workspace has %zu bytes, needs %zu", workspace_bytes, pod_decode_workspace_bytes(ly));
+    if (max_context_len < 0 || max_context_len > ly.maxctx)
+        return pod_fail(POD_ERR_INVALID_ARG, "max_context_len %d outside [0, %d]", max_context_len, ly.maxctx);
+    const bool lowest = layer_lowest_all(cache, layer);
+    const pod_step_args step = {k_new, v_new, positions};
+    int64_t *len = cache->host_len + (size_t)layer * ly.B;
+    if (cache->device_lengths) {
+        if (max_context_len < 1) return pod_fail(POD_ERR_INVALID_ARG, "with lengths taken from the device, max_context_len must be given");
+        if (!lowest && !q_shared) return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block: q_shared is required", layer);
+    } else {
+        int64_t longest = 0;
+        for (int b = 0; b < B; ++b) {
+            if (len[b] >= ly.maxctx)
+                return pod_fail(POD_ERR_CAPACITY, "slot %d at layer %d already holds max_context = %d tokens", b, layer, ly.maxctx);
+            longest = len[b] + 1 > longest ? len[b] + 1 : longest;
+        }
+        if (!lowest && !q_shared && longest > ly.P)
+            return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest of its block and holds distant tokens: q_shared is required", layer);
+        // the lowest layer of every head's block must have taken this token already once distant tokens exist
+        for (int h = 0; h < ly.Hkv; ++h) {
+            const int la = cache->lowest[(size_t)layer * ly.Hkv + h];
+            const int64_t *low = cache->host_len + (size_t)la * ly.B;
+            for (int b = 0; b < B && la != layer; ++b)
+                if (len[b] + 1 > ly.P && low[b] != len[b] + 1)
+                    return pod_fail(POD_ERR_STATE, "slot %d: layer %d would hold %lld tokens but layer %d, the lowest of kv head %d's block, holds %lld",
+                                    b, layer, (long long)len[b] + 1, la, h, (long long)low[b]);
+        }
+        if (max_context_len == 0) max_context_len = (int)longest;
+    }
+    rc = pod_launch_decode(cache, layer, q, lowest ? nullptr : q_shared, nullptr, B, max_context_len, scale, workspace,
+                           workspace_bytes, nullptr, -1.f, out, (hipStream_t)stream, &step);
+    if (rc) return rc;
+    for (int b = 0; b < B; ++b) len[b] += 1;
+    return POD_OK;
 }
 
 extern "C" int pod_layer_similarity(const float *att, int num_layers, int num_heads, int rows, int n, float *sim,

@@ -20,6 +20,13 @@ __global__ void clear_header_kernel(char *base, pod_layout ly, int seq_slot)
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x)
         if (seq_slot < 0 || i % ly.B == seq_slot) lens_ptr(base, ly)[i] = 0;
     if (seq_slot < 0 && blockIdx.x == 0 && threadIdx.x == 0) *flag_ptr(base, ly) = 0;
+    // arrival counters of the decode kernels (zero whenever no decode kernel is running)
+    unsigned long long *tickets = (unsigned long long *)(base + ly.off_tickets);
+    int32_t *done = (int32_t *)(base + ly.off_stepdone);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < ly.B * ly.Hkv; i += gridDim.x * blockDim.x)
+        if (seq_slot < 0 || i / ly.Hkv == seq_slot) tickets[i] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < ly.B; i += gridDim.x * blockDim.x)
+        if (seq_slot < 0 || i == seq_slot) done[i] = 0;
 }
 
 // One block per sequence.  Each thread moves 16-byte pieces of the (kv head, dim) row.

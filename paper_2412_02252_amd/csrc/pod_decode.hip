@@ -93,6 +93,24 @@ struct decode_params {
     float *gate_d;   // [B][Hq][2]: maximum and sum of the distant exponentials at the lowest layer (base-2 domain)
     int32_t *skip;   // [B][Hq]: 1 where the upper layer left the distant part out (written by its distant pass)
     float tau;
+    // merge inside the streaming kernel (FUSE >= 1): arrival counters, zero between launches.  tickets[b][kv head]
+    // counts the workgroups of a (sequence, kv head) pair that have stored their partial; the last one merges.
+    unsigned long long *tickets; // [max_batch][Hkv]: arrivals in bits 0-19, sum of the arrivals' XCC ids in 20-41, of their squares in 42-63
+    // decode step (FUSE == 2): the new token's rows, its position, and what the cache update writes
+    const u32x4 *k_new, *v_new;  // [B][Hkv][D]
+    const int32_t *positions;    // [B]: position of the new token = tokens held before the call
+    int32_t *lens_w;             // this layer's device-side lengths [B], advanced by the call
+    int32_t *step_done;          // [max_batch]: kv heads of a sequence whose cache update is done; the last one stores the length
+    int32_t low_is_self;         // lens_lowest is this layer's own array (compare it with the length before the update)
+    int32_t step;                // 1: this launch is a decode step (read by decode_combine_kernel when it merges one)
+    int32_t sink, window;
+    // XCD-local hand-off (LOC): the launch is one-dimensional, workgroup w belongs to (sequence, kv head) pair
+    // (w / nxcd / slots) * nxcd + w % nxcd
+    int32_t nxcd, npairs, slots;
+    // measurement aid (pod_profile_set_trace): per workgroup of a fused launch 8 words = (pair << 32 | piece, XCC id,
+    // then device clock at: start, end of the tile loop, partial stored, arrival counted, end); NULL = off
+    unsigned long long *trace;
+    int32_t trace_cap;
     int32_t hlen[kMaxHostLens];
     // per kv head: (slot * max_batch of the distant-key store the head reads at this layer) | sign bit if this
     // layer is the lowest of the head's block (then every logit of the head uses q, not q_shared)
@@ -190,14 +208,106 @@ __device__ inline bool gate_skips(float mp, float lp, float md, float ld, float 
     return __fmul_rn(1.f - tau, lp) >= __fmul_rn(__fmul_rn(tau, ld), __builtin_amdgcn_exp2f(md - mp));
 }
 
+// Partials that are merged inside the same launch travel between workgroups.  The chip is 8 XCDs, each with its own L2,
+// and the L2s are not coherent with each other.  Two ways to hand a partial over:
+//  * LOC (the fast one): every workgroup of a (sequence, kv head) pair runs on ONE XCD - the launch is one-dimensional
+//    and workgroups go to the XCDs round-robin, so the pair is chosen from (workgroup index) mod (number of XCDs).
+//    Producer and consumer then meet in that XCD's L2: ordinary stores (the vector L1 writes through), an atomic
+//    counter executed in the L2, ordinary loads after the consumer has dropped its own L1.  A round trip is a few
+//    hundred ns.  The placement is checked, not assumed: every arrival adds the id of the XCD it runs on (XCC_ID
+//    hardware register) and its square to the pair's counter word, and the merging workgroup accepts the partials
+//    only if all ids were equal (n * sum of squares == square of the sum); otherwise it zeroes the output rows and
+//    raises the sticky flag.  (Eager launches were seen to start their round-robin at XCD 0 and graph replays at XCD
+//    7: the XCD of a position differs between launches, but a launch's workgroups of one position share it.)
+//  * otherwise device-scope relaxed atomic stores (write-through: in memory when acknowledged), a device-scope atomic
+//    counter and device-scope atomic loads, all of which go through to the memory fabric: correct wherever the
+//    workgroups run, but ~1.6 us per round trip.  (Device-scope release/acquire FENCES are not an option here: each
+//    one writes back / invalidates a whole L2, which made the launch 5x slower.)
+__device__ inline int xcc_id() { return (int)(__builtin_amdgcn_s_getreg((4 - 1) << 11 | 20) & 0xf); } // HW_REG_XCC_ID[3:0]
+
+template <bool LOC>
+__device__ inline void store_part(float *p, float v)
+{
+    if constexpr (LOC) *(__attribute__((address_space(1))) float *)p = v;
+    else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool LOC, int VEC>
+__device__ inline void load_part(const float *p, float (&out)[VEC])
+{
+    static_assert(LOC ? VEC == 4 : VEC == 2, "");
+    if constexpr (LOC) {
+        const f32x4 v = *(const __attribute__((address_space(1))) f32x4 *)p;
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else {
+        const unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        out[0] = __uint_as_float((unsigned)u); out[1] = __uint_as_float((unsigned)(u >> 32));
+    }
+}
+template <bool LOC>
+__device__ inline float2 load_ml(const float *p)
+{
+    if constexpr (LOC) {
+        typedef __attribute__((ext_vector_type(2))) float f32x2;
+        const f32x2 v = *(const __attribute__((address_space(1))) f32x2 *)p;
+        return make_float2(v.x, v.y);
+    }
+    const unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+
+// Arrival of a workgroup whose partial is stored: returns 0 if it is not the last of `expected` arrivals; else 1 (every
+// other workgroup's partial can now be read; the counter is back to zero for the next launch), or 2 if LOC and the
+// arrivals did not all come from one XCD (the partials may then not be readable here).  Every thread first waits for its
+// own stores to be acknowledged (by the L2 if LOC, by memory otherwise); after the barrier one thread counts, with a
+// 64-bit vector atomic at device scope.
+template <bool LOC>
+__device__ inline int arrive_last(unsigned long long *ticket, int expected)
+{
+    __shared__ int sm_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long x = LOC ? (unsigned long long)xcc_id() : 0ull;
+        const unsigned long long inc = 1ull | (x << 20) | ((x * x) << 42);
+        const unsigned long long tot = __hip_atomic_fetch_add(ticket, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
+        const unsigned long long n = tot & 0xfffffull, sx = (tot >> 20) & 0x3fffffull, sxx = tot >> 42;
+        int last = (int)n == expected;
+        if (last) {
+            __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (LOC && n * sxx != sx * sx) last = 2;
+        }
+        sm_last = last;
+    }
+    __syncthreads();
+    const int last = sm_last;
+    if (LOC && last) asm volatile("buffer_inv sc0" ::: "memory");   // this CU's vector L1: read the partials from the L2
+    return last;
+}
+
 // MODE 3 and 4 are the two launches of a gated upper layer (appendix "Computation Optimization for Distant
 // Tokens"): MODE 3 walks the proximal chunks only; MODE 4 walks the distant chunks, and each
 // workgroup first evaluates the gate g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)) of Eq. 4 for its
 // query heads from the proximal partials of MODE 3 and the lowest layer's distant sums, records
 // which heads have g >= tau, and leaves if all of its heads do.
-template <int D, int MODE>
+template <int D, bool LOC>
+__device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
+                                bool bad);
+template <int D, bool LOC>
+__device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg);
+
+// FUSE 0: partials only, decode_combine_kernel follows.  FUSE 1 (MODE 0 only): the last workgroup of a (sequence, kv
+// head) pair to store its partial merges them all and writes the output rows.  FUSE 2: FUSE 1 for a decode STEP: the
+// cache holds the tokens before the new one; the workgroup of a pair's first proximal piece first handles the new token
+// and the token it displaces from the window and performs the cache update (step_workgroup), then walks its piece
+// like everybody else walks theirs: over the old rows.  FUSE 3: a step whose partials decode_combine_kernel merges
+// (launches of several rounds of workgroups: there a workgroup that waits for its arrival to be counted holds its
+// slot idle, which costs more than the second launch).
+template <int D, int MODE, int FUSE = 0, bool LOC = false>
 __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_params p)
 {
+    static_assert(FUSE == 0 || MODE == 0, "the fused forms serve the plain mode");
+    constexpr bool STEP = FUSE == 2 || FUSE == 3, MERGE = FUSE == 1 || FUSE == 2;
+    static_assert(!LOC || MERGE, "the XCD-local launch shape serves the fused merge");
     constexpr int CPR = D / 8;        // 16-byte pieces per row
     constexpr int RPI = 64 / CPR;     // rows one K load instruction covers
     constexpr int NLD = kTile / RPI;  // K load instructions per tile
@@ -205,33 +315,98 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     constexpr int XN = 16 / CPR;      // lanes sharing one V piece (1 for D=128, 2 for D=64)
     constexpr int NPV = 8 / XN;       // PV MFMAs per tile
 
-    const int b = blockIdx.z, h = blockIdx.y;
     // The arguments the first loads depend on, in one round trip to the argument block.
     const decode_hot hot = load_hot_args();
-    const int c = MODE == 3 ? (int)blockIdx.x + hot.max_nd : (int)blockIdx.x;
+    int b = blockIdx.z, h = blockIdx.y, c = MODE == 3 ? (int)blockIdx.x + hot.max_nd : (int)blockIdx.x;
+    if constexpr (LOC) {
+        // one-dimensional launch: position x = w mod nxcd picks the XCD (and with it the pairs x, x + nxcd, ...), the
+        // workgroups of one XCD take their pairs one after the other, each pair's pieces in order
+        const int w = blockIdx.x, x = w % p.nxcd, j = w / p.nxcd;
+        const int pl = j / p.slots;
+        c = j - pl * p.slots;
+        const int pr = pl * p.nxcd + x;
+        if (pr >= p.npairs) return;
+        b = pr / hot.hkv;
+        h = pr - b * hot.hkv;
+    }
     const int n_host = load_hlen_arg(b);
     const int head_arg = load_head_arg(h);
+    unsigned long long tr_t0 = 0, tr_t1 = 0, tr_t2 = 0;
+    if (MERGE && p.trace) tr_t0 = wall_clock64();
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
     const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, max_nd = hot.max_nd;
     const int chunk_p = (int)((unsigned)hot.chunk >> 16);
     const bool use_hlen = hot.use_hlen != 0;
     // The host mirror's length is always within the buffers; whether it agrees with context_lens
-    // and the device-side lengths is checked by the combine kernel, which zeroes the output and
-    // raises the flag if not.  Only batches beyond kMaxHostLens read the device arrays here.
-    int n = n_host;
+    // and the device-side lengths is checked where the partials are merged (the combine kernel or the last
+    // workgroup), which zeroes the output and raises the flag if not.  Without the mirror (batches beyond
+    // kMaxHostLens, or a cache set to take lengths from the device) the length comes from the call's device
+    // array and is only held to the buffer and launch bounds here.
+    int n = n_host;     // tokens this launch's workgroups walk (a step: the tokens held BEFORE the new one)
     if (!use_hlen) {
-        bool bad;
-        n = decode_seq_len(p, b, &bad);
+        if constexpr (STEP) {
+            n = p.positions[b];
+            if (n < 0 || n >= p.maxctx || n >= p.max_len) n = -1;
+        } else if constexpr (FUSE == 1) {
+            n = hot.ctx[b];
+            if (n < 0 || n > p.maxctx || n > p.max_len) n = -1;
+        } else {
+            bool bad;
+            n = decode_seq_len(p, b, &bad);
+        }
     }
-    if (n <= 0) return;
+    if constexpr (MERGE) {
+        // nothing to walk and nobody to merge: the first workgroup of the pair leaves the zeroed output rows
+        // (an inactive entry), and raises the flag where the entry is not allowed to be empty
+        if (n < 0 || (FUSE == 1 && n == 0)) {
+            if (c == 0) {
+                for (int t = threadIdx.x; t < hot.rep * (D / 2); t += blockDim.x)
+                    ((unsigned *)(p.out + ((size_t)b * hot.hq + (size_t)h * hot.rep) * D))[t] = 0u;
+                const bool bad = FUSE == 2 || n < 0 || hot.ctx[b] != 0;
+                if (bad && h == 0 && threadIdx.x == 0) atomicOr(p.flag, 2);
+            }
+            return;
+        }
+    } else if constexpr (STEP) {
+        if (n < 0) return;   // (the combine kernel zeroes the rows and raises the flag)
+    } else {
+        if (n <= 0) return;
+    }
     const int n_prox = n < prows ? n : prows;
     const int n_dist = n - n_prox;
+    // workgroups of this (sequence, kv head) pair that store a partial (FUSE >= 1): the pieces of the two regions
+    // this launch's grid holds, and a step's extra workgroup
+    int nd_eff = 0, np_eff = 0;
+    if constexpr (MERGE) {
+        nd_eff = min((n_dist + (hot.chunk & 0xffff) - 1) / (hot.chunk & 0xffff), max_nd);
+        np_eff = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - max_nd);
+    }
+    // FUSE 2: the workgroup of the first proximal piece also takes the new token and the cache update; it arrives once
+    // for both partials, also when the cache was empty and it has no piece of its own
+    const bool hosts_step = STEP && c == max_nd;
+    const int expected = nd_eff + (FUSE == 2 && np_eff == 0 ? 1 : np_eff);
+    if (hosts_step) step_workgroup<D, LOC>(p, hot, b, h, n, head_arg);
     const bool distant = c < max_nd;
     const int region_len = distant ? n_dist : n_prox;
     const int chunk = distant ? (hot.chunk & 0xffff) : chunk_p;
     const int start = (distant ? c : c - max_nd) * chunk;
-    if (start >= region_len) return;
+    if (start >= region_len) {
+        if constexpr (FUSE == 2) {
+            if (hosts_step) {   // (an empty cache: the new token is all there is)
+                const int last = arrive_last<LOC>(p.tickets + (size_t)b * hkv + h, expected);
+                if (last) {
+                    if (last == 2 && threadIdx.x == 0) atomicOr(p.flag, 4);
+                    merge_and_store<D, LOC>(p, hot, b, h, nd_eff, np_eff, true, last == 1, last == 2);
+                }
+            }
+        }
+        return;
+    }
     const int end = min(start + chunk, region_len);
+    // FUSE 2: the ring slot the new token replaces is being rewritten by step_workgroup, which also accounts for the
+    // token it held: everybody else leaves that row out (its probability is forced to zero; old or new, its bytes
+    // are those of a real token, so the masked products stay finite)
+    const int excl = (STEP && !distant && n >= prows) ? p.sink + (n - p.sink) % p.window : -1;
 
     // Score reuse with head-wise blocks: the writing launch (MODE 1) serves the kv heads for which this layer is
     // the lowest of the block, the reading launches (MODE 2, 3, 4) the others; with uniform blocks one of the
@@ -468,8 +643,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tok0 = t0 + 4 * j + i, tok1 = tok0 + 16;
-            sc[i] = tok0 < end ? s0[i] * hot.scale_log2e : kNegBig;
-            sc[4 + i] = tok1 < end ? s1[i] * hot.scale_log2e : kNegBig;
+            sc[i] = (tok0 < end && (!STEP || tok0 != excl)) ? s0[i] * hot.scale_log2e : kNegBig;
+            sc[4 + i] = (tok1 < end && (!STEP || tok1 != excl)) ? s1[i] * hot.scale_log2e : kNegBig;
         }
         if constexpr (MODE == 1) {
             if (distant && m16 < hot.rep) { // the lowest layer's distant logits, for the block's upper layers
@@ -489,6 +664,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     // acc[x][i] is O^T[dim slot 4j+i][head m16]; the slot's dim is
     //   XN = 1: 8*(4j+i) + x        XN = 2: 8*((4j+i) % 8) + 2x + (4j+i)/8
     __syncthreads(); // all waves are done with their K tiles
+    if (MERGE && p.trace) tr_t1 = wall_clock64();
     float *sm_acc = (float *)&lds[0][0];              // [kWaves][rep][D]
     __shared__ float sm_m[kWaves][16], sm_l[kWaves][16];
     if (m16 < hot.rep) {
@@ -503,7 +679,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         if (j == 0) { sm_m[wave][m16] = m_run; sm_l[wave][m16] = l_run; }
     }
     __syncthreads();
-    const int NC = hot.nc;
+    const int NC = hot.nc + (STEP ? 1 : 0); // (a step keeps one more slot per head: step_workgroup's)
     for (int t = threadIdx.x; t < hot.rep * D; t += blockDim.x) {
         const int head = t / D, dim = t % D;
         float M = sm_m[0][head];
@@ -518,8 +694,219 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         }
         typedef __attribute__((address_space(1))) float *gfloat_ptr;
         const size_t slot = ((size_t)b * hot.hq + (size_t)h * hot.rep + head) * NC + c;
-        ((gfloat_ptr)hot.part_acc)[slot * D + dim] = A;
-        if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
+        if constexpr (MERGE) {   // read by another workgroup of this launch
+            store_part<LOC>(hot.part_acc + slot * D + dim, A);
+            if (dim == 0) { store_part<LOC>(hot.part_ml + slot * 2, M); store_part<LOC>(hot.part_ml + slot * 2 + 1, Lsum); }
+        } else {
+            ((gfloat_ptr)hot.part_acc)[slot * D + dim] = A;
+            if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
+        }
+    }
+    if constexpr (MERGE) {
+        if (p.trace) tr_t2 = wall_clock64();
+        const int last = arrive_last<LOC>(p.tickets + (size_t)b * hkv + h, expected);
+        const unsigned long long tr_t3 = p.trace ? wall_clock64() : 0;
+        auto trace_out = [&]() {
+            const size_t wg = LOC ? (size_t)blockIdx.x : ((size_t)b * hkv + h) * hot.nc + c;
+            if (p.trace && threadIdx.x == 0 && wg < (size_t)p.trace_cap) {
+                unsigned long long *t = p.trace + 8 * wg;
+                t[0] = ((unsigned long long)(b * hkv + h) << 32) | (unsigned)c | (last ? 0x80000000u : 0u);
+                t[1] = (unsigned long long)xcc_id();
+                t[2] = tr_t0; t[3] = tr_t1; t[4] = tr_t2; t[5] = tr_t3; t[6] = wall_clock64();
+            }
+        };
+        if (!last) { trace_out(); return; }
+        bool valid = last == 1, bad = last == 2;
+        if (bad && threadIdx.x == 0) atomicOr(p.flag, 4);
+        if constexpr (FUSE == 1) { // the same rule as decode_seq_len, with the host mirror's length where the walk used it
+            const int v_ctx = hot.ctx[b], v_dev = hot.lens_layer[b], v_low = hot.lens_lowest[b];
+            if (v_ctx == 0) valid = false;
+            else if (!valid) {}
+            else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx > p.max_len || v_ctx != v_dev || (v_ctx > prows && v_low != v_ctx) || v_ctx != n) {
+                valid = false; bad = true;
+            }
+        }
+        merge_and_store<D, LOC>(p, hot, b, h, nd_eff, np_eff, FUSE == 2, valid, bad);
+        trace_out();
+    }
+}
+
+// The merge of a (sequence, kv head) pair's partials by the last workgroup to arrive: the same running-max merge as
+// decode_combine_kernel (the paper's gate, Eq. 4, applied to unnormalised sums), one wave per query head, the lanes of
+// a wave split in 64 / (D / 4) groups that take every other partial and are summed with shuffles at the end.
+// nd, np: distant and proximal pieces that stored a partial; special: a step's extra partial in slot hot.nc, whose
+// normaliser is negative if the step's validation failed.
+template <int D, bool LOC>
+__device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
+                                bool bad)
+{
+    // a lane takes VEC floats of a partial row; the 64 / LPR lane groups of a wave take every NGW-th partial; one pass
+    // with a running maximum, UN partials in flight per lane (one round covers 36 partials per head at D = 128, LOC)
+    constexpr int VEC = LOC ? 4 : 2, LPR = D / VEC, NGW = 64 / LPR, UN = 18;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, x = lane % LPR, g = lane / LPR;
+    const int nv = nd + np + (special ? 1 : 0);
+    const size_t stride = (size_t)hot.nc + (special ? 1 : 0);
+    auto chunk_slot = [&](int v) { return v < nd ? v : (v < nd + np ? hot.max_nd + (v - nd) : hot.nc); };
+    if (special) {
+        const float2 mark = load_ml<LOC>(hot.part_ml + (((size_t)b * hot.hq + (size_t)h * hot.rep) * stride + hot.nc) * 2);
+        if (mark.y < 0.f) { valid = false; bad = true; }
+    }
+    for (int r = wave; r < hot.rep; r += kWaves) {
+        const int head = h * hot.rep + r;
+        const float *ml = hot.part_ml + ((size_t)b * hot.hq + head) * stride * 2;
+        const float *pa = hot.part_acc + ((size_t)b * hot.hq + head) * stride * D + VEC * x;
+        float m_run = kNegBig, L = 0.f, a[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] = 0.f;
+        for (int v0 = g; v0 < nv; v0 += NGW * UN) {
+            float2 mk[UN];
+            float ak[UN][VEC];
+#pragma unroll
+            for (int k = 0; k < UN; ++k) {
+                const int v = v0 + k * NGW;
+                const int cs = chunk_slot(v < nv ? v : v0);
+                mk[k] = load_ml<LOC>(ml + cs * 2);
+                load_part<LOC, VEC>(pa + (size_t)cs * D, ak[k]);
+                if (v >= nv) mk[k] = make_float2(kNegBig, 0.f);   // (weight exp2(-big) = 0 for whatever was loaded)
+            }
+            float mb = mk[0].x;
+#pragma unroll
+            for (int k = 1; k < UN; ++k) mb = fmaxf(mb, mk[k].x);
+            const float m_new = fmaxf(m_run, mb);
+            const float alpha = exp2f(m_run - m_new);
+            L *= alpha;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) a[e] *= alpha;
+#pragma unroll
+            for (int k = 0; k < UN; ++k) {
+                const float f = (v0 + k * NGW < nv) ? exp2f(mk[k].x - m_new) : 0.f;
+                L += f * mk[k].y;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) a[e] += f * ak[k][e];
+            }
+            m_run = m_new;
+        }
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {   // the lane groups of the wave, each with its own maximum
+            const float m2 = __shfl_xor(m_run, off), L2 = __shfl_xor(L, off);
+            const float m_new = fmaxf(m_run, m2);
+            const float f1 = exp2f(m_run - m_new), f2 = exp2f(m2 - m_new);
+            L = f1 * L + f2 * L2;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) a[e] = f1 * a[e] + f2 * __shfl_xor(a[e], off);
+            m_run = m_new;
+        }
+        if (g == 0) {
+            unsigned res[VEC / 2];
+#pragma unroll
+            for (int e = 0; e < VEC / 2; ++e) res[e] = 0u;
+            if (valid) {
+                const float inv = 1.f / L;
+#pragma unroll
+                for (int e = 0; e < VEC / 2; ++e) res[e] = pack_bf16(a[2 * e] * inv, a[2 * e + 1] * inv);
+            }
+            unsigned *dst = (unsigned *)(p.out + ((size_t)b * hot.hq + head) * D) + (VEC / 2) * x;
+#pragma unroll
+            for (int e = 0; e < VEC / 2; ++e) dst[e] = res[e];
+        }
+    }
+    if (bad && threadIdx.x == 0) atomicOr(p.flag, 2);
+}
+
+__device__ inline float dot8_bf16(u32x4 a, u32x4 b)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        s = fmaf(__uint_as_float(a[w] << 16), __uint_as_float(b[w] << 16), s);
+        s = fmaf(__uint_as_float(a[w] & 0xffff0000u), __uint_as_float(b[w] & 0xffff0000u), s);
+    }
+    return s;
+}
+
+// A decode step's extra work for one (sequence, kv head) pair, done by the workgroup of the pair's first proximal piece
+// before it turns to that piece: the new token at position pos and, once the
+// window is full, the token at pos - W that it displaces (derived from the index ranges of Eq. 3: that token turns
+// distant).  It (1) checks the position against the stored length, (2) stores a partial over these two tokens - the
+// new one proximal, with the layer's own query and the new key; the displaced one distant, with the key the block's
+// lowest layer holds for it and that layer's query - taking the displaced token's value and (at a lowest layer) key
+// from the ring slot before (3) it overwrites that slot with the new rows and moves the old ones to the distant
+// stores, exactly as the append kernel does.  Nobody else in the launch reads or writes those rows' results: the other
+// workgroups walk the rows held before the call and leave the ring slot out.  (4) The last of a sequence's kv heads
+// to finish advances the stored length; (5) the partial (in the slot behind the pieces' slots) takes part in the merge
+// like any other.
+template <int D, bool LOC>
+__device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg)
+{
+    constexpr int CPR = D / 8;
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+    typedef __attribute__((address_space(1))) u32x4 *gvec_w;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int prows = hot.prows;
+    const int v_pos = p.positions[b], v_dev = hot.lens_layer[b], v_low = hot.lens_lowest[b];
+    const bool demote = pos >= prows;           // the ring is full: its slot holds position pos - W
+    bool ok = v_pos == pos && v_dev == pos && pos < p.maxctx && pos < p.max_len;
+    if (demote && !p.low_is_self && v_low != pos + 1) ok = false;   // the block's lowest layer took this token first
+    const int slot = pos < p.sink ? pos : p.sink + (pos - p.sink) % p.window;
+    const size_t pair = (size_t)b * hot.hkv + h;
+    const bool low_head = head_arg < 0;
+    const size_t t = demote ? (size_t)(pos - prows) : 0;   // distant row of position pos - W
+    const gvec_w proxK = (gvec_w)(hot.kprox + (pair * prows + slot) * CPR), proxV = (gvec_w)(hot.vprox + (pair * prows + slot) * CPR);
+    const gvec_w dV = (gvec_w)(hot.vdist + (pair * hot.cd + t) * CPR);
+    const gvec_w dK = (gvec_w)(hot.kdist + (((size_t)(head_arg & 0x7fffffff) + b) * hot.cd + t) * CPR);
+    const int i = lane < CPR ? lane : 0;        // this lane's 16-byte piece of a row
+    const u32x4 kn = ((gvec_ptr)p.k_new)[pair * CPR + i], vn = ((gvec_ptr)p.v_new)[pair * CPR + i];
+    u32x4 ko = {0u, 0u, 0u, 0u}, vo = ko, kd = ko;
+    if (demote) {
+        ko = proxK[i];
+        vo = proxV[i];
+        kd = low_head ? ko : dK[i];
+    }
+    const pod_bf16 *qd_src = (hot.q_shared && !low_head) ? hot.q_shared : hot.q;
+    const size_t stride = (size_t)hot.nc + 1;
+    for (int r = wave; r < hot.rep; r += kWaves) {
+        const size_t head = (size_t)b * hot.hq + (size_t)h * hot.rep + r;
+        const u32x4 qn = ((gvec_ptr)(hot.q + head * D))[i], qd = ((gvec_ptr)(qd_src + head * D))[i];
+        float sn = lane < CPR ? dot8_bf16(qn, kn) : 0.f, sd = (lane < CPR && demote) ? dot8_bf16(qd, kd) : 0.f;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) { sn += __shfl_xor(sn, off); sd += __shfl_xor(sd, off); }
+        sn *= hot.scale_log2e;
+        sd = demote ? sd * hot.scale_log2e : kNegBig;
+        const float m = fmaxf(sn, sd);
+        const float pn = exp2f(sn - m), pd = demote ? exp2f(sd - m) : 0.f;
+        const size_t ps = head * stride + hot.nc;
+        if (lane < CPR) {
+            float *dst = hot.part_acc + ps * D + 8 * lane;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                store_part<LOC>(dst + 2 * w, pn * __uint_as_float(vn[w] << 16) + pd * __uint_as_float(vo[w] << 16));
+                store_part<LOC>(dst + 2 * w + 1, pn * __uint_as_float(vn[w] & 0xffff0000u) + pd * __uint_as_float(vo[w] & 0xffff0000u));
+            }
+        }
+        if (lane == 0) {
+            store_part<LOC>(hot.part_ml + ps * 2, m);
+            store_part<LOC>(hot.part_ml + ps * 2 + 1, ok ? pn + pd : -1.f);
+        }
+    }
+    __syncthreads(); // every wave holds the old rows it needs
+    if (ok && wave == 0 && lane < CPR) {
+        if (demote) {
+            dV[lane] = vo;
+            if (low_head) dK[lane] = ko;
+        }
+        proxK[lane] = kn;
+        proxV[lane] = vn;
+    }
+    // every kv head's workgroup has compared the position with the stored length before the length moves
+    // (a sequence's kv heads run on different XCDs; nothing but the count travels through this counter, and nobody
+    // waits for it; by this barrier every wave has used the stored length it loaded)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(p.step_done + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == hot.hkv - 1) {
+            __hip_atomic_store(p.step_done + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (ok) p.lens_w[b] = pos + 1;
+        }
     }
 }
 
@@ -544,22 +931,34 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     const int head = blockIdx.x, b = blockIdx.y;
     const decode_hot hot = load_hot_args();
     const int n_host = load_hlen_arg(b);
+    const bool step = p.step != 0;   // the partials of a decode step: the pieces of the rows held before the new token
+                                     // plus the step's own partial in slot hot.nc, whose normaliser says whether the step was valid
     bool bad = false;
     int n = n_host;
-    if (!hot.use_hlen) n = decode_seq_len(p, b, &bad);
+    if (!hot.use_hlen) {
+        if (step) {
+            n = p.positions[b];
+            if (n < 0 || n >= p.maxctx || n >= p.max_len) { bad = true; n = -1; }
+        } else {
+            n = decode_seq_len(p, b, &bad);
+        }
+    }
     // validation inputs (independent loads, consumed at the very end)
-    const int v_ctx = ((gint_ptr)hot.ctx)[b], v_dev = ((gint_ptr)hot.lens_layer)[b], v_low = ((gint_ptr)hot.lens_lowest)[b];
+    int v_ctx = 0, v_dev = 0, v_low = 0;
+    if (!step) { v_ctx = ((gint_ptr)hot.ctx)[b]; v_dev = ((gint_ptr)hot.lens_layer)[b]; v_low = ((gint_ptr)hot.lens_lowest)[b]; }
 
-    const int n_prox = n < hot.prows ? n : hot.prows;
-    const int n_dist = n - n_prox;
+    const int nn = n > 0 ? n : 0;
+    const int n_prox = nn < hot.prows ? nn : hot.prows;
+    const int n_dist = nn - n_prox;
     const int chunk_d = hot.chunk & 0xffff, chunk_p = (int)((unsigned)hot.chunk >> 16);
-    const int nd = (n_dist + chunk_d - 1) / chunk_d;
-    const int np = (n_prox + chunk_p - 1) / chunk_p;
-    const int NC = hot.nc;
-    const int nvalid = n > 0 ? nd + np : 0;
+    const int nd = min((n_dist + chunk_d - 1) / chunk_d, hot.max_nd);
+    const int np = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - hot.max_nd);
+    const int NC = hot.nc + (step ? 1 : 0);
+    const int nvalid = step ? (n >= 0 ? nd + np + 1 : 0) : (n > 0 ? nd + np : 0);
     const gfloat_ptr ml = (gfloat_ptr)hot.part_ml + ((size_t)b * hot.hq + head) * NC * 2;
     const gf4_ptr pa = (gf4_ptr)hot.part_acc + ((size_t)b * hot.hq + head) * NC * ROW + xs;
-    auto chunk_slot = [&](int v) { return v < nd ? v : hot.max_nd + (v - nd); };
+    auto chunk_slot = [&](int v) { return v < nd ? v : (v < nd + np ? hot.max_nd + (v - nd) : hot.nc); };
+    if (step && n >= 0 && ml[hot.nc * 2 + 1] < 0.f) { bad = true; n = -1; }   // the step's own validation failed
 
     const int g = threadIdx.x / LPR, x = threadIdx.x % LPR;
     const int head_arg = load_head_arg(head / hot.rep);
@@ -622,7 +1021,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
         L += f * sl[k];
     }
     // validation: the same rule as decode_seq_len, on the values loaded at the top
-    if (hot.use_hlen) {
+    if (hot.use_hlen && !step) {
         if (v_ctx == 0) n = 0;
         else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx > p.max_len || v_ctx != v_dev || (v_ctx > hot.prows && v_low != v_ctx) || v_ctx != n_host) {
             bad = true;
@@ -635,7 +1034,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
             p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e)) { bad = true; n = 0; }
     }
     uint2 res = make_uint2(0u, 0u);
-    if (n > 0) {
+    if (step ? n >= 0 : n > 0) {
         const float inv = 1.f / L;
         res.x = pack_bf16(o.x * inv, o.y * inv);
         res.y = pack_bf16(o.z * inv, o.w * inv);
@@ -663,6 +1062,88 @@ constexpr int kMaxDevices = 64;
 void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on device i (NULL: not looked up yet)
 std::mutex g_scratch_mutex;
 } // namespace
+
+// Measurement aid: the plainest kernel that reads `bytes` once: one resident round of workgroups (2 per CU), each
+// walking its own contiguous part with 8 x 16 bytes in flight per thread, results folded into a word nobody stores.
+// What it reaches on cold memory is the ceiling a streaming launch of that size can be held to on this device.
+__device__ unsigned pod_stream_read_sink; // (external linkage: a store the compiler cannot prove dead)
+namespace {
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restrict__ src, size_t n16, size_t per_wg)
+{
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+    const size_t lo = (size_t)blockIdx.x * per_wg, hi = lo + per_wg < n16 ? lo + per_wg : n16;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (size_t i = lo + threadIdx.x; i < hi; i += 8 * 256) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = i + (size_t)u * 256 < hi ? ((gvec_ptr)src)[i + (size_t)u * 256] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    if ((acc.x ^ acc.y) == 0x9e3779b9u && (acc.z ^ acc.w) == 0x7f4a7c15u) pod_stream_read_sink = acc.x; // practically never
+}
+} // namespace
+
+int pod_launch_stream_read(pod_cache *c, const void *buf, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    int dev = 0, cus = 256;
+    POD_HIP_TRY(hipGetDevice(&dev));
+    POD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    size_t grid = (size_t)2 * cus;
+    size_t per_wg = (n16 + grid - 1) / grid;
+    per_wg = (per_wg + 255) / 256 * 256;
+    grid = (n16 + per_wg - 1) / per_wg;
+    const bool prof = c && c->prof_ev && c->prof_n < c->prof_cap;   // timed like the decode kernel's launches
+    if (prof) POD_HIP_TRY(hipEventRecord(c->prof_ev[2 * c->prof_n], st));
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)grid), dim3(256), 0, st, (const u32x4 *)buf, n16, per_wg);
+    if (prof) { POD_HIP_TRY(hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st)); c->prof_n += 1; }
+    POD_HIP_TRY(hipGetLastError());
+    return POD_OK;
+}
+
+namespace {
+__global__ void xcc_probe_kernel(int32_t *out) { if (threadIdx.x == 0) out[blockIdx.x] = xcc_id(); }
+struct xcd_map { bool probed; int nxcd; };
+xcd_map g_xcd[kMaxDevices];
+} // namespace
+
+// Over how many XCDs does a one-dimensional launch spread its workgroups round-robin?  Probed once per device with a
+// launch of 256 workgroups that record their XCC_ID: k = number of distinct ids, accepted if workgroup w reports the
+// same id as workgroup w mod k and the first k ids are all different.  *nxcd = k, or 0 (no such pattern: the
+// XCD-local hand-off is not used).  Which XCD a position lands on may differ from launch to launch; only the modulus
+// is taken from here, and every launch checks its own placement.
+int pod_probe_xcds(int *nxcd)
+{
+    int dev = -1;
+    POD_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return pod_fail(POD_ERR_INVALID_ARG, "device %d outside [0, %d)", dev, kMaxDevices);
+    void *buf = nullptr;
+    size_t bytes = 0;
+    int rc = pod_decode_static_scratch(&buf, &bytes);
+    if (rc) return rc;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    xcd_map &m = g_xcd[dev];
+    if (!m.probed) {
+        constexpr int kProbe = 256;
+        int32_t ids[kProbe];
+        hipLaunchKernelGGL(xcc_probe_kernel, dim3(kProbe), dim3(64), 0, 0, (int32_t *)buf);
+        POD_HIP_TRY(hipGetLastError());
+        POD_HIP_TRY(hipMemcpy(ids, buf, sizeof ids, hipMemcpyDeviceToHost));   // (waits for the probe)
+        int k = 0;
+        bool seen[16] = {};
+        for (int w = 0; w < kProbe; ++w)
+            if (ids[w] >= 0 && ids[w] < 16 && !seen[ids[w]]) { seen[ids[w]] = true; ++k; }
+        bool ok = k >= 1 && k <= 16;
+        for (int w = 0; ok && w < kProbe; ++w) ok = ids[w] >= 0 && ids[w] < 16 && ids[w] == ids[w % k];
+        for (int x = 0; ok && x < k; ++x)
+            for (int y = 0; y < x; ++y) ok = ok && ids[x] != ids[y];
+        m.nxcd = ok ? k : 0;
+        m.probed = true;
+    }
+    *nxcd = m.nxcd;
+    return POD_OK;
+}
 
 int pod_decode_static_scratch(void **ptr, size_t *bytes)
 {
@@ -701,7 +1182,7 @@ size_t pod_score_header_bytes(const pod_layout &ly)
 
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared, const int32_t *ctx, int B,
                       int max_len, float scale, void *ws, size_t ws_bytes, void *scores, float tau, void *out,
-                      hipStream_t st)
+                      hipStream_t st, const pod_step_args *step)
 {
     const pod_layout &ly = c->ly;
     const size_t row16 = (size_t)ly.D / 8; // u32x4 per row
@@ -739,7 +1220,22 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.tau = tau;
     p.scores = scores ? (float *)((char *)scores + pod_score_header_bytes(ly)) : nullptr;
     p.score_stride = (int32_t)pod_score_stride(ly);
-    p.hot.use_hlen = B <= kMaxHostLens;
+    p.tickets = (unsigned long long *)(c->base + ly.off_tickets);
+    p.step_done = (int32_t *)(c->base + ly.off_stepdone);
+    p.k_new = step ? (const u32x4 *)step->k_new : nullptr;
+    p.v_new = step ? (const u32x4 *)step->v_new : nullptr;
+    p.positions = step ? step->positions : nullptr;
+    p.lens_w = (int32_t *)(c->base + ly.off_lens) + (size_t)layer * ly.B;
+    p.low_is_self = lowest == layer;
+    p.sink = ly.S; p.window = ly.W;
+    p.trace = (unsigned long long *)c->trace; p.trace_cap = c->trace_cap;
+    // 0: separate combine kernel; 1: the last workgroup of a (sequence, kv head) pair merges; 2: 1 + the cache update
+    p.step = step ? 1 : 0;
+    // XCD-local hand-off: only where the pairs spread evenly over the XCDs (else some XCDs would sit idle)
+    const int npairs = B * ly.Hkv;
+    p.nxcd = c->nxcd > 0 ? c->nxcd : 1;
+    p.npairs = npairs;
+    p.hot.use_hlen = B <= kMaxHostLens && !c->device_lengths;
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
 
@@ -767,7 +1263,7 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     const int max_dist = max_len - max_prox;
     p.hot.max_nd = chunk_slots(max_dist, (int)chunk);
     p.hot.nc = p.hot.max_nd + chunk_slots(max_prox, (int)chunk_p);
-    const size_t NC = (size_t)p.hot.nc;
+    const size_t NC = (size_t)p.hot.nc + (step ? 1 : 0); // partial slots per query head (a step keeps one more)
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
     if (acc_bytes + ml_bytes > ws_bytes)
@@ -776,19 +1272,39 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.hot.part_acc = (float *)ws;
     p.hot.part_ml = (float *)((char *)ws + acc_bytes);
 
-    const dim3 grid((unsigned)NC, (unsigned)ly.Hkv, (unsigned)B);
+    const size_t WGS = (size_t)p.hot.nc;   // workgroups per (sequence, kv head) pair
+    p.slots = (int32_t)WGS;
+    // Merge inside the streaming kernel only where the launch is about one resident round of workgroups (2 per CU):
+    // a workgroup waits for its arrival to be counted before it leaves, and in a launch of several rounds that wait
+    // keeps the next workgroup from starting (measured: 4 sequences of 128K tokens 13.1 ms per step against 12.0 ms
+    // with the separate merge kernel).  0: separate combine kernel; 1: the last workgroup of a (sequence, kv head)
+    // pair merges; 2: 1 + the cache update; 3: the cache update, separate combine kernel.
+    int cus = 256;
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
+    const bool one_round = WGS * (size_t)npairs <= (size_t)cus * 5 / 2;
+    const bool merge_inside = !scores && c->fused_merge && one_round;
+    const int fuse = step ? (merge_inside ? 2 : 3) : (merge_inside ? 1 : 0);
+    const bool loc = merge_inside && c->xcd_local && c->nxcd >= 1 && (npairs % c->nxcd == 0 || npairs >= 8 * c->nxcd);
+    const size_t loc_wgs = (size_t)((npairs + p.nxcd - 1) / p.nxcd) * p.nxcd * WGS;
+    if (loc && loc_wgs > 0x7fffffffu) return pod_fail(POD_ERR_CAPACITY, "launch too large");
+    const dim3 grid = loc ? dim3((unsigned)loc_wgs) : dim3((unsigned)WGS, (unsigned)ly.Hkv, (unsigned)B);
     const dim3 cgrid((unsigned)ly.Hq, (unsigned)B);
     pod_cache *mc = const_cast<pod_cache *>(c);
     const bool prof = mc->prof_ev && mc->prof_n < mc->prof_cap;
     if (prof) POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n], st));
 #define POD_LAUNCH_PARTIAL(DD, MM, GRID) hipLaunchKernelGGL((decode_partial_kernel<DD, MM>), GRID, dim3(kWaves * 64), 0, st, p)
     // gated upper layer: proximal chunks first, then the distant chunks, whose workgroups read the proximal partials
-    const dim3 grid_p((unsigned)(NC - p.hot.max_nd), (unsigned)ly.Hkv, (unsigned)B);
+    const dim3 grid_p((unsigned)(WGS - p.hot.max_nd), (unsigned)ly.Hkv, (unsigned)B);
     const dim3 grid_d((unsigned)(p.hot.max_nd > 0 ? p.hot.max_nd : 1), (unsigned)ly.Hkv, (unsigned)B);
     // score reuse: the writing launch for the kv heads whose block starts at this layer, the reading launch(es) for
     // the others (workgroups of the other kind leave at once); a gated read is two launches, proximal chunks first
 #define POD_LAUNCH_ALL(DD)                                                                   \
-    if (p.mode == 0) POD_LAUNCH_PARTIAL(DD, 0, grid);                                        \
+    if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(kWaves * 64), 0, st, p);       \
+    else if (fuse == 1 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1, true>), grid, dim3(kWaves * 64), 0, st, p);  \
+    else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2>), grid, dim3(kWaves * 64), 0, st, p);               \
+    else if (fuse == 3) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 3>), grid, dim3(kWaves * 64), 0, st, p);               \
+    else if (fuse == 1) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1>), grid, dim3(kWaves * 64), 0, st, p);               \
+    else if (p.mode == 0) POD_LAUNCH_PARTIAL(DD, 0, grid);                                   \
     else {                                                                                   \
         if (lowest_any) POD_LAUNCH_PARTIAL(DD, 1, grid);                                     \
         if (!lowest_all && p.mode == 2) POD_LAUNCH_PARTIAL(DD, 2, grid);                     \
@@ -801,10 +1317,12 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 #undef POD_LAUNCH_ALL
 #undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }
-    if (ly.D == 128)
-        hipLaunchKernelGGL((decode_combine_kernel<128, 256, 8, 64>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL((decode_combine_kernel<64, 256, 8, 32>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
+    if (fuse == 0 || fuse == 3) {
+        if (ly.D == 128)
+            hipLaunchKernelGGL((decode_combine_kernel<128, 256, 8, 64>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((decode_combine_kernel<64, 256, 8, 32>), dim3(cgrid.x, cgrid.y, 2), dim3(256), 0, st, p);
+    }
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }

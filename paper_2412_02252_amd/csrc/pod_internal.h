@@ -10,7 +10,7 @@
 // ---------------------------------------------------------------------------
 // Device-memory layout of one cache.
 //
-// header   : int32 lens[L][B] (tokens held per layer and slot), int32 flag
+// header   : int32 lens[L][B] (tokens held per layer and slot), int32 flag, arrival counters of the decode kernels
 // proxK/V  : [L][B][Hkv][P][D]   P = S + W slots per (layer, slot, kv head):
 //            slots [0,S) are the sink tokens, slot S + (p - S) % W is the ring
 //            slot of position p >= S.  While fewer than W tokens >= S exist
@@ -31,6 +31,7 @@ struct pod_layout {
     int32_t Cd;  // distant rows per (layer, slot, head)
     int32_t rep; // Hq / Hkv
     int32_t nslots; // distant-key stores: (kv head, block) pairs
+    size_t off_tickets, off_stepdone; // uint64 [B][Hkv] and int32 [B]: arrival counters of the fused decode kernels (zero between launches)
     size_t off_lens, off_flag, off_proxK, off_proxV, off_distV, off_distK, total_bytes;
 };
 
@@ -71,12 +72,18 @@ struct pod_cache {
     // tuning overrides read once from the environment in pod_cache_init (0 = none): tokens per split-K piece of the
     // distant / proximal region (POD_DECODE_CHUNK, POD_DECODE_CHUNK_PROX)
     int tune_chunk, tune_chunk_prox;
+    bool fused_merge;      // plain decode merges its partials inside the streaming kernel (POD_DECODE_FUSED=0: separate kernel)
+    bool xcd_local;        // hand partials over inside one XCD's L2 where the launch shape allows (POD_DECODE_XCD_LOCAL=0: never)
+    int nxcd;              // XCDs a one-dimensional launch is spread over round-robin (0: no such pattern seen by the probe)
+    bool device_lengths;   // kernels take sequence lengths from the calls' device arrays only (pod_cache_set_length_source)
     // the library's own split-K scratch on `device` (pod_decode_attention_static): device address and size
     void *static_scratch;
     size_t static_scratch_bytes;
     // optional event pairs around the decode partial kernel (pod_profile_*)
     hipEvent_t *prof_ev; // [2 * prof_cap]
     int prof_cap, prof_n;
+    void *trace;   // device buffer for per-workgroup clock records of the fused decode launches (pod_profile_set_trace)
+    int trace_cap; // workgroups it holds (8 x 8 bytes each)
 };
 
 // error reporting (pod_api.hip)
@@ -109,9 +116,13 @@ int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, vo
                       void *recK, void *recV, void *distK, void *distV, hipStream_t st);
 // scores == NULL: plain decode; else the score-reuse buffer (lowest layer writes, upper layers read).
 // tau >= 0 (needs scores): upper layers leave the distant part out for heads whose gate reaches tau.
+// step != NULL: a decode step (the new token's cache update inside the same launch); ctx is then NULL and the
+// lengths in the host mirror are those before the update.
+struct pod_step_args { const void *k_new, *v_new; const int32_t *positions; };
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
-                      void *scores, float tau, void *out, hipStream_t st);
+                      void *scores, float tau, void *out, hipStream_t st, const pod_step_args *step = nullptr);
+int pod_launch_stream_read(pod_cache *c, const void *buf, size_t bytes, hipStream_t st); // measurement aid: read bytes once, keep nothing
 int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *sim, hipStream_t st);
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
@@ -119,6 +130,7 @@ size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flag
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 // device address and size of the library's own split-K scratch array on the current device (looked up once per device)
 int pod_decode_static_scratch(void **ptr, size_t *bytes);
+int pod_probe_xcds(int *nxcd); // once per device: over how many XCDs one-dimensional launches spread round-robin
 // lowest_mask: bit h set = kv head h takes every logit from (q, k); clear = distant logits from (q_shared, k_shared)
 // k, v, k_shared: rows for positions 0 .. n-1; q, q_shared, out: rows for positions q0 .. n-1
 int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,

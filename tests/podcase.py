@@ -93,6 +93,22 @@ class Case:
             self.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), positions)
         assert B <= self.B
 
+    def step(self, layer, positions, max_context_len=0):
+        """pod_decode_step on the GPU (append + attention in one launch) and the plain append on the oracle's model;
+        returns the GPU output for contexts positions + 1."""
+        k = torch.cat([self.keys(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)]).contiguous()
+        v = torch.cat([self.values(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)]).contiguous()
+        ctx = [p + 1 for p in positions]
+        q = self.decode_queries(layer, ctx, self.dev)
+        qs = self.shared_queries(layer, ctx, self.dev)
+        pos = torch.tensor(positions, dtype=torch.int32, device=self.dev)
+        out = self.gpu.pod_decode_step(layer, k, v, q, qs, pos, self.scale, max_context_len=max_context_len)
+        if self.cpu is not None:
+            kc = torch.cat([self.keys(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            vc = torch.cat([self.values(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            self.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), positions)
+        return out
+
     def decode_queries(self, layer, ctx, device):
         """Query of the token at position ctx[b]-1 of each sequence: [B][Hq][d]."""
         return torch.cat([self.queries(layer, b, 1, device, pos0=max(n, 1) - 1) for b, n in enumerate(ctx)]).contiguous()

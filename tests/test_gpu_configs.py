@@ -68,6 +68,40 @@ def test_config2_llama_decode_64_steps_with_demotion():
         assert g["distV"].shape[0] == n0 + steps - S - W
 
 
+def test_config2_llama_decode_steps_in_one_launch_per_layer():
+    """The same workload through pod_decode_step (cache update + attention in one launch per layer), 24 steps, every
+    output compared, the stores bit for bit at the end."""
+    L, G, Hq, Hkv, d, S, W, n0, steps = 2, 2, 32, 8, 128, 64, 2048, 32768, 24
+    seed = SEED0 + 2
+    max_ctx = n0 + steps
+    rope = dict(rope_base=500000.0, rope_max_pos=max_ctx)
+    cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, 1, max_ctx), DEV)
+    oc = po.Cache(L, G, Hkv, d, S, W, 1, max_ctx)
+    scale = 1.0 / math.sqrt(d)
+    K = [gen.keys_bf16(seed, l, 0, max_ctx, Hkv, d, device=DEV, **rope) for l in range(L)]
+    V = [gen.values_bf16(seed, l, 0, max_ctx, Hkv, d, device=DEV) for l in range(L)]
+    Q = [gen.queries_bf16(seed, l, 0, steps, Hq, d, device=DEV, pos0=n0) for l in range(L)]
+    Kh, Vh, Qh = [host_bits(t) for t in K], [host_bits(t) for t in V], [host_bits(t) for t in Q]
+    for l in range(L):
+        cache.pod_cache_fill(l, 0, K[l][:n0].contiguous(), V[l][:n0].contiguous())
+        oc.fill(l, 0, Kh[l][:n0], Vh[l][:n0])
+    assert cache.pod_cache_launch_info()["xcds"] >= 1
+    for s in range(steps):
+        p = n0 + s
+        pos = torch.tensor([p], dtype=torch.int32, device=DEV)
+        for l in range(L):
+            out = cache.pod_decode_step(l, K[l][p:p + 1].contiguous(), V[l][p:p + 1].contiguous(), Q[l][s:s + 1].contiguous(),
+                                        Q[0][s:s + 1].contiguous() if l else None, pos, scale, max_context_len=p + 1)
+            oc.append(l, Kh[l][p:p + 1], Vh[l][p:p + 1], [p])
+            ref = oc.decode_attention(l, Qh[l][s:s + 1], Qh[0][s:s + 1] if l else None, [p + 1], scale)
+            assert_close(out, ref, f"step {s} layer {l}")
+    cache.pod_cache_check()
+    for l in range(L):
+        g, c = cache.pod_cache_export_logical(l, 0), oc.export(l, 0)
+        for name in c:
+            assert np.array_equal(host_bits(g[name]), c[name]), (l, name)
+
+
 def test_config2_shape_with_score_reuse():
     """Config-2 shape, 8 decode steps through the score-reuse entry point, every output compared."""
     L, G, Hq, Hkv, d, S, W, n0, steps = 2, 2, 32, 8, 128, 64, 2048, 32768, 8
@@ -100,7 +134,7 @@ def test_config2_shape_with_score_reuse():
 
 
 # ----------------------------------------------------------------------------- configs 3 and 5
-def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0):
+def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0, one_launch=False):
     Hq, Hkv, d = 32, 8, 128
     rep = Hq // Hkv
     max_ctx = max(lens) + 1
@@ -125,9 +159,12 @@ def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0):
     for l in range(L):           # one decode step across all layers
         kn = torch.cat([keys(l, b, 1, pos0=lens[b]) for b in range(B)]).contiguous()
         vn = torch.cat([values(l, b, 1, pos0=lens[b]) for b in range(B)]).contiguous()
-        cache.pod_cache_append(l, kn, vn, pos)
         qs[l] = torch.cat([gen.queries_bf16(seed, l, b, 1, Hq, d, device=DEV, pos0=lens[b]) for b in range(B)]).contiguous()
         low = l - l % G
+        if one_launch:           # cache update + attention through pod_decode_step
+            outs[l] = cache.pod_decode_step(l, kn, vn, qs[l], qs[low] if low != l else None, pos, scale, max_context_len=max_ctx)
+            continue
+        cache.pod_cache_append(l, kn, vn, pos)
         outs[l] = cache.pod_decode_attention(l, qs[l], qs[low] if low != l else None, ctx, scale, max_context_len=max_ctx)
     cache.pod_cache_check()
     torch.cuda.synchronize()
@@ -145,22 +182,24 @@ def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0):
     return cache, outs
 
 
-def test_config3_batched_ragged_decode_32_layers():
+@pytest.mark.parametrize("one_launch", [False, True], ids=["append+decode", "decode_step"])
+def test_config3_batched_ragged_decode_32_layers(one_launch):
     """32 layers in 16 blocks (G=2), B=16, contexts uniform in [4096, 32768], one decode step over all layers."""
     seed = SEED0 + 3
     lens = [n - 1 for n in gen.ragged_lengths(seed, 16, 4096, 32768)]   # cache holds n-1, the step appends one
     order = np.argsort(lens)
     picks = [int(order[0]), int(order[-1]), int(order[7]), int(order[12])]
     samples = [(l, b, (l * 5 + b * 3) % 8) for l in (0, 1, 14, 15, 30, 31) for b in picks]
-    _big_decode(32, 2, 16, lens, 64, 2048, seed, samples)
+    _big_decode(32, 2, 16, lens, 64, 2048, seed, samples, one_launch=one_launch)
 
 
-def test_config5_long_context_g4_with_outlier_keys():
+@pytest.mark.parametrize("one_launch", [False, True], ids=["append+decode", "decode_step"])
+def test_config5_long_context_g4_with_outlier_keys(one_launch):
     """G=4 (8 blocks over 32 layers), B=4, context 131072, S=128, W=4096, 1 % of distant keys scaled x8."""
     seed = SEED0 + 5
     lens = [131071] * 4
     samples = [(0, 0, 1), (1, 0, 6), (3, 3, 2), (28, 2, 0), (31, 3, 7), (14, 1, 4)]
-    cache, _ = _big_decode(32, 4, 4, lens, 128, 4096, seed, samples, outlier_rate=0.01)
+    cache, _ = _big_decode(32, 4, 4, lens, 128, 4096, seed, samples, outlier_rate=0.01, one_launch=one_launch)
     live, dense = pod.pod_cache_live_bytes(cache.cfg, 131072)
     assert abs((1 - live / dense) - 0.363) < 5e-4       # memory accounting at this configuration
 

@@ -129,3 +129,72 @@ def test_chunked_prefill_in_a_graph_equals_eager_on_every_replay():
         c.gpu.pod_cache_check()
         c.gpu.pod_cache_reset(-1)          # eager work between replays: empty again, as at capture
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("variant", ["step", "append+decode"])
+def test_one_captured_step_graph_serves_successive_tokens(variant):
+    """Lengths from device arrays only (pod_cache_set_length_source(1)): ONE captured step (both layers of a block, two
+    ragged sequences) is replayed for 8 successive tokens; between replays only device memory changes (positions,
+    context lengths, the new token's k, v and the queries are copied into the buffers the graph reads).  Every replay is
+    compared with the oracle's append + attention, the stores at the end bit for bit."""
+    S, W = 8, 64
+    n0 = [S + W - 3, 700]            # the first sequence crosses S + W during the replays
+    c = Case(2, 2, 8, 2, 128, S, W, 2, 900, seed=902)
+    for layer in range(2):
+        for b, n in enumerate(n0):
+            c.fill(layer, b, n)
+    c.gpu.pod_cache_set_length_source(1)
+    pos = torch.tensor(n0, dtype=torch.int32, device=c.dev)
+    ctx = torch.tensor([n + 1 for n in n0], dtype=torch.int32, device=c.dev)
+    k = [torch.zeros((2, 2, 128), dtype=torch.bfloat16, device=c.dev) for _ in range(2)]
+    v = [torch.zeros_like(k[0]) for _ in range(2)]
+    q = [torch.zeros((2, 8, 128), dtype=torch.bfloat16, device=c.dev) for _ in range(2)]
+    out = [torch.zeros_like(q[0]) for _ in range(2)]
+    bound = max(n0) + 8              # the launch is sized for the longest context any replay will see
+
+    def load_inputs(s):
+        p = [n + s for n in n0]
+        pos.copy_(torch.tensor(p, dtype=torch.int32, device=c.dev))
+        ctx.copy_(torch.tensor([x + 1 for x in p], dtype=torch.int32, device=c.dev))
+        for layer in range(2):
+            k[layer].copy_(torch.cat([c.keys(layer, b, 1, c.dev, pos0=x) for b, x in enumerate(p)]))
+            v[layer].copy_(torch.cat([c.values(layer, b, 1, c.dev, pos0=x) for b, x in enumerate(p)]))
+            q[layer].copy_(c.decode_queries(layer, [x + 1 for x in p], c.dev))
+        return p
+
+    def one_step():
+        for layer in range(2):
+            if variant == "step":
+                c.gpu.pod_decode_step(layer, k[layer], v[layer], q[layer], q[0] if layer else None, pos, c.scale,
+                                      out=out[layer], max_context_len=bound)
+            else:
+                c.gpu.pod_cache_append(layer, k[layer], v[layer], pos)
+        if variant != "step":
+            for layer in range(2):
+                c.gpu.pod_decode_attention(layer, q[layer], q[0] if layer else None, ctx, c.scale, out=out[layer],
+                                           max_context_len=bound)
+
+    load_inputs(0)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        one_step()
+    for s in range(8):
+        p = load_inputs(s)
+        for o in out:
+            o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for layer in range(2):
+            kc = torch.cat([c.keys(layer, b, 1, "cpu", pos0=x) for b, x in enumerate(p)])
+            vc = torch.cat([c.values(layer, b, 1, "cpu", pos0=x) for b, x in enumerate(p)])
+            c.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), p)
+        for layer in range(2):
+            assert_close(out[layer], c.decode_ref(layer, [x + 1 for x in p]), f"{variant} replay {s} layer {layer}")
+    c.gpu.pod_cache_check()
+    c.gpu.pod_cache_sync_lengths()
+    c.gpu.pod_cache_set_length_source(0)
+    for layer in range(2):
+        for b in range(2):
+            assert c.gpu.pod_cache_seq_len(layer, b) == n0[b] + 8
+            c.assert_cache_equal(layer, b)
