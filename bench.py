@@ -571,6 +571,31 @@ def main():
                               "tflops": round(G * flops / tot / 1e12, 2),
                               "vs_one_call": round((res["lowest_layer"]["ms"] + res["upper_layer"]["ms"]) / (tot * 1e3), 3)}
             del ws
+        # what the matrix pipes can do at all when every MFMA takes an operand fragment out of LDS (synthetic loops at the
+        # kernel's occupancy; 32 cycles per MFMA and SIMD = never idle)
+        feed = {}
+        scratch = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+        it_feed = 20000
+        for variant, name in ((0, "mfma_only"), (1, "one_lds_fragment_per_mfma"), (2, "one_lds_fragment_per_mfma_plus_softmax_valu"),
+                              (3, "one_lds_fragment_per_two_mfma_plus_softmax_valu")):
+            pod.pod_profile_mfma_feed(variant, 2000, scratch)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pod.pod_profile_mfma_feed(variant, it_feed, scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            per_simd = it_feed * 16 * (2 if variant == 3 else 1)
+            feed[name] = {"ns_per_mfma_per_simd": round(e0.elapsed_time(e1) * 1e6 / per_simd, 2)}
+        base_ns = feed["mfma_only"]["ns_per_mfma_per_simd"]
+        for v in feed.values():
+            v["pipe_busy"] = round(base_ns / v["ns_per_mfma_per_simd"], 3)
+        # the kernel: MFMAs it issues per SIMD (causal pairs, both products: 2 * 2 * d * pairs flops / 32768 flops per MFMA)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        k_ns = res["lowest_layer"]["ms"] * 1e6 / (flops / 32768.0 / (4 * cus))
+        res["mfma_feed"] = {"what": "synthetic loops, two waves per SIMD: what LDS-fed 32x32x16 MFMAs reach on this chip", **feed,
+                            "kernel_ns_per_counted_mfma_per_simd": round(k_ns, 2), "kernel_pipe_busy_counted_work": round(base_ns / k_ns, 3),
+                            "kernel_vs_lds_fed_loop_with_softmax_valu": round(feed["one_lds_fragment_per_mfma_plus_softmax_valu"]["ns_per_mfma_per_simd"] / k_ns, 3)}
+        del scratch
         pc.pod_cache_check()
         out["prefill"] = {"workload": f"configs[3]: one block G=2, 32q/8kv, d=128, prompt {n}, S=64, W=2048, "
                                       "attention + cache construction", "flops_per_layer": flops,

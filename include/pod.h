@@ -413,6 +413,16 @@ int pod_profile_read(pod_cache *cache, double *total_ms, int *launches);
  * call order, *launches how many were written; the records are then forgotten. */
 int pod_profile_read_each(pod_cache *cache, float *ms_each, int capacity, int *launches);
 /*
+ * Measurement aid for the prefill kernel's roofline: a synthetic loop of 32x32x16 bf16 MFMAs on every CU at the
+ * prefill kernel's occupancy (two waves per SIMD), timed by the caller.  variant 0: MFMAs only; 1: each MFMA takes one
+ * operand fragment (1 KB per wave) out of LDS; 2: the same plus 3 fma + 1 exponential per MFMA (about the kernel's
+ * vector work); 3: one LDS fragment per two MFMAs, same vector work.  Each SIMD executes
+ * iters * 16 (variant 3: * 32) MFMAs; 13.6 ns per MFMA and SIMD = the pipe never idles.  dev_out: scratch of at least
+ * 2048 * (number of CUs) bytes, contents undefined afterwards.
+ */
+int pod_profile_mfma_feed(int variant, int iters, void *dev_out, size_t out_bytes, void *stream);
+
+/*
  * Measurement aid: while dev_buf is set (NULL = off), every workgroup of a pod_decode_step / fused
  * pod_decode_attention launch that stores a partial result leaves 8 uint64 words in it, at index (workgroup number
  * in the launch) * 8: (sequence * num_kv_heads + kv head) << 32 | piece (bit 31 set: this workgroup merged), the id of

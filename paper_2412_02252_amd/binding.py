@@ -19,7 +19,7 @@ EXPORTS = [
     "pod_last_error", "pod_cache_bytes", "pod_cache_live_bytes", "pod_cache_init", "pod_cache_destroy",
     "pod_cache_reset", "pod_cache_seq_len", "pod_cache_check", "pod_workspace_bytes", "pod_cache_append",
     "pod_cache_fill", "pod_decode_attention", "pod_prefill_attention", "pod_cache_export_logical",
-    "pod_profile_enable", "pod_profile_disable", "pod_profile_read", "pod_profile_read_each", "pod_profile_stream_read", "pod_profile_set_trace",
+    "pod_profile_enable", "pod_profile_disable", "pod_profile_read", "pod_profile_read_each", "pod_profile_stream_read", "pod_profile_set_trace", "pod_profile_mfma_feed",
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
@@ -96,6 +96,7 @@ def load():
         "pod_profile_read_each": [vp, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)],
         "pod_profile_stream_read": [vp, vp, C.c_size_t, vp],
         "pod_profile_set_trace": [vp, vp, C.c_size_t],
+        "pod_profile_mfma_feed": [C.c_int, C.c_int, vp, C.c_size_t, vp],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -194,15 +195,50 @@ def pod_profile_stream_read(buf: torch.Tensor, nbytes: int, cache=None):
     _check(load().pod_profile_stream_read(cache.handle if cache is not None else None, buf.data_ptr(), nbytes, _stream()))
 
 
-class PodCache:
-    """Owns the torch buffers (cache + decode workspace) and the libpod handle."""
+def pod_profile_mfma_feed(variant: int, iters: int, scratch: torch.Tensor):
+    """Enqueue the synthetic MFMA loop `variant` (see pod.h) on the current stream; scratch: CUDA tensor of >= 2048 bytes per CU."""
+    _check(load().pod_profile_mfma_feed(variant, iters, scratch.data_ptr(), scratch.numel() * scratch.element_size(), _stream()))
 
-    def __init__(self, cfg: PodConfig, device="cuda:0"):
+
+GUARD_BYTE = 0xA5
+_guarded = []   # (weak reference to the owner, name, whole tensor, guard bytes): every guarded buffer handed out
+
+
+def guarded_empty(nbytes: int, device, guard_bytes: int, owner=None, name="buffer") -> torch.Tensor:
+    """nbytes of device memory, 256-byte aligned; with guard_bytes > 0 the allocation carries that many bytes of a
+    fixed pattern in front of and behind the part that is handed out, which guards_intact() checks afterwards."""
+    if guard_bytes <= 0:
+        return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    import weakref
+    g = (guard_bytes + 255) // 256 * 256
+    whole = torch.full((nbytes + 2 * g,), GUARD_BYTE, dtype=torch.uint8, device=device)
+    _guarded.append((weakref.ref(owner) if owner is not None else None, name, whole, g))
+    return whole[g:g + nbytes]
+
+
+def guards_intact(clear: bool = True):
+    """Names of the guarded buffers whose guard bands were written to (empty list = all intact)."""
+    torch.cuda.synchronize()
+    bad = []
+    for ref, name, whole, g in _guarded:
+        if not (bool((whole[:g] == GUARD_BYTE).all()) and bool((whole[-g:] == GUARD_BYTE).all())):
+            bad.append(name)
+    if clear:
+        _guarded.clear()
+    return bad
+
+
+class PodCache:
+    """Owns the torch buffers (cache + decode workspace) and the libpod handle.  guard_bytes > 0: every buffer this
+    object hands to the library sits between guard bands (see guards_intact)."""
+
+    def __init__(self, cfg: PodConfig, device="cuda:0", guard_bytes=0):
         self.cfg = cfg
         self.device = torch.device(device)
+        self.guard_bytes = guard_bytes
         nbytes = pod_cache_bytes(cfg)
-        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        self.workspace = torch.empty(pod_workspace_bytes(cfg), dtype=torch.uint8, device=self.device)
+        self.buf = guarded_empty(nbytes, self.device, guard_bytes, self, "cache")
+        self.workspace = guarded_empty(pod_workspace_bytes(cfg), self.device, guard_bytes, self, "decode workspace")
         h = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(load().pod_cache_init(C.byref(cfg), self.buf.data_ptr(), nbytes, _stream(), C.byref(h)))
@@ -320,7 +356,12 @@ class PodCache:
 
     def new_score_buffer(self):
         """Device buffer for pod_decode_attention_reuse (one block's distant logits)."""
-        return torch.empty(pod_score_buffer_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        return guarded_empty(pod_score_buffer_bytes(self.cfg), self.device, self.guard_bytes, self, "score buffer")
+
+    def new_chunk_workspace(self, n_total):
+        """Device buffer for pod_prefill_attention_chunk of a sequence that holds n_total tokens after the chunk."""
+        return guarded_empty(pod_prefill_chunk_workspace_bytes(self.cfg, n_total), self.device, self.guard_bytes, self,
+                             "chunk workspace")
 
     def pod_prefill_attention(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, out=None, write_cache=False):
         n = q.shape[0]

@@ -286,6 +286,12 @@ extern "C" int pod_profile_read_each(pod_cache *cache, float *ms_each, int capac
     return POD_OK;
 }
 
+extern "C" int pod_profile_mfma_feed(int variant, int iters, void *dev_out, size_t out_bytes, void *stream)
+{
+    if (!dev_out || iters < 1 || iters > (1 << 24)) return pod_fail(POD_ERR_INVALID_ARG, "dev_out is NULL or iters outside [1, 2^24]");
+    return pod_launch_mfma_feed(variant, iters, (float *)dev_out, out_bytes, (hipStream_t)stream);
+}
+
 extern "C" int pod_profile_set_trace(pod_cache *cache, void *dev_buf, size_t bytes)
 {
     if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");

@@ -123,6 +123,7 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
                       void *scores, float tau, void *out, hipStream_t st, const pod_step_args *step = nullptr);
 int pod_launch_stream_read(pod_cache *c, const void *buf, size_t bytes, hipStream_t st); // measurement aid: read bytes once, keep nothing
+int pod_launch_mfma_feed(int variant, int iters, float *out, size_t out_bytes, hipStream_t st); // measurement aid (pod_probe.hip)
 int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *sim, hipStream_t st);
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows

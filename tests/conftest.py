@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _guard_bands_stay_intact(request):
+    """After every GPU test: the 4 KB guard bands around the buffers the test handed to the library (cache, decode
+    workspace, score buffer, chunk workspace; allocated through PodCache(..., guard_bytes=4096)) still hold their
+    pattern, i.e. no kernel wrote outside what it was given."""
+    yield
+    if "gpu" in request.keywords and _have_gpu():
+        import paper_2412_02252_amd as pod
+        bad = pod.guards_intact()
+        assert not bad, f"guard bands overwritten: {bad}"

@@ -59,7 +59,7 @@ class Case:
         self.lowest = (np.array([[l - l % G] * Hkv for l in range(L)], dtype=np.int32) if block_lowest is None
                        else np.ascontiguousarray(block_lowest, dtype=np.int32))
         self.cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, B, max_ctx, block_lowest=block_lowest)
-        self.gpu = pod.PodCache(self.cfg, device)
+        self.gpu = pod.PodCache(self.cfg, device, guard_bytes=4096)   # guard bands around every caller buffer (conftest checks them)
         self.cpu = po.Cache(L, G, Hkv, d, S, W, B, max_ctx, block_lowest=block_lowest) if with_oracle_cache else None
         self.scale = 1.0 / math.sqrt(d)
 

@@ -115,7 +115,7 @@ def run_chunks(c, chunks, seq=0, check_rows=None):
     """Every layer processes the prompt chunk by chunk (attention, then the chunk enters the cache) on the GPU
     and in the oracle's cache model; outputs are compared chunk by chunk."""
     n_total = sum(chunks)
-    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, n_total), dtype=torch.uint8, device=c.dev)
+    ws = c.gpu.new_chunk_workspace(n_total)
     p = 0
     for t in chunks:
         for layer in range(c.L):
@@ -148,7 +148,7 @@ def test_chunked_prefill_equals_one_shot_prefill_rows():
     agree with each other to bf16 rounding of the same sums taken in a different tile order."""
     c = Case(2, 2, 8, 2, 128, 64, 512, 2, 1600, seed=331, with_oracle_cache=False)
     n, cuts = 1500, [0, 700, 701, 1100, 1500]
-    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, n), dtype=torch.uint8, device=c.dev)
+    ws = c.gpu.new_chunk_workspace(n)
     t = {}
     for layer in range(2):
         t[layer] = (c.queries(layer, 0, n, c.dev), c.keys(layer, 0, n, c.dev), c.values(layer, 0, n, c.dev))
@@ -172,7 +172,7 @@ def test_chunked_prefill_head_wise_blocks_and_deferred_cache_writes():
     table = [[0, 0], [0, 1], [0, 1], [3, 1]]
     for defer in (False, True):
         c = Case(4, 1, 4, 2, 128, 8, 40, 1, 400, seed=332, block_lowest=table)
-        ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, 330), dtype=torch.uint8, device=c.dev)
+        ws = c.gpu.new_chunk_workspace(330)
         p = 0
         for t in (100, 30, 200):
             held = []
@@ -207,7 +207,7 @@ def test_chunked_prefill_then_decode():
 
 def test_chunked_prefill_contract_violations():
     c = Case(2, 2, 4, 2, 128, 8, 40, 1, 200, seed=334, with_oracle_cache=False)
-    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, 200), dtype=torch.uint8, device=c.dev)
+    ws = c.gpu.new_chunk_workspace(200)
     q, k, v, qs, ks = chunk_inputs(c, 1, 0, 0, 100, c.dev)
     with pytest.raises(pod.PodError) as e:        # upper layer, distant tokens, no shared tensors
         c.gpu.pod_prefill_attention_chunk(1, 0, q, k, v, None, None, c.scale, ws)

@@ -97,7 +97,7 @@ def test_chunked_prefill_in_a_graph_equals_eager_on_every_replay():
     k = [c.keys(l, 0, n, c.dev) for l in range(2)]
     v = [c.values(l, 0, n, c.dev) for l in range(2)]
     out = [torch.zeros_like(q[0]) for _ in range(2)]
-    ws = torch.empty(pod.pod_prefill_chunk_workspace_bytes(c.cfg, n), dtype=torch.uint8, device=c.dev)
+    ws = c.gpu.new_chunk_workspace(n)
 
     def run():
         for a, b in zip(cuts[:-1], cuts[1:]):
