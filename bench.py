@@ -158,7 +158,8 @@ def run_large(workload, K, Wm, variant):
         per_launch = nbytes / (K * L)
         kus = statistics.median(each) * 1e3 if each else float("nan")
         res.update({"GBs": round(nbytes / dt / 1e9, 1), "frac_of_hbm_peak": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4),
-                    "kernel": {"name": "decode_partial_kernel<128, 0, %d>" % (2 if variant == "step" else 1),
+                    "kernel": {"name": ("decode_partial_kernel<128, 0, 3, false, 4> (step; a launch of several rounds of workgroups, decode_combine_kernel merges)"
+                                        if variant == "step" else "decode_partial_kernel<128, 0, 0, false, 4>"),
                                "bytes_per_launch": int(per_launch), "median_us": round(kus, 3),
                                "GBs": round(per_launch / (kus * 1e-6) / 1e9, 1),
                                "frac_of_hbm_peak": round(per_launch / (kus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "launches": len(each)}})
@@ -357,7 +358,7 @@ def main():
                    "rotating_blocks": R, "launch": mode, "launch_info": cache.pod_cache_launch_info(), "bytes_per_step": step_bytes(segs[0][0]),
                    "segments": NSEG, "ms_per_step_segments": stats(seg_ms_per_step),
                    "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBS, 4)},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0, 2> (streams K/V, updates the cache, merges the partials)",
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0, 2, true, 8> (streams K/V, updates the cache, merges the partials)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None, "bytes_per_launch": int(bytes_per_launch),
                      "avg_kernel_us": round(cold_us, 3), "launches": len(each),

@@ -41,6 +41,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4; // native 128-bit vector (plain loads/stores, no struct copies)
 
 constexpr int kWaves = 4;          // waves per workgroup
+// ... but 8 where the last workgroup of a (sequence, kv head) pair merges the partials: that merge is one CU reading
+// every partial of the pair, which goes the faster the fewer and larger the pieces are and the more waves read
+// (measured, one workgroup reading 128 KB it finds in the L2: 4 waves 1.7 us, 8 waves 0.9 us).
+constexpr int fuse_waves(int fuse) { return fuse == 1 || fuse == 2 ? 8 : kWaves; }
 constexpr int kTile = 32;          // tokens per wave iteration
 constexpr float kNegBig = -1.0e30f; // stands in for -inf (keeps exp2 arguments finite)
 constexpr int kMinChunk = 128;     // smallest chunk (tokens) a workgroup takes
@@ -289,10 +293,10 @@ __device__ inline int arrive_last(unsigned long long *ticket, int expected)
 // workgroup first evaluates the gate g = sum exp(a^P) / (sum exp(a^P) + sum exp(a^D)) of Eq. 4 for its
 // query heads from the proximal partials of MODE 3 and the lowest layer's distant sums, records
 // which heads have g >= tau, and leaves if all of its heads do.
-template <int D, bool LOC>
+template <int D, bool LOC, int NW>
 __device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
                                 bool bad);
-template <int D, bool LOC>
+template <int D, bool LOC, int NW>
 __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg);
 
 // FUSE 0: partials only, decode_combine_kernel follows.  FUSE 1 (MODE 0 only): the last workgroup of a (sequence, kv
@@ -302,8 +306,8 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 // like everybody else walks theirs: over the old rows.  FUSE 3: a step whose partials decode_combine_kernel merges
 // (launches of several rounds of workgroups: there a workgroup that waits for its arrival to be counted holds its
 // slot idle, which costs more than the second launch).
-template <int D, int MODE, int FUSE = 0, bool LOC = false>
-__global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_params p)
+template <int D, int MODE, int FUSE = 0, bool LOC = false, int NW = fuse_waves(FUSE)>
+__global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_params p)
 {
     static_assert(FUSE == 0 || MODE == 0, "the fused forms serve the plain mode");
     constexpr bool STEP = FUSE == 2 || FUSE == 3, MERGE = FUSE == 1 || FUSE == 2;
@@ -385,23 +389,14 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     // for both partials, also when the cache was empty and it has no piece of its own
     const bool hosts_step = STEP && c == max_nd;
     const int expected = nd_eff + (FUSE == 2 && np_eff == 0 ? 1 : np_eff);
-    if (hosts_step) step_workgroup<D, LOC>(p, hot, b, h, n, head_arg);
+    if (hosts_step) step_workgroup<D, LOC, NW>(p, hot, b, h, n, head_arg);
     const bool distant = c < max_nd;
     const int region_len = distant ? n_dist : n_prox;
     const int chunk = distant ? (hot.chunk & 0xffff) : chunk_p;
     const int start = (distant ? c : c - max_nd) * chunk;
-    if (start >= region_len) {
-        if constexpr (FUSE == 2) {
-            if (hosts_step) {   // (an empty cache: the new token is all there is)
-                const int last = arrive_last<LOC>(p.tickets + (size_t)b * hkv + h, expected);
-                if (last) {
-                    if (last == 2 && threadIdx.x == 0) atomicOr(p.flag, 4);
-                    merge_and_store<D, LOC>(p, hot, b, h, nd_eff, np_eff, true, last == 1, last == 2);
-                }
-            }
-        }
-        return;
-    }
+    // (a step on an empty cache: the workgroup that hosts the step walks no tile - the loads below read the region's
+    // first row, which is allocated, and every position is masked - and arrives like everybody else)
+    if (start >= region_len && !(FUSE == 2 && hosts_step)) return;
     const int end = min(start + chunk, region_len);
     // FUSE 2: the ring slot the new token replaces is being rewritten by step_workgroup, which also accounts for the
     // token it held: everybody else leaves that row out (its probability is forced to zero; old or new, its bytes
@@ -429,9 +424,9 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m16 = lane & 15, j = lane >> 4;
 
-    // kWaves K tiles of kTile rows; the same bytes later hold the merge buffer
-    // [kWaves][rep <= 16][D] floats, which is exactly as large.
-    __shared__ u32x4 lds[kWaves][kTile * CPR];
+    // NW K tiles of kTile rows; the same bytes later hold the merge buffer
+    // [NW][rep <= 16][D] floats, which is exactly as large.
+    __shared__ u32x4 lds[NW][kTile * CPR];
     static_assert(sizeof(u32x4) * kTile * CPR == sizeof(float) * 16 * D, "merge buffer must fit the K tiles");
     u32x4 *ldsK = lds[wave];
 
@@ -443,7 +438,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     const int kr = lane / CPR, kc = lane % CPR; // K load: row within the instruction, piece
     const int vc = lane % CPR;                  // V load: piece
     const int vx = (lane / CPR) % XN;           // which of the XN dims per piece pair this lane serves
-    const int last = end - 1;
+    const int last = end > 0 ? end - 1 : 0;
 
     // Tile loads.  Rows past the chunk are clamped to its last row (valid memory, masked later),
     // so the loads are unconditional: the software pipeline below needs no branches around them.
@@ -451,12 +446,12 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #define POD_LOAD_TILE(T0)                                                         \
     _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                             \
         const int row = min((T0) + RPI * i + kr, last);                           \
-        kreg[i] = Kb[(size_t)row * CPR + kc];                                     \
+        kreg[i] = __builtin_nontemporal_load(&Kb[(size_t)row * CPR + kc]);        \
     }                                                                             \
     _Pragma("unroll") for (int e = 0; e < 8; ++e) {                               \
         const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);               \
         const int row = min((T0) + tok, last);                                    \
-        vreg[e] = Vb[(size_t)row * CPR + vc];                                     \
+        vreg[e] = __builtin_nontemporal_load(&Vb[(size_t)row * CPR + vc]);        \
     }
 
     int t0 = start + wave * kTile;
@@ -600,7 +595,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
             POD_LOAD_SV(SR, VR, TNEXT)                                                \
             softmax_pv(sc, vcur);                                                     \
         }
-        constexpr int kStep = kWaves * kTile;
+        constexpr int kStep = NW * kTile;
         POD_LOAD_SV(sregA, vreg, t0)
         POD_LOAD_SV(sregB, vregB, t0 + kStep)
         for (; t0 < end; t0 += 2 * kStep) {
@@ -610,7 +605,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
 #undef POD_CONSUME_SV
 #undef POD_LOAD_SV
     } else
-    for (; t0 < end; t0 += kWaves * kTile) {
+    for (; t0 < end; t0 += NW * kTile) {
         // ---- K tile through LDS into A-operand order
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -636,7 +631,7 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         __builtin_amdgcn_wave_barrier();
 
         // ---- next tile's loads go out before the softmax / PV work of this one
-        POD_LOAD_TILE(t0 + kWaves * kTile)
+        POD_LOAD_TILE(t0 + NW * kTile)
 
         // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
         float sc[8];
@@ -665,8 +660,8 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
     //   XN = 1: 8*(4j+i) + x        XN = 2: 8*((4j+i) % 8) + 2x + (4j+i)/8
     __syncthreads(); // all waves are done with their K tiles
     if (MERGE && p.trace) tr_t1 = wall_clock64();
-    float *sm_acc = (float *)&lds[0][0];              // [kWaves][rep][D]
-    __shared__ float sm_m[kWaves][16], sm_l[kWaves][16];
+    float *sm_acc = (float *)&lds[0][0];              // [NW][rep][D]
+    __shared__ float sm_m[NW][16], sm_l[NW][16];
     if (m16 < hot.rep) {
 #pragma unroll
         for (int x = 0; x < NPV; ++x)
@@ -684,16 +679,18 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
         const int head = t / D, dim = t % D;
         float M = sm_m[0][head];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w][head]);
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][head]);
         float A = 0.f, Lsum = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float f = exp2f(sm_m[w][head] - M);
             A += f * sm_acc[((size_t)w * hot.rep + head) * D + dim];
             Lsum += f * sm_l[w][head];
         }
         typedef __attribute__((address_space(1))) float *gfloat_ptr;
-        const size_t slot = ((size_t)b * hot.hq + (size_t)h * hot.rep + head) * NC + c;
+        // (merged inside the launch: a sequence's pieces stand one after the other, its proximal ones right behind its
+        // distant ones, so that the merging workgroup addresses them by one stride)
+        const size_t slot = ((size_t)b * hot.hq + (size_t)h * hot.rep + head) * NC + (MERGE && !distant ? nd_eff + (c - max_nd) : c);
         if constexpr (MERGE) {   // read by another workgroup of this launch
             store_part<LOC>(hot.part_acc + slot * D + dim, A);
             if (dim == 0) { store_part<LOC>(hot.part_ml + slot * 2, M); store_part<LOC>(hot.part_ml + slot * 2 + 1, Lsum); }
@@ -726,77 +723,153 @@ __global__ __launch_bounds__(kWaves * 64) void decode_partial_kernel(decode_para
                 valid = false; bad = true;
             }
         }
-        merge_and_store<D, LOC>(p, hot, b, h, nd_eff, np_eff, FUSE == 2, valid, bad);
+        merge_and_store<D, LOC, NW>(p, hot, b, h, nd_eff, np_eff, FUSE == 2, valid, bad);
         trace_out();
     }
 }
 
-// The merge of a (sequence, kv head) pair's partials by the last workgroup to arrive: the same running-max merge as
-// decode_combine_kernel (the paper's gate, Eq. 4, applied to unnormalised sums), one wave per query head, the lanes of
-// a wave split in 64 / (D / 4) groups that take every other partial and are summed with shuffles at the end.
-// nd, np: distant and proximal pieces that stored a partial; special: a step's extra partial in slot hot.nc, whose
-// normaliser is negative if the step's validation failed.
-template <int D, bool LOC>
-__device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
-                                bool bad)
+// Reductions over the 64 lanes of a wave without LDS round trips (a cross-lane read through LDS takes about 60 ns,
+// and a reduction is a chain of six): four DPP steps inside the rows of 16 lanes, then the four rows through SGPRs.
+// Call with all lanes active.
+template <int CTRL>
+__device__ inline float dpp_move(float v)
 {
-    // a lane takes VEC floats of a partial row; the 64 / LPR lane groups of a wave take every NGW-th partial; one pass
-    // with a running maximum, UN partials in flight per lane (one round covers 36 partials per head at D = 128, LOC)
-    constexpr int VEC = LOC ? 4 : 2, LPR = D / VEC, NGW = 64 / LPR, UN = 18;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, x = lane % LPR, g = lane / LPR;
-    const int nv = nd + np + (special ? 1 : 0);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ inline float lane_value(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
+__device__ inline float wave_max(float v)
+{
+    v = fmaxf(v, dpp_move<0xB1>(v));    // quad_perm [1, 0, 3, 2]
+    v = fmaxf(v, dpp_move<0x4E>(v));    // quad_perm [2, 3, 0, 1]
+    v = fmaxf(v, dpp_move<0x141>(v));   // row_half_mirror
+    v = fmaxf(v, dpp_move<0x140>(v));   // row_mirror
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+__device__ inline float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+
+// The merge of a (sequence, kv head) pair's partials by the last workgroup to arrive: the same merge as
+// decode_combine_kernel (the paper's gate, Eq. 4, applied to unnormalised sums).  Its time is the time of one CU's
+// loads, so as many waves as possible take part and every load of a wave is in flight before the first is used:
+// a query head goes to SPLIT waves (2 where the workgroup has at least two waves per head), wave s of them takes the
+// partials s, s + SPLIT, ...; lane i of a wave takes the (maximum, normaliser) pair of the wave's i-th partial, each
+// of the wave's 64 / LPR lane groups every NGW-th of the wave's rows, VEC floats per lane, CAP rows per lane group at
+// a time (more only in launches with more than CAP * NGW * SPLIT pieces per pair: then by a running maximum).
+// Maximum and normaliser are reduced over the wave, each lane computes the weight of its own partial once, and the row
+// weights reach the lane groups through SGPRs; the waves of a head meet in LDS.
+// nd, np: distant and proximal pieces that stored a partial; special: a step's extra partial in slot hot.nc, whose
+// normaliser is negative if the step's validation failed; it is the state the head's first wave starts from.
+// Called by every thread of the workgroup.
+template <int D, bool LOC, int NW, int SPLIT>
+__device__ void merge_and_store_split(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
+                                      bool bad)
+{
+    constexpr int VEC = LOC ? 4 : 2, LPR = D / VEC, NGW = 64 / LPR, CAP = 32 / NGW, ROWS = CAP * NGW;   // ROWS = 32 per wave
+    constexpr unsigned ROWB = D * sizeof(float);
+    __shared__ float sm_a[NW][D], sm_ml[NW][2];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, x = lane % LPR, g = lane / LPR;
+    const int nv = nd + np;         // the pieces' partials are rows 0 .. nv - 1 of a head's block, the step's is row hot.nc
     const size_t stride = (size_t)hot.nc + (special ? 1 : 0);
-    auto chunk_slot = [&](int v) { return v < nd ? v : (v < nd + np ? hot.max_nd + (v - nd) : hot.nc); };
-    if (special) {
-        const float2 mark = load_ml<LOC>(hot.part_ml + (((size_t)b * hot.hq + (size_t)h * hot.rep) * stride + hot.nc) * 2);
-        if (mark.y < 0.f) { valid = false; bad = true; }
-    }
-    for (int r = wave; r < hot.rep; r += kWaves) {
-        const int head = h * hot.rep + r;
-        const float *ml = hot.part_ml + ((size_t)b * hot.hq + head) * stride * 2;
-        const float *pa = hot.part_acc + ((size_t)b * hot.hq + head) * stride * D + VEC * x;
+    constexpr int split = SPLIT, heads_at_once = NW / split;
+    for (int r0 = 0; r0 < hot.rep; r0 += heads_at_once) {
+        const int r = r0 + wave / split, s = wave % split;
+        const bool active = r < hot.rep;
+        const int head = h * hot.rep + (active ? r : 0);
+        // (wave-uniform bases and 32-bit lane offsets: the address arithmetic stands between the arrival and the first
+        // load, so it is kept to two or three instructions per load)
+        const char *ml = (const char *)(hot.part_ml + ((size_t)b * hot.hq + head) * stride * 2);
+        const char *pa = (const char *)(hot.part_acc + ((size_t)b * hot.hq + head) * stride * D);
         float m_run = kNegBig, L = 0.f, a[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) a[e] = 0.f;
-        for (int v0 = g; v0 < nv; v0 += NGW * UN) {
-            float2 mk[UN];
-            float ak[UN][VEC];
+        if (active) {
+            float2 mark = make_float2(kNegBig, 0.f);
+            float as[VEC];
 #pragma unroll
-            for (int k = 0; k < UN; ++k) {
-                const int v = v0 + k * NGW;
-                const int cs = chunk_slot(v < nv ? v : v0);
-                mk[k] = load_ml<LOC>(ml + cs * 2);
-                load_part<LOC, VEC>(pa + (size_t)cs * D, ak[k]);
-                if (v >= nv) mk[k] = make_float2(kNegBig, 0.f);   // (weight exp2(-big) = 0 for whatever was loaded)
+            for (int e = 0; e < VEC; ++e) as[e] = 0.f;
+            const bool mine = special && s == 0;
+            if (mine) {
+                mark = load_ml<LOC>((const float *)(ml + (unsigned)hot.nc * 8u));
+                load_part<LOC, VEC>((const float *)(pa + ((unsigned)hot.nc * ROWB + VEC * 4u * x)), as);
             }
-            float mb = mk[0].x;
+            // this wave's i-th row of a block starting at v0 is partial v0 + i * split + s; lane group g takes its
+            // rows g, g + NGW, ...
+            constexpr unsigned kstride = (unsigned)(NGW * split) * ROWB;
+            for (int v0 = 0; v0 == 0 || v0 + s < nv; v0 += ROWS * split) {
+                const int first = v0 + s;
+                const int vl = first + lane * split;
+                const bool have = lane < ROWS && vl < nv;
+                float2 mk = make_float2(kNegBig, 0.f);
+                if (have) mk = load_ml<LOC>((const float *)(ml + (unsigned)vl * 8u));
+                // rows past the end read the lane group's last valid row (or the wave's first) and get weight 0
+                const int gfirst = first + g * split;
+                int cnt = gfirst < nv ? (nv - gfirst + NGW * split - 1) / (NGW * split) : 0;
+                cnt = cnt < CAP ? cnt : CAP;
+                const unsigned off0 = (unsigned)gfirst * ROWB + VEC * 4u * x;
+                const unsigned off_last = cnt > 0 ? off0 + (unsigned)(cnt - 1) * kstride : (unsigned)first * ROWB + VEC * 4u * x;
+                float ak[CAP][VEC];
 #pragma unroll
-            for (int k = 1; k < UN; ++k) mb = fmaxf(mb, mk[k].x);
-            const float m_new = fmaxf(m_run, mb);
-            const float alpha = exp2f(m_run - m_new);
-            L *= alpha;
+                for (int k = 0; k < CAP; ++k) {
+                    const unsigned off = off0 + (unsigned)k * kstride;
+                    // (wave-uniform: whole instructions past the end are not issued)
+                    if (first + k * NGW * split < nv) load_part<LOC, VEC>((const float *)(pa + (off < off_last ? off : off_last)), ak[k]);
+                    else
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) a[e] *= alpha;
+                        for (int e = 0; e < VEC; ++e) ak[k][e] = 0.f;
+                }
+                if (v0 == 0 && mine) {     // (loaded above, so that its latency overlaps the block's)
+                    if (mark.y < 0.f) { valid = false; bad = true; }
+                    m_run = mark.x; L = mark.y;
 #pragma unroll
-            for (int k = 0; k < UN; ++k) {
-                const float f = (v0 + k * NGW < nv) ? exp2f(mk[k].x - m_new) : 0.f;
-                L += f * mk[k].y;
+                    for (int e = 0; e < VEC; ++e) a[e] = g == 0 ? as[e] : 0.f;
+                }
+                const float m_new = fmaxf(m_run, wave_max(mk.x));
+                const float alpha = exp2f(m_run - m_new);
+                const float w = have ? exp2f(mk.x - m_new) : 0.f;
+                L = L * alpha + wave_sum(w * mk.y);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) a[e] += f * ak[k][e];
+                for (int e = 0; e < VEC; ++e) a[e] *= alpha;
+#pragma unroll
+                for (int k = 0; k < CAP; ++k) {
+                    if (first + k * NGW * split >= nv) break;
+                    float f = lane_value(w, k * NGW);     // the weight of this lane group's k-th row
+#pragma unroll
+                    for (int gg = 1; gg < NGW; ++gg) f = g == gg ? lane_value(w, k * NGW + gg) : f;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) a[e] += f * ak[k][e];
+                }
+                m_run = m_new;
             }
-            m_run = m_new;
-        }
 #pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) {   // the lane groups of the wave, each with its own maximum
-            const float m2 = __shfl_xor(m_run, off), L2 = __shfl_xor(L, off);
-            const float m_new = fmaxf(m_run, m2);
-            const float f1 = exp2f(m_run - m_new), f2 = exp2f(m2 - m_new);
-            L = f1 * L + f2 * L2;
+            for (int off = LPR; off < 64; off <<= 1)     // the lane groups of the wave (one maximum for all of them)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) a[e] = f1 * a[e] + f2 * __shfl_xor(a[e], off);
-            m_run = m_new;
+                for (int e = 0; e < VEC; ++e) a[e] += __shfl_xor(a[e], off);
         }
-        if (g == 0) {
+        if (split == 2) {                                // the head's second wave hands its sums to the first
+            if (active && s == 1) {
+                if (g == 0)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) sm_a[wave][VEC * x + e] = a[e];
+                if (lane == 0) { sm_ml[wave][0] = m_run; sm_ml[wave][1] = L; }
+            }
+            __syncthreads();
+            if (active && s == 0) {
+                const float m2 = sm_ml[wave + 1][0], L2 = sm_ml[wave + 1][1];
+                const float m_new = fmaxf(m_run, m2);
+                const float f1 = exp2f(m_run - m_new), f2 = exp2f(m2 - m_new);
+                L = f1 * L + f2 * L2;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) a[e] = f1 * a[e] + f2 * sm_a[wave + 1][VEC * x + e];
+            }
+            if (r0 + heads_at_once < hot.rep) __syncthreads();   // (before the next round writes the buffer again)
+        }
+        if (active && s == 0 && g == 0) {
             unsigned res[VEC / 2];
 #pragma unroll
             for (int e = 0; e < VEC / 2; ++e) res[e] = 0u;
@@ -811,6 +884,13 @@ __device__ void merge_and_store(const decode_params &p, const decode_hot &hot, i
         }
     }
     if (bad && threadIdx.x == 0) atomicOr(p.flag, 2);
+}
+template <int D, bool LOC, int NW>
+__device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
+                                bool bad)
+{
+    if (hot.rep * 2 <= NW) merge_and_store_split<D, LOC, NW, 2>(p, hot, b, h, nd, np, special, valid, bad);
+    else merge_and_store_split<D, LOC, NW, 1>(p, hot, b, h, nd, np, special, valid, bad);
 }
 
 __device__ inline float dot8_bf16(u32x4 a, u32x4 b)
@@ -835,7 +915,7 @@ __device__ inline float dot8_bf16(u32x4 a, u32x4 b)
 // workgroups walk the rows held before the call and leave the ring slot out.  (4) The last of a sequence's kv heads
 // to finish advances the stored length; (5) the partial (in the slot behind the pieces' slots) takes part in the merge
 // like any other.
-template <int D, bool LOC>
+template <int D, bool LOC, int NW>
 __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg)
 {
     constexpr int CPR = D / 8;
@@ -864,7 +944,7 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
     }
     const pod_bf16 *qd_src = (hot.q_shared && !low_head) ? hot.q_shared : hot.q;
     const size_t stride = (size_t)hot.nc + 1;
-    for (int r = wave; r < hot.rep; r += kWaves) {
+    for (int r = wave; r < hot.rep; r += NW) {
         const size_t head = (size_t)b * hot.hq + (size_t)h * hot.rep + r;
         const u32x4 qn = ((gvec_ptr)(hot.q + head * D))[i], qd = ((gvec_ptr)(qd_src + head * D))[i];
         float sn = lane < CPR ? dot8_bf16(qn, kn) : 0.f, sd = (lane < CPR && demote) ? dot8_bf16(qd, kd) : 0.f;
@@ -1239,30 +1319,69 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
 
-    // Chunk size.  Small problems (config 2: 262K rows) want exactly one resident round of
-    // workgroups (2 per CU x 256 CUs): rows / 512.  Large or ragged problems want many rounds of
-    // moderately sized chunks so that the tail stays short: measured best near 1024 tokens for
+    // Chunk size, for workgroups of nw waves (8 / nw of them fit a CU).  Small problems (config 2: 262K rows) want
+    // exactly one resident round of workgroups: rows / (CUs x 8 / nw).  Large or ragged problems want many rounds
+    // of moderately sized chunks so that the tail stays short: measured best near 256 tokens per wave for
     // 16 ragged sequences of 4K-32K tokens and within 2 % of best for 4 sequences of 128K.
-    // Never below kMinChunk tokens, so the partials stay a small fraction of the K/V bytes.
+    // Never below one tile per wave, so the partials stay a small fraction of the K/V bytes.
     const int env_chunk = c->tune_chunk; // tuning / test override
     const long rows = (long)max_len * ly.Hkv * B;
-    long chunk = env_chunk > 0 ? env_chunk : rows / 512;
-    chunk = (chunk + kTile - 1) / kTile * kTile;
-    if (chunk < kMinChunk) chunk = kMinChunk;
-    if (chunk > 1024 && env_chunk <= 0) chunk = 1024;
-    if (chunk > 8192) chunk = 8192;
-    // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time of
-    // one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
-    // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
-    long chunk_p = c->tune_chunk_prox > 0 ? c->tune_chunk_prox : ((scores && !lowest_all && tau >= 0.f) ? kMinChunk : chunk);
-    chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
-    if (chunk_p < kMinChunk) chunk_p = kMinChunk;
-    if (chunk_p > 8192) chunk_p = 8192;
-    p.hot.chunk = (int)(chunk | (chunk_p << 16));
     const int max_prox = max_len < ly.P ? max_len : ly.P;
     const int max_dist = max_len - max_prox;
-    p.hot.max_nd = chunk_slots(max_dist, (int)chunk);
-    p.hot.nc = p.hot.max_nd + chunk_slots(max_prox, (int)chunk_p);
+    int cus = 256;
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
+    struct plan_t { long chunk, chunk_p; int max_nd, nc; };
+    auto plan = [&](int nw) {
+        const long min_chunk = (long)kTile * nw, auto_max = 256L * nw, round = (long)cus * 8 / nw;
+        long chunk = env_chunk > 0 ? env_chunk : rows / round;
+        chunk = (chunk + kTile - 1) / kTile * kTile;
+        if (chunk < min_chunk) chunk = min_chunk;
+        if (chunk > auto_max && env_chunk <= 0) chunk = auto_max;
+        if (chunk > 8192) chunk = 8192;
+        // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time
+        // of one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
+        // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
+        long chunk_p = c->tune_chunk_prox > 0 ? c->tune_chunk_prox : ((scores && !lowest_all && tau >= 0.f) ? min_chunk : chunk);
+        chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
+        if (chunk_p < min_chunk) chunk_p = min_chunk;
+        if (chunk_p > 8192) chunk_p = 8192;
+        // Where the rule above lands just past one resident round (the proximal region's ragged last piece, a distant
+        // region a few tokens over a multiple of the chunk), the workgroups beyond it start only when a first one
+        // has left, near the end of the launch, and the launch ends that much later (measured on the 32K-token shape:
+        // 8 of 520 workgroups started at 18 us of a 30 us launch).  There the distant pieces keep their size (or grow
+        // tile by tile) and the proximal region is cut into the slots that are left.
+        const long resident = round / npairs;
+        if (env_chunk <= 0 && c->tune_chunk_prox <= 0 && !scores && resident >= 2 && chunk <= auto_max &&
+            chunk_slots(max_dist, (int)chunk) + chunk_slots(max_prox, (int)chunk_p) > resident)
+            for (long t = chunk; t <= auto_max + 8 * kTile; t += kTile) {
+                const long left = resident - chunk_slots(max_dist, (int)t);
+                if (left < 1) continue;
+                long tp = ((max_prox + left - 1) / left + kTile - 1) / kTile * kTile;
+                if (tp < min_chunk) tp = min_chunk;
+                if (tp > 2 * t) continue;
+                chunk = t;
+                chunk_p = tp;
+                break;
+            }
+        plan_t r;
+        r.chunk = chunk; r.chunk_p = chunk_p;
+        r.max_nd = chunk_slots(max_dist, (int)chunk);
+        r.nc = r.max_nd + chunk_slots(max_prox, (int)chunk_p);
+        return r;
+    };
+    // Merge inside the streaming kernel only where the launch is about one resident round of workgroups:
+    // a workgroup waits for its arrival to be counted before it leaves, and in a launch of several rounds that wait
+    // keeps the next workgroup from starting (measured: 4 sequences of 128K tokens 13.1 ms per step against 12.0 ms
+    // with the separate merge kernel).  Such launches run workgroups of 8 waves, all others of kWaves.
+    // 0: separate combine kernel; 1: the last workgroup of a (sequence, kv head)
+    // pair merges; 2: 1 + the cache update; 3: the cache update, separate combine kernel.
+    plan_t pl = plan(fuse_waves(1));
+    const bool one_round = (size_t)pl.nc * (size_t)npairs <= (size_t)cus * 5 / 4;
+    const bool merge_inside = !scores && c->fused_merge && one_round;
+    if (!merge_inside) pl = plan(kWaves);
+    p.hot.chunk = (int)(pl.chunk | (pl.chunk_p << 16));
+    p.hot.max_nd = pl.max_nd;
+    p.hot.nc = pl.nc;
     const size_t NC = (size_t)p.hot.nc + (step ? 1 : 0); // partial slots per query head (a step keeps one more)
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
@@ -1274,15 +1393,6 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 
     const size_t WGS = (size_t)p.hot.nc;   // workgroups per (sequence, kv head) pair
     p.slots = (int32_t)WGS;
-    // Merge inside the streaming kernel only where the launch is about one resident round of workgroups (2 per CU):
-    // a workgroup waits for its arrival to be counted before it leaves, and in a launch of several rounds that wait
-    // keeps the next workgroup from starting (measured: 4 sequences of 128K tokens 13.1 ms per step against 12.0 ms
-    // with the separate merge kernel).  0: separate combine kernel; 1: the last workgroup of a (sequence, kv head)
-    // pair merges; 2: 1 + the cache update; 3: the cache update, separate combine kernel.
-    int cus = 256;
-    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
-    const bool one_round = WGS * (size_t)npairs <= (size_t)cus * 5 / 2;
-    const bool merge_inside = !scores && c->fused_merge && one_round;
     const int fuse = step ? (merge_inside ? 2 : 3) : (merge_inside ? 1 : 0);
     const bool loc = merge_inside && c->xcd_local && c->nxcd >= 1 && (npairs % c->nxcd == 0 || npairs >= 8 * c->nxcd);
     const size_t loc_wgs = (size_t)((npairs + p.nxcd - 1) / p.nxcd) * p.nxcd * WGS;
@@ -1299,11 +1409,11 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // score reuse: the writing launch for the kv heads whose block starts at this layer, the reading launch(es) for
     // the others (workgroups of the other kind leave at once); a gated read is two launches, proximal chunks first
 #define POD_LAUNCH_ALL(DD)                                                                   \
-    if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(kWaves * 64), 0, st, p);       \
-    else if (fuse == 1 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1, true>), grid, dim3(kWaves * 64), 0, st, p);  \
-    else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2>), grid, dim3(kWaves * 64), 0, st, p);               \
+    if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
+    else if (fuse == 1 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1, true>), grid, dim3(fuse_waves(1) * 64), 0, st, p); \
+    else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);    \
     else if (fuse == 3) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 3>), grid, dim3(kWaves * 64), 0, st, p);               \
-    else if (fuse == 1) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1>), grid, dim3(kWaves * 64), 0, st, p);               \
+    else if (fuse == 1) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1>), grid, dim3(fuse_waves(1) * 64), 0, st, p);    \
     else if (p.mode == 0) POD_LAUNCH_PARTIAL(DD, 0, grid);                                   \
     else {                                                                                   \
         if (lowest_any) POD_LAUNCH_PARTIAL(DD, 1, grid);                                     \
