@@ -360,7 +360,10 @@ def main():
                    "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<128, 0, 2, true, 8> (streams K/V, updates the cache, merges the partials)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": int(bytes_per_launch),
+                     "traffic": None,
+                     "traffic_note": "counters need a rocprofv3 run: profiles/decode_step_kernel_cfg2_pmc.txt holds "
+                                     "FETCH_SIZE + WRITE_SIZE of this kernel on this workload, 135.99 MB per launch = 1.012 x algorithmic",
+                     "bytes_per_launch": int(bytes_per_launch),
                      "avg_kernel_us": round(cold_us, 3), "launches": len(each),
                      "timed": "HIP event pair per launch (reads 1-2 us more than the kernel's own begin-to-end time); "
                               "achieved/frac are the lowest-layer launches, whose bytes all come from HBM",
