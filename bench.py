@@ -206,7 +206,8 @@ def main():
     RU = a.reuse_steps
     GR = K          # replays of the token-reusable step graph (each replay = R steps)
     seed = 20241202 + 2
-    total_steps = Wm + NSEG * K + K + P + RU
+    TL = 8           # eager steps whose lowest-layer launch leaves per-workgroup device clocks
+    total_steps = Wm + NSEG * K + K + P + TL + RU
     per_block = (total_steps + R - 1) // R + GR + 2
     max_ctx = n0 + per_block + 1
     L = G * R
@@ -335,6 +336,38 @@ def main():
     bytes_per_launch = sum(step_bytes(e) for e in prof) / max(len(each), 1)
     cold_us = statistics.median(low_us)
     achieved = bytes_per_launch / (cold_us * 1e-6) / 1e9
+    # where a cold launch's time goes: per-workgroup device clocks (100 MHz) of TL lowest-layer launches
+    import numpy as np
+    tl = steps[cursor:cursor + TL]
+    cursor += TL
+    trace = torch.zeros(8 * 4096, dtype=torch.int64, device=dev)
+    phases = {"tile_loops_end": [], "partials_stored": [], "arrivals_counted": [], "end": []}
+    for e in tl:
+        l0, l1 = e["layers"]
+        trace.zero_()
+        cache.pod_profile_set_trace(trace)
+        cache.pod_decode_step(l0, e["k0"], e["v0"], e["q0"], None, e["pos"], scale, out=e["o0"], max_context_len=e["n"])
+        torch.cuda.synchronize()
+        cache.pod_profile_set_trace(None)
+        cache.pod_decode_step(l1, e["k1"], e["v1"], e["q1"], e["q0"], e["pos"], scale, out=e["o1"], max_context_len=e["n"])
+        t = trace.cpu().numpy().reshape(-1, 8)
+        t = t[t[:, 2] > 0]
+        if len(t):
+            t0 = t[:, 2].min()
+            for name, col in (("tile_loops_end", 3), ("partials_stored", 4), ("arrivals_counted", 5), ("end", 6)):
+                phases[name].append(float((t[:, col].max() - t0) / 100.0))
+    torch.cuda.synchronize()
+    cache.pod_cache_check()
+    del trace
+    timeline = None
+    if phases["end"]:
+        tm = {k: round(statistics.median(v), 2) for k, v in phases.items()}
+        timeline = {"what": "device clocks of every workgroup of a cold lowest-layer launch, us after the first workgroup's "
+                            f"start, last workgroup to reach each point, median of {len(phases['end'])} launches",
+                    **tm,
+                    "streaming_phase_GBs": round(bytes_per_launch / (tm["tile_loops_end"] * 1e-6) / 1e9, 1),
+                    "streaming_phase_frac_of_peak": round(bytes_per_launch / (tm["tile_loops_end"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                    "hand_over_us": round(tm["end"] - tm["tile_loops_end"], 2)}
     # a plain streaming read of the same number of bytes from memory that left the caches long ago
     sweep = torch.empty(8 * int(bytes_per_launch) // 16 * 16 + 4096, dtype=torch.uint8, device=dev).fill_(1)
     part = int(bytes_per_launch) // 256 * 256
@@ -369,6 +402,7 @@ def main():
                               "achieved/frac are the lowest-layer launches, whose bytes all come from HBM",
                      "lowest_layer_launch_us": stats(low_us), "upper_layer_launch_us": stats(up_us),
                      "upper_layer_frac": round(bytes_per_launch / (statistics.median(up_us) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "timeline": timeline,
                      "streaming_ceiling": {"what": "plain read-only kernel over the same number of cold bytes, same event timing",
                                            "us": stats(ceil_us), "GBs": round(part / (ceil_med * 1e-6) / 1e9, 1),
                                            "frac_of_peak": round(part / (ceil_med * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
