@@ -423,6 +423,17 @@ int pod_profile_read_each(pod_cache *cache, float *ms_each, int capacity, int *l
 int pod_profile_mfma_feed(int variant, int iters, void *dev_out, size_t out_bytes, void *stream);
 
 /*
+ * Host logic, no device needed: how a plain pod_decode_attention / pod_decode_step launch for `batch` sequences of up
+ * to max_context_len tokens is cut into split-K pieces on a device with num_cus compute units, without tuning
+ * overrides (proximal_rows = sink + window).  plan[0] waves per workgroup, plan[1] tokens per distant piece, plan[2]
+ * tokens per proximal piece, plan[3] distant pieces per (sequence, kv head) pair, plan[4] all pieces per pair,
+ * plan[5] 1 if the last workgroup of a pair merges the partials inside the launch, 0 if a second kernel does.
+ * Pieces are whole tiles of 32 tokens and cover the regions; plan[4] never exceeds what pod_workspace_bytes provides for.
+ * Returns POD_ERR_INVALID_ARG for non-positive arguments or a NULL plan.
+ */
+int pod_decode_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, int max_context_len, int32_t plan[6]);
+
+/*
  * Measurement aid: while dev_buf is set (NULL = off), every workgroup of a pod_decode_step / fused
  * pod_decode_attention launch that stores a partial result leaves 8 uint64 words in it, at index (workgroup number
  * in the launch) * 8: (sequence * num_kv_heads + kv head) << 32 | piece (bit 31 set: this workgroup merged), the id of

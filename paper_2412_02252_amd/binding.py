@@ -24,6 +24,7 @@ EXPORTS = [
     "pod_group_layers", "pod_layer_similarity",
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
+    "pod_decode_plan",
 ]
 
 
@@ -69,6 +70,7 @@ def load():
         "pod_cache_region_counts": [vp, C.c_int, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int)],
         "pod_cache_sync_lengths": [vp, vp],
         "pod_workspace_bytes": [cfgp, szp],
+        "pod_decode_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)],
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
@@ -187,6 +189,12 @@ def pod_workspace_bytes(cfg: PodConfig) -> int:
     out = C.c_size_t()
     _check(load().pod_workspace_bytes(C.byref(cfg), C.byref(out)))
     return out.value
+
+
+def pod_decode_plan(num_cus: int, batch: int, num_kv_heads: int, proximal_rows: int, max_context_len: int) -> dict:
+    plan = (C.c_int32 * 6)()
+    _check(load().pod_decode_plan(num_cus, batch, num_kv_heads, proximal_rows, max_context_len, plan))
+    return dict(waves=plan[0], chunk=plan[1], chunk_prox=plan[2], distant_pieces=plan[3], pieces=plan[4], merge_inside=bool(plan[5]))
 
 
 def pod_profile_stream_read(buf: torch.Tensor, nbytes: int, cache=None):

@@ -292,6 +292,18 @@ extern "C" int pod_profile_mfma_feed(int variant, int iters, void *dev_out, size
     return pod_launch_mfma_feed(variant, iters, (float *)dev_out, out_bytes, (hipStream_t)stream);
 }
 
+extern "C" int pod_decode_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, int max_context_len, int32_t plan[6])
+{
+    if (!plan) return pod_fail(POD_ERR_INVALID_ARG, "plan is NULL");
+    if (num_cus < 1 || batch < 1 || num_kv_heads < 1 || proximal_rows < 1 || max_context_len < 1)
+        return pod_fail(POD_ERR_INVALID_ARG, "num_cus, batch, num_kv_heads, proximal_rows and max_context_len must be positive");
+    if ((long long)batch * num_kv_heads > 0x7fffffffLL || (long long)batch * num_kv_heads * max_context_len > (1LL << 50))
+        return pod_fail(POD_ERR_INVALID_ARG, "shape too large");
+    const pod_decode_plan_t pl = pod_plan_decode(num_cus, batch, num_kv_heads, proximal_rows, max_context_len, 0, 0, false, false, true);
+    plan[0] = pl.waves; plan[1] = pl.chunk; plan[2] = pl.chunk_p; plan[3] = pl.max_nd; plan[4] = pl.nc; plan[5] = pl.merge_inside ? 1 : 0;
+    return POD_OK;
+}
+
 extern "C" int pod_profile_set_trace(pod_cache *cache, void *dev_buf, size_t bytes)
 {
     if (!cache) return pod_fail(POD_ERR_INVALID_ARG, "cache is NULL");

@@ -1265,6 +1265,71 @@ size_t pod_score_header_bytes(const pod_layout &ly)
     return score_tag_bytes(ly) + score_gate_bytes(ly) + ((size_t)ly.B * ly.Hq * sizeof(int32_t) + 255) / 256 * 256;
 }
 
+// The split-K plan of a decode launch: host logic only, a function of the shape (also exported for the CPU tests).
+// Chunk size, for workgroups of nw waves (8 / nw of them fit a CU).  Small problems (config 2: 262K rows) want
+// exactly one resident round of workgroups: rows / (CUs x 8 / nw).  Large or ragged problems want many rounds
+// of moderately sized chunks so that the tail stays short: measured best near 256 tokens per wave for
+// 16 ragged sequences of 4K-32K tokens and within 2 % of best for 4 sequences of 128K.
+// Never below one tile per wave, so the partials stay a small fraction of the K/V bytes.
+// env_chunk, env_chunk_prox: tuning / test overrides (0 = none); scores: a score-reuse or gated call; small_prox: the
+// gated form's proximal launch.
+pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, int env_chunk, int env_chunk_prox, bool scores,
+                                  bool small_prox, bool fused_allowed)
+{
+    const int npairs = B * Hkv;
+    const long rows = (long)max_len * npairs;
+    const int max_prox = max_len < P ? max_len : P;
+    const int max_dist = max_len - max_prox;
+    auto plan = [&](int nw) {
+        const long min_chunk = (long)kTile * nw, auto_max = 256L * nw, round = (long)cus * 8 / nw;
+        long chunk = env_chunk > 0 ? env_chunk : rows / round;
+        chunk = (chunk + kTile - 1) / kTile * kTile;
+        if (chunk < min_chunk) chunk = min_chunk;
+        if (chunk > auto_max && env_chunk <= 0) chunk = auto_max;
+        if (chunk > 8192) chunk = 8192;
+        // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time
+        // of one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
+        // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
+        long chunk_p = env_chunk_prox > 0 ? env_chunk_prox : (small_prox ? min_chunk : chunk);
+        chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
+        if (chunk_p < min_chunk) chunk_p = min_chunk;
+        if (chunk_p > 8192) chunk_p = 8192;
+        // Where the rule above lands just past one resident round (the proximal region's ragged last piece, a distant
+        // region a few tokens over a multiple of the chunk), the workgroups beyond it start only when a first one
+        // has left, near the end of the launch, and the launch ends that much later (measured on the 32K-token shape:
+        // 8 of 520 workgroups started at 18 us of a 30 us launch).  There the distant pieces keep their size (or grow
+        // tile by tile) and the proximal region is cut into the slots that are left.
+        const long resident = round / npairs;
+        if (env_chunk <= 0 && env_chunk_prox <= 0 && !scores && resident >= 2 && chunk <= auto_max &&
+            chunk_slots(max_dist, (int)chunk) + chunk_slots(max_prox, (int)chunk_p) > resident)
+            for (long t = chunk; t <= auto_max + 8 * kTile; t += kTile) {
+                const long left = resident - chunk_slots(max_dist, (int)t);
+                if (left < 1) continue;
+                long tp = ((max_prox + left - 1) / left + kTile - 1) / kTile * kTile;
+                if (tp < min_chunk) tp = min_chunk;
+                if (tp > 2 * t) continue;
+                chunk = t;
+                chunk_p = tp;
+                break;
+            }
+        pod_decode_plan_t r;
+        r.waves = nw;
+        r.chunk = (int)chunk; r.chunk_p = (int)chunk_p;
+        r.max_nd = chunk_slots(max_dist, (int)chunk);
+        r.nc = r.max_nd + chunk_slots(max_prox, (int)chunk_p);
+        r.merge_inside = false;
+        return r;
+    };
+    // Merge inside the streaming kernel only where the launch is about one resident round of workgroups:
+    // a workgroup waits for its arrival to be counted before it leaves, and in a launch of several rounds that wait
+    // keeps the next workgroup from starting (measured: 4 sequences of 128K tokens 13.1 ms per step against 12.0 ms
+    // with the separate merge kernel).  Such launches run workgroups of 8 waves, all others of kWaves.
+    pod_decode_plan_t pl = plan(fuse_waves(1));
+    pl.merge_inside = !scores && fused_allowed && (long)pl.nc * npairs <= (long)cus * 5 / 4;
+    if (!pl.merge_inside) pl = plan(kWaves);
+    return pl;
+}
+
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared, const int32_t *ctx, int B,
                       int max_len, float scale, void *ws, size_t ws_bytes, void *scores, float tau, void *out,
                       hipStream_t st, const pod_step_args *step)
@@ -1324,67 +1389,12 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     if (p.hot.use_hlen)
         for (int b = 0; b < B; ++b) p.hlen[b] = (int32_t)c->host_len[(size_t)layer * ly.B + b];
 
-    // Chunk size, for workgroups of nw waves (8 / nw of them fit a CU).  Small problems (config 2: 262K rows) want
-    // exactly one resident round of workgroups: rows / (CUs x 8 / nw).  Large or ragged problems want many rounds
-    // of moderately sized chunks so that the tail stays short: measured best near 256 tokens per wave for
-    // 16 ragged sequences of 4K-32K tokens and within 2 % of best for 4 sequences of 128K.
-    // Never below one tile per wave, so the partials stay a small fraction of the K/V bytes.
-    const int env_chunk = c->tune_chunk; // tuning / test override
-    const long rows = (long)max_len * ly.Hkv * B;
-    const int max_prox = max_len < ly.P ? max_len : ly.P;
-    const int max_dist = max_len - max_prox;
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
-    struct plan_t { long chunk, chunk_p; int max_nd, nc; };
-    auto plan = [&](int nw) {
-        const long min_chunk = (long)kTile * nw, auto_max = 256L * nw, round = (long)cus * 8 / nw;
-        long chunk = env_chunk > 0 ? env_chunk : rows / round;
-        chunk = (chunk + kTile - 1) / kTile * kTile;
-        if (chunk < min_chunk) chunk = min_chunk;
-        if (chunk > auto_max && env_chunk <= 0) chunk = auto_max;
-        if (chunk > 8192) chunk = 8192;
-        // Proximal chunks.  In the gated form the proximal region is a launch of its own, whose duration is the time
-        // of one workgroup: its waves walk their tiles one after the other.  There the region is cut into the smallest
-        // chunks (one tile per wave); everywhere else proximal and distant workgroups take equally many tokens.
-        long chunk_p = c->tune_chunk_prox > 0 ? c->tune_chunk_prox : ((scores && !lowest_all && tau >= 0.f) ? min_chunk : chunk);
-        chunk_p = (chunk_p + kTile - 1) / kTile * kTile;
-        if (chunk_p < min_chunk) chunk_p = min_chunk;
-        if (chunk_p > 8192) chunk_p = 8192;
-        // Where the rule above lands just past one resident round (the proximal region's ragged last piece, a distant
-        // region a few tokens over a multiple of the chunk), the workgroups beyond it start only when a first one
-        // has left, near the end of the launch, and the launch ends that much later (measured on the 32K-token shape:
-        // 8 of 520 workgroups started at 18 us of a 30 us launch).  There the distant pieces keep their size (or grow
-        // tile by tile) and the proximal region is cut into the slots that are left.
-        const long resident = round / npairs;
-        if (env_chunk <= 0 && c->tune_chunk_prox <= 0 && !scores && resident >= 2 && chunk <= auto_max &&
-            chunk_slots(max_dist, (int)chunk) + chunk_slots(max_prox, (int)chunk_p) > resident)
-            for (long t = chunk; t <= auto_max + 8 * kTile; t += kTile) {
-                const long left = resident - chunk_slots(max_dist, (int)t);
-                if (left < 1) continue;
-                long tp = ((max_prox + left - 1) / left + kTile - 1) / kTile * kTile;
-                if (tp < min_chunk) tp = min_chunk;
-                if (tp > 2 * t) continue;
-                chunk = t;
-                chunk_p = tp;
-                break;
-            }
-        plan_t r;
-        r.chunk = chunk; r.chunk_p = chunk_p;
-        r.max_nd = chunk_slots(max_dist, (int)chunk);
-        r.nc = r.max_nd + chunk_slots(max_prox, (int)chunk_p);
-        return r;
-    };
-    // Merge inside the streaming kernel only where the launch is about one resident round of workgroups:
-    // a workgroup waits for its arrival to be counted before it leaves, and in a launch of several rounds that wait
-    // keeps the next workgroup from starting (measured: 4 sequences of 128K tokens 13.1 ms per step against 12.0 ms
-    // with the separate merge kernel).  Such launches run workgroups of 8 waves, all others of kWaves.
-    // 0: separate combine kernel; 1: the last workgroup of a (sequence, kv head)
-    // pair merges; 2: 1 + the cache update; 3: the cache update, separate combine kernel.
-    plan_t pl = plan(fuse_waves(1));
-    const bool one_round = (size_t)pl.nc * (size_t)npairs <= (size_t)cus * 5 / 4;
-    const bool merge_inside = !scores && c->fused_merge && one_round;
-    if (!merge_inside) pl = plan(kWaves);
-    p.hot.chunk = (int)(pl.chunk | (pl.chunk_p << 16));
+    const pod_decode_plan_t pl = pod_plan_decode(cus, B, ly.Hkv, ly.P, max_len, c->tune_chunk, c->tune_chunk_prox, scores != nullptr,
+                                                 scores && !lowest_all && tau >= 0.f, c->fused_merge != 0);
+    const bool merge_inside = pl.merge_inside;
+    p.hot.chunk = (int)((unsigned)pl.chunk | ((unsigned)pl.chunk_p << 16));
     p.hot.max_nd = pl.max_nd;
     p.hot.nc = pl.nc;
     const size_t NC = (size_t)p.hot.nc + (step ? 1 : 0); // partial slots per query head (a step keeps one more)

@@ -119,6 +119,11 @@ int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, vo
 // step != NULL: a decode step (the new token's cache update inside the same launch); ctx is then NULL and the
 // lengths in the host mirror are those before the update.
 struct pod_step_args { const void *k_new, *v_new; const int32_t *positions; };
+// the split-K plan of a decode launch (host logic, pod_decode.hip): waves per workgroup, tokens per distant and per
+// proximal piece, distant pieces and all pieces per (sequence, kv head) pair, whether the partials are merged inside
+struct pod_decode_plan_t { int waves, chunk, chunk_p, max_nd, nc; bool merge_inside; };
+pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, int env_chunk, int env_chunk_prox, bool scores,
+                                  bool small_prox, bool fused_allowed);
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
                       void *scores, float tau, void *out, hipStream_t st, const pod_step_args *step = nullptr);
