@@ -3,9 +3,11 @@
 // One query token per sequence (Eq. 3 of the paper with i = n-1) and one joint softmax over
 // proximal and distant tokens (Eq. 4 / appendix derivation).  The token axis of every
 // (sequence, kv head) pair is cut in chunks; a workgroup reduces one chunk to a partial
-// (running max m, normaliser l, unnormalised output acc) and a second kernel merges the
-// partials.  The merge of two partials is exactly the paper's gate: with l_P, l_D the two
-// normalisers brought to a common max, g = l_P / (l_P + l_D).
+// (running max m, normaliser l, unnormalised output acc) and the partials are merged by the
+// last workgroup of the pair to finish (launches of about one resident round of workgroups) or
+// by a second kernel (larger launches).  The merge of two partials is exactly the paper's gate:
+// with l_P, l_D the two normalisers brought to a common max, g = l_P / (l_P + l_D).
+// A decode step (pod_decode_step) also performs the new token's cache update inside the launch.
 //
 // The kernel is bound by streaming K and V rows from HBM once, so the design goals are
 // (1) every global load instruction reads whole contiguous rows, (2) enough loads in flight
@@ -40,7 +42,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4; // native 128-bit vector (plain loads/stores, no struct copies)
 
-constexpr int kWaves = 4;          // waves per workgroup
+constexpr int kWaves = 4;          // waves per workgroup ...
 // ... but 8 where the last workgroup of a (sequence, kv head) pair merges the partials: that merge is one CU reading
 // every partial of the pair, which goes the faster the fewer and larger the pieces are and the more waves read
 // (measured, one workgroup reading 128 KB it finds in the L2: 4 waves 1.7 us, 8 waves 0.9 us).
