@@ -204,10 +204,11 @@ int pod_decode_attention(pod_cache *cache, int layer, const void *q, const void 
  * One decode step of a layer in one launch: pod_cache_append(layer, k_new, v_new, positions) followed by
  * pod_decode_attention(layer, q, q_shared, context_lens = positions + 1): same cache contents afterwards
  * (bit for bit) and the same attention (Eq. 3 + Eq. 4 over the tokens including the new one).  The kernel
- * walks the rows held before the call; one more workgroup per (sequence, kv head) takes the new token
+ * walks the rows held before the call; one workgroup per (sequence, kv head) also takes the new token
  * (proximal: this layer's query and the new key) and the token it displaces from the recent window
- * (distant from now on: the key the block's lowest layer holds for it, with that layer's query),
- * performs the cache update, and the last workgroup to finish merges the partial results.
+ * (distant from now on: the key the block's lowest layer holds for it, with that layer's query) and
+ * performs the cache update.  Where the launch is about one resident round of workgroups the last
+ * workgroup to finish merges the partial results; larger launches are followed by the merging kernel.
  *   k_new, v_new : dev bf16 [B][Hkv][d];  positions : dev int32 [B], as in pod_cache_append
  *   q, q_shared, scale, workspace, out : as in pod_decode_attention
  *   max_context_len : host upper bound on positions + 1; 0 = the host mirror's maximum + 1
@@ -250,8 +251,8 @@ int pod_cache_launch_info(const pod_cache *cache, int32_t info[4]);
  * a caller's workspace.  The call allocates and frees nothing.
  *  - POD_ERR_CAPACITY if this call's launch needs more than the 16 MiB: it needs
  *    4 * B * num_q_heads * chunks * (head_dim + 2) bytes, chunks = the split-K pieces of the longest
- *    sequence (128 to 1024 tokens each).  With 32 query heads x 128: batch 1 at 32K tokens takes
- *    1.1 MB, 16 sequences of up to 32K tokens 8.8 MB, 4 sequences of 128K tokens 8.6 MB.  Larger
+ *    sequence (pod_decode_plan gives their number).  With 32 query heads x 128: batch 1 at 32K tokens takes
+ *    0.6 MB, 16 sequences of up to 32K tokens 8.8 MB, 4 sequences of 128K tokens 8.6 MB.  Larger
  *    launches go through pod_decode_attention.
  *  - Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (other
  *    streams, other caches, other host threads) race; issue them in order on one stream.
