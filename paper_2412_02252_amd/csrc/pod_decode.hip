@@ -844,12 +844,13 @@ __device__ void merge_and_store_split(const decode_params &p, const decode_hot &
                 for (int e = 0; e < VEC; ++e) a[e] *= alpha;
 #pragma unroll
                 for (int k = 0; k < CAP; ++k) {
-                    if (first + k * NGW * split >= nv) break;
-                    float f = lane_value(w, k * NGW);     // the weight of this lane group's k-th row
+                    if (first + k * NGW * split < nv) {       // (wave-uniform; rows past the end were not loaded)
+                        float f = lane_value(w, k * NGW);     // the weight of this lane group's k-th row
 #pragma unroll
-                    for (int gg = 1; gg < NGW; ++gg) f = g == gg ? lane_value(w, k * NGW + gg) : f;
+                        for (int gg = 1; gg < NGW; ++gg) f = g == gg ? lane_value(w, k * NGW + gg) : f;
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) a[e] += f * ak[k][e];
+                        for (int e = 0; e < VEC; ++e) a[e] += f * ak[k][e];
+                    }
                 }
                 m_run = m_new;
             }
