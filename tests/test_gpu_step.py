@@ -234,3 +234,25 @@ def test_merge_inside_the_launch_with_many_pieces_per_pair(d, Hq, Hkv, n):
     for layer in range(2):
         c.assert_cache_equal(layer, 0)
     c.gpu.pod_cache_check()
+
+
+def test_pairs_that_do_not_divide_over_the_xcds_evenly():
+    """13 sequences x 5 kv heads = 65 (sequence, kv head) pairs on 8 XCDs: the XCD-local hand-off is still used (the
+    one-dimensional launch is padded to 72 pair positions, the surplus workgroups leave at once), ragged lengths,
+    steps and plain decode."""
+    S, W, B = 8, 56, 13
+    c = Case(2, 2, 10, 5, 64, S, W, B, 700, seed=511)
+    lens = [20 + (97 * b) % 640 for b in range(B)]
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            c.fill(layer, b, n)
+    for layer in range(2):
+        assert_close(c.decode(layer, lens), c.decode_ref(layer, lens), f"decode layer {layer}")
+    for s in range(2):
+        pos = [n + s for n in lens]
+        for layer in range(2):
+            assert_close(c.step(layer, pos), c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+    for b in (0, 6, 12):
+        c.assert_cache_equal(0, b)
+        c.assert_cache_equal(1, b)
+    c.gpu.pod_cache_check()
