@@ -221,6 +221,24 @@ int pod_decode_step(pod_cache *cache, int layer, const void *k_new, const void *
                     void *workspace, size_t workspace_bytes, void *out, void *stream);
 
 /*
+ * pod_decode_step with score reuse (the reading of Eq. 3 line 3 in which a block's upper layers take the lowest layer's
+ * distant attention scores instead of recomputing them from the shared keys): pod_cache_append(layer, ...) followed by
+ * pod_decode_attention_reuse(layer, q, context_lens = positions + 1, ..., scores), same cache contents and the same
+ * attention.  Call it for the block's lowest layer first (it writes the scaled distant logits of this token's query
+ * into `scores`, among them the logit of the token the new one displaces from the window), then for the block's
+ * upper layers with the same `scores` (they stream values, proximal keys and those logits only).
+ * Where a plain pod_decode_step would merge inside its launch and all kv heads are of one kind at this layer, the step is
+ * one launch; otherwise the library runs the cache update, a one-thread-per-sequence kernel that forms the context
+ * lengths, and the score-reuse decode launches.  Arguments as in pod_decode_step and pod_decode_attention_reuse.
+ * Errors and device-side checks as there; logits left by this call carry no distant sums, so a later
+ * pod_decode_attention_gated on an upper layer refuses them (flag) - use pod_decode_attention_gated at the lowest layer
+ * for that.
+ */
+int pod_decode_step_reuse(pod_cache *cache, int layer, const void *k_new, const void *v_new, const void *q,
+                          const int32_t *positions, int B, int max_context_len, float scale, void *workspace,
+                          size_t workspace_bytes, void *scores, size_t scores_bytes, void *out, void *stream);
+
+/*
  * Where the decode kernels take sequence lengths from.  0 (default): batches of up to 256
  * sequences pass the host mirror's lengths as kernel arguments (the shortest way to the first
  * load; the device-side arrays are still compared with them).  1: only from the device arrays the

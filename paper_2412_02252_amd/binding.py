@@ -24,7 +24,7 @@ EXPORTS = [
     "pod_group_layers", "pod_layer_similarity",
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
-    "pod_decode_plan",
+    "pod_decode_plan", "pod_decode_step_reuse",
 ]
 
 
@@ -75,6 +75,7 @@ def load():
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
         "pod_decode_step": [vp, C.c_int, vp, vp, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
+        "pod_decode_step_reuse": [vp, C.c_int, vp, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, C.c_size_t, vp, vp],
         "pod_cache_set_length_source": [vp, C.c_int],
         "pod_cache_launch_info": [vp, C.POINTER(C.c_int32)],
         "pod_decode_attention_static": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, vp],
@@ -316,6 +317,15 @@ class PodCache:
                                       _ptr(q, torch.bfloat16), _ptr(q_shared, torch.bfloat16), _ptr(positions, torch.int32),
                                       q.shape[0], max_context_len, scale, self.workspace.data_ptr(), self.workspace.numel(),
                                       _ptr(out, torch.bfloat16), _stream()))
+        return out
+
+    def pod_decode_step_reuse(self, layer, k_new, v_new, q, positions, scale, scores, out=None, max_context_len=0):
+        if out is None:
+            out = torch.empty_like(q)
+        _check(load().pod_decode_step_reuse(self.handle, layer, _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+                                            _ptr(q, torch.bfloat16), _ptr(positions, torch.int32), q.shape[0], max_context_len,
+                                            scale, self.workspace.data_ptr(), self.workspace.numel(), scores.data_ptr(),
+                                            scores.numel() * scores.element_size(), _ptr(out, torch.bfloat16), _stream()))
         return out
 
     def pod_cache_launch_info(self):

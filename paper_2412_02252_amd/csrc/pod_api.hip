@@ -622,6 +622,63 @@ extern "C" int pod_decode_step(pod_cache *cache, int layer, const void *k_new, c
     return POD_OK;
 }
 
+extern "C" int pod_decode_step_reuse(pod_cache *cache, int layer, const void *k_new, const void *v_new, const void *q,
+                                     const int32_t *positions, int B, int max_context_len, float scale, void *workspace,
+                                     size_t workspace_bytes, void *scores, size_t scores_bytes, void *out, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (!k_new || !v_new || !q || !positions || !out || !workspace || !scores)
+        return pod_fail(POD_ERR_INVALID_ARG, "k_new, v_new, q, positions, workspace, scores and out must not be NULL");
+    if ((uintptr_t)scores % 256) return pod_fail(POD_ERR_INVALID_ARG, "scores must be 256-byte aligned");
+    if (B < 1 || B > ly.B) return pod_fail(POD_ERR_INVALID_ARG, "B = %d outside [1, max_batch = %d]", B, ly.B);
+    if (workspace_bytes < pod_decode_workspace_bytes(ly))
+        return pod_fail(POD_ERR_CAPACITY, "workspace has %zu bytes, needs %zu", workspace_bytes, pod_decode_workspace_bytes(ly));
+    const size_t need = pod_score_header_bytes(ly) + (size_t)ly.B * ly.Hq * pod_score_stride(ly) * sizeof(float);
+    if (scores_bytes < need) return pod_fail(POD_ERR_CAPACITY, "score buffer has %zu bytes, needs %zu", scores_bytes, need);
+    if (max_context_len < 0 || max_context_len > ly.maxctx)
+        return pod_fail(POD_ERR_INVALID_ARG, "max_context_len %d outside [0, %d]", max_context_len, ly.maxctx);
+    const pod_step_args step = {k_new, v_new, positions};
+    int64_t *len = cache->host_len + (size_t)layer * ly.B;
+    if (cache->device_lengths) {
+        if (max_context_len < 1) return pod_fail(POD_ERR_INVALID_ARG, "with lengths taken from the device, max_context_len must be given");
+    } else {
+        int64_t longest = 0;
+        for (int b = 0; b < B; ++b) {
+            if (len[b] >= ly.maxctx)
+                return pod_fail(POD_ERR_CAPACITY, "slot %d at layer %d already holds max_context = %d tokens", b, layer, ly.maxctx);
+            longest = len[b] + 1 > longest ? len[b] + 1 : longest;
+        }
+        // the lowest layer of every head's block must have taken this token (and written its logits) already
+        for (int h = 0; h < ly.Hkv; ++h) {
+            const int la = cache->lowest[(size_t)layer * ly.Hkv + h];
+            const int64_t *low = cache->host_len + (size_t)la * ly.B;
+            for (int b = 0; b < B && la != layer; ++b)
+                if (len[b] + 1 > ly.P && low[b] != len[b] + 1)
+                    return pod_fail(POD_ERR_STATE, "slot %d: layer %d would hold %lld tokens but layer %d, the lowest of kv head %d's block, holds %lld",
+                                    b, layer, (long long)len[b] + 1, la, h, (long long)low[b]);
+        }
+        if (max_context_len == 0) max_context_len = (int)longest;
+    }
+    rc = pod_launch_decode(cache, layer, q, nullptr, nullptr, B, max_context_len, scale, workspace, workspace_bytes, scores, -1.f, out,
+                           (hipStream_t)stream, &step);
+    if (rc == POD_NOT_FUSED) {
+        // this launch shape (several rounds of workgroups, or kv heads of both kinds at this layer) runs the step as
+        // the cache update followed by the score-reuse decode call; the context lengths are made on the device
+        int32_t *ctx = (int32_t *)((char *)scores + pod_score_ctx_offset_bytes(ly));
+        rc = pod_cache_append(cache, layer, k_new, v_new, positions, B, stream);
+        if (rc) return rc;
+        rc = pod_launch_ctx_from_positions(positions, ctx, B, (hipStream_t)stream);
+        if (rc) return rc;
+        return decode_with_scores(cache, layer, q, ctx, B, max_context_len, scale, workspace, workspace_bytes, scores, scores_bytes,
+                                  -1.f, out, stream);
+    }
+    if (rc) return rc;
+    for (int b = 0; b < B; ++b) len[b] += 1;
+    return POD_OK;
+}
+
 extern "C" int pod_layer_similarity(const float *att, int num_layers, int num_heads, int rows, int n, float *sim,
                                     void *stream)
 {

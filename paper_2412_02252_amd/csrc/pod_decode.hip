@@ -298,7 +298,7 @@ __device__ inline int arrive_last(unsigned long long *ticket, int expected)
 template <int D, bool LOC, int NW>
 __device__ void merge_and_store(const decode_params &p, const decode_hot &hot, int b, int h, int nd, int np, bool special, bool valid,
                                 bool bad);
-template <int D, bool LOC, int NW>
+template <int D, bool LOC, int NW, int MODE>
 __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg);
 
 // FUSE 0: partials only, decode_combine_kernel follows.  FUSE 1 (MODE 0 only): the last workgroup of a (sequence, kv
@@ -311,7 +311,8 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 template <int D, int MODE, int FUSE = 0, bool LOC = false, int NW = fuse_waves(FUSE)>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_params p)
 {
-    static_assert(FUSE == 0 || MODE == 0, "the fused forms serve the plain mode");
+    static_assert(FUSE == 0 || MODE == 0 || (FUSE == 2 && (MODE == 1 || MODE == 2)),
+                  "the fused forms serve the plain mode and, as a decode step in one launch, score reuse");
     constexpr bool STEP = FUSE == 2 || FUSE == 3, MERGE = FUSE == 1 || FUSE == 2;
     static_assert(!LOC || MERGE, "the XCD-local launch shape serves the fused merge");
     constexpr int CPR = D / 8;        // 16-byte pieces per row
@@ -391,7 +392,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     // for both partials, also when the cache was empty and it has no piece of its own
     const bool hosts_step = STEP && c == max_nd;
     const int expected = nd_eff + (FUSE == 2 && np_eff == 0 ? 1 : np_eff);
-    if (hosts_step) step_workgroup<D, LOC, NW>(p, hot, b, h, n, head_arg);
+    if (hosts_step) step_workgroup<D, LOC, NW, MODE>(p, hot, b, h, n, head_arg);
     const bool distant = c < max_nd;
     const int region_len = distant ? n_dist : n_prox;
     const int chunk = distant ? (hot.chunk & 0xffff) : chunk_p;
@@ -410,10 +411,14 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     // two kinds is empty and is not launched.
     if (MODE == 1 && head_arg >= 0) return;
     if (MODE >= 2 && head_arg < 0) return;
-    if (MODE == 1 && c == 0 && threadIdx.x == 0) { // tag this head's logits: which token, which block's keys
-        p.score_hdr[4 * ((size_t)b * hkv + h)] = n;
+    // (a step tags from the workgroup that hosts the step: the first distant piece may have no row to walk yet)
+    if (MODE == 1 && (STEP ? hosts_step : c == 0) && threadIdx.x == 0) { // tag this head's logits: which token, which block's keys
+        p.score_hdr[4 * ((size_t)b * hkv + h)] = STEP ? n + 1 : n;   // (the context the attention is over)
         p.score_hdr[4 * ((size_t)b * hkv + h) + 1] = head_arg & 0x7fffffff;
         p.score_hdr[4 * ((size_t)b * hkv + h) + 2] = __float_as_int(hot.scale_log2e);
+        // word 3: 1 once the heads' distant (maximum, sum) pairs are there too (decode_combine_kernel leaves them; the
+        // merge inside the launch does not), which is what a gated upper layer needs besides the logits
+        if (MERGE) p.score_hdr[4 * ((size_t)b * hkv + h) + 3] = 0;
     }
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
@@ -654,8 +659,17 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
                 const size_t tile = (size_t)(t0 >> 5);
                 const gf4_w dst = (gf4_w)(p.scores + ((size_t)b * hkv + h) * p.score_stride * hot.rep) +
                                   (tile * 4 * hot.rep + (size_t)j * hot.rep + m16) * 2;
-                dst[0] = f32x4{sc[0], sc[1], sc[2], sc[3]};   // tokens past the chunk carry the mask value
-                dst[1] = f32x4{sc[4], sc[5], sc[6], sc[7]};
+                if (!STEP || t0 + kTile <= end) {
+                    dst[0] = f32x4{sc[0], sc[1], sc[2], sc[3]};   // tokens past the chunk carry the mask value
+                    dst[1] = f32x4{sc[4], sc[5], sc[6], sc[7]};
+                } else {   // a step's last, partly filled tile: the element behind the last row is step_workgroup's to store
+                    typedef __attribute__((address_space(1))) float *gf_w;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (t0 + 4 * j + i < end) ((gf_w)dst)[i] = sc[i];
+                        if (t0 + 16 + 4 * j + i < end) ((gf_w)dst)[4 + i] = sc[4 + i];
+                    }
+                }
             }
         }
         softmax_pv(sc, vcur);
@@ -727,6 +741,14 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
             if (v_ctx == 0) valid = false;
             else if (!valid) {}
             else if (v_ctx < 0 || v_ctx > p.maxctx || v_ctx > p.max_len || v_ctx != v_dev || (v_ctx > prows && v_low != v_ctx) || v_ctx != n) {
+                valid = false; bad = true;
+            }
+        }
+        if constexpr (MODE == 2) { // the distant logits must be those of this token and of the head's block
+            const size_t tag = 4 * ((size_t)b * hkv + h);
+            const int n_ctx = STEP ? n + 1 : n;
+            if (n_ctx > prows && (p.score_hdr[tag] != n_ctx || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff) ||
+                                  p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e))) {
                 valid = false; bad = true;
             }
         }
@@ -923,7 +945,10 @@ __device__ inline float dot8_bf16(u32x4 a, u32x4 b)
 // workgroups walk the rows held before the call and leave the ring slot out.  (4) The last of a sequence's kv heads
 // to finish advances the stored length; (5) the partial (in the slot behind the pieces' slots) takes part in the merge
 // like any other.
-template <int D, bool LOC, int NW>
+// With score reuse (MODE 1: this layer is the lowest of the block; MODE 2: an upper layer) the displaced token's
+// distant logit is computed once, by the lowest layer, which stores it at that token's place in the score tiles (the
+// workgroups that walk the rows held before the call leave that place alone); the block's upper layers read it there.
+template <int D, bool LOC, int NW, int MODE>
 __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, int b, int h, int pos, int head_arg)
 {
     constexpr int CPR = D / 8;
@@ -948,18 +973,27 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
     if (demote) {
         ko = proxK[i];
         vo = proxV[i];
-        kd = low_head ? ko : dK[i];
+        if (MODE != 2) kd = low_head ? ko : dK[i];
     }
     const pod_bf16 *qd_src = (hot.q_shared && !low_head) ? hot.q_shared : hot.q;
     const size_t stride = (size_t)hot.nc + 1;
     for (int r = wave; r < hot.rep; r += NW) {
         const size_t head = (size_t)b * hot.hq + (size_t)h * hot.rep + r;
         const u32x4 qn = ((gvec_ptr)(hot.q + head * D))[i], qd = ((gvec_ptr)(qd_src + head * D))[i];
-        float sn = lane < CPR ? dot8_bf16(qn, kn) : 0.f, sd = (lane < CPR && demote) ? dot8_bf16(qd, kd) : 0.f;
+        float sn = lane < CPR ? dot8_bf16(qn, kn) : 0.f, sd = (MODE != 2 && lane < CPR && demote) ? dot8_bf16(qd, kd) : 0.f;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) { sn += __shfl_xor(sn, off); sd += __shfl_xor(sd, off); }
         sn *= hot.scale_log2e;
         sd = demote ? sd * hot.scale_log2e : kNegBig;
+        if constexpr (MODE == 1 || MODE == 2) {
+            if (demote) {   // distant row t of the score tiles: tile t / 32, element (lane group j, half, i) of query head r
+                const int tok = (int)(t & 31);
+                float *slot = p.scores + pair * p.score_stride * hot.rep +
+                              ((((t >> 5) * 4 + ((tok & 15) >> 2)) * hot.rep + r) * 2 + (tok >> 4)) * 4 + (tok & 3);
+                if (MODE == 1) { if (lane == 0) *slot = sd; }
+                else sd = *slot;
+            }
+        }
         const float m = fmaxf(sn, sd);
         const float pn = exp2f(sn - m), pd = demote ? exp2f(sd - m) : 0.f;
         const size_t ps = head * stride + hot.nc;
@@ -1060,6 +1094,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
         if (threadIdx.x == 0) {
             p.gate_d[((size_t)b * hot.hq + head) * 2] = dl.x;
             p.gate_d[((size_t)b * hot.hq + head) * 2 + 1] = dl.y;
+            if (head % hot.rep == 0) p.score_hdr[4 * ((size_t)b * hot.hkv + head / hot.rep) + 3] = 1;
         }
     }
     float m_run = kNegBig, l_run = 0.f;
@@ -1119,7 +1154,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     if (p.mode != 0 && !low && n > hot.prows) { // the distant logits must be those of this token and of the head's block
         const size_t tag = 4 * ((size_t)b * hot.hkv + head / hot.rep);
         if (p.score_hdr[tag] != n || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff) ||
-            p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e)) { bad = true; n = 0; }
+            p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e) || (p.mode == 3 && p.score_hdr[tag + 3] != 1)) { bad = true; n = 0; }
     }
     uint2 res = make_uint2(0u, 0u);
     if (step ? n >= 0 : n > 0) {
@@ -1171,6 +1206,22 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restric
     if ((acc.x ^ acc.y) == 0x9e3779b9u && (acc.z ^ acc.w) == 0x7f4a7c15u) pod_stream_read_sink = acc.x; // practically never
 }
 } // namespace
+
+namespace {
+__global__ void ctx_from_positions_kernel(const int32_t *positions, int32_t *ctx, int B)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) ctx[b] = positions[b] + 1;
+}
+} // namespace
+
+// context_lens = positions + 1 on the device, for a step that runs as pod_cache_append + a decode call
+int pod_launch_ctx_from_positions(const int32_t *positions, int32_t *ctx, int B, hipStream_t st)
+{
+    hipLaunchKernelGGL(ctx_from_positions_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, positions, ctx, B);
+    POD_HIP_TRY(hipGetLastError());
+    return POD_OK;
+}
 
 int pod_launch_stream_read(pod_cache *c, const void *buf, size_t bytes, hipStream_t st)
 {
@@ -1259,14 +1310,18 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
 
 size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
 
-// header of the score buffer: int32 [B][Hkv][4] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
+// header of the score buffer: int32 [B][Hkv][4] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags,
+// int32 [B] context lengths of a step that runs as separate calls
 static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hkv * 4 * sizeof(int32_t) + 255) / 256 * 256; }
 static size_t score_gate_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * 2 * sizeof(float) + 255) / 256 * 256; }
+static size_t score_skip_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * sizeof(int32_t) + 255) / 256 * 256; }
+static size_t score_ctx_bytes(const pod_layout &ly) { return ((size_t)ly.B * sizeof(int32_t) + 255) / 256 * 256; }
 size_t pod_score_skip_offset_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly); }
-size_t pod_score_header_bytes(const pod_layout &ly)
+size_t pod_score_ctx_offset_bytes(const pod_layout &ly)
 {
-    return score_tag_bytes(ly) + score_gate_bytes(ly) + ((size_t)ly.B * ly.Hq * sizeof(int32_t) + 255) / 256 * 256;
+    return score_tag_bytes(ly) + score_gate_bytes(ly) + score_skip_bytes(ly);
 }
+size_t pod_score_header_bytes(const pod_layout &ly) { return pod_score_ctx_offset_bytes(ly) + score_ctx_bytes(ly); }
 
 // The split-K plan of a decode launch: host logic only, a function of the shape (also exported for the CPU tests).
 // Chunk size, for workgroups of nw waves (8 / nw of them fit a CU).  Small problems (config 2: 262K rows) want
@@ -1276,8 +1331,10 @@ size_t pod_score_header_bytes(const pod_layout &ly)
 // Never below one tile per wave, so the partials stay a small fraction of the K/V bytes.
 // env_chunk, env_chunk_prox: tuning / test overrides (0 = none); scores: a score-reuse or gated call; small_prox: the
 // gated form's proximal launch.
+// reader: a score-reuse step of an upper layer in one launch: its distant pieces stream values and logits but no keys,
+// about half the bytes per token of a proximal piece, so they take about twice the tokens.
 pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, int env_chunk, int env_chunk_prox, bool scores,
-                                  bool small_prox, bool fused_allowed)
+                                  bool small_prox, bool fused_allowed, bool reader)
 {
     const int npairs = B * Hkv;
     const long rows = (long)max_len * npairs;
@@ -1315,6 +1372,21 @@ pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, i
                 chunk_p = tp;
                 break;
             }
+        if (reader && env_chunk <= 0 && env_chunk_prox <= 0 && resident >= 2) {
+            // one resident round whose longest piece (in bytes) is as short as possible: a distant token counts 17 / 32
+            // of a proximal one (values + 4 bytes of logit per query head against keys + values)
+            long best = -1, best_t = chunk, best_tp = chunk_p;
+            for (long t = min_chunk; t <= 4096; t += kTile) {
+                const long left = resident - chunk_slots(max_dist, (int)t);
+                if (left < 1) continue;
+                long tp = ((max_prox + left - 1) / left + kTile - 1) / kTile * kTile;
+                if (tp < min_chunk) tp = min_chunk;
+                if (tp > 8192) continue;
+                const long cost = t * 17 > tp * 32 ? t * 17 : tp * 32;
+                if (best < 0 || cost < best) { best = cost; best_t = t; best_tp = tp; }
+            }
+            if (best >= 0) { chunk = best_t; chunk_p = best_tp; }
+        }
         pod_decode_plan_t r;
         r.waves = nw;
         r.chunk = (int)chunk; r.chunk_p = (int)chunk_p;
@@ -1394,9 +1466,14 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
-    const pod_decode_plan_t pl = pod_plan_decode(cus, B, ly.Hkv, ly.P, max_len, c->tune_chunk, c->tune_chunk_prox, scores != nullptr,
-                                                 scores && !lowest_all && tau >= 0.f, c->fused_merge != 0);
+    // A score-reuse step runs in one launch where a plain step would and every kv head is of one kind at this layer
+    // (all write the logits or all read them); otherwise the caller runs it as separate calls.
+    const bool reuse_step = step && scores;
+    if (reuse_step && (tau >= 0.f || (lowest_any && !lowest_all))) return POD_NOT_FUSED;
+    const pod_decode_plan_t pl = pod_plan_decode(cus, B, ly.Hkv, ly.P, max_len, c->tune_chunk, c->tune_chunk_prox, scores && !reuse_step,
+                                                 scores && !lowest_all && tau >= 0.f, c->fused_merge != 0, reuse_step && !lowest_any);
     const bool merge_inside = pl.merge_inside;
+    if (reuse_step && !merge_inside) return POD_NOT_FUSED;
     p.hot.chunk = (int)((unsigned)pl.chunk | ((unsigned)pl.chunk_p << 16));
     p.hot.max_nd = pl.max_nd;
     p.hot.nc = pl.nc;
@@ -1427,7 +1504,11 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // score reuse: the writing launch for the kv heads whose block starts at this layer, the reading launch(es) for
     // the others (workgroups of the other kind leave at once); a gated read is two launches, proximal chunks first
 #define POD_LAUNCH_ALL(DD)                                                                   \
-    if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
+    if (reuse_step && lowest_all && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
+    else if (reuse_step && lowest_all) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);    \
+    else if (reuse_step && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p);     \
+    else if (reuse_step) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);                  \
+    else if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
     else if (fuse == 1 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1, true>), grid, dim3(fuse_waves(1) * 64), 0, st, p); \
     else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);    \
     else if (fuse == 3) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 3>), grid, dim3(kWaves * 64), 0, st, p);               \

@@ -109,6 +109,20 @@ class Case:
             self.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), positions)
         return out
 
+    def step_reuse(self, layer, positions, scores, max_context_len=0):
+        """pod_decode_step_reuse on the GPU (the block's lowest layer must take the token first) and the plain append on
+        the oracle's model; returns the GPU output for contexts positions + 1."""
+        k = torch.cat([self.keys(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)]).contiguous()
+        v = torch.cat([self.values(layer, b, 1, self.dev, pos0=p) for b, p in enumerate(positions)]).contiguous()
+        q = self.decode_queries(layer, [p + 1 for p in positions], self.dev)
+        pos = torch.tensor(positions, dtype=torch.int32, device=self.dev)
+        out = self.gpu.pod_decode_step_reuse(layer, k, v, q, pos, self.scale, scores, max_context_len=max_context_len)
+        if self.cpu is not None:
+            kc = torch.cat([self.keys(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            vc = torch.cat([self.values(layer, b, 1, "cpu", pos0=p) for b, p in enumerate(positions)])
+            self.cpu.append(layer, gen.bf16_bits(kc), gen.bf16_bits(vc), positions)
+        return out
+
     def decode_queries(self, layer, ctx, device):
         """Query of the token at position ctx[b]-1 of each sequence: [B][Hq][d]."""
         return torch.cat([self.queries(layer, b, 1, device, pos0=max(n, 1) - 1) for b, n in enumerate(ctx)]).contiguous()
