@@ -37,7 +37,7 @@ def _step_inputs(c, n0, steps):
     return ins
 
 
-@pytest.mark.parametrize("variant", ["plain", "reuse", "gated"])
+@pytest.mark.parametrize("variant", ["plain", "reuse", "gated", "step_reuse"])
 def test_decode_steps_in_a_graph_equal_eager_steps_on_every_replay(variant):
     n0, steps = [700, 150], 3
     c = Case(2, 2, 8, 2, 128, 8, 64, 2, 800, seed=900)
@@ -45,6 +45,11 @@ def test_decode_steps_in_a_graph_equal_eager_steps_on_every_replay(variant):
     scores = c.gpu.new_score_buffer()
 
     def run(e):
+        if variant == "step_reuse":
+            for layer in range(2):
+                c.gpu.pod_decode_step_reuse(layer, e[f"k{layer}"], e[f"v{layer}"], e[f"q{layer}"], e["pos"], c.scale, scores,
+                                            out=e[f"o{layer}"], max_context_len=e["n"])
+            return
         for layer in range(2):
             c.gpu.pod_cache_append(layer, e[f"k{layer}"], e[f"v{layer}"], e["pos"])
         for layer in range(2):
