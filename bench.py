@@ -118,11 +118,11 @@ def run_large(workload, K, Wm, variant):
                 cache.pod_decode_step(l, kn[s * L + l], vn[s * L + l], q[l], q[l - l % G] if l % G else None, pos[s], scale,
                                       out=out, max_context_len=bound)
                 continue
-            cache.pod_cache_append(l, kn[s * L + l], vn[s * L + l], pos[s])
             if variant == "reuse":  # upper layers of a block take the lowest layer's distant logits instead of its keys
-                cache.pod_decode_attention_reuse(l, q[l], ctx[s], scale, scores, out=out, max_context_len=bound)
-            else:
-                cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out, max_context_len=bound)
+                cache.pod_decode_step_reuse(l, kn[s * L + l], vn[s * L + l], q[l], pos[s], scale, scores, out=out, max_context_len=bound)
+                continue
+            cache.pod_cache_append(l, kn[s * L + l], vn[s * L + l], pos[s])
+            cache.pod_decode_attention(l, q[l], q[l - l % G] if l % G else None, ctx[s], scale, out=out, max_context_len=bound)
 
     for s in range(Wm):
         run_step(s)
@@ -142,7 +142,7 @@ def run_large(workload, K, Wm, variant):
     nbytes = sum(sum(2 * (n + s + 1) * row for n in lens) * L for s in range(Wm, total))
     res = {"workload": name + "; step = one new token per sequence through 32 layers, " +
                        {"step": "one pod_decode_step launch per layer", "separate": "pod_cache_append + pod_decode_attention per layer",
-                        "reuse": "pod_cache_append + pod_decode_attention_reuse per layer"}[variant],
+                        "reuse": "one pod_decode_step_reuse launch per layer"}[variant],
            "launch": "eager", "steps": K, "warmup": Wm, "ms_per_step": stats(per_step), "bytes_per_step": nbytes // K}
     if variant == "reuse":
         # its own, smaller byte count: an upper layer reads V rows, proximal K rows and 4 B per (query head, distant

@@ -227,9 +227,9 @@ int pod_decode_step(pod_cache *cache, int layer, const void *k_new, const void *
  * attention.  Call it for the block's lowest layer first (it writes the scaled distant logits of this token's query
  * into `scores`, among them the logit of the token the new one displaces from the window), then for the block's
  * upper layers with the same `scores` (they stream values, proximal keys and those logits only).
- * Where a plain pod_decode_step would merge inside its launch and all kv heads are of one kind at this layer, the step is
- * one launch; otherwise the library runs the cache update, a one-thread-per-sequence kernel that forms the context
- * lengths, and the score-reuse decode launches.  Arguments as in pod_decode_step and pod_decode_attention_reuse.
+ * One streaming launch per layer (two for a layer whose kv heads are of both kinds under a head-wise block table),
+ * followed by the merging kernel where the launch is several rounds of workgroups.  Arguments as in pod_decode_step
+ * and pod_decode_attention_reuse.
  * Errors and device-side checks as there; logits left by this call carry no distant sums, so a later
  * pod_decode_attention_gated on an upper layer refuses them (flag) - use pod_decode_attention_gated at the lowest layer
  * for that.

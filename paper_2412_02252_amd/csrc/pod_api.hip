@@ -663,17 +663,6 @@ extern "C" int pod_decode_step_reuse(pod_cache *cache, int layer, const void *k_
     }
     rc = pod_launch_decode(cache, layer, q, nullptr, nullptr, B, max_context_len, scale, workspace, workspace_bytes, scores, -1.f, out,
                            (hipStream_t)stream, &step);
-    if (rc == POD_NOT_FUSED) {
-        // this launch shape (several rounds of workgroups, or kv heads of both kinds at this layer) runs the step as
-        // the cache update followed by the score-reuse decode call; the context lengths are made on the device
-        int32_t *ctx = (int32_t *)((char *)scores + pod_score_ctx_offset_bytes(ly));
-        rc = pod_cache_append(cache, layer, k_new, v_new, positions, B, stream);
-        if (rc) return rc;
-        rc = pod_launch_ctx_from_positions(positions, ctx, B, (hipStream_t)stream);
-        if (rc) return rc;
-        return decode_with_scores(cache, layer, q, ctx, B, max_context_len, scale, workspace, workspace_bytes, scores, scores_bytes,
-                                  -1.f, out, stream);
-    }
     if (rc) return rc;
     for (int b = 0; b < B; ++b) len[b] += 1;
     return POD_OK;

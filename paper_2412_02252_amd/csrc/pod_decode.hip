@@ -311,8 +311,8 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 template <int D, int MODE, int FUSE = 0, bool LOC = false, int NW = fuse_waves(FUSE)>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_params p)
 {
-    static_assert(FUSE == 0 || MODE == 0 || (FUSE == 2 && (MODE == 1 || MODE == 2)),
-                  "the fused forms serve the plain mode and, as a decode step in one launch, score reuse");
+    static_assert(FUSE == 0 || MODE == 0 || ((FUSE == 2 || FUSE == 3) && (MODE == 1 || MODE == 2)),
+                  "the fused forms serve the plain mode and, as a decode step, score reuse");
     constexpr bool STEP = FUSE == 2 || FUSE == 3, MERGE = FUSE == 1 || FUSE == 2;
     static_assert(!LOC || MERGE, "the XCD-local launch shape serves the fused merge");
     constexpr int CPR = D / 8;        // 16-byte pieces per row
@@ -338,6 +338,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     }
     const int n_host = load_hlen_arg(b);
     const int head_arg = load_head_arg(h);
+    // Score reuse with head-wise blocks: the writing launch (MODE 1) serves the kv heads for which this layer is
+    // the lowest of the block, the reading launches (MODE 2, 3, 4) the others; with uniform blocks one of the
+    // two kinds is empty and is not launched.  (Before anything else: a step's cache update belongs to one launch.)
+    if (MODE == 1 && head_arg >= 0) return;
+    if (MODE >= 2 && head_arg < 0) return;
     unsigned long long tr_t0 = 0, tr_t1 = 0, tr_t2 = 0;
     if (MERGE && p.trace) tr_t0 = wall_clock64();
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
@@ -406,19 +411,15 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     // are those of a real token, so the masked products stay finite)
     const int excl = (STEP && !distant && n >= prows) ? p.sink + (n - p.sink) % p.window : -1;
 
-    // Score reuse with head-wise blocks: the writing launch (MODE 1) serves the kv heads for which this layer is
-    // the lowest of the block, the reading launches (MODE 2, 3, 4) the others; with uniform blocks one of the
-    // two kinds is empty and is not launched.
-    if (MODE == 1 && head_arg >= 0) return;
-    if (MODE >= 2 && head_arg < 0) return;
     // (a step tags from the workgroup that hosts the step: the first distant piece may have no row to walk yet)
     if (MODE == 1 && (STEP ? hosts_step : c == 0) && threadIdx.x == 0) { // tag this head's logits: which token, which block's keys
         p.score_hdr[4 * ((size_t)b * hkv + h)] = STEP ? n + 1 : n;   // (the context the attention is over)
         p.score_hdr[4 * ((size_t)b * hkv + h) + 1] = head_arg & 0x7fffffff;
         p.score_hdr[4 * ((size_t)b * hkv + h) + 2] = __float_as_int(hot.scale_log2e);
-        // word 3: 1 once the heads' distant (maximum, sum) pairs are there too (decode_combine_kernel leaves them; the
-        // merge inside the launch does not), which is what a gated upper layer needs besides the logits
-        if (MERGE) p.score_hdr[4 * ((size_t)b * hkv + h) + 3] = 0;
+        // word 3: 1 once the heads' distant (maximum, sum) pairs are there too (decode_combine_kernel leaves them after a
+        // pod_decode_attention_reuse / _gated call; a step and the merge inside the launch do not), which is what a
+        // gated upper layer needs besides the logits
+        if (MERGE || STEP) p.score_hdr[4 * ((size_t)b * hkv + h) + 3] = 0;
     }
     // (pointers rebuilt from the raw argument words are generic; say they are global memory)
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
@@ -1089,7 +1090,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     int v_begin = 0;
     if (p.mode == 3 && !low && nd > 0 && p.skip[(size_t)b * hot.hq + head] != 0) v_begin = nd;
     // lowest layer of a score-reuse block: leave the distant maximum and sum for the gates of the upper layers
-    if (p.mode != 0 && low && xs == 0 && threadIdx.x < 64) {
+    if (p.mode != 0 && low && !step && xs == 0 && threadIdx.x < 64) {
         const float2 dl = merged_ml((const float *)ml, n > 0 ? nd : 0, (int)threadIdx.x);
         if (threadIdx.x == 0) {
             p.gate_d[((size_t)b * hot.hq + head) * 2] = dl.x;
@@ -1151,10 +1152,11 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
             n = 0;
         }
     }
-    if (p.mode != 0 && !low && n > hot.prows) { // the distant logits must be those of this token and of the head's block
+    const int n_ctx = step && n >= 0 ? n + 1 : n;   // the context the attention is over
+    if (p.mode != 0 && !low && n_ctx > hot.prows) { // the distant logits must be those of this token and of the head's block
         const size_t tag = 4 * ((size_t)b * hot.hkv + head / hot.rep);
-        if (p.score_hdr[tag] != n || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff) ||
-            p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e) || (p.mode == 3 && p.score_hdr[tag + 3] != 1)) { bad = true; n = 0; }
+        if (p.score_hdr[tag] != n_ctx || p.score_hdr[tag + 1] != (head_arg & 0x7fffffff) ||
+            p.score_hdr[tag + 2] != __float_as_int(hot.scale_log2e) || (p.mode == 3 && p.score_hdr[tag + 3] != 1)) { bad = true; n = step ? -1 : 0; }
     }
     uint2 res = make_uint2(0u, 0u);
     if (step ? n >= 0 : n > 0) {
@@ -1206,22 +1208,6 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restric
     if ((acc.x ^ acc.y) == 0x9e3779b9u && (acc.z ^ acc.w) == 0x7f4a7c15u) pod_stream_read_sink = acc.x; // practically never
 }
 } // namespace
-
-namespace {
-__global__ void ctx_from_positions_kernel(const int32_t *positions, int32_t *ctx, int B)
-{
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) ctx[b] = positions[b] + 1;
-}
-} // namespace
-
-// context_lens = positions + 1 on the device, for a step that runs as pod_cache_append + a decode call
-int pod_launch_ctx_from_positions(const int32_t *positions, int32_t *ctx, int B, hipStream_t st)
-{
-    hipLaunchKernelGGL(ctx_from_positions_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, positions, ctx, B);
-    POD_HIP_TRY(hipGetLastError());
-    return POD_OK;
-}
 
 int pod_launch_stream_read(pod_cache *c, const void *buf, size_t bytes, hipStream_t st)
 {
@@ -1310,18 +1296,12 @@ size_t pod_decode_workspace_bytes(const pod_layout &ly)
 
 size_t pod_score_stride(const pod_layout &ly) { return ((size_t)ly.Cd + kTile - 1) / kTile * kTile; } // whole tiles
 
-// header of the score buffer: int32 [B][Hkv][4] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags,
-// int32 [B] context lengths of a step that runs as separate calls
+// header of the score buffer: int32 [B][Hkv][4] tags, float [B][Hq][2] distant (max, sum), int32 [B][Hq] skip flags
 static size_t score_tag_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hkv * 4 * sizeof(int32_t) + 255) / 256 * 256; }
 static size_t score_gate_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * 2 * sizeof(float) + 255) / 256 * 256; }
 static size_t score_skip_bytes(const pod_layout &ly) { return ((size_t)ly.B * ly.Hq * sizeof(int32_t) + 255) / 256 * 256; }
-static size_t score_ctx_bytes(const pod_layout &ly) { return ((size_t)ly.B * sizeof(int32_t) + 255) / 256 * 256; }
 size_t pod_score_skip_offset_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly); }
-size_t pod_score_ctx_offset_bytes(const pod_layout &ly)
-{
-    return score_tag_bytes(ly) + score_gate_bytes(ly) + score_skip_bytes(ly);
-}
-size_t pod_score_header_bytes(const pod_layout &ly) { return pod_score_ctx_offset_bytes(ly) + score_ctx_bytes(ly); }
+size_t pod_score_header_bytes(const pod_layout &ly) { return score_tag_bytes(ly) + score_gate_bytes(ly) + score_skip_bytes(ly); }
 
 // The split-K plan of a decode launch: host logic only, a function of the shape (also exported for the CPU tests).
 // Chunk size, for workgroups of nw waves (8 / nw of them fit a CU).  Small problems (config 2: 262K rows) want
@@ -1466,14 +1446,13 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
 
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
-    // A score-reuse step runs in one launch where a plain step would and every kv head is of one kind at this layer
-    // (all write the logits or all read them); otherwise the caller runs it as separate calls.
+    // A score-reuse step: the step forms of the writing launch (kv heads whose block starts at this layer) and of
+    // the reading launch (the others); a layer with heads of both kinds takes both.  (No gated form.)
     const bool reuse_step = step && scores;
-    if (reuse_step && (tau >= 0.f || (lowest_any && !lowest_all))) return POD_NOT_FUSED;
+    if (reuse_step && tau >= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "a decode step has no gated form");
     const pod_decode_plan_t pl = pod_plan_decode(cus, B, ly.Hkv, ly.P, max_len, c->tune_chunk, c->tune_chunk_prox, scores && !reuse_step,
                                                  scores && !lowest_all && tau >= 0.f, c->fused_merge != 0, reuse_step && !lowest_any);
     const bool merge_inside = pl.merge_inside;
-    if (reuse_step && !merge_inside) return POD_NOT_FUSED;
     p.hot.chunk = (int)((unsigned)pl.chunk | ((unsigned)pl.chunk_p << 16));
     p.hot.max_nd = pl.max_nd;
     p.hot.nc = pl.nc;
@@ -1504,10 +1483,18 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // score reuse: the writing launch for the kv heads whose block starts at this layer, the reading launch(es) for
     // the others (workgroups of the other kind leave at once); a gated read is two launches, proximal chunks first
 #define POD_LAUNCH_ALL(DD)                                                                   \
-    if (reuse_step && lowest_all && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
-    else if (reuse_step && lowest_all) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);    \
-    else if (reuse_step && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p);     \
-    else if (reuse_step) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);                  \
+    if (reuse_step) {                                                                        \
+        if (lowest_any) {                                                                    \
+            if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
+            else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);         \
+            else hipLaunchKernelGGL((decode_partial_kernel<DD, 1, 3>), grid, dim3(kWaves * 64), 0, st, p);                               \
+        }                                                                                    \
+        if (!lowest_all) {                                                                   \
+            if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
+            else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);         \
+            else hipLaunchKernelGGL((decode_partial_kernel<DD, 2, 3>), grid, dim3(kWaves * 64), 0, st, p);                               \
+        }                                                                                    \
+    }                                                                                        \
     else if (fuse == 2 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2, true>), grid, dim3(fuse_waves(2) * 64), 0, st, p); \
     else if (fuse == 1 && loc) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 1, true>), grid, dim3(fuse_waves(1) * 64), 0, st, p); \
     else if (fuse == 2) hipLaunchKernelGGL((decode_partial_kernel<DD, 0, 2>), grid, dim3(fuse_waves(2) * 64), 0, st, p);    \

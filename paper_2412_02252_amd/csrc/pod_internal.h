@@ -133,11 +133,7 @@ int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *s
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
-size_t pod_score_ctx_offset_bytes(const pod_layout &ly);  // where int32 [B] context lengths of a step run as separate calls go
-// pod_launch_decode's answer to a score-reuse step that this launch shape does not run in one launch (nothing was
-// enqueued): the caller runs it as separate calls
-constexpr int POD_NOT_FUSED = 1;
-int pod_launch_ctx_from_positions(const int32_t *positions, int32_t *ctx, int B, hipStream_t st);
+
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 // device address and size of the library's own split-K scratch array on the current device (looked up once per device)
 int pod_decode_static_scratch(void **ptr, size_t *bytes);

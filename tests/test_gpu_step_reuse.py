@@ -1,5 +1,5 @@
-"""GPU: pod_decode_step_reuse = pod_cache_append + pod_decode_attention_reuse of one layer: one launch where the launch
-shape allows, the separate calls otherwise; against the oracle's append + attention, stores bit for bit."""
+"""GPU: pod_decode_step_reuse = pod_cache_append + pod_decode_attention_reuse of one layer in one streaming launch (two
+for a layer with kv heads of both kinds); against the oracle's append + attention, stores bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -28,10 +28,10 @@ def test_reuse_steps_from_an_empty_cache_across_every_region_edge(d, Hq, Hkv, G)
 
 
 @pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}],
-                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-calls"])
+                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel"])
 def test_reuse_steps_on_long_contexts_ragged_batch(env, monkeypatch):
     """Three sequences of different lengths (one inside S + W, one just past it, one with many split-K pieces), two
-    blocks of two layers, 40 steps; in one launch with either hand-off, and as separate calls."""
+    blocks of two layers, 40 steps; merged inside the launch with either hand-off, and by the separate kernel."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     S, W = 16, 96
@@ -83,7 +83,7 @@ def test_reuse_step_equals_the_separate_calls():
     b.gpu.pod_cache_check()
 
 
-def test_launch_of_several_rounds_runs_the_reuse_step_as_separate_calls():
+def test_launch_of_several_rounds_merges_the_reuse_step_in_the_second_kernel():
     S, W, B = 8, 56, 40
     c = Case(2, 2, 16, 8, 64, S, W, B, 700, seed=603)
     lens = [30 + (53 * b) % 600 for b in range(B)]
@@ -101,23 +101,37 @@ def test_launch_of_several_rounds_runs_the_reuse_step_as_separate_calls():
     c.gpu.pod_cache_check()
 
 
-def test_head_wise_blocks_run_the_reuse_step_with_mixed_layers_as_separate_calls():
+def test_head_wise_blocks_with_layers_that_write_and_read_logits():
     """Layer 1 is the lowest layer of kv head 1's second block and an upper layer for kv head 0: such a layer both
-    writes and reads logits, which the one-launch form leaves to the separate calls."""
+    writes and reads logits (a writing and a reading launch, each performing the cache update of its own kv heads);
+    small contexts merge inside the launches, the long one through the separate kernel."""
     S, W = 4, 28
     tab = np.array([[0, 0], [0, 1], [2, 1], [2, 3]], dtype=np.int32)
     c = Case(4, 1, 8, 2, 128, S, W, 2, 400, seed=604, block_lowest=tab)
     lens = [200, 31]
+    _mixed_steps(c, lens)
+
+
+def test_head_wise_blocks_large_batch():
+    S, W = 4, 28
+    tab = np.array([[0, 0, 0, 0], [0, 1, 0, 1], [2, 1, 0, 1], [2, 3, 0, 3]], dtype=np.int32)
+    B = 48
+    c = Case(4, 1, 8, 4, 64, S, W, B, 300, seed=607, block_lowest=tab)
+    _mixed_steps(c, [20 + (37 * b) % 250 for b in range(B)], steps=2)
+
+
+def _mixed_steps(c, lens, steps=6):
+    S, W = c.S, c.W
     for layer in range(4):
         for b, n in enumerate(lens):
             c.fill(layer, b, n)
     scores = c.gpu.new_score_buffer()
-    for s in range(6):
+    for s in range(steps):
         pos = [n + s for n in lens]
         for layer in range(4):
             assert_close(c.step_reuse(layer, pos, scores), c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
     for layer in range(4):
-        for b in range(2):
+        for b in (0, len(lens) - 1):
             c.assert_cache_equal(layer, b)
     c.gpu.pod_cache_check()
 
