@@ -3,25 +3,33 @@
 // rows, averaged over the sampled rows; the similarity is 1 minus that average with base-2 logarithms
 // (base-2 JS lies in [0, 1], so identical rows give 1 and rows with disjoint support give 0).
 //
-// Memory-bound elementwise work followed by a reduction: one workgroup per (layer pair a < b, head)
-// streams the two layers' rows once, 16 bytes per lane and load.  Nothing here is on the inference
-// path; it feeds pod_group_layers.
+// Elementwise work followed by a reduction.  A workgroup takes one head and a block pair (A, B) of kBL layers each
+// (A <= B) and walks the heads' rows once, 16 bytes per lane and load: every element of up to 2 kBL layers is loaded
+// once, its logarithm taken once, and all the kBL x kBL (or, on the diagonal, kBL (kBL - 1) / 2) layer pairs of the
+// block pair are accumulated from those registers.  Against one workgroup per layer pair this reads each row
+// ceil(L / kBL) times instead of L - 1 times (32 layers: 4 instead of 31) and takes 1 + 2 / kBL instead of 3
+// logarithms per pair and element.  Nothing here is on the inference path; it feeds pod_group_layers.
 #include "pod_internal.h"
 
 namespace {
 
 constexpr int kSimThreads = 256;
+constexpr int kBL = 8;   // layers per block
+typedef __attribute__((ext_vector_type(4))) float sim_f4;
 
-// p log2(p / m) + q log2(q / m) with m = (p + q) / 2 and 0 log 0 = 0
-__device__ inline float js_term(float p, float q)
+// (subnormal probabilities count as 0: the hardware logarithm flushes them, and x log x < 1e-35 there)
+constexpr float kMinNormal = 1.17549435e-38f;
+
+// sum over the 4 elements of p log2(p / m) + q log2(q / m) with m = (p + q) / 2 and 0 log 0 = 0; lp, lq = log2 of p, q
+__device__ inline float js_term4(const sim_f4 &p, const sim_f4 &lp, const sim_f4 &q, const sim_f4 &lq)
 {
-    const float m = 0.5f * (p + q);
-    const float lm = __log2f(m);
-    // (subnormal probabilities count as 0: the hardware logarithm flushes them, and x log x < 1e-35 there)
-    constexpr float kMinNormal = 1.17549435e-38f;
     float t = 0.f;
-    if (p >= kMinNormal) t += p * (__log2f(p) - lm);
-    if (q >= kMinNormal) t += q * (__log2f(q) - lm);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lm = __log2f(0.5f * (p[e] + q[e]));
+        if (p[e] >= kMinNormal) t += p[e] * (lp[e] - lm);
+        if (q[e] >= kMinNormal) t += q[e] * (lq[e] - lm);
+    }
     return t;
 }
 
@@ -29,32 +37,74 @@ __device__ inline float js_term(float p, float q)
 __global__ __launch_bounds__(kSimThreads) void similarity_kernel(const float *__restrict__ att, int L, int H, int R, int n,
                                                                  float *__restrict__ sim)
 {
-    // pair index -> (a, b), a < b
-    int a = 0, rem = blockIdx.x;
-    while (rem >= L - 1 - a) { rem -= L - 1 - a; ++a; }
-    const int b = a + 1 + rem, h = blockIdx.y;
+    // block pair index -> (A, B), A <= B
+    const int nblk = (L + kBL - 1) / kBL;
+    int A = 0, rem = blockIdx.x;
+    while (rem >= nblk - A) { rem -= nblk - A; ++A; }
+    const int B = A + rem, h = blockIdx.y;
+    const bool diag = A == B;
     const size_t rows = (size_t)R * n; // the R rows of one (layer, head) are contiguous
-    const float *pa = att + ((size_t)a * H + h) * rows;
-    const float *pb = att + ((size_t)b * H + h) * rows;
-    float acc = 0.f;
-    const size_t vec = rows / 4;
-    for (size_t i = threadIdx.x; i < vec; i += kSimThreads) {
-        const float4 x = ((const float4 *)pa)[i], y = ((const float4 *)pb)[i];
-        acc += js_term(x.x, y.x) + js_term(x.y, y.y) + js_term(x.z, y.z) + js_term(x.w, y.w);
-    }
-    for (size_t i = vec * 4 + threadIdx.x; i < rows; i += kSimThreads) acc += js_term(pa[i], pb[i]);
-    // workgroup reduction
-    __shared__ float part[kSimThreads / 64];
+    const size_t vec = rows / 4;       // (the entry point takes R * n in multiples of 4 only)
+    float acc[kBL][kBL];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    for (int i = 0; i < kBL; ++i)
+#pragma unroll
+        for (int j = 0; j < kBL; ++j) acc[i][j] = 0.f;
+    auto row_ptr = [&](int layer) { return att + ((size_t)(layer < L ? layer : L - 1) * H + h) * rows; };
+    auto log4 = [](const sim_f4 &x) {
+        sim_f4 l;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) l[e] = __log2f(x[e]);
+        return l;
+    };
+    auto accumulate = [&](const sim_f4 (&xa)[kBL], const sim_f4 (&la)[kBL], const sim_f4 (&xb)[kBL], const sim_f4 (&lb)[kBL]) {
+#pragma unroll
+        for (int i = 0; i < kBL; ++i)
+#pragma unroll
+            for (int j = 0; j < kBL; ++j)
+                if (!diag || i < j) acc[i][j] += js_term4(xa[i], la[i], xb[j], lb[j]);   // (wave-uniform)
+    };
+    for (size_t v = threadIdx.x; v < vec; v += kSimThreads) {
+        sim_f4 xa[kBL], la[kBL], xb[kBL], lb[kBL];
+#pragma unroll
+        for (int i = 0; i < kBL; ++i) xa[i] = ((const sim_f4 *)row_ptr(A * kBL + i))[v];
+        if (!diag) {
+#pragma unroll
+            for (int j = 0; j < kBL; ++j) xb[j] = ((const sim_f4 *)row_ptr(B * kBL + j))[v];
+        }
+#pragma unroll
+        for (int i = 0; i < kBL; ++i) la[i] = log4(xa[i]);
+        if (!diag) {
+#pragma unroll
+            for (int j = 0; j < kBL; ++j) lb[j] = log4(xb[j]);
+            accumulate(xa, la, xb, lb);
+        } else {
+            accumulate(xa, la, xa, la);
+        }
+    }
+    // workgroup reduction, pair by pair
+    __shared__ float part[kSimThreads / 64][kBL * kBL];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < kBL; ++i)
+#pragma unroll
+        for (int j = 0; j < kBL; ++j) {
+            float t = acc[i][j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
+            if (lane == 0) part[wave][i * kBL + j] = t;
+        }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float js = 0.f;
-        for (int w = 0; w < kSimThreads / 64; ++w) js += part[w];
-        const float s = 1.f - 0.5f * js / (float)R; // JS = (KL(p||m) + KL(q||m)) / 2, mean over the rows
-        sim[((size_t)h * L + a) * L + b] = s;
-        sim[((size_t)h * L + b) * L + a] = s;
+    if (threadIdx.x < kBL * kBL) {
+        const int i = threadIdx.x / kBL, j = threadIdx.x % kBL;
+        const int a = A * kBL + i, b = B * kBL + j;
+        if (a < L && b < L && a < b) {
+            float js = 0.f;
+            for (int w = 0; w < kSimThreads / 64; ++w) js += part[w][threadIdx.x];
+            const float s = 1.f - 0.5f * js / (float)R; // JS = (KL(p||m) + KL(q||m)) / 2, mean over the rows
+            sim[((size_t)h * L + a) * L + b] = s;
+            sim[((size_t)h * L + b) * L + a] = s;
+        }
     }
 }
 
@@ -70,7 +120,8 @@ int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *s
 {
     hipLaunchKernelGGL(similarity_diagonal_kernel, dim3((L * H + 255) / 256), dim3(256), 0, st, L, H, sim);
     if (L > 1)
-        hipLaunchKernelGGL(similarity_kernel, dim3((unsigned)(L * (L - 1) / 2), (unsigned)H), dim3(kSimThreads), 0, st, att, L, H, R, n, sim);
+        hipLaunchKernelGGL(similarity_kernel, dim3((unsigned)(((L + kBL - 1) / kBL) * ((L + kBL - 1) / kBL + 1) / 2), (unsigned)H),
+                           dim3(kSimThreads), 0, st, att, L, H, R, n, sim);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }

@@ -180,7 +180,8 @@ def test_gated_skip_with_a_headwise_table():
 from oracle import pod_grouping as pg
 
 
-@pytest.mark.parametrize("L,H,R,n", [(3, 2, 4, 64), (5, 4, 6, 1000), (2, 1, 1, 4), (4, 3, 3, 4100)])
+@pytest.mark.parametrize("L,H,R,n", [(3, 2, 4, 64), (5, 4, 6, 1000), (2, 1, 1, 4), (4, 3, 3, 4100), (19, 2, 2, 514), (32, 1, 2, 1024),
+                                     (8, 2, 1, 8), (9, 1, 4, 333)])
 def test_layer_similarity_matches_the_oracle(L, H, R, n):
     rng = np.random.default_rng(L * 1000 + n)
     att = rng.dirichlet(np.full(n, 0.3), size=(L, H, R)).astype(np.float32)
