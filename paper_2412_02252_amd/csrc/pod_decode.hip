@@ -432,11 +432,13 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m16 = lane & 15, j = lane >> 4;
 
-    // NW K tiles of kTile rows; the same bytes later hold the merge buffer
-    // [NW][rep <= 16][D] floats, which is exactly as large.
-    __shared__ u32x4 lds[NW][kTile * CPR];
-    static_assert(sizeof(u32x4) * kTile * CPR == sizeof(float) * 16 * D, "merge buffer must fit the K tiles");
-    u32x4 *ldsK = lds[wave];
+    // NW K tiles of kTile rows; the same bytes later hold the merge buffer [NW][rep <= 16][RS] floats.  Its rows are
+    // padded (4 floats after every 32 dims, row stride 1 mod 32): the 16 lanes of a wave that hold real heads write
+    // the same (i, x) element of 4 heads x 4 dim groups at once, which would otherwise all fall into one LDS bank.
+    constexpr int RS = D + 4 * (D / 32) + 1;
+    constexpr size_t kTileBytes = sizeof(u32x4) * NW * kTile * CPR, kMergeBytes = sizeof(float) * NW * 16 * RS;
+    __shared__ __attribute__((aligned(16))) char lds_raw[kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes];
+    u32x4 *ldsK = (u32x4 *)lds_raw + (size_t)wave * kTile * CPR;
 
     f32x4 acc[NPV];
 #pragma unroll
@@ -682,7 +684,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     //   XN = 1: 8*(4j+i) + x        XN = 2: 8*((4j+i) % 8) + 2x + (4j+i)/8
     __syncthreads(); // all waves are done with their K tiles
     if (MERGE && p.trace) tr_t1 = wall_clock64();
-    float *sm_acc = (float *)&lds[0][0];              // [NW][rep][D]
+    float *sm_acc = (float *)lds_raw;                 // [NW][rep][RS], dim d of a row at d + 4 (d / 32)
     __shared__ float sm_m[NW][16], sm_l[NW][16];
     if (m16 < hot.rep) {
 #pragma unroll
@@ -691,7 +693,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
             for (int i = 0; i < 4; ++i) {
                 const int slot = 4 * j + i;
                 const int dim = (XN == 1) ? 8 * slot + x : 8 * (slot % 8) + 2 * x + slot / 8;
-                sm_acc[((size_t)wave * hot.rep + m16) * D + dim] = acc[x][i];
+                sm_acc[((size_t)wave * hot.rep + m16) * RS + dim + 4 * (dim >> 5)] = acc[x][i];
             }
         if (j == 0) { sm_m[wave][m16] = m_run; sm_l[wave][m16] = l_run; }
     }
@@ -706,7 +708,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const float f = exp2f(sm_m[w][head] - M);
-            A += f * sm_acc[((size_t)w * hot.rep + head) * D + dim];
+            A += f * sm_acc[((size_t)w * hot.rep + head) * RS + dim + 4 * (dim >> 5)];
             Lsum += f * sm_l[w][head];
         }
         typedef __attribute__((address_space(1))) float *gfloat_ptr;
