@@ -136,7 +136,7 @@ def test_chunked_prefill_in_a_graph_equals_eager_on_every_replay():
         torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("variant", ["step", "append+decode"])
+@pytest.mark.parametrize("variant", ["step", "append+decode", "step_reuse"])
 def test_one_captured_step_graph_serves_successive_tokens(variant):
     """Lengths from device arrays only (pod_cache_set_length_source(1)): ONE captured step (both layers of a block, two
     ragged sequences) is replayed for 8 successive tokens; between replays only device memory changes (positions,
@@ -167,14 +167,20 @@ def test_one_captured_step_graph_serves_successive_tokens(variant):
             q[layer].copy_(c.decode_queries(layer, [x + 1 for x in p], c.dev))
         return p
 
+    scores = c.gpu.new_score_buffer()
+
     def one_step():
         for layer in range(2):
+            if variant == "step_reuse":
+                c.gpu.pod_decode_step_reuse(layer, k[layer], v[layer], q[layer], pos, c.scale, scores, out=out[layer],
+                                            max_context_len=bound)
+                continue
             if variant == "step":
                 c.gpu.pod_decode_step(layer, k[layer], v[layer], q[layer], q[0] if layer else None, pos, c.scale,
                                       out=out[layer], max_context_len=bound)
             else:
                 c.gpu.pod_cache_append(layer, k[layer], v[layer], pos)
-        if variant != "step":
+        if variant == "append+decode":
             for layer in range(2):
                 c.gpu.pod_decode_attention(layer, q[layer], q[0] if layer else None, ctx, c.scale, out=out[layer],
                                            max_context_len=bound)
