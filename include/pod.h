@@ -244,7 +244,7 @@ int pod_decode_step_reuse(pod_cache *cache, int layer, const void *k_new, const 
  * load; the device-side arrays are still compared with them).  1: only from the device arrays the
  * calls name (context_lens, positions) and the cache's own header; nothing a call enqueues then
  * depends on the mirror, so a HIP graph captured over pod_cache_append / pod_decode_attention /
- * pod_decode_step calls can be replayed for successive tokens: refresh the device arrays between
+ * pod_decode_step / pod_decode_step_reuse calls can be replayed for successive tokens: refresh the device arrays between
  * replays, pass max_context_len >= every length the replays will see (it sizes the launch and must
  * be given), always pass q_shared for an upper layer, and call pod_cache_sync_lengths once the
  * replays are done.  Checks the host can no longer make are made on the device (flag).
