@@ -256,3 +256,42 @@ def test_pairs_that_do_not_divide_over_the_xcds_evenly():
         c.assert_cache_equal(0, b)
         c.assert_cache_equal(1, b)
     c.gpu.pod_cache_check()
+
+
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(count):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        rep = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+        S = int(rng.integers(0, 40))
+        W = int(rng.integers(1, 200))
+        B = int(rng.choice([1, 1, 2, 3, 5, 9]))
+        lens = [int(x) for x in rng.integers(0, 2500, size=B)]
+        shapes.append((d, Hkv * rep, Hkv, S, W, lens))
+    return shapes
+
+
+
+@pytest.mark.parametrize("shape", _random_shapes(24, 20241205), ids=lambda s: f"d{s[0]}-q{s[1]}-kv{s[2]}-S{s[3]}-W{s[4]}-B{len(s[5])}")
+def test_steps_and_reuse_steps_on_seeded_random_shapes(shape):
+    """Seeded random head counts, sink and window sizes (sink 0 included), batch sizes and ragged lengths (empty
+    sequences included): two steps through pod_decode_step and two through pod_decode_step_reuse, every output against
+    the oracle, stores bit for bit."""
+    d, Hq, Hkv, S, W, lens = shape
+    c = Case(2, 2, Hq, Hkv, d, S, W, len(lens), max(lens) + 8, seed=700 + Hq + W)
+    for layer in range(2):
+        for b, n in enumerate(lens):
+            if n:
+                c.fill(layer, b, n)
+    scores = c.gpu.new_score_buffer()
+    for s in range(4):
+        pos = [n + s for n in lens]
+        for layer in range(2):
+            out = c.step(layer, pos) if s < 2 else c.step_reuse(layer, pos, scores)
+            assert_close(out, c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+    for layer in range(2):
+        for b in range(len(lens)):
+            c.assert_cache_equal(layer, b)
+    c.gpu.pod_cache_check()
