@@ -136,17 +136,20 @@ def test_launch_of_several_rounds_uses_the_separate_merge_and_matches():
     c.gpu.pod_cache_check()
 
 
-def test_more_than_256_sequences_step_with_device_side_lengths():
+@pytest.mark.parametrize("reuse", [False, True], ids=["plain", "score-reuse"])
+def test_more_than_256_sequences_step_with_device_side_lengths(reuse):
     B, S, W = 300, 4, 16
     c = Case(2, 2, 4, 2, 64, S, W, B, 100, seed=505)
     lens = [1 + (37 * b) % 90 for b in range(B)]
     for layer in range(2):
         for b in range(B):
             c.fill(layer, b, lens[b])
+    scores = c.gpu.new_score_buffer() if reuse else None
     for s in range(2):
         pos = [n + s for n in lens]
         for layer in range(2):
-            assert_close(c.step(layer, pos), c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+            out = c.step_reuse(layer, pos, scores) if reuse else c.step(layer, pos)
+            assert_close(out, c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
     for b in (0, 17, 123, 299):
         c.assert_cache_equal(1, b)
         c.assert_cache_equal(0, b)
