@@ -381,9 +381,13 @@ int pod_prefill_attention(pod_cache *cache, int layer, int seq_slot, int n, cons
 int pod_cache_append_many(pod_cache *cache, int layer, const void *k_new, const void *v_new,
                           const int32_t *positions, const int32_t *counts, int T, int B, void *stream);
 
-/* Bytes of device scratch pod_prefill_attention_chunk needs for a sequence that holds n_total
- * tokens after the chunk (contiguous copies of its keys and values). host out. */
+/* Bytes of device scratch that suffice for pod_prefill_attention_chunk on a sequence that holds
+ * n_total tokens after the chunk, whichever way the call takes (see there). host out. */
 int pod_prefill_chunk_workspace_bytes(const pod_config *cfg, int64_t n_total, size_t *bytes);
+/* The smaller scratch that suffices when the call takes its first way (see there) for a chunk of
+ * T tokens that brings the sequence to n_total: for callers that always store the chunk, lowest
+ * layers first.  A call that needs more than it is given returns POD_ERR_CAPACITY. host out. */
+int pod_prefill_chunk_in_place_bytes(const pod_config *cfg, int64_t n_total, int64_t T, size_t *bytes);
 
 /*
  * Prefill attention for a chunk of T new tokens of a sequence whose first p0 tokens are in
@@ -397,10 +401,23 @@ int pod_prefill_chunk_workspace_bytes(const pod_config *cfg, int64_t n_total, si
  *              `layer` is the lowest of its block for every kv head
  *   workspace: dev scratch of pod_prefill_chunk_workspace_bytes(cfg, p0 + T) bytes, 256-byte aligned
  *   out      : dev bf16 [T][Hq][d]
- *   write_cache : nonzero = afterwards store the chunk at (layer, seq_slot) as pod_cache_append_many does
+ *   write_cache : nonzero = store the chunk at (layer, seq_slot) as pod_cache_append_many does
  * Keys of earlier positions come from the cache: this layer's sink and recent window, and the
  * stores of the lowest layer of each head's block, which must hold either p0 tokens or
  * p0 + T (it has stored this chunk already): otherwise POD_ERR_STATE.
+ *
+ * Two ways, same result.  With write_cache set and the lowest layers already at p0 + T (the
+ * usual order: every layer takes the chunk, lowest layers first) the chunk is stored FIRST and
+ * the attention kernel reads keys and values where the cache holds them; the workspace then
+ * carries only the own keys that this update drops but the chunk's queries still see inside
+ * their windows (at most T rows per kv head), a few staged 64-row tiles and a table of tile
+ * addresses.  If the stored length on the device is not p0 (a host mirror that ran ahead),
+ * nothing is stored, `out` is undefined and the sticky flag is raised, as in
+ * pod_cache_append_many.  Otherwise (write_cache 0, a lowest layer still at p0, or
+ * POD_CHUNK_IN_PLACE=0 in the environment when the cache was created) keys and values of all
+ * p0 + T positions are first copied into the workspace as contiguous arrays and the chunk is
+ * stored afterwards if asked.  k_shared is not read on the first way: the lowest layer's cache
+ * holds the same rows.
  */
 int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T, const void *q, const void *k,
                                 const void *v, const void *q_shared, const void *k_shared, float scale,

@@ -23,7 +23,7 @@ EXPORTS = [
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
-    "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_attention_chunk",
+    "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_chunk_in_place_bytes", "pod_prefill_attention_chunk",
     "pod_decode_plan", "pod_decode_step_reuse",
 ]
 
@@ -91,6 +91,7 @@ def load():
                                        C.c_size_t, vp, vp],
         "pod_cache_append_many": [vp, C.c_int, vp, vp, i32p, i32p, C.c_int, C.c_int, vp],
         "pod_prefill_chunk_workspace_bytes": [cfgp, C.c_int64, szp],
+        "pod_prefill_chunk_in_place_bytes": [cfgp, C.c_int64, C.c_int64, szp],
         "pod_prefill_attention_chunk": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_size_t, vp,
                                         C.c_int, vp],
         "pod_profile_enable": [vp, C.c_int],
@@ -183,6 +184,12 @@ def pod_score_buffer_bytes(cfg: PodConfig) -> int:
 def pod_prefill_chunk_workspace_bytes(cfg: PodConfig, n_total: int) -> int:
     b = C.c_size_t()
     _check(load().pod_prefill_chunk_workspace_bytes(C.byref(cfg), n_total, C.byref(b)))
+    return b.value
+
+
+def pod_prefill_chunk_in_place_bytes(cfg: PodConfig, n_total: int, T: int) -> int:
+    b = C.c_size_t(0)
+    _check(load().pod_prefill_chunk_in_place_bytes(C.byref(cfg), n_total, T, C.byref(b)))
     return b.value
 
 
@@ -376,10 +383,12 @@ class PodCache:
         """Device buffer for pod_decode_attention_reuse (one block's distant logits)."""
         return guarded_empty(pod_score_buffer_bytes(self.cfg), self.device, self.guard_bytes, self, "score buffer")
 
-    def new_chunk_workspace(self, n_total):
-        """Device buffer for pod_prefill_attention_chunk of a sequence that holds n_total tokens after the chunk."""
-        return guarded_empty(pod_prefill_chunk_workspace_bytes(self.cfg, n_total), self.device, self.guard_bytes, self,
-                             "chunk workspace")
+    def new_chunk_workspace(self, n_total, in_place_chunk=0):
+        """Device buffer for pod_prefill_attention_chunk of a sequence that holds n_total tokens after the chunk;
+        in_place_chunk = T > 0: the smaller one that suffices when chunks of at most T tokens are stored by the call."""
+        size = (pod_prefill_chunk_in_place_bytes(self.cfg, n_total, in_place_chunk) if in_place_chunk > 0
+                else pod_prefill_chunk_workspace_bytes(self.cfg, n_total))
+        return guarded_empty(size, self.device, self.guard_bytes, self, "chunk workspace")
 
     def pod_prefill_attention(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, out=None, write_cache=False):
         n = q.shape[0]

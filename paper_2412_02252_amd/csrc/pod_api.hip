@@ -203,6 +203,8 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
         c->xcd_local = !(e4 && atoi(e4) == 0);
         c->nxcd = 0;
         c->device_lengths = false;
+        const char *e5 = getenv("POD_CHUNK_IN_PLACE");
+        c->chunk_in_place = !(e5 && atoi(e5) == 0);
     }
     c->prof_ev = nullptr; c->prof_cap = 0; c->prof_n = 0;
     c->trace = nullptr; c->trace_cap = 0;
@@ -771,7 +773,19 @@ extern "C" int pod_prefill_chunk_workspace_bytes(const pod_config *cfg, int64_t 
     if (rc) return rc;
     if (!bytes || n_total < 1) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL or n_total < 1");
     if (n_total > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n_total = %lld exceeds max_context = %d", (long long)n_total, ly.maxctx);
-    *bytes = 3 * chunk_rows_bytes(ly, n_total);
+    const size_t copies = 3 * chunk_rows_bytes(ly, n_total), in_place = pod_chunk_direct_bytes(ly, n_total, 0);
+    *bytes = copies > in_place ? copies : in_place;
+    return POD_OK;
+}
+
+extern "C" int pod_prefill_chunk_in_place_bytes(const pod_config *cfg, int64_t n_total, int64_t T, size_t *bytes)
+{
+    pod_layout ly;
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    if (!bytes || n_total < 1 || T < 1 || T > n_total) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL, or not 1 <= T <= n_total");
+    if (n_total > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n_total = %lld exceeds max_context = %d", (long long)n_total, ly.maxctx);
+    *bytes = pod_chunk_direct_bytes(ly, n_total, T);
     return POD_OK;
 }
 
@@ -784,6 +798,7 @@ extern "C" int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_
     const pod_layout &ly = cache->ly;
     if (!q || !k || !v || !out || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "q, k, v, out and workspace must not be NULL");
     if (T < 1) return pod_fail(POD_ERR_INVALID_ARG, "T must be >= 1");
+    if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
     if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
     if ((q_shared == nullptr) != (k_shared == nullptr))
         return pod_fail(POD_ERR_INVALID_ARG, "q_shared and k_shared must be given together");
@@ -800,11 +815,29 @@ extern "C" int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_
             return pod_fail(POD_ERR_STATE, "layer %d (lowest of kv head %d's block) holds %lld tokens of slot %d; layer %d holds %lld and the chunk has %d",
                             la, h, (long long)na, seq_slot, layer, (long long)p0, T);
     }
+    if (lowest) { q_shared = nullptr; k_shared = nullptr; }
+    hipStream_t st = (hipStream_t)stream;
+    // Usual case: the chunk is stored first and the attention kernel takes keys and values straight from the cache.
+    // That needs the block's lowest layers to hold the chunk already (their keys are read where they lie) and the
+    // caller's leave to store it here.
+    bool in_place = write_cache && cache->chunk_in_place;
+    for (int h = 0; h < ly.Hkv && in_place; ++h) {
+        const int la = cache->lowest[(size_t)layer * ly.Hkv + h];
+        if (la != layer && cache->host_len[(size_t)la * ly.B + seq_slot] != n) in_place = false;
+    }
+    if (in_place) {
+        const unsigned long long *tab = nullptr;
+        int ntiles = 0;
+        rc = pod_launch_chunk_update(cache, layer, seq_slot, (int)p0, T, k, v, workspace, workspace_bytes, &tab, &ntiles, st);
+        if (rc) return rc;
+        cache->host_len[(size_t)layer * ly.B + seq_slot] = n;
+        return pod_launch_prefill_tiles(ly, (int)n, (int)p0, q, q_shared, tab, ntiles,
+                                        (int *)(cache->base + ly.off_lens) + (size_t)layer * ly.B + seq_slot, (int *)(cache->base + ly.off_flag),
+                                        pod_make_headmap(cache, layer).lowest_mask, scale, out, st);
+    }
     const size_t part = chunk_rows_bytes(ly, n);
     if (workspace_bytes < 3 * part) return pod_fail(POD_ERR_CAPACITY, "chunk workspace too small: %zu < %zu", workspace_bytes, 3 * part);
-    if (lowest) { q_shared = nullptr; k_shared = nullptr; }
     char *k_all = (char *)workspace, *v_all = k_all + part, *ks_all = q_shared ? v_all + part : nullptr;
-    hipStream_t st = (hipStream_t)stream;
     rc = pod_launch_gather(cache, layer, seq_slot, (int)p0, T, k, v, k_shared, k_all, v_all, ks_all, st);
     if (rc) return rc;
     rc = pod_launch_prefill(ly, layer, (int)n, (int)p0, q, k_all, v_all, q_shared, ks_all, pod_make_headmap(cache, layer).lowest_mask,

@@ -75,6 +75,7 @@ struct pod_cache {
     bool fused_merge;      // plain decode merges its partials inside the streaming kernel (POD_DECODE_FUSED=0: separate kernel)
     bool xcd_local;        // hand partials over inside one XCD's L2 where the launch shape allows (POD_DECODE_XCD_LOCAL=0: never)
     int nxcd;              // XCDs a one-dimensional launch is spread over round-robin (0: no such pattern seen by the probe)
+    bool chunk_in_place;   // chunk attention reads keys and values where the cache holds them (POD_CHUNK_IN_PLACE=0: from a contiguous copy)
     bool device_lengths;   // kernels take sequence lengths from the calls' device arrays only (pod_cache_set_length_source)
     // the library's own split-K scratch on `device` (pod_decode_attention_static): device address and size
     void *static_scratch;
@@ -112,6 +113,13 @@ int pod_launch_append_many(const pod_cache *c, int layer, const void *k_new, con
 // contiguous [p0 + T][Hkv][D] keys / values / lowest layers' keys of one sequence (ks_all may be NULL)
 int pod_launch_gather(const pod_cache *c, int layer, int seq_slot, int p0, int T, const void *k_chunk, const void *v_chunk,
                       const void *ks_chunk, void *k_all, void *v_all, void *ks_all, hipStream_t st);
+// Chunk attention straight from the cache: stores the chunk at (layer, seq_slot) as pod_launch_append_many would, keeps the
+// own keys this drops in the workspace and writes the per-tile address table pod_launch_prefill_tiles reads.  The stored
+// length is left for pod_launch_prefill_tiles to change (no workgroup of the update may change what the others test).
+size_t pod_chunk_direct_bytes(const pod_layout &ly, int64_t n_total, int64_t T); // workspace bytes that suffice (T <= 0: for any chunk length)
+int pod_launch_chunk_update(const pod_cache *c, int layer, int seq_slot, int p0, int T, const void *k_chunk, const void *v_chunk,
+                            void *workspace, size_t workspace_bytes, const unsigned long long **tile_tab, int *ntiles,
+                            hipStream_t st);
 int pod_launch_export(const pod_cache *c, int layer, int seq_slot, int64_t n, void *sinkK, void *sinkV,
                       void *recK, void *recV, void *distK, void *distV, hipStream_t st);
 // scores == NULL: plain decode; else the score-reuse buffer (lowest layer writes, upper layers read).
@@ -133,6 +141,13 @@ int pod_launch_similarity(const float *att, int L, int H, int R, int n, float *s
 size_t pod_score_stride(const pod_layout &ly);       // fp32 elements per (sequence, query head) row
 size_t pod_score_header_bytes(const pod_layout &ly); // tags, distant sums and skip flags in front of the rows
 size_t pod_score_skip_offset_bytes(const pod_layout &ly); // where the skip flags int32 [B][Hq] start
+
+// the same with keys and values located through a table: tile_tab[(stream * Hkv + kv head) * ntiles + tile] = device
+// address of the first row of that head's 64-position tile, rows D * 2 bytes apart (stream 0 k, 1 v, 2 k_shared).
+// Completes pod_launch_chunk_update: *len becomes n if it still is q0, else *flag is raised.
+int pod_launch_prefill_tiles(const pod_layout &ly, int n, int q0, const void *q, const void *q_shared,
+                             const unsigned long long *tile_tab, int ntiles, int *len, int *flag, uint64_t lowest_mask, float scale,
+                             void *out, hipStream_t st);
 
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 // device address and size of the library's own split-K scratch array on the current device (looked up once per device)

@@ -53,6 +53,14 @@ struct prefill_params {
     pod_bf16 *out;
     float scale_log2e;
     unsigned long long lowest_mask; // bit h: kv head h takes every logit from (q, k) even if qs/ks are given
+    // TAB kernels: k, v, ks are not used.  tile_tab[(stream * Hkv + kv head) * ntiles + key tile] is the device
+    // address of that tile's first row for that head, rows D * 2 bytes apart; stream 0 = k, 1 = v, 2 = ks
+    const unsigned long long *tile_tab;
+    int ntiles;
+    // TAB kernels also finish the cache update that wrote the table: if *len still is len_old it becomes len_new,
+    // else *flag is raised (the update kernel made the same test and stored nothing)
+    int *len, *flag;
+    int len_old, len_new;
 };
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -145,7 +153,7 @@ __device__ inline float dot2_ones(unsigned pk, float acc)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, acc, false);
 }
 
-template <int D>
+template <int D, bool TAB>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 {
     constexpr int CPR = D / 8, KST = D / 16, NDB = D / 32, NKB = kBN / 32, NPS = kBN / 16;
@@ -168,6 +176,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     const int kvh = wg % p.Hkv;
     const int rest = wg / p.Hkv;
     const int head = kvh * p.rep + rest % p.rep;
+    // (Query tiles are handed out from the last, which has most keys, to the first.  Which tiles share a CU does not
+    // matter: a workgroup takes about as long per key tile alone on its CU as next to a second one, so a launch of
+    // one round takes as long as its longest tile either way; pairing long tiles with short ones measured no gain.)
     const int qt = nqt - 1 - rest / p.rep;
     const int i0 = qt * BM;
     const int i_last = min(i0 + BM, p.n) - 1;
@@ -201,15 +212,19 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     // A request is ONE scalar base per tile plus a per-lane offset that never changes (one register per
     // request of the wave), so a tile costs neither vector nor scalar address arithmetic; only the
     // prompt's last, partly filled tile takes a separate path that clamps its rows per lane.
-    const unsigned rowb = (unsigned)p.Hkv * D * 2;
+    const unsigned rowb = TAB ? (unsigned)(D * 2) : (unsigned)p.Hkv * D * 2; // TAB: one head's rows, back to back
+    const unsigned head_col = TAB ? 0u : (unsigned)(kvh * D * 2);
+    typedef const __attribute__((address_space(4))) unsigned long long *tab_ptr;  // read with scalar loads
+    const tab_ptr tab_k = (tab_ptr)(p.tile_tab + (size_t)kvh * p.ntiles);
+    const size_t tab_stream = (size_t)p.Hkv * p.ntiles;
     const int v_r = lane / CPR;                                         // row inside a V instruction
     // K rows: a lane of a request fetches piece (slot piece ^ krot(row)) of its row, krot(row) = row * CPR / 16 mod CPR
     // (16 consecutive rows then put the same piece into 16 different 16-byte bank groups)
     auto k_col = [&](int x) { // x-th request of the wave: LDS rows 16 wave + VRI x + v_r
         const int rot = (((VRI * x + v_r) * CPR) / 16) & (CPR - 1);
-        return (unsigned)(kvh * D * 2 + 16 * ((lane % CPR) ^ rot));
+        return head_col + (unsigned)(16 * ((lane % CPR) ^ rot));
     };
-    const unsigned v_col = (unsigned)(kvh * D * 2 + 16 * ((lane % CPR) ^ ((4 * (v_r & 3)) & VSWZ)));
+    const unsigned v_col = head_col + (unsigned)(16 * ((lane % CPR) ^ ((4 * (v_r & 3)) & VSWZ)));
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);            // scalar copy: LDS destinations stay scalar
     unsigned k_off[VPW], v_off[VPW];
 #pragma unroll
@@ -221,9 +236,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     typedef __attribute__((address_space(3))) void *lvoid_ptr;
     const char *const k_dst0 = ldsK + wave_s * (16 * D * 2);            // this wave's part of K slot 0
     const char *const v_dst0 = ldsV + wave_s * (16 * D * 2);            // this wave's part of V slot 0
-    auto request_k = [&](int kt, bool phaseD, int slot) {
+    // TAB: the tile's address comes out of the table with a scalar load; the callers fetch it an iteration ahead
+    auto k_tile = [&](int kt, bool phaseD) { return tab_k[(phaseD ? 2 * tab_stream : 0) + kt]; };
+    auto v_tile = [&](int kt) { return tab_k[tab_stream + kt]; };
+    auto request_k = [&](int kt, bool phaseD, int slot, unsigned long long tile) {
         const int j0 = kt * kBN;
-        const gbyte_ptr base = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
+        gbyte_ptr base;
+        if constexpr (TAB) base = (gbyte_ptr)tile;
+        else base = (gbyte_ptr)(phaseD ? p.ks : p.k) + (size_t)j0 * rowb;
         if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
             for (int x = 0; x < VPW; ++x) {
@@ -240,9 +260,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
             }
         }
     };
-    auto request_v = [&](int kt, int slot) {
+    auto request_v = [&](int kt, int slot, unsigned long long tile) {
         const int j0 = kt * kBN;
-        const gbyte_ptr base = (gbyte_ptr)p.v + (size_t)j0 * rowb;
+        gbyte_ptr base;
+        if constexpr (TAB) base = (gbyte_ptr)tile;
+        else base = (gbyte_ptr)p.v + (size_t)j0 * rowb;
         if (__builtin_expect(j0 + kBN <= p.n, 1)) {
 #pragma unroll
             for (int x = 0; x < VPW; ++x) {
@@ -336,8 +358,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
     tile_of(0, kt_a, ph_a);
     tile_of(1, kt_b, ph_b);
     tile_of(2, kt_c, ph_c);
-    request_k(kt_a, ph_a, 0);
-    if (T > 1) request_k(kt_b, ph_b, 1);
+    unsigned long long k_next = 0, v_next = 0; // TAB: addresses of the tiles the next iteration requests
+    if constexpr (TAB) {
+        if (wg == 0 && tid == 0) { // the update launch before this one left the length for here
+            if (*p.len == p.len_old) *p.len = p.len_new;
+            else atomicOr(p.flag, 1);
+        }
+        request_k(kt_a, ph_a, 0, k_tile(kt_a, ph_a));
+        if (T > 1) request_k(kt_b, ph_b, 1, k_tile(kt_b, ph_b));
+        if (T > 2) k_next = k_tile(kt_c, ph_c);
+        v_next = v_tile(kt_a);
+    } else {
+        request_k(kt_a, ph_a, 0, 0);
+        if (T > 1) request_k(kt_b, ph_b, 1, 0);
+    }
     load_q(nD > 0 ? p.qs : p.q);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -367,8 +401,14 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
         constexpr int slot = decltype(slot_tag)::value; // = t % 2: every LDS address below is a compile-time offset
         // K(t+2) replaces K(t) and V(t) replaces V(t-2), both last read before the previous barrier.
         // (Spreading the requests over the slots instead of issuing them here measured 10 % slower.)
-        if (t + 2 < T) request_k(kt_c, ph_c, slot);
-        request_v(kt_a, slot);
+        if (t + 2 < T) request_k(kt_c, ph_c, slot, k_next);
+        request_v(kt_a, slot, v_next);
+        if constexpr (TAB) {
+            int kt_d; bool ph_d;
+            tile_of(t + 3, kt_d, ph_d);
+            if (t + 3 < T) k_next = k_tile(kt_d, ph_d);
+            if (t + 1 < T) v_next = v_tile(kt_b);
+        }
         if (mx_next > m_ref + kLazy) { // (rows with nothing valid so far have mx = -inf and never trigger)
             // The reference moves before tile t is exponentiated: everything computed with the old one is brought
             // to the new one.  That is the row sum, the output accumulators (tiles <= t-2), and P(t-1), whose
@@ -525,11 +565,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(prefill_params p)
 
 } // namespace
 
-int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,
-                       const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
-                       hipStream_t st)
+// tile_tab != NULL: keys and values are located through the per-tile address table (k, v, k_shared are not read)
+static int launch_prefill(const pod_layout &ly, int n, int q0, const void *q, const void *k, const void *v,
+                          const void *q_shared, const void *k_shared, const unsigned long long *tile_tab, int ntiles,
+                          int *len, int *flag, uint64_t lowest_mask, float scale, void *out, hipStream_t st)
 {
-    (void)layer;
     prefill_params p;
     p.n = n; p.q0 = q0; p.Hq = ly.Hq; p.Hkv = ly.Hkv; p.rep = ly.rep; p.S = ly.S; p.W = ly.W;
     p.q = (const pod_bf16 *)q; p.k = (const pod_bf16 *)k; p.v = (const pod_bf16 *)v;
@@ -537,7 +577,10 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const voi
     p.out = (pod_bf16 *)out;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.lowest_mask = lowest_mask;
+    p.tile_tab = tile_tab; p.ntiles = ntiles;
+    p.len = len; p.flag = flag; p.len_old = q0; p.len_new = n;
     if (scale <= 0.f) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
+    if (tile_tab && ntiles < (n + kBN - 1) / kBN) return pod_fail(POD_ERR_INVALID_ARG, "tile table of %d entries for %d keys", ntiles, n);
     // query tiles of 128 positions, counted from the end: the kernel takes tile (n + 127) / 128 - 1 - blockIdx.x / Hq
     const dim3 grid((unsigned)((n + 127) / 128 - q0 / 128) * (unsigned)ly.Hq);
     // dynamic LDS: two K slots and two V slots of kBN tokens x D bf16 each (64 KB at D = 128)
@@ -551,15 +594,35 @@ int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const voi
         if (dev < 0 || dev >= 64) return pod_fail(POD_ERR_INVALID_ARG, "device %d outside [0, 64)", dev);
         std::lock_guard<std::mutex> lock(attr_mutex);
         if (!attr_done[dev]) {
-            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+            POD_HIP_TRY(hipFuncSetAttribute((const void *)prefill_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(64)));
             attr_done[dev] = true;
         }
     }
-    if (ly.D == 128)
-        hipLaunchKernelGGL((prefill_kernel<128>), grid, dim3(256), lds_bytes(128), st, p);
-    else
-        hipLaunchKernelGGL((prefill_kernel<64>), grid, dim3(256), lds_bytes(64), st, p);
+    if (ly.D == 128) {
+        if (tile_tab) hipLaunchKernelGGL((prefill_kernel<128, true>), grid, dim3(256), lds_bytes(128), st, p);
+        else hipLaunchKernelGGL((prefill_kernel<128, false>), grid, dim3(256), lds_bytes(128), st, p);
+    } else {
+        if (tile_tab) hipLaunchKernelGGL((prefill_kernel<64, true>), grid, dim3(256), lds_bytes(64), st, p);
+        else hipLaunchKernelGGL((prefill_kernel<64, false>), grid, dim3(256), lds_bytes(64), st, p);
+    }
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
+}
+
+int pod_launch_prefill(const pod_layout &ly, int layer, int n, int q0, const void *q, const void *k, const void *v,
+                       const void *q_shared, const void *k_shared, uint64_t lowest_mask, float scale, void *out,
+                       hipStream_t st)
+{
+    (void)layer;
+    return launch_prefill(ly, n, q0, q, k, v, q_shared, k_shared, nullptr, 0, nullptr, nullptr, lowest_mask, scale, out, st);
+}
+
+int pod_launch_prefill_tiles(const pod_layout &ly, int n, int q0, const void *q, const void *q_shared,
+                             const unsigned long long *tile_tab, int ntiles, int *len, int *flag, uint64_t lowest_mask, float scale,
+                             void *out, hipStream_t st)
+{
+    return launch_prefill(ly, n, q0, q, nullptr, nullptr, q_shared, nullptr, tile_tab, ntiles, len, flag, lowest_mask, scale, out, st);
 }

@@ -111,11 +111,12 @@ def chunk_inputs(c, layer, seq, p0, t, device):
     return q, k, v, qs, ks
 
 
-def run_chunks(c, chunks, seq=0, check_rows=None):
+def run_chunks(c, chunks, seq=0, check_rows=None, small_workspace=False):
     """Every layer processes the prompt chunk by chunk (attention, then the chunk enters the cache) on the GPU
-    and in the oracle's cache model; outputs are compared chunk by chunk."""
+    and in the oracle's cache model; outputs are compared chunk by chunk.  small_workspace: the scratch sized for
+    calls that store the chunk themselves (guard bands around it: the fixture checks them after the test)."""
     n_total = sum(chunks)
-    ws = c.gpu.new_chunk_workspace(n_total)
+    ws = c.gpu.new_chunk_workspace(n_total, in_place_chunk=max(chunks) if small_workspace else 0)
     p = 0
     for t in chunks:
         for layer in range(c.L):
@@ -134,13 +135,38 @@ def run_chunks(c, chunks, seq=0, check_rows=None):
     c.gpu.pod_cache_check()
 
 
+@pytest.mark.parametrize("in_place", [True, False], ids=["from_the_cache", "from_a_copy"])
 @pytest.mark.parametrize("d,Hq,Hkv", [(128, 4, 2), (64, 4, 1)])
 @pytest.mark.parametrize("chunks", [[300], [1, 1, 1], [5, 59, 1, 63], [64, 64, 64], [127, 2, 128, 43], [40, 200, 17], [129, 300]])
-def test_chunked_prefill_matches_the_oracle(d, Hq, Hkv, chunks):
+def test_chunked_prefill_matches_the_oracle(d, Hq, Hkv, chunks, in_place, monkeypatch):
     """S = 8, W = 40, 64-key tiles and 128-row query tiles: chunk starts inside tiles, chunks shorter and longer
-    than the window, a first chunk that is the whole prompt."""
+    than the window, a first chunk that is the whole prompt.  Both ways the library has of finding the keys and
+    values below the chunk: where the cache holds them (the chunk is stored first), or in a contiguous copy."""
+    if not in_place:
+        monkeypatch.setenv("POD_CHUNK_IN_PLACE", "0")   # read when the cache is created
     c = Case(2, 2, Hq, Hkv, d, 8, 40, 2, 600, seed=320 + len(chunks))
     run_chunks(c, chunks, seq=1)
+
+
+@pytest.mark.parametrize("S,W,chunks", [
+    (64, 128, [256, 256, 128, 64]),          # every region edge on a 64-key tile edge: no tile is staged
+    (64, 128, [64, 64, 64, 64, 64, 64]),     # chunks shorter than the window, the ring wraps on a tile edge
+    (64, 192, [100, 156, 64, 192, 1]),       # edges inside tiles after an odd first chunk
+    (0, 64, [64, 128, 70]),                  # no sink tokens
+    (128, 64, [32, 96, 64, 200]),            # sink longer than the window
+    (8, 40, [700]),                          # one chunk far longer than the window: most of it goes straight to the distant stores
+    (8, 300, [50, 100, 100]),                # everything still inside the window (no distant token)
+])
+def test_chunked_prefill_region_edges_and_key_tiles(S, W, chunks):
+    """Where the sink, the distant stores, the rows kept for this call and the two parts of the ring meet, relative to
+    the 64-key tiles the kernel requests by one address each."""
+    c = Case(2, 2, 4, 2, 128, S, W, 1, 1024, seed=340 + len(chunks))
+    run_chunks(c, chunks, small_workspace=True)
+
+
+def test_chunked_prefill_g4_block_three_upper_layers():
+    c = Case(4, 4, 8, 2, 128, 16, 100, 1, 700, seed=347)
+    run_chunks(c, [130, 64, 300, 77])
 
 
 def test_chunked_prefill_equals_one_shot_prefill_rows():
@@ -225,6 +251,29 @@ def test_chunked_prefill_contract_violations():
     assert e.value.code == pod.binding.ERR_CAPACITY
     with pytest.raises(pod.PodError):
         pod.pod_prefill_chunk_workspace_bytes(c.cfg, 201)
+    with pytest.raises(pod.PodError):
+        pod.pod_prefill_chunk_in_place_bytes(c.cfg, 100, 101)
+    assert pod.pod_prefill_chunk_in_place_bytes(c.cfg, 200, 50) < pod.pod_prefill_chunk_workspace_bytes(c.cfg, 200)
+
+
+def test_chunk_on_a_mirror_that_is_ahead_of_the_device_stores_nothing_and_raises_the_flag():
+    """A rejected append leaves the host mirror one token ahead of the stored length.  The next chunk call then starts
+    from the wrong position: both of its launches see that, the cache keeps its content, the flag goes up."""
+    c = Case(1, 1, 4, 2, 128, 8, 40, 1, 400, seed=335)
+    run_chunks(c, [100])
+    k1 = c.keys(0, 0, 1, c.dev, pos0=100).contiguous()
+    c.gpu.pod_cache_append(0, k1, k1, torch.tensor([7], dtype=torch.int32, device=c.dev))   # wrong position: rejected on the device
+    with pytest.raises(pod.PodError) as e:
+        c.gpu.pod_cache_check()
+    assert e.value.code == pod.binding.ERR_STATE                    # (the check clears the flag; the mirror says 101)
+    ws = c.gpu.new_chunk_workspace(400)
+    q, k, v, _, _ = chunk_inputs(c, 0, 0, 101, 150, c.dev)
+    c.gpu.pod_prefill_attention_chunk(0, 0, q, k, v, None, None, c.scale, ws, write_cache=True)
+    with pytest.raises(pod.PodError) as e:
+        c.gpu.pod_cache_check()
+    assert e.value.code == pod.binding.ERR_STATE
+    c.gpu.pod_cache_sync_lengths()
+    c.assert_cache_equal(0, 0)                                      # still the 100 tokens of the first chunk
 
 
 def test_append_many_more_sequences_than_one_launch_covers():
