@@ -51,6 +51,7 @@ constexpr int kTile = 32;          // tokens per wave iteration
 constexpr float kNegBig = -1.0e30f; // stands in for -inf (keeps exp2 arguments finite)
 constexpr int kMinChunk = 128;     // smallest chunk (tokens) a workgroup takes
 constexpr int kMaxHostLens = 256;  // batch sizes up to this pass the host mirror's lengths as kernel arguments
+constexpr int kUnit = kWaves * kTile; // tokens of one step of a four-wave workgroup: the unit the even split counts in
 
 // Kernel arguments.  Everything is resolved on the host so that the kernel's way to its first
 // K/V load is short: the fields a workgroup needs for its first load addresses sit at the start
@@ -117,7 +118,11 @@ struct decode_params {
     // then device clock at: start, end of the tile loop, partial stored, arrival counted, end); NULL = off
     unsigned long long *trace;
     int32_t trace_cap;
+    // even split (decode_even_kernel): bal_q units of kUnit tokens per workgroup (0: not this kind of launch), bal_nwg
+    // workgroups that walk rows, bal_total units in all; unit_cum[b] = units of the sequences before b (per kv head)
+    int32_t bal_q, bal_nwg, bal_total;
     int32_t hlen[kMaxHostLens];
+    int32_t unit_cum[kMaxHostLens + 1];
     // per kv head: (slot * max_batch of the distant-key store the head reads at this layer) | sign bit if this
     // layer is the lowest of the head's block (then every logit of the head uses q, not q_shared)
     int32_t head_arg[kMaxKvHeads];
@@ -144,6 +149,12 @@ __device__ inline int load_head_arg(int h)
     const volatile __attribute__((address_space(4))) int32_t *ka =
         (const volatile __attribute__((address_space(4))) int32_t *)__builtin_amdgcn_kernarg_segment_ptr();
     return ka[offsetof(decode_params, head_arg) / 4 + (h < kMaxKvHeads ? h : 0)];
+}
+__device__ inline int load_cum_arg(int b)
+{
+    const volatile __attribute__((address_space(4))) int32_t *ka =
+        (const volatile __attribute__((address_space(4))) int32_t *)__builtin_amdgcn_kernarg_segment_ptr();
+    return ka[offsetof(decode_params, unit_cum) / 4 + (b <= kMaxHostLens ? b : 0)];
 }
 __device__ inline int load_hlen_arg(int b)
 {
@@ -344,7 +355,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     if (MODE == 1 && head_arg >= 0) return;
     if (MODE >= 2 && head_arg < 0) return;
     unsigned long long tr_t0 = 0, tr_t1 = 0, tr_t2 = 0;
-    if (MERGE && p.trace) tr_t0 = wall_clock64();
+    if (p.trace) tr_t0 = wall_clock64();
     const u32x4 *kdist = hot.kdist, *vdist = hot.vdist, *kprox = hot.kprox, *vprox = hot.vprox;
     const int cd = hot.cd, prows = hot.prows, hkv = hot.hkv, max_nd = hot.max_nd;
     const int chunk_p = (int)((unsigned)hot.chunk >> 16);
@@ -450,8 +461,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     const int vx = (lane / CPR) % XN;           // which of the XN dims per piece pair this lane serves
     const int last = end > 0 ? end - 1 : 0;
 
-    // Tile loads.  Rows past the chunk are clamped to its last row (valid memory, masked later),
-    // so the loads are unconditional: the software pipeline below needs no branches around them.
+    // Tile loads.  Rows of a tile past the chunk's end are clamped to its last row (valid memory, masked later), so
+    // a tile's loads need no per-lane branches; whole tiles past the end are not requested (a wave-uniform test).
     // V is read non-temporally, K with ordinary loads: every row is used once per launch, and a stream that does not
     // settle in the L2 leaves the partials, the queries and the other stream alone.  Measured, whole decode steps
     // (one sequence of 32K tokens in us; 16 ragged sequences and 4 x 128K tokens in ms; plain / score reuse):
@@ -507,7 +518,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         }
         if (all_skip) return;
     }
-    if (!reads_scores) { POD_LOAD_TILE(t0) }
+    if (!reads_scores && t0 < end) { POD_LOAD_TILE(t0) }
 
     // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
     bf16x8 qf[KST];
@@ -607,12 +618,12 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
             if (m16 >= hot.rep) {                                                     \
                 _Pragma("unroll") for (int i = 0; i < 8; ++i) sc[i] = 0.f; /* padding heads: any finite value */ \
             }                                                                         \
-            POD_LOAD_SV(SR, VR, TNEXT)                                                \
+            if ((TNEXT) < end) { POD_LOAD_SV(SR, VR, TNEXT) } /* (never past the piece: see the K/V loop) */ \
             softmax_pv(sc, vcur);                                                     \
         }
         constexpr int kStep = NW * kTile;
-        POD_LOAD_SV(sregA, vreg, t0)
-        POD_LOAD_SV(sregB, vregB, t0 + kStep)
+        if (t0 < end) { POD_LOAD_SV(sregA, vreg, t0) }
+        if (t0 + kStep < end) { POD_LOAD_SV(sregB, vregB, t0 + kStep) }
         for (; t0 < end; t0 += 2 * kStep) {
             POD_CONSUME_SV(sregA, vreg, t0, t0 + 2 * kStep)
             if (t0 + kStep < end) POD_CONSUME_SV(sregB, vregB, t0 + kStep, t0 + 3 * kStep)
@@ -645,8 +656,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        // ---- next tile's loads go out before the softmax / PV work of this one
-        POD_LOAD_TILE(t0 + NW * kTile)
+        // ---- next tile's loads go out before the softmax / PV work of this one.  Not past the piece's end: nothing
+        // would use them, and the wave would still wait for them before it may hand its partial over and end (as long
+        // as any other load on a saturated memory system: 3 us per workgroup measured).
+        if (t0 + NW * kTile < end) { POD_LOAD_TILE(t0 + NW * kTile) }
 
         // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
         float sc[8];
@@ -683,7 +696,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
     // acc[x][i] is O^T[dim slot 4j+i][head m16]; the slot's dim is
     //   XN = 1: 8*(4j+i) + x        XN = 2: 8*((4j+i) % 8) + 2x + (4j+i)/8
     __syncthreads(); // all waves are done with their K tiles
-    if (MERGE && p.trace) tr_t1 = wall_clock64();
+    if (p.trace) tr_t1 = wall_clock64();
     float *sm_acc = (float *)lds_raw;                 // [NW][rep][RS], dim d of a row at d + 4 (d / 32)
     __shared__ float sm_m[NW][16], sm_l[NW][16];
     if (m16 < hot.rep) {
@@ -721,6 +734,15 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         } else {
             ((gfloat_ptr)hot.part_acc)[slot * D + dim] = A;
             if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
+        }
+    }
+    if constexpr (!MERGE) {
+        const size_t wg = ((size_t)b * hkv + h) * hot.nc + c;
+        if (p.trace && threadIdx.x == 0 && wg < (size_t)p.trace_cap) {
+            unsigned long long *t = p.trace + 8 * wg;
+            t[0] = ((unsigned long long)(b * hkv + h) << 32) | (unsigned)c;
+            t[1] = (unsigned long long)xcc_id() | ((unsigned long long)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4) << 8);
+            t[2] = tr_t0; t[3] = tr_t1; t[6] = wall_clock64();
         }
     }
     if constexpr (MERGE) {
@@ -1035,6 +1057,230 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Launches of several rounds of workgroups (large batches, long contexts), plain mode: the even split.
+//
+// With one piece of a fixed number of tokens per workgroup such a launch ends with a round that is partly empty, and
+// every workgroup pays its start and its hand-over (measured at 16 ragged sequences: 188 us where the same bytes take a
+// plain read 166 us; 4 x 128K tokens: 319-330 against 302).  Here the launch is ONE round: two workgroups per CU, and
+// each walks the same number of rows.  All rows of the batch stand in one line - sequence after sequence, inside a
+// sequence kv head after kv head, inside a (sequence, kv head) pair its distant rows, then its proximal rows - counted
+// in units of kUnit tokens (a region's last unit may be short).  Workgroup w takes units [w q, (w + 1) q).  Where its
+// part crosses from one pair into the next it hands a partial over and starts afresh; where it crosses from a pair's
+// distant rows into its proximal rows it only switches operands (the softmax runs over both, Eq. 3).  A pair's
+// partials come from consecutive workgroups w_lo .. w_hi and sit in its slots 0 .. w_hi - w_lo; decode_combine_kernel
+// works the same numbers out from the lengths.  The lengths are the host mirror's (kernel arguments): without a
+// mirror the launch keeps to fixed pieces.  STEP: bal_nwg more workgroups follow, one per pair, for the new token and
+// the cache update (step_workgroup); the others leave the ring slot it rewrites out, as in decode_partial_kernel.
+// The tile loop is decode_partial_kernel's plain one.
+template <int D, bool STEP>
+__global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_params p)
+{
+    constexpr int NW = kWaves;
+    constexpr int CPR = D / 8, RPI = 64 / CPR, NLD = kTile / RPI, KST = D / 32, XN = 16 / CPR, NPV = 8 / XN;
+    typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+    const decode_hot hot = load_hot_args();
+    const int hkv = hot.hkv, prows = hot.prows;
+    const int w = blockIdx.x;
+    if (w >= p.bal_nwg) {
+        if constexpr (STEP) {
+            const int pr = w - p.bal_nwg;
+            if (pr >= p.npairs) return;
+            const int b = pr / hkv, h = pr - b * hkv;
+            const int n = load_hlen_arg(b);
+            if (n >= 0) step_workgroup<D, false, NW, 0>(p, hot, b, h, n, load_head_arg(h));
+        }
+        return;
+    }
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m16 = lane & 15, j = lane >> 4;
+    const int kr = lane / CPR, kc = lane % CPR, vc = lane % CPR, vx = (lane / CPR) % XN;
+    constexpr int RS = D + 4 * (D / 32) + 1;
+    constexpr size_t kTileBytes = sizeof(u32x4) * NW * kTile * CPR, kMergeBytes = sizeof(float) * NW * 16 * RS;
+    __shared__ __attribute__((aligned(16))) char lds_raw[kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes];
+    __shared__ float sm_m[NW][16], sm_l[NW][16];
+    u32x4 *ldsK = (u32x4 *)lds_raw + (size_t)wave * kTile * CPR;
+    float *sm_acc = (float *)lds_raw;
+
+    const int g_end = min((w + 1) * p.bal_q, p.bal_total);
+    int g = w * p.bal_q;
+    // the sequence that holds unit g: the last b with unit_cum[b] * hkv <= g (unit_cum[nseq] * hkv = bal_total > g)
+    int b = 0;
+    {
+        int hi = p.npairs / hkv;
+        while (hi - b > 1) { // (at most 8 steps)
+            const int mid = (b + hi) >> 1;
+            if (load_cum_arg(mid) * hkv <= g) b = mid; else hi = mid;
+        }
+    }
+    const int nseq = p.npairs / hkv;
+    while (g < g_end && b < nseq) {
+        const int cb = load_cum_arg(b), U = load_cum_arg(b + 1) - cb;   // units per kv head of sequence b
+        const int rel = g - cb * hkv;
+        if (U <= 0 || rel >= U * hkv) { ++b; continue; }
+        const int h = rel / U, u0 = rel - h * U;
+        const int cnt = min(U - u0, g_end - g);
+        g += cnt;
+        const int n = load_hlen_arg(b), head_arg = load_head_arg(h);
+        const int n_prox = n < prows ? n : prows, n_dist = n - n_prox;
+        const int UD = (n_dist + kUnit - 1) / kUnit;
+        const size_t pair = (size_t)b * hkv + h;
+        const size_t kslot_row = (size_t)(head_arg & 0x7fffffff) + b;
+
+        f32x4 acc[NPV];
+#pragma unroll
+        for (int x = 0; x < NPV; ++x) acc[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m_run = kNegBig, l_run = 0.f;
+
+        for (int part = 0; part < 2; ++part) {
+            const bool distant = part == 0;
+            const int ua = distant ? u0 : max(u0, UD) - UD, ub = distant ? min(u0 + cnt, UD) : u0 + cnt - UD;
+            const int region_len = distant ? n_dist : n_prox;
+            const int start = ua * kUnit, end = min(ub * kUnit, region_len);
+            if (ua >= ub || start >= end) continue;
+            const int last = end - 1;
+            const int excl = (STEP && !distant && n >= prows) ? p.sink + (n - p.sink) % p.window : -1;
+            const gvec_ptr Kb = (gvec_ptr)(distant ? hot.kdist + kslot_row * hot.cd * CPR : hot.kprox + pair * prows * CPR);
+            const gvec_ptr Vb = (gvec_ptr)(distant ? hot.vdist + pair * hot.cd * CPR : hot.vprox + pair * prows * CPR);
+            const pod_bf16 *qsrc = (distant && hot.q_shared && head_arg >= 0) ? hot.q_shared : hot.q;
+            u32x4 kreg[NLD], vreg[8];
+#define POD_LOAD_TILE(T0)                                                         \
+    _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                             \
+        const int row = min((T0) + RPI * i + kr, last);                           \
+        kreg[i] = Kb[(size_t)row * CPR + kc];                                     \
+    }                                                                             \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e) {                               \
+        const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);               \
+        const int row = min((T0) + tok, last);                                    \
+        vreg[e] = __builtin_nontemporal_load(&Vb[(size_t)row * CPR + vc]);        \
+    }
+            int t0 = start + wave * kTile;
+            if (t0 < end) { POD_LOAD_TILE(t0) }
+            bf16x8 qf[KST];
+            {
+                const gvec_ptr qrow = (gvec_ptr)(qsrc + ((size_t)b * hot.hq + (size_t)h * hot.rep + m16) * D);
+#pragma unroll
+                for (int s = 0; s < KST; ++s) {
+                    u32x4 t = u32x4{0u, 0u, 0u, 0u};
+                    if (m16 < hot.rep) t = qrow[4 * s + j];
+                    qf[s] = as_bf16x8(t);
+                }
+            }
+            for (; t0 < end; t0 += NW * kTile) {
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) {
+                    const int r = RPI * i + kr;
+                    ldsK[r * CPR + (kc ^ (r % CPR))] = kreg[i];
+                }
+                u32x4 vcur[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vcur[e] = vreg[e];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                // the next tile's loads go out as soon as the registers are free (K is in LDS, V is copied)
+                if (t0 + NW * kTile < end) { POD_LOAD_TILE(t0 + NW * kTile) }
+                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KST; ++s) {
+                    const int col = 4 * s + j;
+                    const u32x4 a0 = ldsK[m16 * CPR + (col ^ (m16 % CPR))];
+                    const u32x4 a1 = ldsK[(16 + m16) * CPR + (col ^ ((16 + m16) % CPR))];
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a0), qf[s], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a1), qf[s], s1, 0, 0, 0);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                float sc[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int tok0 = t0 + 4 * j + i, tok1 = tok0 + 16;
+                    sc[i] = (tok0 < end && (!STEP || tok0 != excl)) ? s0[i] * hot.scale_log2e : kNegBig;
+                    sc[4 + i] = (tok1 < end && (!STEP || tok1 != excl)) ? s1[i] * hot.scale_log2e : kNegBig;
+                }
+                // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain), then O^T += V^T P
+                float mx = sc[0];
+#pragma unroll
+                for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = exp2f(m_run - m_new);
+                float ps = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { sc[i] = exp2f(sc[i] - m_new); ps += sc[i]; }
+                ps += __shfl_xor(ps, 16);
+                ps += __shfl_xor(ps, 32);
+                l_run = l_run * alpha + ps;
+                m_run = m_new;
+#pragma unroll
+                for (int x = 0; x < NPV; ++x) acc[x] *= alpha;
+                u32x4 pw;
+                pw.x = pack_bf16(sc[0], sc[1]); pw.y = pack_bf16(sc[2], sc[3]);
+                pw.z = pack_bf16(sc[4], sc[5]); pw.w = pack_bf16(sc[6], sc[7]);
+                const bf16x8 pf = as_bf16x8(pw);
+#pragma unroll
+                for (int x = 0; x < NPV; ++x) {
+                    u32x4 tlo, thi;
+                    const int wd = (XN == 1) ? (x >> 1) : x;
+                    auto dw = [&](const u32x4 &u) -> unsigned { return u[wd]; };
+                    tlo.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x05040100u);
+                    tlo.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x05040100u);
+                    tlo.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x05040100u);
+                    tlo.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x05040100u);
+                    thi.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x07060302u);
+                    thi.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x07060302u);
+                    thi.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x07060302u);
+                    thi.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x07060302u);
+                    u32x4 vt;
+                    if (XN == 1) {
+                        vt = (x & 1) ? thi : tlo;
+                    } else {
+                        vt.x = vx ? thi.x : tlo.x; vt.y = vx ? thi.y : tlo.y;
+                        vt.z = vx ? thi.z : tlo.z; vt.w = vx ? thi.w : tlo.w;
+                    }
+                    acc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt), pf, acc[x], 0, 0, 0);
+                }
+            }
+#undef POD_LOAD_TILE
+        }
+
+        // ---- this workgroup's partial of the pair: merge the waves, store it in the pair's slot w - w_lo
+        __syncthreads(); // all waves are done with their K tiles
+        if (m16 < hot.rep) {
+#pragma unroll
+            for (int x = 0; x < NPV; ++x)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int slot = 4 * j + i;
+                    const int dim = (XN == 1) ? 8 * slot + x : 8 * (slot % 8) + 2 * x + slot / 8;
+                    sm_acc[((size_t)wave * hot.rep + m16) * RS + dim + 4 * (dim >> 5)] = acc[x][i];
+                }
+            if (j == 0) { sm_m[wave][m16] = m_run; sm_l[wave][m16] = l_run; }
+        }
+        __syncthreads();
+        const int NC = hot.nc + (STEP ? 1 : 0);
+        const int w_lo = (cb * hkv + h * U) / p.bal_q;
+        for (int t = threadIdx.x; t < hot.rep * D; t += blockDim.x) {
+            const int head = t / D, dim = t % D;
+            float M = sm_m[0][head];
+#pragma unroll
+            for (int v = 1; v < NW; ++v) M = fmaxf(M, sm_m[v][head]);
+            float A = 0.f, Lsum = 0.f;
+#pragma unroll
+            for (int v = 0; v < NW; ++v) {
+                const float f = exp2f(sm_m[v][head] - M);
+                A += f * sm_acc[((size_t)v * hot.rep + head) * RS + dim + 4 * (dim >> 5)];
+                Lsum += f * sm_l[v][head];
+            }
+            typedef __attribute__((address_space(1))) float *gfloat_ptr;
+            const size_t slot = ((size_t)b * hot.hq + (size_t)h * hot.rep + head) * NC + (w - w_lo);
+            ((gfloat_ptr)hot.part_acc)[slot * D + dim] = A;
+            if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
+        }
+        __syncthreads(); // the merge buffer is the next pair's K tiles
+    }
+}
+
 // One workgroup per (query head, sequence): merge the chunk partials, normalise, round to bf16.
 // Merging two partials brought to a common max is the paper's gate (Eq. 4) applied to unnormalised
 // sums; over many chunks it is the same running-max merge the partial kernel uses over tiles.
@@ -1076,8 +1322,14 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     const int n_prox = nn < hot.prows ? nn : hot.prows;
     const int n_dist = nn - n_prox;
     const int chunk_d = hot.chunk & 0xffff, chunk_p = (int)((unsigned)hot.chunk >> 16);
-    const int nd = min((n_dist + chunk_d - 1) / chunk_d, hot.max_nd);
-    const int np = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - hot.max_nd);
+    int nd = min((n_dist + chunk_d - 1) / chunk_d, hot.max_nd);
+    int np = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - hot.max_nd);
+    if (p.bal_q > 0) { // even split: the pair's partials are those of the workgroups its units fall to, in its first slots
+        const int U = (n_dist + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
+        const int g0 = load_cum_arg(b) * hot.hkv + (head / hot.rep) * U;
+        nd = U > 0 ? (g0 + U - 1) / p.bal_q - g0 / p.bal_q + 1 : 0;
+        np = 0;
+    }
     const int NC = hot.nc + (step ? 1 : 0);
     const int nvalid = step ? (n >= 0 ? nd + np + 1 : 0) : (n > 0 ? nd + np : 0);
     const gfloat_ptr ml = (gfloat_ptr)hot.part_ml + ((size_t)b * hot.hq + head) * NC * 2;
@@ -1192,7 +1444,9 @@ std::mutex g_scratch_mutex;
 
 // Measurement aid: the plainest kernel that reads `bytes` once: one resident round of workgroups (2 per CU), each
 // walking its own contiguous part with 8 x 16 bytes in flight per thread, results folded into a word nobody stores.
-// What it reaches on cold memory is the ceiling a streaming launch of that size can be held to on this device.
+// Non-temporal loads: the fastest plain read found on this chip (134 MB cold: 21.4-22.4 us against 24.7 us with
+// ordinary loads; 1-2 GB: 7.0-7.2 against 6.1-6.4 TB/s).  What it reaches on cold memory is the ceiling a streaming
+// launch of that size can be held to on this device.
 __device__ unsigned pod_stream_read_sink; // (external linkage: a store the compiler cannot prove dead)
 namespace {
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restrict__ src, size_t n16, size_t per_wg)
@@ -1203,7 +1457,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restric
     for (size_t i = lo + threadIdx.x; i < hi; i += 8 * 256) {
         u32x4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = i + (size_t)u * 256 < hi ? ((gvec_ptr)src)[i + (size_t)u * 256] : u32x4{0u, 0u, 0u, 0u};
+        for (int u = 0; u < 8; ++u) v[u] = i + (size_t)u * 256 < hi ? __builtin_nontemporal_load(&((gvec_ptr)src)[i + (size_t)u * 256]) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u];
     }
@@ -1458,6 +1712,40 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.hot.chunk = (int)((unsigned)pl.chunk | ((unsigned)pl.chunk_p << 16));
     p.hot.max_nd = pl.max_nd;
     p.hot.nc = pl.nc;
+    // The even split (decode_even_kernel) for plain launches of several rounds whose lengths the host knows: one round
+    // of two workgroups per CU, every workgroup the same number of kUnit-token units.
+    p.bal_q = 0; p.bal_nwg = 0; p.bal_total = 0;
+    bool even = !merge_inside && p.mode == 0 && p.hot.use_hlen && c->even_split;
+    if (even) {
+        p.unit_cum[0] = 0;
+        for (int b = 0; b < B; ++b) {
+            const int n = p.hlen[b] > 0 ? p.hlen[b] : 0, n_prox = n < ly.P ? n : ly.P;
+            p.unit_cum[b + 1] = p.unit_cum[b] + (n - n_prox + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
+        }
+        const long total = (long)p.unit_cum[B] * H;
+        if (total <= 0 || total > 0x3fffffff) even = false;
+        else {
+            const long q = (total + 2 * cus - 1) / (2 * cus);
+            p.bal_q = (int32_t)q; p.bal_total = (int32_t)total; p.bal_nwg = (int32_t)((total + q - 1) / q);
+            int most = 1; // partials of the pair that is cut into most parts
+            for (int b = 0; b < B; ++b) {
+                const long U = p.unit_cum[b + 1] - p.unit_cum[b];
+                for (int h = 0; h < H && U > 0; ++h) {
+                    const long g0 = (long)p.unit_cum[b] * H + h * U;
+                    const int parts = (int)((g0 + U - 1) / q - g0 / q) + 1;
+                    most = parts > most ? parts : most;
+                }
+            }
+            // (a batch of one very long and many short sequences cuts the long one into more parts than fixed pieces
+            // would: where the caller's scratch does not hold them the launch keeps to fixed pieces)
+            if ((size_t)B * ly.Hq * ((size_t)most + (step ? 1 : 0)) * (ly.D + 2) * sizeof(float) > ws_bytes) {
+                even = false;
+                p.bal_q = 0; p.bal_nwg = 0; p.bal_total = 0;
+            } else {
+                p.hot.nc = most; p.hot.max_nd = most;
+            }
+        }
+    }
     const size_t NC = (size_t)p.hot.nc + (step ? 1 : 0); // partial slots per query head (a step keeps one more)
     const size_t acc_bytes = (size_t)B * ly.Hq * NC * ly.D * sizeof(float);
     const size_t ml_bytes = (size_t)B * ly.Hq * NC * 2 * sizeof(float);
@@ -1511,7 +1799,14 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
             if (p.hot.max_nd > 0) POD_LAUNCH_PARTIAL(DD, 4, grid_d);                         \
         }                                                                                    \
     }
-    if (ly.D == 128) { POD_LAUNCH_ALL(128) } else { POD_LAUNCH_ALL(64) }
+    if (even) {
+        const dim3 egrid((unsigned)p.bal_nwg + (step ? (unsigned)npairs : 0u));
+        if (ly.D == 128 && step) hipLaunchKernelGGL((decode_even_kernel<128, true>), egrid, dim3(kWaves * 64), 0, st, p);
+        else if (ly.D == 128) hipLaunchKernelGGL((decode_even_kernel<128, false>), egrid, dim3(kWaves * 64), 0, st, p);
+        else if (step) hipLaunchKernelGGL((decode_even_kernel<64, true>), egrid, dim3(kWaves * 64), 0, st, p);
+        else hipLaunchKernelGGL((decode_even_kernel<64, false>), egrid, dim3(kWaves * 64), 0, st, p);
+    }
+    else if (ly.D == 128) { POD_LAUNCH_ALL(128) } else { POD_LAUNCH_ALL(64) }
 #undef POD_LAUNCH_ALL
 #undef POD_LAUNCH_PARTIAL
     if (prof) { POD_HIP_TRY(hipEventRecord(mc->prof_ev[2 * mc->prof_n + 1], st)); mc->prof_n += 1; }

@@ -28,8 +28,8 @@ def test_steps_from_an_empty_cache_across_every_region_edge(d, Hq, Hkv):
     assert c.gpu.pod_cache_seq_len(1, 0) == 40
 
 
-@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}],
-                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel"])
+@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}, {"POD_DECODE_FUSED": "0", "POD_DECODE_EVEN": "0"}],
+                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel-even-split", "separate-merge-kernel-fixed-pieces"])
 def test_steps_on_long_contexts_ragged_batch_several_tiles(env, monkeypatch):
     """Three sequences of different lengths (one still inside S + W, one just past it, one with many split-K
     pieces), 70 steps: the short one crosses S + W on the way.  Through the three ways the partials get merged
@@ -76,8 +76,8 @@ def test_step_equals_append_then_decode_bit_for_bit_in_the_cache():
                 assert torch.equal(ga[name], gb[name]), (layer, seq, name)
 
 
-@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}],
-                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel"])
+@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}, {"POD_DECODE_FUSED": "0", "POD_DECODE_EVEN": "0"}],
+                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel-even-split", "separate-merge-kernel-fixed-pieces"])
 def test_wrong_position_is_flagged_nothing_stored_other_entries_exact(env, monkeypatch):
     for k, v in env.items():
         monkeypatch.setenv(k, v)

@@ -27,8 +27,8 @@ def test_reuse_steps_from_an_empty_cache_across_every_region_edge(d, Hq, Hkv, G)
     assert c.gpu.pod_cache_seq_len(G - 1, 0) == 40
 
 
-@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}],
-                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel"])
+@pytest.mark.parametrize("env", [{}, {"POD_DECODE_XCD_LOCAL": "0"}, {"POD_DECODE_FUSED": "0"}, {"POD_DECODE_FUSED": "0", "POD_DECODE_EVEN": "0"}],
+                         ids=["merge-in-one-xcd", "merge-at-device-scope", "separate-merge-kernel-even-split", "separate-merge-kernel-fixed-pieces"])
 def test_reuse_steps_on_long_contexts_ragged_batch(env, monkeypatch):
     """Three sequences of different lengths (one inside S + W, one just past it, one with many split-K pieces), two
     blocks of two layers, 40 steps; merged inside the launch with either hand-off, and by the separate kernel."""
