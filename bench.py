@@ -419,7 +419,7 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None,
                      "traffic_note": "counters need a rocprofv3 run: profiles/decode_step_kernel_cfg2_pmc.txt holds "
-                                     "FETCH_SIZE + WRITE_SIZE of this kernel on this workload, 135.98 MB per launch = 1.012 x algorithmic",
+                                     "FETCH_SIZE + WRITE_SIZE of this kernel on this workload, 135.89 MB per launch = 1.011 x algorithmic",
                      "bytes_per_launch": int(bytes_per_launch),
                      "avg_kernel_us": round(cold_us, 3), "launches": len(each),
                      "timed": "HIP event pair per launch (reads 1-2 us more than the kernel's own begin-to-end time); "

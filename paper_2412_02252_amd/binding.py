@@ -23,7 +23,7 @@ EXPORTS = [
     "pod_score_buffer_bytes", "pod_decode_attention_reuse", "pod_decode_attention_gated", "pod_score_skip_offset",
     "pod_group_layers", "pod_layer_similarity",
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
-    "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_chunk_in_place_bytes", "pod_prefill_attention_chunk",
+    "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_chunk_in_place_bytes", "pod_prefill_attention_chunk", "pod_decode_even_plan",
     "pod_decode_plan", "pod_decode_step_reuse",
 ]
 
@@ -71,6 +71,7 @@ def load():
         "pod_cache_sync_lengths": [vp, vp],
         "pod_workspace_bytes": [cfgp, szp],
         "pod_decode_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)],
+        "pod_decode_even_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
@@ -203,6 +204,16 @@ def pod_decode_plan(num_cus: int, batch: int, num_kv_heads: int, proximal_rows: 
     plan = (C.c_int32 * 6)()
     _check(load().pod_decode_plan(num_cus, batch, num_kv_heads, proximal_rows, max_context_len, plan))
     return dict(waves=plan[0], chunk=plan[1], chunk_prox=plan[2], distant_pieces=plan[3], pieces=plan[4], merge_inside=bool(plan[5]))
+
+
+def pod_decode_even_plan(num_cus: int, num_kv_heads: int, proximal_rows: int, context_lens) -> dict:
+    """Host logic (no GPU): the even split of a plain decode launch over several rounds' worth of rows."""
+    B = len(context_lens)
+    lens = (C.c_int32 * B)(*[int(n) for n in context_lens])
+    plan = (C.c_int32 * 4)()
+    cum = (C.c_int32 * (B + 1))()
+    _check(load().pod_decode_even_plan(num_cus, B, num_kv_heads, proximal_rows, lens, plan, cum))
+    return dict(units_per_workgroup=plan[0], workgroups=plan[1], units=plan[2], partials_per_pair=plan[3], unit_cum=list(cum))
 
 
 def pod_profile_stream_read(buf: torch.Tensor, nbytes: int, cache=None):

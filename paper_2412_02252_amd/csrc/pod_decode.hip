@@ -1641,6 +1641,35 @@ pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, i
     return pl;
 }
 
+// The even split of a plain launch (host logic): lens[b] tokens per sequence (<= 0: none), `slots` workgroups at most.
+// unit_cum[b] = units of kUnit tokens (distant rows, then proximal rows, each region's last unit may be short) of the
+// sequences before b, per kv head.  All units stand in one line, sequence after sequence, kv head after kv head
+// inside a sequence; workgroup w takes units [w q, (w + 1) q).  most = partials of the pair cut into most parts.
+// Returns false if there is nothing to split.
+bool pod_plan_even(int slots, int B, int Hkv, int P, const int32_t *lens, int32_t *unit_cum, pod_even_plan_t *pl)
+{
+    unit_cum[0] = 0;
+    for (int b = 0; b < B; ++b) {
+        const int n = lens[b] > 0 ? lens[b] : 0, n_prox = n < P ? n : P;
+        unit_cum[b + 1] = unit_cum[b] + (n - n_prox + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
+    }
+    const long total = (long)unit_cum[B] * Hkv;
+    if (total <= 0 || total > 0x3fffffff || slots < 1) return false;
+    const long q = (total + slots - 1) / slots;
+    pl->q = (int32_t)q; pl->total = (int32_t)total; pl->nwg = (int32_t)((total + q - 1) / q);
+    int most = 1;
+    for (int b = 0; b < B; ++b) {
+        const long U = unit_cum[b + 1] - unit_cum[b];
+        for (int h = 0; h < Hkv && U > 0; ++h) {
+            const long g0 = (long)unit_cum[b] * Hkv + h * U;
+            const int parts = (int)((g0 + U - 1) / q - g0 / q) + 1;
+            most = parts > most ? parts : most;
+        }
+    }
+    pl->most = most;
+    return true;
+}
+
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared, const int32_t *ctx, int B,
                       int max_len, float scale, void *ws, size_t ws_bytes, void *scores, float tau, void *out,
                       hipStream_t st, const pod_step_args *step)
@@ -1717,33 +1746,14 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.bal_q = 0; p.bal_nwg = 0; p.bal_total = 0;
     bool even = !merge_inside && p.mode == 0 && p.hot.use_hlen && c->even_split;
     if (even) {
-        p.unit_cum[0] = 0;
-        for (int b = 0; b < B; ++b) {
-            const int n = p.hlen[b] > 0 ? p.hlen[b] : 0, n_prox = n < ly.P ? n : ly.P;
-            p.unit_cum[b + 1] = p.unit_cum[b] + (n - n_prox + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
-        }
-        const long total = (long)p.unit_cum[B] * H;
-        if (total <= 0 || total > 0x3fffffff) even = false;
-        else {
-            const long q = (total + 2 * cus - 1) / (2 * cus);
-            p.bal_q = (int32_t)q; p.bal_total = (int32_t)total; p.bal_nwg = (int32_t)((total + q - 1) / q);
-            int most = 1; // partials of the pair that is cut into most parts
-            for (int b = 0; b < B; ++b) {
-                const long U = p.unit_cum[b + 1] - p.unit_cum[b];
-                for (int h = 0; h < H && U > 0; ++h) {
-                    const long g0 = (long)p.unit_cum[b] * H + h * U;
-                    const int parts = (int)((g0 + U - 1) / q - g0 / q) + 1;
-                    most = parts > most ? parts : most;
-                }
-            }
-            // (a batch of one very long and many short sequences cuts the long one into more parts than fixed pieces
-            // would: where the caller's scratch does not hold them the launch keeps to fixed pieces)
-            if ((size_t)B * ly.Hq * ((size_t)most + (step ? 1 : 0)) * (ly.D + 2) * sizeof(float) > ws_bytes) {
-                even = false;
-                p.bal_q = 0; p.bal_nwg = 0; p.bal_total = 0;
-            } else {
-                p.hot.nc = most; p.hot.max_nd = most;
-            }
+        pod_even_plan_t ev;
+        even = pod_plan_even(2 * cus, B, H, ly.P, p.hlen, p.unit_cum, &ev);
+        // (a batch of one very long and many short sequences cuts the long one into more parts than fixed pieces
+        // would: where the caller's scratch does not hold them the launch keeps to fixed pieces)
+        if (even && (size_t)B * ly.Hq * ((size_t)ev.most + (step ? 1 : 0)) * (ly.D + 2) * sizeof(float) > ws_bytes) even = false;
+        if (even) {
+            p.bal_q = ev.q; p.bal_total = ev.total; p.bal_nwg = ev.nwg;
+            p.hot.nc = ev.most; p.hot.max_nd = ev.most;
         }
     }
     const size_t NC = (size_t)p.hot.nc + (step ? 1 : 0); // partial slots per query head (a step keeps one more)

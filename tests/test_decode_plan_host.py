@@ -3,6 +3,8 @@ tiles, cover both regions, fit the workspace bound, and the partials are merged 
 launch is about one resident round of workgroups."""
 import itertools
 
+import numpy as np
+
 import pytest
 
 import paper_2412_02252_amd as pod
@@ -51,3 +53,73 @@ def test_plan_rejects_bad_arguments():
         with pytest.raises(pod.PodError) as e:
             pod.pod_decode_plan(*args)
         assert e.value.code == pod.binding.ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------------------------------------- the even split
+
+def walk_even_split(plan, Hkv, P, lens):
+    """The walk decode_even_kernel makes, in Python: for every workgroup the (sequence, kv head, first unit, units)
+    parts it takes, and the slot (workgroup - first workgroup of the pair) its partial goes to."""
+    q, nwg, total, cum = plan["units_per_workgroup"], plan["workgroups"], plan["units"], plan["unit_cum"]
+    parts = []
+    for w in range(nwg):
+        g, g_end = w * q, min((w + 1) * q, total)
+        b = max(i for i in range(len(lens)) if cum[i] * Hkv <= g)      # (the kernel's binary search finds the same one)
+        while g < g_end:
+            U = cum[b + 1] - cum[b]
+            rel = g - cum[b] * Hkv
+            if U <= 0 or rel >= U * Hkv:
+                b += 1
+                continue
+            h, u0 = divmod(rel, U)
+            cnt = min(U - u0, g_end - g)
+            w_lo = (cum[b] * Hkv + h * U) // q
+            parts.append((w, b, h, u0, cnt, w - w_lo))
+            g += cnt
+    return parts
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_even_split_covers_every_unit_once_and_the_merge_counts_agree(seed):
+    rng = np.random.default_rng(7000 + seed)
+    cus = int(rng.choice([4, 64, 256, 304]))
+    Hkv = int(rng.choice([1, 2, 8, 11]))
+    P = int(rng.choice([40, 136, 2112, 4224]))
+    B = int(rng.integers(1, 40))
+    lens = [int(x) for x in rng.choice([0, 0, 1, 127, 128, 129, P, P + 1, 5000, 40000, 131072], size=B)]
+    plan = pod.pod_decode_even_plan(cus, Hkv, P, lens)
+    units = [(max(n - P, 0) + 127) // 128 + (min(n, P) + 127) // 128 for n in lens]
+    assert plan["unit_cum"] == [sum(units[:b]) for b in range(B + 1)]
+    total = Hkv * sum(units)
+    if total == 0:
+        assert plan["workgroups"] == 0
+        return
+    q, nwg = plan["units_per_workgroup"], plan["workgroups"]
+    assert plan["units"] == total and nwg <= 2 * cus and (nwg - 1) * q < total <= nwg * q
+    parts = walk_even_split(plan, Hkv, P, lens)
+    seen = {}
+    for w, b, h, u0, cnt, slot in parts:
+        assert 0 <= slot < plan["partials_per_pair"]
+        for u in range(u0, u0 + cnt):
+            assert (b, h, u) not in seen
+            seen[(b, h, u)] = w
+    assert len(seen) == total
+    # what decode_combine_kernel derives from a pair's length alone: as many partials as workgroups touch the pair,
+    # in slots 0 .. count - 1, each written by exactly one workgroup
+    most = 0
+    for b in range(B):
+        for h in range(Hkv):
+            U = units[b]
+            g0 = plan["unit_cum"][b] * Hkv + h * U
+            count = (g0 + U - 1) // q - g0 // q + 1 if U else 0
+            slots = sorted(s for w, bb, hh, u0, cnt, s in parts if (bb, hh) == (b, h))
+            assert slots == list(range(count)), (b, h)
+            most = max(most, count)
+    assert most == plan["partials_per_pair"]
+
+
+def test_even_split_rejects_bad_arguments():
+    with pytest.raises(pod.PodError):
+        pod.pod_decode_even_plan(0, 8, 2112, [100])
+    with pytest.raises(pod.PodError):
+        pod.pod_decode_even_plan(256, 8, 2112, [100] * 257)
