@@ -487,14 +487,17 @@ int pod_decode_even_plan(int num_cus, int batch, int num_kv_heads, int proximal_
  * pod_decode_attention launch that stores a partial result leaves 8 uint64 words in it, at index (workgroup number
  * in the launch) * 8: (sequence * num_kv_heads + kv head) << 32 | piece (bit 31 set: this workgroup merged), the id of
  * the XCD it ran on, and the device's 100 MHz clock at its start, at the end of its tile loop, when its partial was
- * stored, when its arrival was counted, and at its end.  bytes / 64 workgroups are recorded; later launches overwrite
+ * stored, when its arrival was counted, and at its end.  Launches whose partials a second kernel merges record too:
+ * words 0, 2, 3 and 6 as above (start, end of the tile loop, end), word 1 = XCD id | hardware id register << 8 (which
+ * CU); an even-split launch (pod_decode_even_plan) records per walking workgroup its number, that word 1, and the
+ * clock at its start (words 2 and 3) and end (word 6).  bytes / 64 workgroups are recorded; later launches overwrite
  * earlier ones.  The caller owns dev_buf.
  */
 int pod_profile_set_trace(pod_cache *cache, void *dev_buf, size_t bytes);
 
 /*
- * Measurement aid: enqueue the plainest possible kernel that reads `bytes` of device memory once (16-byte loads,
- * one resident round of workgroups, nothing stored).  Timed by the caller on memory that is not in any cache, it
+ * Measurement aid: enqueue the plainest possible kernel that reads `bytes` of device memory once (16-byte
+ * non-temporal loads, one resident round of workgroups, nothing stored).  Timed by the caller on memory that is not in any cache, it
  * gives the rate a streaming launch of that size can reach on this device: the ceiling the decode kernel's
  * launches are compared with.  dev_buf 16-byte aligned, bytes a positive multiple of 16.  With a cache whose
  * profiling is enabled (cache may be NULL) the launch is recorded like a decode launch: same events, read back

@@ -1092,6 +1092,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
         }
         return;
     }
+    const unsigned long long tr_t0 = p.trace ? wall_clock64() : 0;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m16 = lane & 15, j = lane >> 4;
     const int kr = lane / CPR, kc = lane % CPR, vc = lane % CPR, vx = (lane / CPR) % XN;
@@ -1278,6 +1279,12 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
             if (dim == 0) { ((gfloat_ptr)hot.part_ml)[slot * 2] = M; ((gfloat_ptr)hot.part_ml)[slot * 2 + 1] = Lsum; }
         }
         __syncthreads(); // the merge buffer is the next pair's K tiles
+    }
+    if (p.trace && threadIdx.x == 0 && w < p.trace_cap) { // measurement aid: workgroup, XCD and CU, clock at start and end
+        unsigned long long *t = p.trace + 8 * (size_t)w;
+        t[0] = (unsigned long long)w;
+        t[1] = (unsigned long long)xcc_id() | ((unsigned long long)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4) << 8);
+        t[2] = tr_t0; t[3] = tr_t0; t[6] = wall_clock64();
     }
 }
 
