@@ -470,17 +470,19 @@ int pod_profile_mfma_feed(int variant, int iters, void *dev_out, size_t out_byte
 int pod_decode_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, int max_context_len, int32_t plan[6]);
 
 /*
- * Host logic, no device needed: the even split a plain launch takes where pod_decode_plan's plan[5] is 0 and the
- * host knows the lengths (batch <= 256, lengths not taken from the device).  context_lens: HOST int32 [batch], tokens
- * each sequence holds (<= 0: none).  The rows of the batch stand in one line - sequence after sequence, inside a
- * sequence kv head after kv head, inside such a pair its distant rows (tokens beyond proximal_rows), then its proximal
- * rows - counted in units of 128 tokens (a region's last unit may be short).  unit_cum: HOST out int32 [batch + 1],
+ * Host logic, no device needed: the even split a launch takes where pod_decode_plan's plan[5] is 0 and the host
+ * knows the lengths (batch <= 256, lengths not taken from the device): plain launches, and score-reuse decode steps
+ * of layers none of whose kv heads starts a block (they read logits).  context_lens: HOST int32 [batch], tokens each sequence holds (<= 0:
+ * none).  The rows of the batch stand in one line - sequence after sequence, inside a sequence kv head after kv head,
+ * inside such a pair its distant rows (tokens beyond proximal_rows), then its proximal rows - counted in units:
+ * distant_unit_tokens distant rows (128; 256 for a score-reuse step of an upper layer, whose distant rows cost about
+ * half the bytes), 128 proximal rows; a region's last unit may be short.  unit_cum: HOST out int32 [batch + 1],
  * units per kv head of the sequences before b.  plan[0] units per workgroup q (workgroup w walks units
  * [w q, (w + 1) q) of the line), plan[1] workgroups, plan[2] units in all, plan[3] the largest number of workgroups
  * that share one (sequence, kv head) pair = partial results per pair; all 0 if no sequence holds a token.
  */
-int pod_decode_even_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, const int32_t *context_lens,
-                         int32_t plan[4], int32_t *unit_cum);
+int pod_decode_even_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, int distant_unit_tokens,
+                         const int32_t *context_lens, int32_t plan[4], int32_t *unit_cum);
 
 /*
  * Measurement aid: while dev_buf is set (NULL = off), every workgroup of a pod_decode_step / fused

@@ -71,7 +71,7 @@ def load():
         "pod_cache_sync_lengths": [vp, vp],
         "pod_workspace_bytes": [cfgp, szp],
         "pod_decode_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)],
-        "pod_decode_even_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
+        "pod_decode_even_plan": [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
         "pod_cache_append": [vp, C.c_int, vp, vp, i32p, C.c_int, vp],
         "pod_cache_fill": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp],
         "pod_decode_attention": [vp, C.c_int, vp, vp, i32p, C.c_int, C.c_int, C.c_float, vp, C.c_size_t, vp, vp],
@@ -206,13 +206,13 @@ def pod_decode_plan(num_cus: int, batch: int, num_kv_heads: int, proximal_rows: 
     return dict(waves=plan[0], chunk=plan[1], chunk_prox=plan[2], distant_pieces=plan[3], pieces=plan[4], merge_inside=bool(plan[5]))
 
 
-def pod_decode_even_plan(num_cus: int, num_kv_heads: int, proximal_rows: int, context_lens) -> dict:
-    """Host logic (no GPU): the even split of a plain decode launch over several rounds' worth of rows."""
+def pod_decode_even_plan(num_cus: int, num_kv_heads: int, proximal_rows: int, context_lens, distant_unit_tokens: int = 128) -> dict:
+    """Host logic (no GPU): the even split of a decode launch over several rounds' worth of rows."""
     B = len(context_lens)
     lens = (C.c_int32 * B)(*[int(n) for n in context_lens])
     plan = (C.c_int32 * 4)()
     cum = (C.c_int32 * (B + 1))()
-    _check(load().pod_decode_even_plan(num_cus, B, num_kv_heads, proximal_rows, lens, plan, cum))
+    _check(load().pod_decode_even_plan(num_cus, B, num_kv_heads, proximal_rows, distant_unit_tokens, lens, plan, cum))
     return dict(units_per_workgroup=plan[0], workgroups=plan[1], units=plan[2], partials_per_pair=plan[3], unit_cum=list(cum))
 
 

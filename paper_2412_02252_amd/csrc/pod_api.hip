@@ -308,14 +308,17 @@ extern "C" int pod_decode_plan(int num_cus, int batch, int num_kv_heads, int pro
     return POD_OK;
 }
 
-extern "C" int pod_decode_even_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, const int32_t *context_lens,
-                                    int32_t plan[4], int32_t *unit_cum)
+extern "C" int pod_decode_even_plan(int num_cus, int batch, int num_kv_heads, int proximal_rows, int distant_unit_tokens,
+                                    const int32_t *context_lens, int32_t plan[4], int32_t *unit_cum)
 {
     if (!plan || !context_lens || !unit_cum) return pod_fail(POD_ERR_INVALID_ARG, "plan, context_lens and unit_cum must not be NULL");
     if (num_cus < 1 || batch < 1 || batch > 256 || num_kv_heads < 1 || proximal_rows < 1)
         return pod_fail(POD_ERR_INVALID_ARG, "num_cus, num_kv_heads and proximal_rows must be positive, batch in [1, 256]");
+    if (distant_unit_tokens != 128 && distant_unit_tokens != 256)
+        return pod_fail(POD_ERR_INVALID_ARG, "distant_unit_tokens must be 128 or 256");
     pod_even_plan_t ev = {0, 0, 0, 0};
-    if (!pod_plan_even(2 * num_cus, batch, num_kv_heads, proximal_rows, context_lens, unit_cum, &ev)) ev = pod_even_plan_t{0, 0, 0, 0};
+    if (!pod_plan_even(2 * num_cus, batch, num_kv_heads, proximal_rows, distant_unit_tokens, context_lens, unit_cum, &ev))
+        ev = pod_even_plan_t{0, 0, 0, 0};
     plan[0] = ev.q; plan[1] = ev.nwg; plan[2] = ev.total; plan[3] = ev.most;
     return POD_OK;
 }

@@ -52,6 +52,9 @@ constexpr float kNegBig = -1.0e30f; // stands in for -inf (keeps exp2 arguments 
 constexpr int kMinChunk = 128;     // smallest chunk (tokens) a workgroup takes
 constexpr int kMaxHostLens = 256;  // batch sizes up to this pass the host mirror's lengths as kernel arguments
 constexpr int kUnit = kWaves * kTile; // tokens of one step of a four-wave workgroup: the unit the even split counts in
+// ... for distant rows of an upper layer with score reuse twice as many: such a row costs a value row and its logits, 17/32
+// of the bytes of a row whose key is read as well, so that all units cost about the same
+__host__ __device__ constexpr int even_unit_distant(int mode) { return mode == 2 ? 2 * kUnit : kUnit; }
 
 // Kernel arguments.  Everything is resolved on the host so that the kernel's way to its first
 // K/V load is short: the fields a workgroup needs for its first load addresses sit at the start
@@ -121,6 +124,7 @@ struct decode_params {
     // even split (decode_even_kernel): bal_q units of kUnit tokens per workgroup (0: not this kind of launch), bal_nwg
     // workgroups that walk rows, bal_total units in all; unit_cum[b] = units of the sequences before b (per kv head)
     int32_t bal_q, bal_nwg, bal_total;
+    int32_t bal_unit_d;          // tokens per unit of distant rows (kUnit; twice that where an upper layer reads logits instead of keys)
     int32_t hlen[kMaxHostLens];
     int32_t unit_cum[kMaxHostLens + 1];
     // per kv head: (slot * max_batch of the distant-key store the head reads at this layer) | sign bit if this
@@ -676,8 +680,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
                 const gf4_w dst = (gf4_w)(p.scores + ((size_t)b * hkv + h) * p.score_stride * hot.rep) +
                                   (tile * 4 * hot.rep + (size_t)j * hot.rep + m16) * 2;
                 if (!STEP || t0 + kTile <= end) {
-                    dst[0] = f32x4{sc[0], sc[1], sc[2], sc[3]};   // tokens past the chunk carry the mask value
-                    dst[1] = f32x4{sc[4], sc[5], sc[6], sc[7]};
+                    // (tokens past the chunk carry the mask value.  Non-temporal stores: stores inside the read stream cost
+                    // far more than their bytes - a layer that writes logits takes 17-22 % longer for 3 % more bytes - and
+                    // lines that do not settle in the L2 cost a little less: score-reuse steps 1-2 % faster)
+                    __builtin_nontemporal_store(f32x4{sc[0], sc[1], sc[2], sc[3]}, &dst[0]);
+                    __builtin_nontemporal_store(f32x4{sc[4], sc[5], sc[6], sc[7]}, &dst[1]);
                 } else {   // a step's last, partly filled tile: the element behind the last row is step_workgroup's to store
                     typedef __attribute__((address_space(1))) float *gf_w;
 #pragma unroll
@@ -1073,11 +1080,13 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 // mirror the launch keeps to fixed pieces.  STEP: bal_nwg more workgroups follow, one per pair, for the new token and
 // the cache update (step_workgroup); the others leave the ring slot it rewrites out, as in decode_partial_kernel.
 // The tile loop is decode_partial_kernel's plain one.
-template <int D, bool STEP>
+template <int D, bool STEP, int MODE>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_params p)
 {
+    static_assert(MODE == 0 || (MODE == 2 && STEP), "plain launches, and score-reuse decode steps of upper layers");
     constexpr int NW = kWaves;
     constexpr int CPR = D / 8, RPI = 64 / CPR, NLD = kTile / RPI, KST = D / 32, XN = 16 / CPR, NPV = 8 / XN;
+    constexpr int kUnitD = even_unit_distant(MODE);   // tokens per unit of distant rows
     typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
     const decode_hot hot = load_hot_args();
     const int hkv = hot.hkv, prows = hot.prows;
@@ -1087,8 +1096,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
             const int pr = w - p.bal_nwg;
             if (pr >= p.npairs) return;
             const int b = pr / hkv, h = pr - b * hkv;
-            const int n = load_hlen_arg(b);
-            if (n >= 0) step_workgroup<D, false, NW, 0>(p, hot, b, h, n, load_head_arg(h));
+            const int n = load_hlen_arg(b), head_arg = load_head_arg(h);
+            if ((MODE == 2 && head_arg < 0) || n < 0) return;
+            step_workgroup<D, false, NW, MODE>(p, hot, b, h, n, head_arg);
         }
         return;
     }
@@ -1123,8 +1133,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
         const int cnt = min(U - u0, g_end - g);
         g += cnt;
         const int n = load_hlen_arg(b), head_arg = load_head_arg(h);
+        if (MODE == 2 && head_arg < 0) continue; // (a head that starts a block here: not launched so)
         const int n_prox = n < prows ? n : prows, n_dist = n - n_prox;
-        const int UD = (n_dist + kUnit - 1) / kUnit;
+        const int UD = (n_dist + kUnitD - 1) / kUnitD;
         const size_t pair = (size_t)b * hkv + h;
         const size_t kslot_row = (size_t)(head_arg & 0x7fffffff) + b;
 
@@ -1133,18 +1144,69 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
         for (int x = 0; x < NPV; ++x) acc[x] = f32x4{0.f, 0.f, 0.f, 0.f};
         float m_run = kNegBig, l_run = 0.f;
 
-        for (int part = 0; part < 2; ++part) {
-            const bool distant = part == 0;
+        // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain), then O^T += V^T P
+        auto softmax_pv = [&](float (&sc)[8], const u32x4 (&vcur)[8]) {
+            float mx = sc[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = exp2f(m_run - m_new);
+            float ps = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { sc[i] = exp2f(sc[i] - m_new); ps += sc[i]; }
+            ps += __shfl_xor(ps, 16);
+            ps += __shfl_xor(ps, 32);
+            l_run = l_run * alpha + ps;
+            m_run = m_new;
+#pragma unroll
+            for (int x = 0; x < NPV; ++x) acc[x] *= alpha;
+            u32x4 pw;
+            pw.x = pack_bf16(sc[0], sc[1]); pw.y = pack_bf16(sc[2], sc[3]);
+            pw.z = pack_bf16(sc[4], sc[5]); pw.w = pack_bf16(sc[6], sc[7]);
+            const bf16x8 pf = as_bf16x8(pw);
+#pragma unroll
+            for (int x = 0; x < NPV; ++x) {
+                u32x4 tlo, thi;
+                const int wd = (XN == 1) ? (x >> 1) : x;
+                auto dw = [&](const u32x4 &u) -> unsigned { return u[wd]; };
+                tlo.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x05040100u);
+                tlo.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x05040100u);
+                tlo.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x05040100u);
+                tlo.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x05040100u);
+                thi.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x07060302u);
+                thi.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x07060302u);
+                thi.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x07060302u);
+                thi.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x07060302u);
+                u32x4 vt;
+                if (XN == 1) {
+                    vt = (x & 1) ? thi : tlo;
+                } else {
+                    vt.x = vx ? thi.x : tlo.x; vt.y = vx ? thi.y : tlo.y;
+                    vt.z = vx ? thi.z : tlo.z; vt.w = vx ? thi.w : tlo.w;
+                }
+                acc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt), pf, acc[x], 0, 0, 0);
+            }
+        };
+
+        // the part [ua, ub) of a region, in units: its rows [start, end)
+        auto rows_of = [&](bool distant, int &start, int &end) {
             const int ua = distant ? u0 : max(u0, UD) - UD, ub = distant ? min(u0 + cnt, UD) : u0 + cnt - UD;
-            const int region_len = distant ? n_dist : n_prox;
-            const int start = ua * kUnit, end = min(ub * kUnit, region_len);
-            if (ua >= ub || start >= end) continue;
+            const int unit = distant ? kUnitD : kUnit;
+            start = ua * unit;
+            end = min(ub * unit, distant ? n_dist : n_prox);
+            return ua < ub && start < end;
+        };
+        // keys and values of rows [start, end) of one region
+        auto walk_kv = [&](const bool distant, const int start, const int end) {
             const int last = end - 1;
             const int excl = (STEP && !distant && n >= prows) ? p.sink + (n - p.sink) % p.window : -1;
             const gvec_ptr Kb = (gvec_ptr)(distant ? hot.kdist + kslot_row * hot.cd * CPR : hot.kprox + pair * prows * CPR);
             const gvec_ptr Vb = (gvec_ptr)(distant ? hot.vdist + pair * hot.cd * CPR : hot.vprox + pair * prows * CPR);
             const pod_bf16 *qsrc = (distant && hot.q_shared && head_arg >= 0) ? hot.q_shared : hot.q;
             u32x4 kreg[NLD], vreg[8];
+            int t0 = start + wave * kTile;
 #define POD_LOAD_TILE(T0)                                                         \
     _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                             \
         const int row = min((T0) + RPI * i + kr, last);                           \
@@ -1155,7 +1217,6 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
         const int row = min((T0) + tok, last);                                    \
         vreg[e] = __builtin_nontemporal_load(&Vb[(size_t)row * CPR + vc]);        \
     }
-            int t0 = start + wave * kTile;
             if (t0 < end) { POD_LOAD_TILE(t0) }
             bf16x8 qf[KST];
             {
@@ -1198,51 +1259,67 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
                     sc[i] = (tok0 < end && (!STEP || tok0 != excl)) ? s0[i] * hot.scale_log2e : kNegBig;
                     sc[4 + i] = (tok1 < end && (!STEP || tok1 != excl)) ? s1[i] * hot.scale_log2e : kNegBig;
                 }
-                // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain), then O^T += V^T P
-                float mx = sc[0];
-#pragma unroll
-                for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = exp2f(m_run - m_new);
-                float ps = 0.f;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) { sc[i] = exp2f(sc[i] - m_new); ps += sc[i]; }
-                ps += __shfl_xor(ps, 16);
-                ps += __shfl_xor(ps, 32);
-                l_run = l_run * alpha + ps;
-                m_run = m_new;
-#pragma unroll
-                for (int x = 0; x < NPV; ++x) acc[x] *= alpha;
-                u32x4 pw;
-                pw.x = pack_bf16(sc[0], sc[1]); pw.y = pack_bf16(sc[2], sc[3]);
-                pw.z = pack_bf16(sc[4], sc[5]); pw.w = pack_bf16(sc[6], sc[7]);
-                const bf16x8 pf = as_bf16x8(pw);
-#pragma unroll
-                for (int x = 0; x < NPV; ++x) {
-                    u32x4 tlo, thi;
-                    const int wd = (XN == 1) ? (x >> 1) : x;
-                    auto dw = [&](const u32x4 &u) -> unsigned { return u[wd]; };
-                    tlo.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x05040100u);
-                    tlo.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x05040100u);
-                    tlo.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x05040100u);
-                    tlo.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x05040100u);
-                    thi.x = __builtin_amdgcn_perm(dw(vcur[1]), dw(vcur[0]), 0x07060302u);
-                    thi.y = __builtin_amdgcn_perm(dw(vcur[3]), dw(vcur[2]), 0x07060302u);
-                    thi.z = __builtin_amdgcn_perm(dw(vcur[5]), dw(vcur[4]), 0x07060302u);
-                    thi.w = __builtin_amdgcn_perm(dw(vcur[7]), dw(vcur[6]), 0x07060302u);
-                    u32x4 vt;
-                    if (XN == 1) {
-                        vt = (x & 1) ? thi : tlo;
-                    } else {
-                        vt.x = vx ? thi.x : tlo.x; vt.y = vx ? thi.y : tlo.y;
-                        vt.z = vx ? thi.z : tlo.z; vt.w = vx ? thi.w : tlo.w;
-                    }
-                    acc[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt), pf, acc[x], 0, 0, 0);
-                }
+                softmax_pv(sc, vcur);
             }
 #undef POD_LOAD_TILE
+        };
+        // Score reuse, upper layer, distant rows [start, end): their logits are the lowest layer's, stored tile by tile in
+        // the per-lane order of the S^T accumulators; only V is streamed, two tiles in flight per wave.
+        auto walk_sv = [&](const int start, const int end) {
+            const int last = end - 1;
+            const gvec_ptr Vb = (gvec_ptr)(hot.vdist + pair * hot.cd * CPR);
+            u32x4 vreg[8];
+            int t0 = start + wave * kTile;
+                typedef const __attribute__((address_space(1))) f32x4 *gf4_r;
+                const gf4_r sbase = (gf4_r)(p.scores + pair * p.score_stride * hot.rep) + ((size_t)j * hot.rep + (m16 < hot.rep ? m16 : 0)) * 2;
+                f32x4 sregA[2], sregB[2];
+                u32x4 vregB[8];
+#define POD_LOAD_SV(SR, VR, T0)                                                   \
+                {                                                                     \
+                    const gf4_r sp = sbase + (size_t)(min((T0), last) >> 5) * 8 * hot.rep; \
+                    SR[0] = sp[0];                                                    \
+                    SR[1] = sp[1];                                                    \
+                }                                                                     \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e) {                       \
+                    const int tok = (e < 4) ? 4 * j + e : 16 + 4 * j + (e - 4);       \
+                    const int row = min((T0) + tok, last);                            \
+                    VR[e] = __builtin_nontemporal_load(&Vb[(size_t)row * CPR + vc]);  \
+                }
+#define POD_CONSUME_SV(SR, VR, T0, TNEXT)                                         \
+                {                                                                     \
+                    u32x4 vcur[8];                                                    \
+                    float sc[8];                                                      \
+                    _Pragma("unroll") for (int e = 0; e < 8; ++e) vcur[e] = VR[e];    \
+                    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                   \
+                        const int tok0 = (T0) + 4 * j + i, tok1 = tok0 + 16;          \
+                        sc[i] = tok0 < end ? SR[0][i] : kNegBig;                      \
+                        sc[4 + i] = tok1 < end ? SR[1][i] : kNegBig;                  \
+                    }                                                                 \
+                    if (m16 >= hot.rep) {                                             \
+                        _Pragma("unroll") for (int i = 0; i < 8; ++i) sc[i] = 0.f; /* padding heads: any finite value */ \
+                    }                                                                 \
+                    if ((TNEXT) < end) { POD_LOAD_SV(SR, VR, TNEXT) }                 \
+                    softmax_pv(sc, vcur);                                             \
+                }
+                constexpr int kStep = NW * kTile;
+                if (t0 < end) { POD_LOAD_SV(sregA, vreg, t0) }
+                if (t0 + kStep < end) { POD_LOAD_SV(sregB, vregB, t0 + kStep) }
+                for (; t0 < end; t0 += 2 * kStep) {
+                    POD_CONSUME_SV(sregA, vreg, t0, t0 + 2 * kStep)
+                    if (t0 + kStep < end) POD_CONSUME_SV(sregB, vregB, t0 + kStep, t0 + 3 * kStep)
+                }
+#undef POD_CONSUME_SV
+#undef POD_LOAD_SV
+        };
+        {
+            int start, end;
+            if constexpr (MODE == 2) {
+                if (rows_of(true, start, end)) walk_sv(start, end);
+                if (rows_of(false, start, end)) walk_kv(false, start, end);
+            } else {
+                for (int part = 0; part < 2; ++part)
+                    if (rows_of(part == 0, start, end)) walk_kv(part == 0, start, end);
+            }
         }
 
         // ---- this workgroup's partial of the pair: merge the waves, store it in the pair's slot w - w_lo
@@ -1332,7 +1409,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(decode_
     int nd = min((n_dist + chunk_d - 1) / chunk_d, hot.max_nd);
     int np = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - hot.max_nd);
     if (p.bal_q > 0) { // even split: the pair's partials are those of the workgroups its units fall to, in its first slots
-        const int U = (n_dist + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
+        const int U = (n_dist + p.bal_unit_d - 1) / p.bal_unit_d + (n_prox + kUnit - 1) / kUnit;
         const int g0 = load_cum_arg(b) * hot.hkv + (head / hot.rep) * U;
         nd = U > 0 ? (g0 + U - 1) / p.bal_q - g0 / p.bal_q + 1 : 0;
         np = 0;
@@ -1649,16 +1726,16 @@ pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, i
 }
 
 // The even split of a plain launch (host logic): lens[b] tokens per sequence (<= 0: none), `slots` workgroups at most.
-// unit_cum[b] = units of kUnit tokens (distant rows, then proximal rows, each region's last unit may be short) of the
-// sequences before b, per kv head.  All units stand in one line, sequence after sequence, kv head after kv head
+// unit_cum[b] = units (unit_d tokens of distant rows, then kUnit tokens of proximal rows, each region's last unit may
+// be short) of the sequences before b, per kv head.  All units stand in one line, sequence after sequence, kv head after kv head
 // inside a sequence; workgroup w takes units [w q, (w + 1) q).  most = partials of the pair cut into most parts.
 // Returns false if there is nothing to split.
-bool pod_plan_even(int slots, int B, int Hkv, int P, const int32_t *lens, int32_t *unit_cum, pod_even_plan_t *pl)
+bool pod_plan_even(int slots, int B, int Hkv, int P, int unit_d, const int32_t *lens, int32_t *unit_cum, pod_even_plan_t *pl)
 {
     unit_cum[0] = 0;
     for (int b = 0; b < B; ++b) {
         const int n = lens[b] > 0 ? lens[b] : 0, n_prox = n < P ? n : P;
-        unit_cum[b + 1] = unit_cum[b] + (n - n_prox + kUnit - 1) / kUnit + (n_prox + kUnit - 1) / kUnit;
+        unit_cum[b + 1] = unit_cum[b] + (n - n_prox + unit_d - 1) / unit_d + (n_prox + kUnit - 1) / kUnit;
     }
     const long total = (long)unit_cum[B] * Hkv;
     if (total <= 0 || total > 0x3fffffff || slots < 1) return false;
@@ -1751,10 +1828,14 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     // The even split (decode_even_kernel) for plain launches of several rounds whose lengths the host knows: one round
     // of two workgroups per CU, every workgroup the same number of kUnit-token units.
     p.bal_q = 0; p.bal_nwg = 0; p.bal_total = 0;
-    bool even = !merge_inside && p.mode == 0 && p.hot.use_hlen && c->even_split;
+    // (score reuse: the decode step of a layer none of whose kv heads starts a block.  A layer that writes the logits
+    // gains nothing from it: 16 sequences 218 us either way, 4 x 128K tokens 399 against 387 us.)
+    const int even_mode = reuse_step ? 2 : 0;
+    bool even = !merge_inside && p.hot.use_hlen && c->even_split && (p.mode == 0 || (reuse_step && !lowest_any));
+    p.bal_unit_d = even_unit_distant(even_mode);
     if (even) {
         pod_even_plan_t ev;
-        even = pod_plan_even(2 * cus, B, H, ly.P, p.hlen, p.unit_cum, &ev);
+        even = pod_plan_even(2 * cus, B, H, ly.P, p.bal_unit_d, p.hlen, p.unit_cum, &ev);
         // (a batch of one very long and many short sequences cuts the long one into more parts than fixed pieces
         // would: where the caller's scratch does not hold them the launch keeps to fixed pieces)
         if (even && (size_t)B * ly.Hq * ((size_t)ev.most + (step ? 1 : 0)) * (ly.D + 2) * sizeof(float) > ws_bytes) even = false;
@@ -1818,10 +1899,12 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     }
     if (even) {
         const dim3 egrid((unsigned)p.bal_nwg + (step ? (unsigned)npairs : 0u));
-        if (ly.D == 128 && step) hipLaunchKernelGGL((decode_even_kernel<128, true>), egrid, dim3(kWaves * 64), 0, st, p);
-        else if (ly.D == 128) hipLaunchKernelGGL((decode_even_kernel<128, false>), egrid, dim3(kWaves * 64), 0, st, p);
-        else if (step) hipLaunchKernelGGL((decode_even_kernel<64, true>), egrid, dim3(kWaves * 64), 0, st, p);
-        else hipLaunchKernelGGL((decode_even_kernel<64, false>), egrid, dim3(kWaves * 64), 0, st, p);
+#define POD_LAUNCH_EVEN(DD)                                                                                                   \
+        if (even_mode == 2) hipLaunchKernelGGL((decode_even_kernel<DD, true, 2>), egrid, dim3(kWaves * 64), 0, st, p);    \
+        else if (step) hipLaunchKernelGGL((decode_even_kernel<DD, true, 0>), egrid, dim3(kWaves * 64), 0, st, p);              \
+        else hipLaunchKernelGGL((decode_even_kernel<DD, false, 0>), egrid, dim3(kWaves * 64), 0, st, p);
+        if (ly.D == 128) { POD_LAUNCH_EVEN(128) } else { POD_LAUNCH_EVEN(64) }
+#undef POD_LAUNCH_EVEN
     }
     else if (ly.D == 128) { POD_LAUNCH_ALL(128) } else { POD_LAUNCH_ALL(64) }
 #undef POD_LAUNCH_ALL

@@ -134,9 +134,10 @@ struct pod_decode_plan_t { int waves, chunk, chunk_p, max_nd, nc; bool merge_ins
 pod_decode_plan_t pod_plan_decode(int cus, int B, int Hkv, int P, int max_len, int env_chunk, int env_chunk_prox, bool scores,
                                   bool small_prox, bool fused_allowed, bool reader = false);
 // the even split of a plain launch of several rounds (host logic, pod_decode.hip): units per workgroup, workgroups,
-// units in all, partials of the (sequence, kv head) pair that is cut into most parts; unit_cum has B + 1 entries
+// units in all, partials of the (sequence, kv head) pair that is cut into most parts; unit_cum has B + 1 entries;
+// unit_d = tokens per unit of distant rows (128, or 256 for an upper layer that reads logits instead of keys)
 struct pod_even_plan_t { int32_t q, nwg, total, most; };
-bool pod_plan_even(int slots, int B, int Hkv, int P, const int32_t *lens, int32_t *unit_cum, pod_even_plan_t *pl);
+bool pod_plan_even(int slots, int B, int Hkv, int P, int unit_d, const int32_t *lens, int32_t *unit_cum, pod_even_plan_t *pl);
 int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *q_shared,
                       const int32_t *ctx, int B, int max_len, float scale, void *ws, size_t ws_bytes,
                       void *scores, float tau, void *out, hipStream_t st, const pod_step_args *step = nullptr);

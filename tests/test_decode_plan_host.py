@@ -87,8 +87,9 @@ def test_even_split_covers_every_unit_once_and_the_merge_counts_agree(seed):
     P = int(rng.choice([40, 136, 2112, 4224]))
     B = int(rng.integers(1, 40))
     lens = [int(x) for x in rng.choice([0, 0, 1, 127, 128, 129, P, P + 1, 5000, 40000, 131072], size=B)]
-    plan = pod.pod_decode_even_plan(cus, Hkv, P, lens)
-    units = [(max(n - P, 0) + 127) // 128 + (min(n, P) + 127) // 128 for n in lens]
+    ud = int(rng.choice([128, 256]))      # 256: a score-reuse step of an upper layer (distant rows cost about half)
+    plan = pod.pod_decode_even_plan(cus, Hkv, P, lens, distant_unit_tokens=ud)
+    units = [(max(n - P, 0) + ud - 1) // ud + (min(n, P) + 127) // 128 for n in lens]
     assert plan["unit_cum"] == [sum(units[:b]) for b in range(B + 1)]
     total = Hkv * sum(units)
     if total == 0:
@@ -123,3 +124,5 @@ def test_even_split_rejects_bad_arguments():
         pod.pod_decode_even_plan(0, 8, 2112, [100])
     with pytest.raises(pod.PodError):
         pod.pod_decode_even_plan(256, 8, 2112, [100] * 257)
+    with pytest.raises(pod.PodError):
+        pod.pod_decode_even_plan(256, 8, 2112, [100], distant_unit_tokens=64)

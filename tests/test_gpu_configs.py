@@ -161,6 +161,11 @@ def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0, one_launch
         vn = torch.cat([values(l, b, 1, pos0=lens[b]) for b in range(B)]).contiguous()
         qs[l] = torch.cat([gen.queries_bf16(seed, l, b, 1, Hq, d, device=DEV, pos0=lens[b]) for b in range(B)]).contiguous()
         low = l - l % G
+        if one_launch == "reuse":   # ... with score reuse: upper layers read the lowest layer's distant logits
+            if l == 0:
+                scores = cache.new_score_buffer()
+            outs[l] = cache.pod_decode_step_reuse(l, kn, vn, qs[l], pos, scale, scores, max_context_len=max_ctx)
+            continue
         if one_launch:           # cache update + attention through pod_decode_step
             outs[l] = cache.pod_decode_step(l, kn, vn, qs[l], qs[low] if low != l else None, pos, scale, max_context_len=max_ctx)
             continue
@@ -182,7 +187,7 @@ def _big_decode(L, G, B, lens, S, W, seed, samples, outlier_rate=0.0, one_launch
     return cache, outs
 
 
-@pytest.mark.parametrize("one_launch", [False, True], ids=["append+decode", "decode_step"])
+@pytest.mark.parametrize("one_launch", [False, True, "reuse"], ids=["append+decode", "decode_step", "decode_step_reuse"])
 def test_config3_batched_ragged_decode_32_layers(one_launch):
     """32 layers in 16 blocks (G=2), B=16, contexts uniform in [4096, 32768], one decode step over all layers."""
     seed = SEED0 + 3
@@ -193,7 +198,7 @@ def test_config3_batched_ragged_decode_32_layers(one_launch):
     _big_decode(32, 2, 16, lens, 64, 2048, seed, samples, one_launch=one_launch)
 
 
-@pytest.mark.parametrize("one_launch", [False, True], ids=["append+decode", "decode_step"])
+@pytest.mark.parametrize("one_launch", [False, True, "reuse"], ids=["append+decode", "decode_step", "decode_step_reuse"])
 def test_config5_long_context_g4_with_outlier_keys(one_launch):
     """G=4 (8 blocks over 32 layers), B=4, context 131072, S=128, W=4096, 1 % of distant keys scaled x8."""
     seed = SEED0 + 5

@@ -22,7 +22,8 @@ def fill_all(c, lens):
 @pytest.mark.parametrize("seed", range(12))
 def test_random_ragged_batches_decode_and_steps(seed, monkeypatch):
     """Seeded shapes: head counts, head dim, sink 0, windows, 1..24 sequences of 0..3000 tokens (empty ones, ones
-    still inside S + W, long ones): three decode steps, then pod_decode_attention, every layer of the block."""
+    still inside S + W, long ones): three decode steps, pod_decode_attention, three score-reuse steps, every layer of
+    the block."""
     monkeypatch.setenv("POD_DECODE_FUSED", "0")
     rng = np.random.default_rng(9000 + seed)
     d = int(rng.choice([64, 128]))
@@ -34,7 +35,7 @@ def test_random_ragged_batches_decode_and_steps(seed, monkeypatch):
     G = int(rng.choice([1, 2, 3]))
     lens = [int(x) for x in rng.choice([0, 1, S + W, S + W + 1, 129, 700, 1500, 3000], size=B)]
     lens = [max(0, n - int(rng.integers(0, 3))) for n in lens]
-    c = Case(G, G, Hkv * rep, Hkv, d, S, W, B, 3100, seed=9100 + seed)
+    c = Case(G, G, Hkv * rep, Hkv, d, S, W, B, 3110, seed=9100 + seed)
     fill_all(c, lens)
     for layer in range(G):      # (the oracle has no notion of an empty entry: here only that such rows come out zero)
         out = c.decode(layer, lens)
@@ -48,6 +49,13 @@ def test_random_ragged_batches_decode_and_steps(seed, monkeypatch):
     ctx = [n + 3 for n in lens]
     for layer in range(G):
         assert_close(c.decode(layer, ctx), c.decode_ref(layer, ctx), f"decode layer {layer} ctx {ctx}")
+    # ... and three steps with score reuse: the lowest layer writes its distant logits, the upper layers walk units of
+    # twice as many distant rows and read them
+    scores = c.gpu.new_score_buffer()
+    for s in range(3, 6):
+        pos = [n + s for n in lens]
+        for layer in range(G):
+            assert_close(c.step_reuse(layer, pos, scores), c.decode_ref(layer, [p + 1 for p in pos]), f"reuse step {s} layer {layer} lens {lens}")
     for layer in range(G):
         for b in range(B):
             c.assert_cache_equal(layer, b)
@@ -66,10 +74,37 @@ def test_even_split_and_fixed_pieces_agree(monkeypatch):
         o = [c.decode(layer, lens).float() for layer in range(2)]
         pos = list(lens)
         o += [c.step(layer, pos).float() for layer in range(2)]
+        scores = c.gpu.new_score_buffer()
+        pos = [n + 1 for n in lens]
+        o += [c.step_reuse(layer, pos, scores).float() for layer in range(2)]
         outs[even] = o
         c.gpu.pod_cache_check()
     for a, b in zip(outs["1"], outs["0"]):
         assert (a - b).abs().max() <= 2.0 ** -7 * b.abs().max()
+
+
+def test_reuse_steps_follow_plain_steps_and_separate_calls_read_their_logits(monkeypatch):
+    """Logits written by an even-split reuse step of the lowest layer are read by the upper layer's reuse step and,
+    after the next token's lowest-layer call through the separate entry point, by pod_decode_attention_reuse."""
+    monkeypatch.setenv("POD_DECODE_FUSED", "0")
+    lens = [1900, 300, 41, 2600]
+    c = Case(3, 3, 8, 2, 128, 8, 32, len(lens), 2700, seed=9500)
+    fill_all(c, lens)
+    scores = c.gpu.new_score_buffer()
+    for s in range(4):
+        pos = [n + s for n in lens]
+        for layer in range(3):
+            assert_close(c.step_reuse(layer, pos, scores), c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+    pos = [n + 4 for n in lens]
+    ctx = [p + 1 for p in pos]
+    for layer in range(3):
+        c.append(layer, pos)
+    for layer in range(3):
+        assert_close(c.decode_reuse(layer, ctx, scores), c.decode_ref(layer, ctx), f"separate calls layer {layer}")
+    for layer in range(3):
+        for b in range(len(lens)):
+            c.assert_cache_equal(layer, b)
+    c.gpu.pod_cache_check()
 
 
 def test_one_long_sequence_among_many_short_ones(monkeypatch):
