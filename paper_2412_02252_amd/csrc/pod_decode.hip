@@ -1065,7 +1065,8 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// Launches of several rounds of workgroups (large batches, long contexts), plain mode: the even split.
+// Launches of several rounds of workgroups (large batches, long contexts): the even split.  MODE 0: plain.  MODE 2: the
+// decode step of an upper layer with score reuse (distant rows: values and the lowest layer's logits, no keys).
 //
 // With one piece of a fixed number of tokens per workgroup such a launch ends with a round that is partly empty, and
 // every workgroup pays its start and its hand-over (measured at 16 ragged sequences: 188 us where the same bytes take a
@@ -1079,7 +1080,8 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 // works the same numbers out from the lengths.  The lengths are the host mirror's (kernel arguments): without a
 // mirror the launch keeps to fixed pieces.  STEP: bal_nwg more workgroups follow, one per pair, for the new token and
 // the cache update (step_workgroup); the others leave the ring slot it rewrites out, as in decode_partial_kernel.
-// The tile loop is decode_partial_kernel's plain one.
+// The tile loops are decode_partial_kernel's: the plain one, and for MODE 2's distant rows the one that reads logits;
+// there a unit of distant rows is twice as many tokens (even_unit_distant), so that all units cost about the same.
 template <int D, bool STEP, int MODE>
 __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_params p)
 {
