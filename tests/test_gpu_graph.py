@@ -37,8 +37,13 @@ def _step_inputs(c, n0, steps):
     return ins
 
 
-@pytest.mark.parametrize("variant", ["plain", "reuse", "gated", "step_reuse"])
-def test_decode_steps_in_a_graph_equal_eager_steps_on_every_replay(variant):
+@pytest.mark.parametrize("rounds", ["one-round", "several-rounds"])
+@pytest.mark.parametrize("variant", ["plain", "step", "reuse", "gated", "step_reuse"])
+def test_decode_steps_in_a_graph_equal_eager_steps_on_every_replay(variant, rounds, monkeypatch):
+    """several-rounds: the launch shapes of large batches (a second kernel merges the partials; plain calls and the upper
+    layers' reuse steps split the rows evenly over the workgroups), forced on this small shape through the environment."""
+    if rounds == "several-rounds":
+        monkeypatch.setenv("POD_DECODE_FUSED", "0")
     n0, steps = [700, 150], 3
     c = Case(2, 2, 8, 2, 128, 8, 64, 2, 800, seed=900)
     ins = _step_inputs(c, n0, steps)
@@ -49,6 +54,11 @@ def test_decode_steps_in_a_graph_equal_eager_steps_on_every_replay(variant):
             for layer in range(2):
                 c.gpu.pod_decode_step_reuse(layer, e[f"k{layer}"], e[f"v{layer}"], e[f"q{layer}"], e["pos"], c.scale, scores,
                                             out=e[f"o{layer}"], max_context_len=e["n"])
+            return
+        if variant == "step":
+            for layer in range(2):
+                c.gpu.pod_decode_step(layer, e[f"k{layer}"], e[f"v{layer}"], e[f"q{layer}"], e["q0"] if layer else None, e["pos"],
+                                      c.scale, out=e[f"o{layer}"], max_context_len=e["n"])
             return
         for layer in range(2):
             c.gpu.pod_cache_append(layer, e[f"k{layer}"], e[f"v{layer}"], e["pos"])
