@@ -175,8 +175,8 @@ def run_large(workload, K, Wm, variant):
                     "us": stats(cus), "GBs": round(part / (cmed * 1e-6) / 1e9, 1), "frac_of_peak": round(part / (cmed * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                     "kernel_vs_ceiling": round(cmed / kus * per_launch / part, 4)}
         res.update({"GBs": round(nbytes / dt / 1e9, 1), "frac_of_hbm_peak": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4),
-                    "kernel": {"name": ("decode_even_kernel<128, true> (step; one round of workgroups, the batch's rows split evenly over them; decode_combine_kernel merges)"
-                                        if variant == "step" else "decode_even_kernel<128, false>"),
+                    "kernel": {"name": ("decode_even_kernel<128, true, 0> (step; one round of workgroups, the batch's rows split evenly over them; decode_combine_kernel merges)"
+                                        if variant == "step" else "decode_even_kernel<128, false, 0>"),
                                "bytes_per_launch": int(per_launch), "median_us": round(kus, 3),
                                "GBs": round(per_launch / (kus * 1e-6) / 1e9, 1),
                                "frac_of_hbm_peak": round(per_launch / (kus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "launches": len(each)}})
