@@ -107,6 +107,28 @@ def test_reuse_steps_follow_plain_steps_and_separate_calls_read_their_logits(mon
     c.gpu.pod_cache_check()
 
 
+@pytest.mark.parametrize("d,Hkv,rep", [(128, 1, 16), (64, 2, 16), (128, 3, 5), (64, 1, 1)])
+def test_sixteen_query_heads_per_kv_head_and_other_group_sizes(d, Hkv, rep, monkeypatch):
+    """All 16 MFMA columns hold real heads; odd group sizes; a single head."""
+    monkeypatch.setenv("POD_DECODE_FUSED", "0")
+    lens = [1500, 0, 333, 64, 2047]
+    c = Case(2, 2, Hkv * rep, Hkv, d, 4, 60, len(lens), 2100, seed=9600 + rep)
+    fill_all(c, lens)
+    scores = c.gpu.new_score_buffer()
+    for s in range(2):
+        pos = [n + s for n in lens]
+        for layer in range(2):
+            assert_close(c.step(layer, pos), c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+    for s in range(2, 4):
+        pos = [n + s for n in lens]
+        for layer in range(2):
+            assert_close(c.step_reuse(layer, pos, scores), c.decode_ref(layer, [p + 1 for p in pos]), f"reuse step {s} layer {layer}")
+    ctx = [n + 4 for n in lens]
+    for layer in range(2):
+        assert_close(c.decode(layer, ctx), c.decode_ref(layer, ctx), f"decode layer {layer}")
+    c.gpu.pod_cache_check()
+
+
 def test_one_long_sequence_among_many_short_ones(monkeypatch):
     """The long sequence is cut into many more parts than any other: its partial count per pair is the launch's."""
     monkeypatch.setenv("POD_DECODE_FUSED", "0")
