@@ -286,9 +286,11 @@ def test_config4_prompt_in_chunks_sampled_rows_and_cache():
     cache.pod_cache_check()
 
 
-def test_long_prompt_100k_sampled_rows():
+@pytest.mark.parametrize("cuts", [None, [0, 30000, 30001, 65536, 69700, 100003]], ids=["one-call", "five-chunks"])
+def test_long_prompt_100k_sampled_rows(cuts):
     """A prompt of 100003 tokens (config 5's geometry: S=128, W=4096, 32/8 heads): index arithmetic far beyond the
-    benchmark's 16384; sampled rows of the upper layer against the definition, and the distant stores it fills."""
+    benchmark's 16384; sampled rows of the upper layer against the definition, and the distant stores it fills.
+    In one call, and in chunks (keys and values read where the cache holds them; the scratch is the small one)."""
     L, G, Hq, Hkv, d, S, W, n = 2, 2, 32, 8, 128, 128, 4096, 100003
     seed = SEED0 + 6
     cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, 1, n), DEV)
@@ -300,9 +302,19 @@ def test_long_prompt_100k_sampled_rows():
     rows = np.array(sorted(set([0, 1, S, S + W - 1, S + W, 65535, 65536, 65537, n - 2, n - 1] +
                                [int(x) for x in rng.integers(S + W, n, 12)])))
     Kh, Vh = [host_bits(t) for t in K], [host_bits(t) for t in V]
+    if cuts:
+        cfg = pod.make_config(L, G, Hq, Hkv, d, S, W, 1, n)
+        ws = torch.empty(pod.pod_prefill_chunk_in_place_bytes(cfg, n, max(b - a for a, b in zip(cuts[:-1], cuts[1:]))),
+                         dtype=torch.uint8, device=DEV)
+        outs = [torch.empty_like(Q[0]) for _ in range(L)]
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            for l in range(L):
+                cache.pod_prefill_attention_chunk(l, 0, Q[l][a:b], K[l][a:b], V[l][a:b], Q[0][a:b] if l else None,
+                                                  K[0][a:b] if l else None, scale, ws, out=outs[l][a:b], write_cache=True)
+        rows = np.array(sorted(set(rows.tolist() + [c for c in cuts[1:-1]] + [c - 1 for c in cuts[1:-1]])))
     for l in range(L):
-        out = cache.pod_prefill_attention(l, 0, Q[l], K[l], V[l], Q[0] if l else None, K[0] if l else None, scale,
-                                          write_cache=True)
+        out = outs[l] if cuts else cache.pod_prefill_attention(l, 0, Q[l], K[l], V[l], Q[0] if l else None, K[0] if l else None,
+                                                               scale, write_cache=True)
         if l == 1:
             ref = po.pod_attention(host_bits(Q[1][rows].contiguous()), Kh[1], Vh[1], host_bits(Q[0][rows].contiguous()),
                                    Kh[0], rows, S, W, scale)
