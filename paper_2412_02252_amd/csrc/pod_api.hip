@@ -203,6 +203,8 @@ extern "C" int pod_cache_init(const pod_config *cfg, void *dev_buf, size_t bytes
         c->xcd_local = !(e4 && atoi(e4) == 0);
         c->nxcd = 0;
         c->device_lengths = false;
+        const char *e7 = getenv("POD_DECODE_WALK_TURNS");
+        c->walk_turns = !(e7 && atoi(e7) == 0);
         const char *e6 = getenv("POD_DECODE_EVEN");
         c->even_split = !(e6 && atoi(e6) == 0);
         const char *e5 = getenv("POD_CHUNK_IN_PLACE");

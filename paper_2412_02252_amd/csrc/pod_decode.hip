@@ -124,6 +124,7 @@ struct decode_params {
     // even split (decode_even_kernel): bal_q units of kUnit tokens per workgroup (0: not this kind of launch), bal_nwg
     // workgroups that walk rows, bal_total units in all; unit_cum[b] = units of the sequences before b (per kv head)
     int32_t bal_q, bal_nwg, bal_total;
+    int32_t walk_rev;            // 1: walk the tiles of the distant keys a lower layer of the block has just read from the last to the first
     int32_t bal_unit_d;          // tokens per unit of distant rows (kUnit; twice that where an upper layer reads logits instead of keys)
     int32_t hlen[kMaxHostLens];
     int32_t unit_cum[kMaxHostLens + 1];
@@ -522,7 +523,15 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         }
         if (all_skip) return;
     }
-    if (!reads_scores && t0 < end) { POD_LOAD_TILE(t0) }
+    // The wave's tiles, first + k NW kTile below `end`.  Every second layer of a block walks its distant tiles from the last
+    // to the first: the layer below has just read the same keys (one launch earlier, same pieces, same XCD), and what of
+    // them is still in that XCD's L2 are the tiles it read last (config 2: 56.6 -> 55.6 us per step).
+    const int first = t0;
+    const int ntile_w = first < end ? (end - first + NW * kTile - 1) / (NW * kTile) : 0;
+    const bool rev = p.walk_rev != 0 && !reads_scores && distant && head_arg >= 0;
+    const int tstep = rev ? -(NW * kTile) : NW * kTile;
+    if (rev && ntile_w > 0) t0 = first + (ntile_w - 1) * (NW * kTile);
+    if (!reads_scores && ntile_w > 0) { POD_LOAD_TILE(t0) }
 
     // Q as B operand: lane (head m16, j) holds dims 32s + 8j .. +7 of its head (zero past rep).
     bf16x8 qf[KST];
@@ -635,7 +644,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
 #undef POD_CONSUME_SV
 #undef POD_LOAD_SV
     } else
-    for (; t0 < end; t0 += NW * kTile) {
+    for (int it = 0; it < ntile_w; ++it, t0 += tstep) {
         // ---- K tile through LDS into A-operand order
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -663,7 +672,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         // ---- next tile's loads go out before the softmax / PV work of this one.  Not past the piece's end: nothing
         // would use them, and the wave would still wait for them before it may hand its partial over and end (as long
         // as any other load on a saturated memory system: 3 us per workgroup measured).
-        if (t0 + NW * kTile < end) { POD_LOAD_TILE(t0 + NW * kTile) }
+        if (it + 1 < ntile_w) { POD_LOAD_TILE(t0 + tstep) }
 
         // ---- online softmax for head m16 over this lane's 8 tokens (base-2 domain)
         float sc[8];
@@ -1209,6 +1218,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
             const pod_bf16 *qsrc = (distant && hot.q_shared && head_arg >= 0) ? hot.q_shared : hot.q;
             u32x4 kreg[NLD], vreg[8];
             int t0 = start + wave * kTile;
+            // (from the last tile to the first where a lower layer of the block has just read these keys: see decode_partial_kernel)
+            const int ntile_w = t0 < end ? (end - t0 + NW * kTile - 1) / (NW * kTile) : 0;
+            const bool rev = p.walk_rev != 0 && distant && head_arg >= 0;
+            const int tstep = rev ? -(NW * kTile) : NW * kTile;
+            if (rev && ntile_w > 0) t0 += (ntile_w - 1) * (NW * kTile);
 #define POD_LOAD_TILE(T0)                                                         \
     _Pragma("unroll") for (int i = 0; i < NLD; ++i) {                             \
         const int row = min((T0) + RPI * i + kr, last);                           \
@@ -1219,7 +1233,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
         const int row = min((T0) + tok, last);                                    \
         vreg[e] = __builtin_nontemporal_load(&Vb[(size_t)row * CPR + vc]);        \
     }
-            if (t0 < end) { POD_LOAD_TILE(t0) }
+            if (ntile_w > 0) { POD_LOAD_TILE(t0) }
             bf16x8 qf[KST];
             {
                 const gvec_ptr qrow = (gvec_ptr)(qsrc + ((size_t)b * hot.hq + (size_t)h * hot.rep + m16) * D);
@@ -1230,7 +1244,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
                     qf[s] = as_bf16x8(t);
                 }
             }
-            for (; t0 < end; t0 += NW * kTile) {
+            for (int it = 0; it < ntile_w; ++it, t0 += tstep) {
 #pragma unroll
                 for (int i = 0; i < NLD; ++i) {
                     const int r = RPI * i + kr;
@@ -1242,7 +1256,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_even_kernel(decode_para
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 // the next tile's loads go out as soon as the registers are free (K is in LDS, V is copied)
-                if (t0 + NW * kTile < end) { POD_LOAD_TILE(t0 + NW * kTile) }
+                if (it + 1 < ntile_w) { POD_LOAD_TILE(t0 + tstep) }
                 f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < KST; ++s) {
@@ -1805,6 +1819,8 @@ int pod_launch_decode(const pod_cache *c, int layer, const void *q, const void *
     p.low_is_self = lowest == layer;
     p.sink = ly.S; p.window = ly.W;
     p.trace = (unsigned long long *)c->trace; p.trace_cap = c->trace_cap;
+    // layers of a block take turns in the direction they walk the block's distant keys (the lowest layer forward)
+    p.walk_rev = c->walk_turns ? ((layer - c->lowest[(size_t)layer * H]) & 1) : 0;
     // 0: separate combine kernel; 1: the last workgroup of a (sequence, kv head) pair merges; 2: 1 + the cache update
     p.step = step ? 1 : 0;
     // XCD-local hand-off: only where the pairs spread evenly over the XCDs (else some XCDs would sit idle)

@@ -73,6 +73,7 @@ struct pod_cache {
     // distant / proximal region (POD_DECODE_CHUNK, POD_DECODE_CHUNK_PROX)
     int tune_chunk, tune_chunk_prox;
     bool fused_merge;      // plain decode merges its partials inside the streaming kernel (POD_DECODE_FUSED=0: separate kernel)
+    bool walk_turns;       // the layers of a block walk the block's distant keys in alternating directions (POD_DECODE_WALK_TURNS=0: all forward)
     bool even_split;       // launches of several rounds give every workgroup the same number of rows (POD_DECODE_EVEN=0: fixed pieces)
     bool xcd_local;        // hand partials over inside one XCD's L2 where the launch shape allows (POD_DECODE_XCD_LOCAL=0: never)
     int nxcd;              // XCDs a one-dimensional launch is spread over round-robin (0: no such pattern seen by the probe)

@@ -157,3 +157,31 @@ def test_wrong_context_length_is_flagged_in_the_even_split(monkeypatch):
     assert float(out[1].float().abs().max()) == 0.0
     ref = c.decode_ref(0, lens)
     assert_close(out[[0, 2]], ref[[0, 2]], "the other sequences")
+
+
+@pytest.mark.parametrize("rounds", ["one-round", "several-rounds"])
+def test_walk_direction_does_not_change_the_result(rounds, monkeypatch):
+    """The layers of a block walk the block's distant keys in alternating directions; with every layer walking forward
+    (POD_DECODE_WALK_TURNS=0) the outputs differ only by the order of the sums.  G = 3: forward, backward, forward."""
+    outs = {}
+    lens = [2500, 700, 90]
+    for turns in ("1", "0"):
+        monkeypatch.setenv("POD_DECODE_WALK_TURNS", turns)
+        if rounds == "several-rounds":
+            monkeypatch.setenv("POD_DECODE_FUSED", "0")
+        c = Case(3, 3, 8, 2, 128, 8, 64, len(lens), 2600, seed=9700, with_oracle_cache=(turns == "1"))
+        fill_all(c, lens)
+        o = []
+        for s in range(2):
+            pos = [n + s for n in lens]
+            for layer in range(3):
+                out = c.step(layer, pos)
+                if turns == "1":
+                    assert_close(out, c.decode_ref(layer, [p + 1 for p in pos]), f"step {s} layer {layer}")
+                o.append(out.float())
+        ctx = [n + 2 for n in lens]
+        o += [c.decode(layer, ctx).float() for layer in range(3)]
+        outs[turns] = o
+        c.gpu.pod_cache_check()
+    for a, b in zip(outs["1"], outs["0"]):
+        assert (a - b).abs().max() <= 2.0 ** -7 * b.abs().max()
