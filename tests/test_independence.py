@@ -33,7 +33,8 @@ def test_importing_the_product_loads_no_oracle_module_and_vice_versa():
     code = ("import sys, {0}; bad = [m for m in sys.modules if m == '{1}' or m.startswith('{1}.')]; "
             "print(bad); sys.exit(1 if bad else 0)")
     for mod, other in (("paper_2412_02252_amd", "oracle"), ("oracle.pod_oracle", "paper_2412_02252_amd"),
-                       ("oracle.pod_grouping", "paper_2412_02252_amd")):
+                       ("oracle.pod_grouping", "paper_2412_02252_amd"),
+                       ("oracle.pod_select", "paper_2412_02252_amd")):
         r = subprocess.run([sys.executable, "-c", code.format(mod, other)], cwd=ROOT, capture_output=True, text=True)
         assert r.returncode == 0, (mod, r.stdout, r.stderr)
 

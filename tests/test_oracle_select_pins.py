@@ -1,0 +1,194 @@
+"""Pins for the token-selection oracle (oracle/pod_select.py; no GPU): library routines, closed forms, brute force and
+invariants, each chosen so that one plausible mistake (a causal edge off by one, a head mapped to the wrong group, a
+window off centre, the wrong tie order, a region shifted by one) fails it."""
+import math
+
+import numpy as np
+import pytest
+import scipy.ndimage
+import scipy.special
+
+from oracle import pod_oracle as po
+from oracle import pod_select as ps
+from pod_inputs import gen
+
+
+def bits(x):
+    return gen.bf16_bits(x)
+
+
+def np_bits(x):
+    """bf16 bit patterns of float32 values that bf16 holds exactly."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    assert not (u & 0xFFFF).any()
+    return (u >> 16).astype(np.uint16)
+
+
+def _qk(seed, n, Hq, Hkv, d, obs):
+    q = bits(gen.queries_bf16(seed, 0, 0, n, Hq, d))[n - obs:]
+    k = bits(gen.keys_bf16(seed, 0, 0, n, Hkv, d))
+    return q, k
+
+
+def test_bf16_bits_decode_to_their_values():
+    u = np.array([0x3F80, 0xBF80, 0x4000, 0x3E80, 0x0000, 0x4049], dtype=np.uint16)
+    assert ps.bf16_to_f64(u).tolist() == [1.0, -1.0, 2.0, 0.25, 0.0, 3.140625]
+
+
+def test_one_query_one_head_is_the_library_softmax():
+    # obs = 1, one head: the vote IS the softmax of the last position's logits, cut to the distant range
+    n, d, S, W = 40, 8, 3, 5
+    q, k = _qk(5, n, 1, 1, d, 1)
+    got = ps.distant_votes(q, k, S, W, 0.3)
+    logits = 0.3 * (ps.bf16_to_f64(k)[:, 0, :] @ ps.bf16_to_f64(q)[0, 0])
+    np.testing.assert_allclose(got[0], scipy.special.softmax(logits)[S:n - W], rtol=1e-13, atol=0)
+
+
+def test_zero_queries_vote_by_the_number_of_keys_each_sees():
+    # all logits 0: query i (position n - obs + i) gives every key it sees 1 / (n - obs + i + 1); a distant token is
+    # seen by all of them, so its vote is rep * sum_i 1 / (n - obs + i + 1) -- off-by-one in the causal edge shows
+    n, Hq, Hkv, d, S, W, obs = 30, 4, 2, 4, 2, 6, 5
+    q = np.zeros((obs, Hq, d), dtype=np.uint16)
+    k = bits(gen.keys_bf16(2, 0, 0, n, Hkv, d))
+    got = ps.distant_votes(q, k, S, W, 1.0)
+    want = (Hq // Hkv) * sum(1.0 / (n - obs + i + 1) for i in range(obs))
+    assert got.shape == (Hkv, n - S - W)
+    np.testing.assert_allclose(got, want, rtol=1e-14)
+
+
+def test_votes_brute_force_and_mass_conservation():
+    n, Hq, Hkv, d, S, W, obs, scale = 26, 6, 3, 4, 3, 7, 4, 0.7
+    q, k = _qk(9, n, Hq, Hkv, d, obs)
+    got = ps.distant_votes(q, k, S, W, scale)
+    qf, kf = ps.bf16_to_f64(q), ps.bf16_to_f64(k)
+    want = np.zeros_like(got)
+    rest = np.zeros(Hkv)                                # attention that goes to sink and recent tokens
+    for hq in range(Hq):
+        h = hq // 2
+        for i in range(obs):
+            pos = n - obs + i
+            e = [math.exp(scale * sum(qf[i, hq, c] * kf[j, h, c] for c in range(d))) for j in range(pos + 1)]
+            z = sum(e)
+            for j in range(pos + 1):
+                if S <= j < n - W:
+                    want[h, j - S] += e[j] / z
+                else:
+                    rest[h] += e[j] / z
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    np.testing.assert_allclose(got.sum(axis=1) + rest, obs * 2, rtol=1e-12)   # every query spends exactly 1
+
+
+def test_votes_use_the_group_of_the_query_head():
+    # only query head 3 (group of kv head 1) is non-zero and it points at one distant key of kv head 1
+    n, Hq, Hkv, d, S, W = 20, 4, 2, 4, 2, 4
+    k = np.zeros((n, Hkv, d), dtype=np.float32)
+    k[9, 1, :] = 4.0
+    q = np.zeros((1, Hq, d), dtype=np.float32)
+    q[0, 3, :] = 4.0
+    v = ps.distant_votes(np_bits(q), np_bits(k), S, W, 1.0)
+    assert v[1].argmax() == 9 - S and v[1, 9 - S] > 0.99 * 1 + 1 / n      # head 3's query + head 2's uniform share
+    np.testing.assert_allclose(v[0], 2.0 / n, rtol=1e-14)                  # kv head 0: two uniform queries
+
+
+def test_pooling_is_the_library_filter():
+    rng = np.random.default_rng(3)
+    v = rng.random((3, 37))
+    for width in (1, 3, 7):
+        avg = ps.pool_votes(v, width, "avg")
+        mx = ps.pool_votes(v, width, "max")
+        for h in range(3):
+            np.testing.assert_allclose(avg[h], np.convolve(v[h], np.ones(width) / width, mode="same"), rtol=1e-13)
+            np.testing.assert_array_equal(
+                mx[h], scipy.ndimage.maximum_filter1d(v[h], width, mode="constant", cval=-np.inf))
+    # float32 in, float32 out, summed left to right in float32
+    v32 = v.astype(np.float32)
+    a32 = ps.pool_votes(v32, 3, "avg")
+    assert a32.dtype == np.float32
+    assert a32[0, 5] == np.float32(np.float32(np.float32(v32[0, 4] + v32[0, 5]) + v32[0, 6]) / np.float32(3))
+    assert a32[0, 0] == np.float32(np.float32(v32[0, 0] + v32[0, 1]) / np.float32(3))     # zeros outside the range
+
+
+def test_selection_order_and_ties():
+    p = np.array([[0.5, 0.9, 0.5, 0.1, 0.9, 0.5, 0.7]])
+    assert ps.select_top(p, 1).tolist() == [[1]]                 # of the two 0.9 the earlier one
+    assert ps.select_top(p, 2).tolist() == [[1, 4]]
+    assert ps.select_top(p, 3).tolist() == [[1, 4, 6]]
+    assert ps.select_top(p, 4).tolist() == [[0, 1, 4, 6]]        # of the three 0.5 the earliest
+    assert ps.select_top(p, 5).tolist() == [[0, 1, 2, 4, 6]]
+    assert ps.select_top(p, 7).tolist() == [[0, 1, 2, 3, 4, 5, 6]]
+    rng = np.random.default_rng(8)
+    x = rng.integers(0, 6, size=(4, 50)).astype(np.float32)      # many ties
+    for keep in (1, 7, 25, 50):
+        sel = ps.select_top(x, keep)
+        for h in range(4):
+            s = sel[h].tolist()
+            assert s == sorted(set(s)) and len(s) == keep
+            thr = np.sort(x[h])[::-1][keep - 1]
+            out = [t for t in range(50) if t not in s]
+            assert all(x[h, t] >= thr for t in s) and all(x[h, t] <= thr for t in out)
+            at_thr_in = [t for t in s if x[h, t] == thr]
+            at_thr_out = [t for t in out if x[h, t] == thr]
+            assert not at_thr_in or not at_thr_out or max(at_thr_in) < min(at_thr_out)
+
+
+def test_compacted_sequence_holds_sink_selection_recent():
+    n, Hkv, d, S, W = 15, 2, 2, 2, 3
+    x = (np.arange(n)[:, None, None] * 100 + np.arange(Hkv)[None, :, None] * 10 + np.arange(d)).astype(np.uint16)
+    sel = np.array([[0, 4, 9], [1, 2, 8]], dtype=np.int32)        # distant index t = position S + t
+    out = ps.compact_sequence(x, sel, S, W)
+    assert out.shape == (S + 3 + W, Hkv, d)
+    assert (out[:, 0, 0] // 100).tolist() == [0, 1, 2, 6, 11, 12, 13, 14]
+    assert (out[:, 1, 0] // 100).tolist() == [0, 1, 3, 4, 10, 12, 13, 14]
+    assert ((out[:, 1, 0] // 10) % 10 == 1).all() and (out[:, :, 1] - out[:, :, 0] == 1).all()
+
+
+def test_keeping_every_distant_token_changes_nothing_downstream():
+    # keep = all: the compacted cache is the original one, so decode over it gives the original result
+    L, G, Hq, Hkv, d, S, W, n = 2, 2, 4, 2, 8, 2, 5, 21
+    ks = [bits(gen.keys_bf16(4, l, 0, n, Hkv, d)) for l in range(L)]
+    vs = [bits(gen.values_bf16(4, l, 0, n, Hkv, d)) for l in range(L)]
+    qs = [bits(gen.queries_bf16(4, l, 0, n, Hq, d)) for l in range(L)]
+    votes = ps.distant_votes(qs[0][n - 3:], ks[0], S, W, 0.4)
+    sel = ps.select_top(ps.pool_votes(votes, 3, "max"), n - S - W)
+    assert (sel == np.arange(n - S - W)).all()
+    a, b = po.Cache(L, G, Hkv, d, S, W, 1, 64), po.Cache(L, G, Hkv, d, S, W, 1, 64)
+    for l in range(L):
+        a.fill(l, 0, ks[l], vs[l])
+        b.fill(l, 0, ps.compact_sequence(ks[l], sel, S, W), ps.compact_sequence(vs[l], sel, S, W))
+    qd = bits(gen.queries_bf16(4, 1, 0, 1, Hq, d))
+    q0 = bits(gen.queries_bf16(4, 0, 0, 1, Hq, d))
+    np.testing.assert_array_equal(a.decode_attention(1, qd, q0, [n], 0.4), b.decode_attention(1, qd, q0, [n], 0.4))
+
+
+def test_dropping_tokens_that_get_no_attention_changes_little():
+    # distant keys the decode query is orthogonal-and-opposed to carry ~no weight: selecting the others keeps the output
+    L, G, Hq, Hkv, d, S, W, n = 1, 1, 1, 1, 4, 1, 3, 40
+    k = np.zeros((n, 1, d), dtype=np.float32)
+    k[:, 0, 0] = -30.0
+    hot = [5, 6, 17, 30]
+    k[hot, 0, 0] = 2.0
+    k[:S, 0, 0] = 1.0
+    k[n - W:, 0, 0] = 1.0
+    v = bits(gen.values_bf16(6, 0, 0, n, 1, d))
+    q = np.zeros((2, 1, d), dtype=np.float32)
+    q[:, 0, 0] = 1.0
+    votes = ps.distant_votes(np_bits(q), np_bits(k), S, W, 1.0)
+    sel = ps.select_top(ps.pool_votes(votes, 1, "avg"), len(hot))
+    assert (sel[0] + S).tolist() == hot
+    a, b = po.Cache(L, G, 1, d, S, W, 1, 64), po.Cache(L, G, 1, d, S, W, 1, 64)
+    a.fill(0, 0, np_bits(k), v)
+    b.fill(0, 0, ps.compact_sequence(np_bits(k), sel, S, W), ps.compact_sequence(v, sel, S, W))
+    assert b.length(0, 0) == S + len(hot) + W
+    qd = np_bits(q[:1])
+    np.testing.assert_allclose(a.decode_attention(0, qd, None, [n], 1.0),
+                               b.decode_attention(0, qd, None, [S + len(hot) + W], 1.0), atol=1e-10)
+
+
+def test_arguments_are_checked():
+    q, k = _qk(1, 12, 2, 1, 4, 2)
+    with pytest.raises(AssertionError):
+        ps.distant_votes(q, k, 4, 8, 1.0)            # no distant token
+    with pytest.raises(AssertionError):
+        ps.pool_votes(np.zeros((1, 4)), 2, "avg")    # even width
+    with pytest.raises(AssertionError):
+        ps.select_top(np.zeros((1, 4)), 5)
