@@ -424,6 +424,54 @@ int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T
                                 void *workspace, size_t workspace_bytes, void *out, int write_cache, void *stream);
 
 /*
+ * Token selection on the distant store: the combination with a token-selection method that the
+ * result tables list as "PoD+SnapKV" (appendix section on SnapKV: observation window of 64 prompt
+ * positions, grouped-query attention).  The paper gives no rule of its own; these calls apply the
+ * published one to the tokens the combination can drop, the distant ones (proximal tokens are
+ * kept in full by definition, Section 3), per block of layers and kv head, since a block shares
+ * the keys and the logits of its distant tokens (Eq. 3):
+ *   1. pod_select_votes at a block's lowest layer, once the prompt's q and k of that layer exist:
+ *      votes[h][t] = attention that distant token S + t receives from the queries of the last
+ *      `obs` prompt positions in the query heads of kv head h's group, each in its joint softmax
+ *      over the keys up to its own position (Eq. 4), summed.  fp32, fixed summation order.
+ *   2. pod_select_top: votes pooled over pool_width neighbours (POD_POOL_AVG: window sum /
+ *      pool_width with zeros outside the distant range; POD_POOL_MAX: maximum over the positions
+ *      that exist), then the `keep` largest per kv head (of equal ones the earlier token), written
+ *      as ascending distant indices t to row (layer, h) of sel.
+ *   3. pod_cache_compact for every layer, after the prompt is stored at it: the selected
+ *      distant rows move to the front of the layer's distant stores (keys only where it keeps
+ *      them), the recent ring is turned, and the stored length of (layer, seq_slot) becomes
+ *      S + keep + W.  From then on the cache is that of the shorter sequence: positions passed to
+ *      the append, step and decode calls count stored tokens, S + keep + W, S + keep + W + 1, ...
+ *      (rotary positions are the caller's and unaffected: keys arrive rotated).
+ * Shapes (all device memory unless said otherwise):
+ *   q_obs : bf16 [obs][Hq][d], queries of prompt positions n - obs .. n - 1 at `layer`;  1 <= obs <= W
+ *   k     : bf16 [n][Hkv][d], the prompt's keys at `layer` (what pod_prefill_attention was given)
+ *   votes : float [Hkv][n - S - W]; rows of kv heads whose block does not start at `layer` are
+ *           neither written (votes) nor read (top)
+ *   sel   : int32 [num_layers][Hkv][keep]; pod_select_top writes rows (layer, h) of the heads whose
+ *           block starts at `layer`; pod_cache_compact reads, for head h, the row of the lowest
+ *           layer of h's block.  1 <= keep <= n - S - W.
+ *   workspace : 256-byte aligned scratch of pod_select_workspace_bytes(cfg, n, obs, keep) bytes
+ *           (host out; the maximum over the three calls), contents undefined afterwards
+ * n is the prompt length (votes, top) and must equal the stored length at compaction, which is
+ * taken from the host mirror; a device-side length that differs, or a sel entry outside
+ * [0, n - S - W), raises the sticky flag (pod_cache_check): a length that differs leaves the cache
+ * untouched, a bad entry is replaced by 0.  POD_ERR_INVALID_ARG for shapes outside the limits above or
+ * a layer that starts no block (votes, top), POD_ERR_STATE for a slot without distant tokens,
+ * POD_ERR_CAPACITY for a workspace that is too small.
+ */
+#define POD_POOL_AVG 0
+#define POD_POOL_MAX 1
+int pod_select_workspace_bytes(const pod_config *cfg, int64_t n, int obs, int keep, size_t *bytes);
+int pod_select_votes(pod_cache *cache, int layer, int n, const void *q_obs, int obs, const void *k, float scale,
+                     float *votes, void *workspace, size_t workspace_bytes, void *stream);
+int pod_select_top(pod_cache *cache, int layer, int n, const float *votes, int pool_width, int pool_kind, int keep,
+                   int32_t *sel, void *workspace, size_t workspace_bytes, void *stream);
+int pod_cache_compact(pod_cache *cache, int layer, int seq_slot, const int32_t *sel, int keep, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
  * Test hook: copy the cache's logical content for (layer, seq_slot) out in position
  * order, each as dev bf16 [tokens][Hkv][d]:
  *   sink   : positions [0, min(n,S))           recent : [max(S, n-W), n), oldest first

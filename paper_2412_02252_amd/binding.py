@@ -25,6 +25,7 @@ EXPORTS = [
     "pod_decode_attention_static", "pod_cache_region_counts", "pod_decode_step", "pod_cache_set_length_source", "pod_cache_launch_info",
     "pod_cache_sync_lengths", "pod_cache_append_many", "pod_prefill_chunk_workspace_bytes", "pod_prefill_chunk_in_place_bytes", "pod_prefill_attention_chunk", "pod_decode_even_plan",
     "pod_decode_plan", "pod_decode_step_reuse",
+    "pod_select_workspace_bytes", "pod_select_votes", "pod_select_top", "pod_cache_compact",
 ]
 
 
@@ -95,6 +96,10 @@ def load():
         "pod_prefill_chunk_in_place_bytes": [cfgp, C.c_int64, C.c_int64, szp],
         "pod_prefill_attention_chunk": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_size_t, vp,
                                         C.c_int, vp],
+        "pod_select_workspace_bytes": [cfgp, C.c_int64, C.c_int, C.c_int, szp],
+        "pod_select_votes": [vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_float, vp, vp, C.c_size_t, vp],
+        "pod_select_top": [vp, C.c_int, C.c_int, vp, C.c_int, C.c_int, C.c_int, vp, vp, C.c_size_t, vp],
+        "pod_cache_compact": [vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_size_t, vp],
         "pod_profile_enable": [vp, C.c_int],
         "pod_profile_disable": [vp],
         "pod_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)],
@@ -192,6 +197,15 @@ def pod_prefill_chunk_in_place_bytes(cfg: PodConfig, n_total: int, T: int) -> in
     b = C.c_size_t(0)
     _check(load().pod_prefill_chunk_in_place_bytes(C.byref(cfg), n_total, T, C.byref(b)))
     return b.value
+
+
+def pod_select_workspace_bytes(cfg: PodConfig, n: int, obs: int, keep: int) -> int:
+    b = C.c_size_t(0)
+    _check(load().pod_select_workspace_bytes(C.byref(cfg), n, obs, keep, C.byref(b)))
+    return b.value
+
+
+POOL_AVG, POOL_MAX = 0, 1
 
 
 def pod_workspace_bytes(cfg: PodConfig) -> int:
@@ -400,6 +414,38 @@ class PodCache:
         size = (pod_prefill_chunk_in_place_bytes(self.cfg, n_total, in_place_chunk) if in_place_chunk > 0
                 else pod_prefill_chunk_workspace_bytes(self.cfg, n_total))
         return guarded_empty(size, self.device, self.guard_bytes, self, "chunk workspace")
+
+    def new_select_workspace(self, n, obs, keep):
+        """Device buffer for pod_select_votes, pod_select_top and pod_cache_compact on a prompt of n tokens."""
+        return guarded_empty(pod_select_workspace_bytes(self.cfg, n, obs, keep), self.device, self.guard_bytes, self,
+                             "selection workspace")
+
+    def pod_select_votes(self, layer, q_obs, k, scale, workspace, votes=None):
+        """q_obs: bf16 [obs][Hq][d] (the prompt's last queries at `layer`), k: bf16 [n][Hkv][d]; returns float
+        [Hkv][n - S - W] (rows of heads whose block does not start at `layer` are not written)."""
+        c, n, obs = self.cfg, k.shape[0], q_obs.shape[0]
+        if votes is None:
+            votes = torch.zeros((c.num_kv_heads, n - c.sink - c.window), dtype=torch.float32, device=self.device)
+        _check(load().pod_select_votes(self.handle, layer, n, _ptr(q_obs, torch.bfloat16), obs, _ptr(k, torch.bfloat16), scale,
+                                       _ptr(votes, torch.float32), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+        return votes
+
+    def pod_select_top(self, layer, n, votes, pool_width, pool_kind, keep, sel, workspace):
+        """sel: int32 [num_layers][Hkv][keep]; rows (layer, h) of the heads whose block starts at `layer` are written."""
+        c = self.cfg
+        assert tuple(sel.shape) == (c.num_layers, c.num_kv_heads, keep)
+        assert tuple(votes.shape) == (c.num_kv_heads, n - c.sink - c.window)
+        _check(load().pod_select_top(self.handle, layer, n, _ptr(votes, torch.float32), pool_width, pool_kind, keep,
+                                     _ptr(sel, torch.int32), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+        return sel
+
+    def pod_cache_compact(self, layer, seq_slot, sel, workspace):
+        c = self.cfg
+        assert sel.dim() == 3 and tuple(sel.shape[:2]) == (c.num_layers, c.num_kv_heads)
+        _check(load().pod_cache_compact(self.handle, layer, seq_slot, _ptr(sel, torch.int32), sel.shape[2],
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
 
     def pod_prefill_attention(self, layer, seq_slot, q, k, v, q_shared, k_shared, scale, out=None, write_cache=False):
         n = q.shape[0]

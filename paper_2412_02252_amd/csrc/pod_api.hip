@@ -871,6 +871,100 @@ extern "C" int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_
     return POD_OK;
 }
 
+// ---- token selection on the distant store (pod_select.hip) ----
+constexpr int kMaxSelectRows = 4096; // query rows per kv head (observation window x query heads of a group)
+
+static int check_select_shape(const pod_layout &ly, int64_t n, int obs, int keep)
+{
+    if (n > ly.maxctx) return pod_fail(POD_ERR_CAPACITY, "n = %lld exceeds max_context = %d", (long long)n, ly.maxctx);
+    if (n < (int64_t)ly.S + ly.W + 1) return pod_fail(POD_ERR_INVALID_ARG, "n = %lld leaves no distant token (S + W = %d)", (long long)n, ly.P);
+    if (obs < 1 || obs > ly.W || obs * ly.rep > kMaxSelectRows)
+        return pod_fail(POD_ERR_INVALID_ARG, "obs = %d outside [1, min(W = %d, %d / %d query heads per kv head)]", obs, ly.W, kMaxSelectRows, ly.rep);
+    if (keep < 1 || keep > n - ly.S - ly.W)
+        return pod_fail(POD_ERR_INVALID_ARG, "keep = %d outside [1, n - S - W = %lld]", keep, (long long)(n - ly.S - ly.W));
+    return POD_OK;
+}
+
+extern "C" int pod_select_workspace_bytes(const pod_config *cfg, int64_t n, int obs, int keep, size_t *bytes)
+{
+    pod_layout ly;
+    int rc = make_layout(cfg, &ly);
+    if (rc) return rc;
+    if (!bytes) return pod_fail(POD_ERR_INVALID_ARG, "bytes is NULL");
+    rc = check_select_shape(ly, n, obs, keep);
+    if (rc) return rc;
+    size_t b = pod_select_votes_bytes(ly, n, obs);
+    if (pod_select_top_bytes(ly, n) > b) b = pod_select_top_bytes(ly, n);
+    if (pod_compact_bytes(ly, keep) > b) b = pod_compact_bytes(ly, keep);
+    *bytes = b;
+    return POD_OK;
+}
+
+extern "C" int pod_select_votes(pod_cache *cache, int layer, int n, const void *q_obs, int obs, const void *k, float scale,
+                                float *votes, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    rc = check_select_shape(ly, n, obs, 1);
+    if (rc) return rc;
+    if (!layer_lowest_any(cache, layer))
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest layer of any head's block: the block's votes are taken at its lowest layer", layer);
+    if (!q_obs || !k || !votes || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "q_obs, k, votes and workspace must not be NULL");
+    if (((uintptr_t)q_obs | (uintptr_t)k) % 16 || (uintptr_t)votes % 4 || (uintptr_t)workspace % 256)
+        return pod_fail(POD_ERR_INVALID_ARG, "q_obs and k must be 16-byte aligned, workspace 256-byte aligned");
+    if (!(scale > 0.f)) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
+    const size_t need = pod_select_votes_bytes(ly, n, obs);
+    if (workspace_bytes < need) return pod_fail(POD_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    return pod_launch_select_votes(ly, pod_make_headmap(cache, layer).lowest_mask, n, q_obs, obs, k, scale, votes, workspace,
+                                   (hipStream_t)stream);
+}
+
+extern "C" int pod_select_top(pod_cache *cache, int layer, int n, const float *votes, int pool_width, int pool_kind, int keep,
+                              int32_t *sel, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    rc = check_select_shape(ly, n, 1, keep);
+    if (rc) return rc;
+    if (!layer_lowest_any(cache, layer))
+        return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest layer of any head's block", layer);
+    if (!votes || !sel || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "votes, sel and workspace must not be NULL");
+    if (pool_width < 1 || pool_width % 2 == 0 || pool_width > 255 || (pool_kind != POD_POOL_AVG && pool_kind != POD_POOL_MAX))
+        return pod_fail(POD_ERR_INVALID_ARG, "pool_width must be odd and in [1, 255], pool_kind POD_POOL_AVG or POD_POOL_MAX");
+    if ((uintptr_t)votes % 4 || (uintptr_t)sel % 4 || (uintptr_t)workspace % 256)
+        return pod_fail(POD_ERR_INVALID_ARG, "votes and sel must be 4-byte aligned, workspace 256-byte aligned");
+    const size_t need = pod_select_top_bytes(ly, n);
+    if (workspace_bytes < need) return pod_fail(POD_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    return pod_launch_select_top(ly.Hkv, pod_make_headmap(cache, layer).lowest_mask, votes, n - ly.S - ly.W, pool_width,
+                                 pool_kind == POD_POOL_MAX, keep, (float *)workspace, sel + (size_t)layer * ly.Hkv * keep, keep,
+                                 (hipStream_t)stream);
+}
+
+extern "C" int pod_cache_compact(pod_cache *cache, int layer, int seq_slot, const int32_t *sel, int keep, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    int rc = check_cache_layer(cache, layer);
+    if (rc) return rc;
+    const pod_layout &ly = cache->ly;
+    if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
+    int64_t *len = cache->host_len + (size_t)layer * ly.B + seq_slot;
+    if (*len < (int64_t)ly.S + ly.W + 1)
+        return pod_fail(POD_ERR_STATE, "slot %d at layer %d holds %lld tokens: no distant token to select from", seq_slot, layer, (long long)*len);
+    rc = check_select_shape(ly, *len, 1, keep);
+    if (rc) return rc;
+    if (!sel || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "sel and workspace must not be NULL");
+    if ((uintptr_t)sel % 4 || (uintptr_t)workspace % 256)
+        return pod_fail(POD_ERR_INVALID_ARG, "sel must be 4-byte aligned, workspace 256-byte aligned");
+    const size_t need = pod_compact_bytes(ly, keep);
+    if (workspace_bytes < need) return pod_fail(POD_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    rc = pod_launch_compact(cache, layer, seq_slot, (int)*len, sel, keep, workspace, (hipStream_t)stream);
+    if (rc) return rc;
+    *len = (int64_t)ly.S + keep + ly.W;
+    return POD_OK;
+}
+
 extern "C" int pod_cache_export_logical(pod_cache *cache, int layer, int seq_slot, void *sinkK, void *sinkV,
                                         void *recentK, void *recentV, void *distK, void *distV, void *stream)
 {

@@ -156,6 +156,17 @@ int pod_launch_prefill_tiles(const pod_layout &ly, int n, int q0, const void *q,
                              const unsigned long long *tile_tab, int ntiles, int *len, int *flag, uint64_t lowest_mask, float scale,
                              void *out, hipStream_t st);
 
+// token selection on the distant store (pod_select.hip): scratch bytes of the three steps and their launchers.
+// head_mask: kv heads to work on; votes: float [Hkv][n - S - W]; sel: int32 rows of sel_stride entries per kv head
+size_t pod_select_votes_bytes(const pod_layout &ly, int64_t n, int obs);
+size_t pod_select_top_bytes(const pod_layout &ly, int64_t n);
+size_t pod_compact_bytes(const pod_layout &ly, int keep);
+int pod_launch_select_votes(const pod_layout &ly, uint64_t head_mask, int n, const void *q_obs, int obs, const void *k,
+                            float scale, float *votes, void *ws, hipStream_t st);
+int pod_launch_select_top(int Hkv, uint64_t head_mask, const float *votes, int m, int width, int use_max, int keep,
+                          float *pooled, int32_t *sel, int sel_stride, hipStream_t st);
+int pod_launch_compact(const pod_cache *c, int layer, int b, int n, const int32_t *sel_all, int keep, void *ws, hipStream_t st);
+
 size_t pod_decode_workspace_bytes(const pod_layout &ly);
 // device address and size of the library's own split-K scratch array on the current device (looked up once per device)
 int pod_decode_static_scratch(void **ptr, size_t *bytes);
