@@ -59,6 +59,7 @@ def parse():
     ap.add_argument("--reuse", action="store_true", help="with --workload cfg3|cfg5: the step through the score-reuse entry point")
     ap.add_argument("--separate-calls", action="store_true", help="with --workload cfg3|cfg5: pod_cache_append + pod_decode_attention instead of pod_decode_step")
     ap.add_argument("--chunk", type=int, default=2048, help="chunk length of the chunked-prefill figure (0 = skip)")
+    ap.add_argument("--select-keep", type=int, default=1984, help="distant tokens kept per kv head in the token-selection figure (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain copy kernels of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -645,6 +646,58 @@ def main():
                               "tflops": round(G * flops / tot / 1e12, 2),
                               "vs_one_call": round((res["lowest_layer"]["ms"] + res["upper_layer"]["ms"]) / (tot * 1e3), 3)}
             del ws
+        # token selection on the distant store of the same prompt: votes of the last 64 queries at the block's lowest layer,
+        # pooled top-k, compaction of both layers down to 4096 stored tokens, then decode steps on the shorter sequence
+        if a.select_keep > 0 and n - S - W > a.select_keep:
+            obs, keep = 64, a.select_keep
+            sws = torch.empty(pod.pod_select_workspace_bytes(pcfg, n, obs, keep), dtype=torch.uint8, device=dev)
+            sel = torch.zeros((G, Hkv, keep), dtype=torch.int32, device=dev)
+            votes = torch.zeros((Hkv, n - S - W), dtype=torch.float32, device=dev)
+            q_obs = q[0][n - obs:].contiguous()
+            tv, tt, tc = [], [], []
+            for it in range(5):
+                pc.pod_cache_reset(-1)
+                for layer in range(G):
+                    pc.pod_cache_fill(layer, 0, k[layer], v[layer])
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                ev[0].record()
+                pc.pod_select_votes(0, q_obs, k[0], scale, sws, votes=votes)
+                ev[1].record()
+                pc.pod_select_top(0, n, votes, 7, pod.POOL_MAX, keep, sel, sws)
+                ev[2].record()
+                for layer in range(G):
+                    pc.pod_cache_compact(layer, 0, sel, sws)
+                ev[3].record()
+                torch.cuda.synchronize()
+                tv.append(ev[0].elapsed_time(ev[1])); tt.append(ev[1].elapsed_time(ev[2])); tc.append(ev[2].elapsed_time(ev[3]))
+            m = S + keep + W
+            kn = [gen.keys_bf16(pseed, l, 0, 1, Hkv, d, device=dev, pos0=n) for l in range(G)]
+            vn = [gen.values_bf16(pseed, l, 0, 1, Hkv, d, device=dev, pos0=n) for l in range(G)]
+            qn = [gen.queries_bf16(pseed, l, 0, 1, Hq, d, device=dev, pos0=n) for l in range(G)]
+            od = torch.empty_like(qn[0])
+            pos = torch.full((1,), m, dtype=torch.int32, device=dev)
+            nst = 24
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(nst + 1)]
+            for st in range(nst):
+                evs[st].record()
+                for layer in range(G):
+                    pc.pod_decode_step(layer, kn[layer], vn[layer], qn[layer], qn[0] if layer else None, pos, scale, out=od)
+                pos += 1
+            evs[nst].record()
+            torch.cuda.synchronize()
+            steps_us = [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(4, nst)]
+            rows = obs * (Hq // Hkv)
+            vflops = 2.0 * d * rows * Hkv * (n + (n - S - W))      # both passes of the votes: all keys, then the distant ones
+            tvm = statistics.median(tv[1:])
+            res["token_selection"] = {
+                "what": f"prompt {n} -> {m} stored tokens per layer: votes of the last {obs} queries (lowest layer), max-pool 7, "
+                        f"top {keep} of {n - S - W} distant tokens per kv head, compaction of both layers; then decode steps",
+                "ms_votes": round(tvm, 4), "votes_tflops": round(vflops / tvm / 1e9, 2),
+                "ms_top": round(statistics.median(tt[1:]), 4), "ms_compact_both_layers": round(statistics.median(tc[1:]), 4),
+                "share_of_block_prefill": round((tvm + statistics.median(tt[1:]) + statistics.median(tc[1:]))
+                                                / (res["lowest_layer"]["ms"] + res["upper_layer"]["ms"]), 4),
+                "decode_step_us_both_layers_after": round(statistics.median(steps_us), 2)}
+            del sws, sel, votes
         # what the matrix pipes can do at all when every MFMA takes an operand fragment out of LDS (synthetic loops at the
         # kernel's occupancy; 32 cycles per MFMA and SIMD = never idle)
         feed = {}

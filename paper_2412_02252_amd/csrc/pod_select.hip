@@ -15,8 +15,9 @@
 //           cache is then the cache of the shorter sequence and every other call works on it unchanged.
 //
 // The votes are a dense contraction (obs * rep query rows x n keys x D per kv head) and run on
-// v_mfma_f32_32x32x16_bf16 with both operands fetched from global memory in fragment order (a lane's fragment is 8
-// consecutive bf16 of one row; the query rows of a kv head are 64 KB and stay in L2).  Two passes over the keys:
+// v_mfma_f32_32x32x16_bf16: the query rows of a kv head (64 KB at 64 positions x 4 heads x 128) are staged in LDS,
+// the keys come from global memory in fragment order (a lane's fragment is 8 consecutive bf16 of one row) once per
+// workgroup, and every key fragment meets all row blocks out of LDS.  Two passes over the keys:
 // the first takes each query row's maximum and sum of exponentials over all keys it sees (S^T = K Q^T: a lane
 // owns a query row, so the reduction over keys is in-lane), the second recomputes the distant logits transposed
 // (S = Q K^T: a lane owns a key, so the sum over query rows is in-lane) and writes one vote per key.  Every sum
@@ -47,7 +48,7 @@ struct select_params {
     float scale_log2; // logit scale times log2(e)
     uint64_t head_mask;
     float2 *part;     // [Hkv][npieces][nrb * 32]  (maximum, sum of exponentials) of a row over one piece of keys
-    float2 *stat;     // [Hkv][nrb * 32]           (maximum, 1 / sum) over all keys the row sees
+    float *stat;      // [Hkv][nrb * 32]           maximum + log2(sum of exponentials) over all keys the row sees
     float *votes;     // [Hkv][n - S - W]
 };
 
@@ -66,6 +67,9 @@ __device__ inline const pod_bf16 *query_row(const select_params &p, int h, int r
     return p.q_obs + ((size_t)(rr / p.rep) * p.Hq + (size_t)h * p.rep + rr % p.rep) * D;
 }
 
+// v_exp_f32: 2^x to 1 ulp; results below the smallest normal number come out as 0, which a softmax weight may
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // (m, l) + (m2, l2) of two disjoint key sets; an empty set is (-inf, 0)
 __device__ inline void merge_stat(float &m, float &l, float m2, float l2)
 {
@@ -76,6 +80,37 @@ __device__ inline void merge_stat(float &m, float &l, float m2, float l2)
     l = a + b;
 }
 
+// Query rows in LDS: a chunk of kSelChunkRows rows (8 blocks of 32) of one kv head, row-major, rows padded by 16
+// bytes so that the 16 lanes of one LDS access (rows r .. r + 15, same column) fall into different banks.  A
+// workgroup stages a chunk once and every fragment it then needs comes out of LDS: the keys are read from global
+// memory once per workgroup and chunk instead of once per MFMA.
+constexpr int kSelChunkBlocks = 8;
+constexpr int kSelChunkRows = 32 * kSelChunkBlocks;
+template <int D> constexpr int kSelRowBytes = D * 2 + 16;
+
+template <int D>
+__device__ inline void stage_query_rows(const select_params &p, int h, int row0, char *lds)
+{
+    constexpr int cpr = D / 8; // 16-byte pieces per row
+    for (int idx = threadIdx.x; idx < kSelChunkRows * cpr; idx += kSelThreads) {
+        const int row = idx / cpr, c = idx % cpr;
+        sel_u32x4 val = {0, 0, 0, 0}; // rows past the end: zeros (their logits are never used)
+        if (row0 + row < p.R) val = *(const sel_u32x4 *)(query_row(p, h, row0 + row, D) + c * 8);
+        *(sel_u32x4 *)(lds + row * kSelRowBytes<D> + c * 16) = val;
+    }
+}
+
+template <int D>
+__device__ inline void lds_row_fragments(const char *lds, int rb, int lane, sel_u32x4 (&f)[D / 16])
+{
+    const char *row = lds + (rb * 32 + (lane & 31)) * kSelRowBytes<D> + (lane >> 5) * 16;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) f[kk] = *(const sel_u32x4 *)(row + kk * 32);
+}
+
+// First pass.  Workgroup = (piece of keys, kv head, chunk of query rows); a wave walks its key blocks of 32 and, per
+// key block, the chunk's row blocks: S^T = K Q^T, a lane owns query row lane % 32 of each row block and keeps that
+// row's running maximum and sum of exponentials.
 template <int D>
 __global__ __launch_bounds__(kSelThreads) void select_stat_kernel(select_params p)
 {
@@ -84,64 +119,113 @@ __global__ __launch_bounds__(kSelThreads) void select_stat_kernel(select_params 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int key_lo = blockIdx.x * p.keys_per_wg;
     const int key_hi = key_lo + p.keys_per_wg < p.n ? key_lo + p.keys_per_wg : p.n;
-    __shared__ float2 red[kSelThreads / 64][32];
-    for (int rb = 0; rb < p.nrb; ++rb) {
-        const int r = rb * 32 + (lane & 31);
-        const int qpos = p.n - p.obs + (r < p.R ? r : 0) / p.rep; // the row's own position: it sees keys 0 .. qpos
-        sel_u32x4 qf[D / 16];
-        load_row_fragments<D>(query_row(p, h, r, D), lane, qf);
-        float m = -INFINITY, l = 0.f;
-        for (int key0 = key_lo + wave * 32; key0 < key_hi; key0 += kSelKeysPerIter) {
-            const int key = key0 + (lane & 31) < p.n ? key0 + (lane & 31) : p.n - 1;
-            sel_u32x4 kf[D / 16];
-            load_row_fragments<D>(p.k + ((size_t)key * p.Hkv + h) * D, lane, kf);
+    const int row0 = blockIdx.z * kSelChunkRows;
+    const int nblk = (p.R - row0 + 31) / 32 < kSelChunkBlocks ? (p.R - row0 + 31) / 32 : kSelChunkBlocks; // row blocks in use
+    __shared__ __align__(16) char ldsq[kSelChunkRows * kSelRowBytes<D>];
+    __shared__ float2 red[kSelThreads / 64][kSelChunkRows];
+    stage_query_rows<D>(p, h, row0, ldsq);
+    __syncthreads();
+    float m[kSelChunkBlocks], l[kSelChunkBlocks];
+    int qpos[kSelChunkBlocks]; // the row's own position: it sees keys 0 .. qpos
+#pragma unroll
+    for (int rb = 0; rb < kSelChunkBlocks; ++rb) {
+        const int r = row0 + rb * 32 + (lane & 31);
+        m[rb] = -INFINITY;
+        l[rb] = 0.f;
+        qpos[rb] = p.n - p.obs + (r < p.R ? r : 0) / p.rep;
+    }
+    sel_u32x4 kf[D / 16], kn[D / 16];
+    auto key_row = [&](int key0) {
+        const int key = key0 + (lane & 31) < p.n ? key0 + (lane & 31) : p.n - 1;
+        return p.k + ((size_t)key * p.Hkv + h) * D;
+    };
+    int key0 = key_lo + wave * 32;
+    if (key0 < key_hi) load_row_fragments<D>(key_row(key0), lane, kn);
+    for (; key0 < key_hi; key0 += kSelKeysPerIter) {
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) kf[kk] = kn[kk];
+        if (key0 + kSelKeysPerIter < key_hi) load_row_fragments<D>(key_row(key0 + kSelKeysPerIter), lane, kn); // next block's keys
+#pragma unroll
+        for (int rb = 0; rb < kSelChunkBlocks; ++rb) {
+            if (rb >= nblk) continue; // (the same in every thread)
+            sel_u32x4 qf[D / 16];
+            lds_row_fragments<D>(ldsq, rb, lane, qf);
             sel_f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int kk = 0; kk < D / 16; ++kk)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sel_bf16x8, kf[kk]),
                                                                __builtin_bit_cast(sel_bf16x8, qf[kk]), acc, 0, 0, 0);
-            // accumulator e of this lane: key key0 + 8 (e / 4) + 4 (lane / 32) + e % 4, query row lane % 32
+            // accumulator e of this lane: key key0 + 8 (e / 4) + 4 (lane / 32) + e % 4, query row lane % 32 of block rb
             float s[16], tmax = -INFINITY;
+            if (key0 + 31 <= p.n - p.obs) { // every query of the window sees all 32 keys (whole wave)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int ke = key0 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                s[e] = ke <= qpos ? acc[e] * p.scale_log2 : -INFINITY; // qpos < n: keys past the end drop out too
-                tmax = fmaxf(tmax, s[e]);
+                for (int e = 0; e < 16; ++e) {
+                    s[e] = acc[e] * p.scale_log2;
+                    tmax = fmaxf(tmax, s[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ke = key0 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    s[e] = ke <= qpos[rb] ? acc[e] * p.scale_log2 : -INFINITY; // qpos < n: keys past the end drop out too
+                    tmax = fmaxf(tmax, s[e]);
+                }
             }
             if (tmax > -INFINITY) {
-                const float mn = fmaxf(m, tmax);
+                const float mn = fmaxf(m[rb], tmax);
                 float add = 0.f;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) add += exp2f(s[e] - mn);
-                l = l * exp2f(m - mn) + add; // m = -inf: l is 0 and stays 0
-                m = mn;
+                for (int e = 0; e < 16; ++e) add += fast_exp2(s[e] - mn);
+                l[rb] = l[rb] * exp2f(m[rb] - mn) + add; // m = -inf: l is 0 and stays 0
+                m[rb] = mn;
             }
         }
-        merge_stat(m, l, __shfl_xor(m, 32), __shfl_xor(l, 32)); // the two lanes of a row hold different keys
-        if (lane < 32) red[wave][lane] = make_float2(m, l);
-        __syncthreads();
-        if (threadIdx.x < 32) {
-            float M = red[0][lane].x, L = red[0][lane].y;
-            for (int w = 1; w < kSelThreads / 64; ++w) merge_stat(M, L, red[w][lane].x, red[w][lane].y);
-            p.part[((size_t)h * p.npieces + blockIdx.x) * (p.nrb * 32) + r] = make_float2(M, L);
-        }
-        __syncthreads();
+    }
+#pragma unroll
+    for (int rb = 0; rb < kSelChunkBlocks; ++rb) {
+        merge_stat(m[rb], l[rb], __shfl_xor(m[rb], 32), __shfl_xor(l[rb], 32)); // the two lanes of a row hold different keys
+        if (lane < 32) red[wave][rb * 32 + lane] = make_float2(m[rb], l[rb]);
+    }
+    __syncthreads();
+    const int r = row0 + threadIdx.x; // kSelThreads == kSelChunkRows: one thread per row of the chunk
+    if (r < p.nrb * 32) {
+        float M = red[0][threadIdx.x].x, L = red[0][threadIdx.x].y;
+        for (int w = 1; w < kSelThreads / 64; ++w) merge_stat(M, L, red[w][threadIdx.x].x, red[w][threadIdx.x].y);
+        p.part[((size_t)h * p.npieces + blockIdx.x) * (p.nrb * 32) + r] = make_float2(M, L);
     }
 }
+static_assert(kSelThreads == kSelChunkRows, "the first pass hands one row of the chunk to every thread");
 
-__global__ void select_reduce_kernel(select_params p)
+// one wave per (kv head, query row): lane c holds piece c (at most 64 pieces).  Writes what the second pass
+// subtracts from a logit: maximum + log2(sum), so that exp2(logit - that) is the attention weight; +infinity for
+// the rows past the end (their weight is then 0).
+__global__ __launch_bounds__(kSelThreads) void select_reduce_kernel(select_params p)
 {
     const int h = blockIdx.y;
     if (!((p.head_mask >> h) & 1)) return;
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * (kSelThreads / 64) + (threadIdx.x >> 6);
     if (r >= p.nrb * 32) return;
-    float M = -INFINITY, L = 0.f;
-    for (int c = 0; c < p.npieces; ++c) {
-        const float2 t = p.part[((size_t)h * p.npieces + c) * (p.nrb * 32) + r];
-        merge_stat(M, L, t.x, t.y);
+    float m = -INFINITY, l = 0.f;
+    if (lane < p.npieces) {
+        const float2 t = p.part[((size_t)h * p.npieces + lane) * (p.nrb * 32) + r];
+        m = t.x;
+        l = t.y;
     }
-    p.stat[(size_t)h * (p.nrb * 32) + r] = make_float2(M, L > 0.f ? 1.f / L : 0.f); // every row sees key 0: L > 0
+    float M = m;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    float L = m > -INFINITY ? l * exp2f(m - M) : 0.f;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) L += __shfl_xor(L, o); // the same order in every lane: all lanes end with the same sum
+    if (lane == 0) p.stat[(size_t)h * (p.nrb * 32) + r] = r < p.R && L > 0.f ? M + log2f(L) : INFINITY; // (every row sees key 0: L > 0)
 }
+
+// Second pass.  Workgroup = (kSelVoteKeys distant keys, kv head); a wave takes key blocks of 32 and, per key block,
+// every chunk's row blocks: S = Q K^T, a lane owns key lane % 32 and adds up the weights of 16 query rows per MFMA
+// tile.  A distant key is older than every query of the observation window (obs <= W): no causal test.
+constexpr int kSelVoteBlocks = 4;                                  // key blocks per wave
+constexpr int kSelVoteKeys = kSelVoteBlocks * kSelKeysPerIter;     // keys per workgroup
 
 template <int D>
 __global__ __launch_bounds__(kSelThreads) void select_vote_kernel(select_params p)
@@ -150,34 +234,53 @@ __global__ __launch_bounds__(kSelThreads) void select_vote_kernel(select_params 
     if (!((p.head_mask >> h) & 1)) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int dist_hi = p.n - p.W;                                         // distant keys: S .. n - W - 1
-    const int key0 = p.S + blockIdx.x * kSelKeysPerIter + wave * 32;
-    if (key0 >= dist_hi) return;                                           // (whole wave)
-    const int key = key0 + (lane & 31) < dist_hi ? key0 + (lane & 31) : dist_hi - 1;
-    sel_u32x4 kf[D / 16];
-    load_row_fragments<D>(p.k + ((size_t)key * p.Hkv + h) * D, lane, kf);
-    const float2 *stat = p.stat + (size_t)h * (p.nrb * 32);
-    float vote = 0.f;
-    for (int rb = 0; rb < p.nrb; ++rb) {
-        sel_u32x4 qf[D / 16];
-        load_row_fragments<D>(query_row(p, h, rb * 32 + (lane & 31), D), lane, qf);
-        sel_f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const int wg_key0 = p.S + blockIdx.x * kSelVoteKeys;
+    __shared__ __align__(16) char ldsq[kSelChunkRows * kSelRowBytes<D>];
+    __shared__ __align__(16) float ldsb[kSelChunkRows];
+    float vote[kSelVoteBlocks];
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sel_bf16x8, qf[kk]),
-                                                           __builtin_bit_cast(sel_bf16x8, kf[kk]), acc, 0, 0, 0);
-        // accumulator e of this lane: query row rb * 32 + 8 (e / 4) + 4 (lane / 32) + e % 4, key lane % 32; a distant
-        // key is older than every query of the observation window (obs <= W), so no causal test is needed
+    for (int kb = 0; kb < kSelVoteBlocks; ++kb) vote[kb] = 0.f;
+    for (int row0 = 0; row0 < p.R; row0 += kSelChunkRows) {
+        if (row0) __syncthreads(); // everyone is done with the previous chunk
+        stage_query_rows<D>(p, h, row0, ldsq);
+        {
+            const int r = row0 + threadIdx.x; // one row of the chunk per thread
+            ldsb[threadIdx.x] = r < p.nrb * 32 ? p.stat[(size_t)h * (p.nrb * 32) + r] : INFINITY;
+        }
+        __syncthreads();
+        const int nblk = (p.R - row0 + 31) / 32 < kSelChunkBlocks ? (p.R - row0 + 31) / 32 : kSelChunkBlocks;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int r = rb * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            if (r < p.R) {
-                const float2 st = stat[r];
-                vote += exp2f(acc[e] * p.scale_log2 - st.x) * st.y;
+        for (int kb = 0; kb < kSelVoteBlocks; ++kb) {
+            const int key0 = wg_key0 + (kb * (kSelThreads / 64) + wave) * 32;
+            if (key0 >= dist_hi) continue; // (whole wave; no barrier inside)
+            const int key = key0 + (lane & 31) < dist_hi ? key0 + (lane & 31) : dist_hi - 1;
+            sel_u32x4 kf[D / 16];
+            load_row_fragments<D>(p.k + ((size_t)key * p.Hkv + h) * D, lane, kf);
+            for (int rb = 0; rb < nblk; ++rb) {
+                sel_u32x4 qf[D / 16];
+                lds_row_fragments<D>(ldsq, rb, lane, qf);
+                sel_f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int kk = 0; kk < D / 16; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sel_bf16x8, qf[kk]),
+                                                                   __builtin_bit_cast(sel_bf16x8, kf[kk]), acc, 0, 0, 0);
+                // accumulator e of this lane: query row rb * 32 + 8 (e / 4) + 4 (lane / 32) + e % 4 of the chunk, key lane % 32
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    typedef __attribute__((ext_vector_type(4))) float f32x4;
+                    const f32x4 bq = *(const f32x4 *)(ldsb + rb * 32 + 8 * e4 + 4 * (lane >> 5));
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) vote[kb] += fast_exp2(acc[4 * e4 + j] * p.scale_log2 - bq[j]);
+                }
             }
         }
     }
-    vote += __shfl_xor(vote, 32); // the two lanes of a key hold different query rows
-    if (lane < 32 && key0 + lane < dist_hi) p.votes[(size_t)h * (dist_hi - p.S) + (key0 + lane - p.S)] = vote;
+#pragma unroll
+    for (int kb = 0; kb < kSelVoteBlocks; ++kb) {
+        const int key0 = wg_key0 + (kb * (kSelThreads / 64) + wave) * 32;
+        const float v = vote[kb] + __shfl_xor(vote[kb], 32); // the two lanes of a key hold different query rows
+        if (lane < 32 && key0 + lane < dist_hi) p.votes[(size_t)h * (dist_hi - p.S) + (key0 + lane - p.S)] = v;
+    }
 }
 
 // order-preserving map of a float's bits to an unsigned (larger float = larger unsigned)
@@ -189,7 +292,26 @@ __device__ inline unsigned ordered_bits(float x)
 
 // One workgroup per kv head: pool the votes, find the keep-th largest pooled vote by four rounds of 8-bit
 // histograms over the ordered bit patterns, then write the indices of the selected tokens in ascending order
-// (everything above the threshold, and the first `need` of those equal to it).
+// (everything above the threshold, and the first `need` of those equal to it).  A thread owns a run of
+// ceil(m / 1024) consecutive tokens and keeps the pooled votes of the first kTopCache of them in registers, so the
+// five passes over the votes read memory only for prompts of more than 1024 * kTopCache distant tokens (the rest
+// of a run then goes through `pooled`); token order is thread order, so one scan over the threads' counts gives
+// every thread the place of its first selected token.
+constexpr int kTopCache = 32;
+
+__device__ inline float pooled_vote(const float *__restrict__ v, int t, int m, int r, int width, int use_max)
+{
+    const int lo = t - r > 0 ? t - r : 0, hi = t + r + 1 < m ? t + r + 1 : m;
+    if (use_max) {
+        float x = v[lo];
+        for (int u = lo + 1; u < hi; ++u) x = fmaxf(x, v[u]);
+        return x;
+    }
+    float acc = 0.f;
+    for (int u = lo; u < hi; ++u) acc = acc + v[u];
+    return acc / (float)width;
+}
+
 __global__ __launch_bounds__(kTopThreads) void select_top_kernel(const float *__restrict__ votes, int m, uint64_t head_mask,
                                                                  int width, int use_max, int keep, float *pooled,
                                                                  int32_t *sel, int sel_stride)
@@ -199,71 +321,99 @@ __global__ __launch_bounds__(kTopThreads) void select_top_kernel(const float *__
     const float *v = votes + (size_t)h * m;
     float *pl = pooled + (size_t)h * m;
     int32_t *out = sel + (size_t)h * sel_stride;
-    const int tid = threadIdx.x, r = width / 2;
-    for (int t = tid; t < m; t += kTopThreads) {
-        const int lo = t - r > 0 ? t - r : 0, hi = t + r + 1 < m ? t + r + 1 : m;
-        float x;
-        if (use_max) {
-            x = v[lo];
-            for (int u = lo + 1; u < hi; ++u) x = fmaxf(x, v[u]);
-        } else {
-            float acc = 0.f;
-            for (int u = lo; u < hi; ++u) acc = acc + v[u];
-            x = acc / (float)width;
-        }
-        pl[t] = x;
-    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = width / 2;
+    const int span = (m + kTopThreads - 1) / kTopThreads; // tokens per thread: t0 .. t0 + span - 1 (those below m)
+    const int t0 = tid * span;
+    unsigned ck[kTopCache]; // ordered bit patterns of the pooled votes of tokens t0 + j
+#pragma unroll
+    for (int j = 0; j < kTopCache; ++j) ck[j] = j < span && t0 + j < m ? ordered_bits(pooled_vote(v, t0 + j, m, r, width, use_max)) : 0u;
+    for (int j = kTopCache; j < span; ++j)
+        if (t0 + j < m) pl[t0 + j] = pooled_vote(v, t0 + j, m, r, width, use_max); // read back by this thread only
     __shared__ unsigned hist[256];
     __shared__ unsigned s_prefix, s_need;
-    __shared__ unsigned wave_tot[kTopThreads / 64];
+    __shared__ unsigned wave_tot[2][kTopThreads / 64];
     if (tid == 0) { s_prefix = 0; s_need = (unsigned)keep; }
     __syncthreads();
     for (int shift = 24; shift >= 0; shift -= 8) {
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        const unsigned prefix = s_prefix;
-        for (int t = tid; t < m; t += kTopThreads) {
-            const unsigned key = ordered_bits(pl[t]);
-            if (shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        const unsigned prefix = s_prefix, need_in = s_need;
+        // The first round's digit is the sign and most of the exponent: pooled votes share a handful of values, and
+        // one LDS atomic per token would queue up on those few counters, so there a wave adds each distinct digit once.
+        auto count = [&](unsigned key, bool valid) {
+            const unsigned digit = (key >> shift) & 255u;
+            if (shift == 24) {
+                unsigned long long todo = __ballot(valid);
+                while (todo) {
+                    const int leader = __ffsll((long long)todo) - 1;
+                    const unsigned d = __shfl(digit, leader);
+                    const unsigned long long same = __ballot(valid && digit == d);
+                    if (lane == leader) atomicAdd(&hist[d], (unsigned)__popcll(same));
+                    todo &= ~same;
+                }
+            } else if (valid && (key >> (shift + 8)) == (prefix >> (shift + 8))) {
+                atomicAdd(&hist[digit], 1u);
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < kTopCache; ++j)
+            if (j < span) count(ck[j], t0 + j < m); // (the same test in every thread)
+        for (int j = kTopCache; j < span; ++j) count(t0 + j < m ? ordered_bits(pl[t0 + j]) : 0u, t0 + j < m);
+        __syncthreads();
+        // thread d < 256: candidates with digit >= d (suffix sums by wave, then over the waves above); the digit whose
+        // bucket holds the need-th largest candidate is the one with fewer than `need` above it and at least `need` from it on
+        unsigned mine = 0, from_here = 0;
+        if (tid < 256) {
+            mine = hist[tid];
+            from_here = mine;
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned up = __shfl_down(from_here, o);
+                if (lane + o < 64) from_here += up;
+            }
+            if (lane == 0) wave_tot[0][wave] = from_here;
         }
         __syncthreads();
-        if (tid == 0) {
-            unsigned need = s_need;
-            int d = 255;
-            for (; d > 0; --d) { // the digit whose bucket holds the need-th largest of the candidates
-                if (hist[d] >= need) break;
-                need -= hist[d];
+        if (tid < 256) {
+            for (int w = wave + 1; w < 4; ++w) from_here += wave_tot[0][w];
+            const unsigned above = from_here - mine;
+            if (above < need_in && need_in <= from_here) {
+                s_prefix = prefix | ((unsigned)tid << shift);
+                s_need = need_in - above;
             }
-            s_prefix = prefix | ((unsigned)d << shift);
-            s_need = need;
         }
         __syncthreads();
     }
     const unsigned thr = s_prefix, need = s_need; // need >= 1 entries equal to the threshold are taken, earliest first
-    unsigned run_gt = 0, run_eq = 0;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int base = 0; base < m; base += kTopThreads) {
-        const int t = base + tid;
-        const unsigned key = t < m ? ordered_bits(pl[t]) : 0u;
-        const bool gt = t < m && key > thr, eq = t < m && key == thr;
-        const unsigned long long bg = __ballot(gt), be = __ballot(eq), below = (1ull << lane) - 1ull;
-        if (lane == 0) wave_tot[wave] = (unsigned)__popcll(bg) | ((unsigned)__popcll(be) << 16);
-        __syncthreads();
-        unsigned before = 0, total = 0;
-        for (int w = 0; w < kTopThreads / 64; ++w) {
-            if (w < wave) before += wave_tot[w];
-            total += wave_tot[w];
-        }
-        const unsigned gt_before = run_gt + (before & 0xFFFFu) + (unsigned)__popcll(bg & below);
-        const unsigned eq_before = run_eq + (before >> 16) + (unsigned)__popcll(be & below);
+    // tokens above / at the threshold in this thread's run, then in all runs before it
+    unsigned n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kTopCache; ++j)
+        if (j < span && t0 + j < m) { n_gt += ck[j] > thr; n_eq += ck[j] == thr; }
+    for (int j = kTopCache; j < span; ++j)
+        if (t0 + j < m) { const unsigned key = ordered_bits(pl[t0 + j]); n_gt += key > thr; n_eq += key == thr; }
+    unsigned inc_gt = n_gt, inc_eq = n_eq;
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned a = __shfl_up(inc_gt, o), b = __shfl_up(inc_eq, o);
+        if (lane >= o) { inc_gt += a; inc_eq += b; }
+    }
+    if (lane == 63) { wave_tot[0][wave] = inc_gt; wave_tot[1][wave] = inc_eq; }
+    __syncthreads();
+    unsigned gt_before = inc_gt - n_gt, eq_before = inc_eq - n_eq;
+    for (int w = 0; w < wave; ++w) { gt_before += wave_tot[0][w]; eq_before += wave_tot[1][w]; }
+    auto place = [&](int t, unsigned key) {
+        const bool gt = key > thr, eq = key == thr;
         if (gt || (eq && eq_before < need)) {
             const unsigned pos = gt_before + (eq_before < need ? eq_before : need);
             if (pos < (unsigned)keep) out[pos] = t;
         }
-        run_gt += total & 0xFFFFu;
-        run_eq += total >> 16;
-        __syncthreads();
-    }
+        gt_before += gt;
+        eq_before += eq;
+    };
+#pragma unroll
+    for (int j = 0; j < kTopCache; ++j)
+        if (j < span && t0 + j < m) place(t0 + j, ck[j]);
+    for (int j = kTopCache; j < span; ++j)
+        if (t0 + j < m) place(t0 + j, ordered_bits(pl[t0 + j]));
 }
 
 struct compact_params {
@@ -356,16 +506,16 @@ int pod_launch_select_votes(const pod_layout &ly, uint64_t head_mask, int n, con
     p.R = s.R; p.nrb = s.nrb; p.keys_per_wg = s.keys_per_wg; p.npieces = s.npieces;
     p.scale_log2 = scale * kLog2e;
     p.head_mask = head_mask;
-    p.part = (float2 *)ws; p.stat = (float2 *)((char *)ws + s.off_stat); p.votes = votes;
+    p.part = (float2 *)ws; p.stat = (float *)((char *)ws + s.off_stat); p.votes = votes;
     const int n_dist = n - ly.S - ly.W;
-    const dim3 g1(s.npieces, ly.Hkv), g2((s.nrb * 32 + 255) / 256, ly.Hkv), g3((n_dist + kSelKeysPerIter - 1) / kSelKeysPerIter, ly.Hkv);
+    const dim3 g1(s.npieces, ly.Hkv, (s.R + kSelChunkRows - 1) / kSelChunkRows), g2((s.nrb * 32 + kSelThreads / 64 - 1) / (kSelThreads / 64), ly.Hkv), g3((n_dist + kSelVoteKeys - 1) / kSelVoteKeys, ly.Hkv);
     if (ly.D == 128) {
         hipLaunchKernelGGL(select_stat_kernel<128>, g1, dim3(kSelThreads), 0, st, p);
-        hipLaunchKernelGGL(select_reduce_kernel, g2, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(select_reduce_kernel, g2, dim3(kSelThreads), 0, st, p);
         hipLaunchKernelGGL(select_vote_kernel<128>, g3, dim3(kSelThreads), 0, st, p);
     } else {
         hipLaunchKernelGGL(select_stat_kernel<64>, g1, dim3(kSelThreads), 0, st, p);
-        hipLaunchKernelGGL(select_reduce_kernel, g2, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(select_reduce_kernel, g2, dim3(kSelThreads), 0, st, p);
         hipLaunchKernelGGL(select_vote_kernel<64>, g3, dim3(kSelThreads), 0, st, p);
     }
     POD_HIP_TRY(hipGetLastError());

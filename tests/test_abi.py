@@ -64,3 +64,23 @@ def test_init_rejects_null_and_small_buffers():
     assert L.pod_cache_init(C.byref(cfg), None, 1 << 20, None, C.byref(h)) == pod.binding.ERR_INVALID_ARG
     assert L.pod_cache_init(C.byref(cfg), 256, 16, None, C.byref(h)) == pod.binding.ERR_CAPACITY
     assert L.pod_cache_init(C.byref(cfg), 257, 1 << 30, None, C.byref(h)) == pod.binding.ERR_INVALID_ARG
+
+
+def test_selection_workspace_sizes_and_shape_checks():
+    cfg = pod.make_config(2, 2, 32, 8, 128, 64, 2048, 1, 40000)
+    n, obs, keep = 32768, 64, 1984
+    b = pod.pod_select_workspace_bytes(cfg, n, obs, keep)
+    rows = 2 * 8 * (keep + 2048) * 128 * 2                   # keys and values on their way during a compaction
+    pooled = 8 * (n - 64 - 2048) * 4                         # one pooled vote per kv head and distant token
+    assert b >= max(rows, pooled) and b % 256 == 0 and b < 2 * max(rows, pooled)
+    assert pod.pod_select_workspace_bytes(cfg, n, obs, 1) >= pooled
+    for bad in ((64 + 2048, obs, 1),                         # no distant token
+                (n, 0, keep), (n, 2049, keep),               # observation window outside [1, W]
+                (n, obs, 0), (n, obs, n - 64 - 2048 + 1),    # keep outside [1, n - S - W]
+                (n, 1025, keep)):                            # more than 4096 query rows per kv head
+        with pytest.raises(pod.PodError) as e:
+            pod.pod_select_workspace_bytes(cfg, *bad)
+        assert e.value.code == pod.binding.ERR_INVALID_ARG
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_select_workspace_bytes(cfg, 40001, obs, keep)
+    assert e.value.code == pod.binding.ERR_CAPACITY

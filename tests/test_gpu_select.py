@@ -89,7 +89,7 @@ def test_votes_of_a_peaked_prompt_with_large_logits():
     assert_votes_close(votes.cpu().numpy().astype(np.float64), ref, "peaked")
 
 
-@pytest.mark.parametrize("m,keep", [(5000, 1), (5000, 700), (5000, 5000), (1024, 1000), (1025, 3), (37, 36), (1, 1)])
+@pytest.mark.parametrize("m,keep", [(40000, 3000), (32769, 1), (5000, 1), (5000, 700), (5000, 5000), (1024, 1000), (1025, 3), (37, 36), (1, 1)])
 @pytest.mark.parametrize("width,kind", [(1, "avg"), (7, "max"), (5, "avg")])
 def test_selection_is_identical_on_the_same_float32_votes(m, keep, width, kind):
     Hkv, S, W = 3, 2, 6
