@@ -446,7 +446,10 @@ int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T
  *      (rotary positions are the caller's and unaffected: keys arrive rotated).
  * Shapes (all device memory unless said otherwise):
  *   q_obs : bf16 [obs][Hq][d], queries of prompt positions n - obs .. n - 1 at `layer`;  1 <= obs <= W
- *   k     : bf16 [n][Hkv][d], the prompt's keys at `layer` (what pod_prefill_attention was given)
+ *   k     : bf16 [n][Hkv][d], the prompt's keys at `layer` (what pod_prefill_attention was given), or
+ *           NULL: the keys are read where the cache holds them; (layer, seq_slot) must then hold the
+ *           n prompt tokens (POD_ERR_STATE otherwise) -- the way for a prompt that was stored in chunks.
+ *           The votes are the same bits either way.  seq_slot is not used when k is given.
  *   votes : float [Hkv][n - S - W]; rows of kv heads whose block does not start at `layer` are
  *           neither written (votes) nor read (top)
  *   sel   : int32 [num_layers][Hkv][keep]; pod_select_top writes rows (layer, h) of the heads whose
@@ -464,8 +467,8 @@ int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T
 #define POD_POOL_AVG 0
 #define POD_POOL_MAX 1
 int pod_select_workspace_bytes(const pod_config *cfg, int64_t n, int obs, int keep, size_t *bytes);
-int pod_select_votes(pod_cache *cache, int layer, int n, const void *q_obs, int obs, const void *k, float scale,
-                     float *votes, void *workspace, size_t workspace_bytes, void *stream);
+int pod_select_votes(pod_cache *cache, int layer, int seq_slot, int n, const void *q_obs, int obs, const void *k,
+                     float scale, float *votes, void *workspace, size_t workspace_bytes, void *stream);
 int pod_select_top(pod_cache *cache, int layer, int n, const float *votes, int pool_width, int pool_kind, int keep,
                    int32_t *sel, void *workspace, size_t workspace_bytes, void *stream);
 int pod_cache_compact(pod_cache *cache, int layer, int seq_slot, const int32_t *sel, int keep, void *workspace,

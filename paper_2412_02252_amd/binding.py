@@ -97,7 +97,7 @@ def load():
         "pod_prefill_attention_chunk": [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, C.c_size_t, vp,
                                         C.c_int, vp],
         "pod_select_workspace_bytes": [cfgp, C.c_int64, C.c_int, C.c_int, szp],
-        "pod_select_votes": [vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_float, vp, vp, C.c_size_t, vp],
+        "pod_select_votes": [vp, C.c_int, C.c_int, C.c_int, vp, C.c_int, vp, C.c_float, vp, vp, C.c_size_t, vp],
         "pod_select_top": [vp, C.c_int, C.c_int, vp, C.c_int, C.c_int, C.c_int, vp, vp, C.c_size_t, vp],
         "pod_cache_compact": [vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_size_t, vp],
         "pod_profile_enable": [vp, C.c_int],
@@ -420,14 +420,16 @@ class PodCache:
         return guarded_empty(pod_select_workspace_bytes(self.cfg, n, obs, keep), self.device, self.guard_bytes, self,
                              "selection workspace")
 
-    def pod_select_votes(self, layer, q_obs, k, scale, workspace, votes=None):
-        """q_obs: bf16 [obs][Hq][d] (the prompt's last queries at `layer`), k: bf16 [n][Hkv][d]; returns float
-        [Hkv][n - S - W] (rows of heads whose block does not start at `layer` are not written)."""
-        c, n, obs = self.cfg, k.shape[0], q_obs.shape[0]
+    def pod_select_votes(self, layer, q_obs, k, scale, workspace, votes=None, seq_slot=0, n=None):
+        """q_obs: bf16 [obs][Hq][d] (the prompt's last queries at `layer`); k: bf16 [n][Hkv][d], or None with n given:
+        keys from the cache of (layer, seq_slot).  Returns float [Hkv][n - S - W] (rows of heads whose block does not
+        start at `layer` are not written)."""
+        c, obs = self.cfg, q_obs.shape[0]
+        n = k.shape[0] if k is not None else n
         if votes is None:
             votes = torch.zeros((c.num_kv_heads, n - c.sink - c.window), dtype=torch.float32, device=self.device)
-        _check(load().pod_select_votes(self.handle, layer, n, _ptr(q_obs, torch.bfloat16), obs, _ptr(k, torch.bfloat16), scale,
-                                       _ptr(votes, torch.float32), workspace.data_ptr(),
+        _check(load().pod_select_votes(self.handle, layer, seq_slot, n, _ptr(q_obs, torch.bfloat16), obs,
+                                       _ptr(k, torch.bfloat16), scale, _ptr(votes, torch.float32), workspace.data_ptr(),
                                        workspace.numel() * workspace.element_size(), _stream()))
         return votes
 

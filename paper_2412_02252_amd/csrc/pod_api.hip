@@ -900,24 +900,28 @@ extern "C" int pod_select_workspace_bytes(const pod_config *cfg, int64_t n, int 
     return POD_OK;
 }
 
-extern "C" int pod_select_votes(pod_cache *cache, int layer, int n, const void *q_obs, int obs, const void *k, float scale,
-                                float *votes, void *workspace, size_t workspace_bytes, void *stream)
+extern "C" int pod_select_votes(pod_cache *cache, int layer, int seq_slot, int n, const void *q_obs, int obs, const void *k,
+                                float scale, float *votes, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = check_cache_layer(cache, layer);
     if (rc) return rc;
     const pod_layout &ly = cache->ly;
+    if (seq_slot < 0 || seq_slot >= ly.B) return pod_fail(POD_ERR_INVALID_ARG, "seq_slot %d outside [0, %d)", seq_slot, ly.B);
     rc = check_select_shape(ly, n, obs, 1);
     if (rc) return rc;
     if (!layer_lowest_any(cache, layer))
         return pod_fail(POD_ERR_INVALID_ARG, "layer %d is not the lowest layer of any head's block: the block's votes are taken at its lowest layer", layer);
-    if (!q_obs || !k || !votes || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "q_obs, k, votes and workspace must not be NULL");
+    if (!q_obs || !votes || !workspace) return pod_fail(POD_ERR_INVALID_ARG, "q_obs, votes and workspace must not be NULL");
     if (((uintptr_t)q_obs | (uintptr_t)k) % 16 || (uintptr_t)votes % 4 || (uintptr_t)workspace % 256)
         return pod_fail(POD_ERR_INVALID_ARG, "q_obs and k must be 16-byte aligned, workspace 256-byte aligned");
     if (!(scale > 0.f)) return pod_fail(POD_ERR_INVALID_ARG, "scale must be positive");
+    if (!k && cache->host_len[(size_t)layer * ly.B + seq_slot] != n)
+        return pod_fail(POD_ERR_STATE, "k is NULL (keys from the cache) but slot %d at layer %d holds %lld tokens, not n = %d", seq_slot,
+                        layer, (long long)cache->host_len[(size_t)layer * ly.B + seq_slot], n);
     const size_t need = pod_select_votes_bytes(ly, n, obs);
     if (workspace_bytes < need) return pod_fail(POD_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
-    return pod_launch_select_votes(ly, pod_make_headmap(cache, layer).lowest_mask, n, q_obs, obs, k, scale, votes, workspace,
-                                   (hipStream_t)stream);
+    return pod_launch_select_votes(cache, layer, seq_slot, pod_make_headmap(cache, layer).lowest_mask, n, q_obs, obs, k, scale, votes,
+                                   workspace, (hipStream_t)stream);
 }
 
 extern "C" int pod_select_top(pod_cache *cache, int layer, int n, const float *votes, int pool_width, int pool_kind, int keep,

@@ -161,7 +161,8 @@ int pod_launch_prefill_tiles(const pod_layout &ly, int n, int q0, const void *q,
 size_t pod_select_votes_bytes(const pod_layout &ly, int64_t n, int obs);
 size_t pod_select_top_bytes(const pod_layout &ly, int64_t n);
 size_t pod_compact_bytes(const pod_layout &ly, int keep);
-int pod_launch_select_votes(const pod_layout &ly, uint64_t head_mask, int n, const void *q_obs, int obs, const void *k,
+// k == NULL: the keys of positions 0 .. n - 1 are read from the cache of (layer, sequence b), which must hold n tokens
+int pod_launch_select_votes(const pod_cache *c, int layer, int b, uint64_t head_mask, int n, const void *q_obs, int obs, const void *k,
                             float scale, float *votes, void *ws, hipStream_t st);
 int pod_launch_select_top(int Hkv, uint64_t head_mask, const float *votes, int m, int width, int use_max, int keep,
                           float *pooled, int32_t *sel, int sel_stride, hipStream_t st);

@@ -39,7 +39,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 struct select_params {
     const pod_bf16 *q_obs; // [obs][Hq][D]
-    const pod_bf16 *k;     // [n][Hkv][D]
+    const pod_bf16 *k;     // [n][Hkv][D], or NULL: the keys are read where the cache holds them (below)
+    // per kv head, in bf16 elements from the cache buffer's start: row 0 of the head's sink + ring rows and of the
+    // distant-key store it reads at this layer (which is its own: the call is made at the block's lowest layer)
+    const pod_bf16 *cache_base;
+    unsigned long long prox0[kMaxKvHeads], dist0[kMaxKvHeads];
     int n, obs, Hq, Hkv, rep, S, W;
     int R;            // obs * rep query rows per kv head; row r = (position n - obs + r / rep, head h * rep + r % rep)
     int nrb;          // blocks of 32 rows
@@ -69,6 +73,16 @@ __device__ inline const pod_bf16 *query_row(const select_params &p, int h, int r
 
 // v_exp_f32: 2^x to 1 ulp; results below the smallest normal number come out as 0, which a softmax weight may
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// where the key of position `key` of kv head h is: in the caller's array, or in the cache (sink slot, distant row,
+// or the ring slot of a recent position)
+__device__ inline const pod_bf16 *key_address(const select_params &p, int h, int key, int D)
+{
+    if (p.k) return p.k + ((size_t)key * p.Hkv + h) * D;
+    if (key < p.S) return p.cache_base + p.prox0[h] + (size_t)key * D;
+    if (key < p.n - p.W) return p.cache_base + p.dist0[h] + (size_t)(key - p.S) * D;
+    return p.cache_base + p.prox0[h] + (size_t)(p.S + (key - p.S) % p.W) * D;
+}
 
 // (m, l) + (m2, l2) of two disjoint key sets; an empty set is (-inf, 0)
 __device__ inline void merge_stat(float &m, float &l, float m2, float l2)
@@ -137,7 +151,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stat_kernel(select_params 
     sel_u32x4 kf[D / 16], kn[D / 16];
     auto key_row = [&](int key0) {
         const int key = key0 + (lane & 31) < p.n ? key0 + (lane & 31) : p.n - 1;
-        return p.k + ((size_t)key * p.Hkv + h) * D;
+        return key_address(p, h, key, D);
     };
     int key0 = key_lo + wave * 32;
     if (key0 < key_hi) load_row_fragments<D>(key_row(key0), lane, kn);
@@ -255,7 +269,7 @@ __global__ __launch_bounds__(kSelThreads) void select_vote_kernel(select_params 
             if (key0 >= dist_hi) continue; // (whole wave; no barrier inside)
             const int key = key0 + (lane & 31) < dist_hi ? key0 + (lane & 31) : dist_hi - 1;
             sel_u32x4 kf[D / 16];
-            load_row_fragments<D>(p.k + ((size_t)key * p.Hkv + h) * D, lane, kf);
+            load_row_fragments<D>(key_address(p, h, key, D), lane, kf);
             for (int rb = 0; rb < nblk; ++rb) {
                 sel_u32x4 qf[D / 16];
                 lds_row_fragments<D>(ldsq, rb, lane, qf);
@@ -496,12 +510,19 @@ size_t pod_select_votes_bytes(const pod_layout &ly, int64_t n, int obs) { return
 size_t pod_select_top_bytes(const pod_layout &ly, int64_t n) { return up256((size_t)ly.Hkv * (size_t)(n - ly.S - ly.W) * sizeof(float)); }
 size_t pod_compact_bytes(const pod_layout &ly, int keep) { return up256((size_t)2 * ly.Hkv * ((size_t)keep + ly.W) * ly.D * 2); }
 
-int pod_launch_select_votes(const pod_layout &ly, uint64_t head_mask, int n, const void *q_obs, int obs, const void *k,
+int pod_launch_select_votes(const pod_cache *c, int layer, int b, uint64_t head_mask, int n, const void *q_obs, int obs, const void *k,
                             float scale, float *votes, void *ws, hipStream_t st)
 {
+    const pod_layout &ly = c->ly;
     const select_plan s = plan_votes(ly, n, obs);
     select_params p;
     p.q_obs = (const pod_bf16 *)q_obs; p.k = (const pod_bf16 *)k;
+    p.cache_base = (const pod_bf16 *)c->base;
+    const pod_headmap hm = pod_make_headmap(c, layer);
+    for (int h = 0; h < ly.Hkv; ++h) {
+        p.prox0[h] = ly.off_proxK / 2 + pod_prox_row0(ly, layer, b, h) * (size_t)ly.D;
+        p.dist0[h] = ly.off_distK / 2 + pod_distk_row0(ly, hm, b, h) * (size_t)ly.D;
+    }
     p.n = n; p.obs = obs; p.Hq = ly.Hq; p.Hkv = ly.Hkv; p.rep = ly.rep; p.S = ly.S; p.W = ly.W;
     p.R = s.R; p.nrb = s.nrb; p.keys_per_wg = s.keys_per_wg; p.npieces = s.npieces;
     p.scale_log2 = scale * kLog2e;

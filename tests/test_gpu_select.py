@@ -213,6 +213,36 @@ def test_select_compact_and_decode_on(name, L, G, Hq, Hkv, d, S, W, n, obs, keep
     c.gpu.pod_cache_check()
 
 
+@pytest.mark.parametrize("d,S,W,n,chunk", [(128, 8, 48, 1000, 300), (64, 0, 32, 555, 555), (128, 5, 100, 106, 50)])
+def test_votes_from_the_cached_keys_are_the_same_bits(d, S, W, n, chunk):
+    # the prompt goes in through the chunk call (sink slots, distant rows and a wrapped ring), then the votes are taken
+    # from where the cache holds the keys; and once more from a cache that pod_cache_fill wrote
+    L, G, Hq, Hkv, obs = 2, 2, 8, 2, min(16, W)
+    c = Case(L, G, Hq, Hkv, d, S, W, 2, n + 8, seed=1234 + n, with_oracle_cache=False)
+    q = [c.queries(l, 1, n, c.dev) for l in range(L)]
+    k = [c.keys(l, 1, n, c.dev) for l in range(L)]
+    v = [c.values(l, 1, n, c.dev) for l in range(L)]
+    cws = c.gpu.new_chunk_workspace(n)
+    for c0 in range(0, n, chunk):
+        c1 = min(n, c0 + chunk)
+        for l in range(L):
+            c.gpu.pod_prefill_attention_chunk(l, 1, q[l][c0:c1], k[l][c0:c1], v[l][c0:c1], q[0][c0:c1] if l else None,
+                                              k[0][c0:c1] if l else None, c.scale, cws, write_cache=True)
+    ws = c.gpu.new_select_workspace(n, obs, 1)
+    q_obs = q[0][n - obs:].contiguous()
+    given = c.gpu.pod_select_votes(0, q_obs, k[0], c.scale, ws)
+    cached = c.gpu.pod_select_votes(0, q_obs, None, c.scale, ws, seq_slot=1, n=n)
+    assert torch.equal(given, cached)
+    c.gpu.pod_cache_fill(0, 0, k[0], v[0])
+    assert torch.equal(given, c.gpu.pod_select_votes(0, q_obs, None, c.scale, ws, seq_slot=0, n=n))
+    ref = ps.distant_votes(gen.bf16_bits(c.queries(0, 1, n, "cpu")[n - obs:]), gen.bf16_bits(c.keys(0, 1, n, "cpu")), S, W, c.scale)
+    assert_votes_close(cached.cpu().numpy().astype(np.float64), ref, "from the cache")
+    with pytest.raises(pod.PodError) as e:                    # the slot does not hold n + 1 tokens
+        c.gpu.pod_select_votes(0, q_obs, None, c.scale, c.gpu.new_select_workspace(n + 1, obs, 1), seq_slot=1, n=n + 1)
+    assert e.value.code == pod.binding.ERR_STATE
+    c.gpu.pod_cache_check()
+
+
 def test_bad_arguments_and_bad_selections_are_reported():
     L, G, Hq, Hkv, d, S, W, n, obs, keep = 2, 2, 4, 2, 64, 2, 16, 100, 8, 10
     c = Case(L, G, Hq, Hkv, d, S, W, 1, 200, seed=77, with_oracle_cache=False)
