@@ -58,3 +58,58 @@ def test_a_planted_mistake_fails_the_pins(tmp_path, name, old, new, count):
     _build(text.replace(old, new), lib)
     ok, tail = _pins_pass(lib)
     assert not ok, f"the pins did not notice: {name}"
+
+
+# ---- the token-selection oracle (oracle/pod_select.py): the same question for its pins ----
+SELECT_SRC = os.path.join(ROOT, "oracle", "pod_select.py")
+SELECT_PINS = os.path.join(ROOT, "tests", "test_oracle_select_pins.py")
+
+SELECT_MUTATIONS = [
+    ("a query sees one key too few", "logits = scale * (kf[:pos + 1, h, :] @ qf[i, hq, :])", "logits = scale * (kf[:pos, h, :] @ qf[i, hq, :])", 1),
+    ("the window starts one position late", "pos = n - obs + i ", "pos = n - obs + i + 1 if i + 1 < obs else n - 1 ", 1),
+    ("votes of a query head go to the wrong kv head", "h = hq // rep", "h = hq % Hkv", 1),
+    ("the distant range starts one token early", "votes[h] += w[S:n - W]", "votes[h] += np.concatenate([w[S - 1:S], w[S:n - W - 1]]) if S else w[S:n - W]", 1),
+    ("weights not normalised", "w /= w.sum()", "w /= w.max()", 1),
+    ("pooling window off centre", "lo, hi = max(0, t - r), min(m, t + r + 1)", "lo, hi = max(0, t - r + 1), min(m, t + r + 2)", 1),
+    ("mean over the positions that exist", "out[h, t] = acc / votes.dtype.type(width)", "out[h, t] = acc / votes.dtype.type(hi - lo)", 1),
+    ("of equal votes the later token wins", "key=lambda t: (-pooled[h, t], t)", "key=lambda t: (-pooled[h, t], -t)", 1),
+    ("selection left in vote order", "sel[h] = sorted(order[:keep])", "sel[h] = order[:keep]", 1),
+    ("selected index taken as a position", "[S + int(t) for t in sel_of_head[h]]", "[int(t) for t in sel_of_head[h]]", 1),
+    ("recent window one token short", "list(range(n - W, n))", "list(range(n - W + 1, n)) + [n - 1]", 1),
+]
+
+_DRIVER = """
+import importlib.util, sys
+sys.path.insert(0, {root!r})
+import oracle
+spec = importlib.util.spec_from_file_location("oracle.pod_select", {mutant!r})
+mod = importlib.util.module_from_spec(spec)
+sys.modules["oracle.pod_select"] = mod
+spec.loader.exec_module(mod)
+oracle.pod_select = mod
+import pytest
+sys.exit(pytest.main(["-x", "-q", "-p", "no:cacheprovider", {pins!r}]))
+"""
+
+
+def _select_pins_pass(path):
+    r = subprocess.run([sys.executable, "-c", _DRIVER.format(root=ROOT, mutant=path, pins=SELECT_PINS)], cwd=ROOT,
+                       capture_output=True, text=True)
+    return r.returncode == 0, r.stdout[-600:]
+
+
+def test_an_unchanged_copy_of_the_selection_oracle_passes_its_pins(tmp_path):
+    path = str(tmp_path / "same_select.py")
+    open(path, "w").write(open(SELECT_SRC).read())
+    ok, tail = _select_pins_pass(path)
+    assert ok, tail
+
+
+@pytest.mark.parametrize("name,old,new,count", SELECT_MUTATIONS, ids=[m[0] for m in SELECT_MUTATIONS])
+def test_a_planted_mistake_fails_the_selection_pins(tmp_path, name, old, new, count):
+    text = open(SELECT_SRC).read()
+    assert text.count(old) == count, f"the oracle's source no longer holds the line this case changes: {old!r}"
+    path = str(tmp_path / "mutant_select.py")
+    open(path, "w").write(text.replace(old, new))
+    ok, tail = _select_pins_pass(path)
+    assert not ok, f"the pins did not notice: {name}"
