@@ -192,3 +192,32 @@ def test_arguments_are_checked():
         ps.pool_votes(np.zeros((1, 4)), 2, "avg")    # even width
     with pytest.raises(AssertionError):
         ps.select_top(np.zeros((1, 4)), 5)
+
+
+def test_memory_of_the_combination_matches_the_papers_table():
+    # Table 4: a selection method that keeps 4096 of 32768 tokens saves 87.5 %; with the cache's own saving on the
+    # kept tokens (the paper's 35 %, from a block map it does not print) the combination saves the printed 91.9 %.
+    # So the combination is "select first, then hold what is kept in the split cache": the compacted sequence.
+    import os
+    facts = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_facts.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            facts[k.strip()] = float(v)
+    n, kept = int(facts["context_32k"]), int(facts["snapkv_kept_tokens"])
+    assert 1 - kept / n == facts["snapkv_saving"]
+    assert round(1 - (kept / n) * (1 - facts["pod_reported_saving"]), 3) == facts["pod_snapkv_saving"]
+    # the oracle's accounting of a compacted sequence (uniform blocks of 2 layers, S + W = 2112): entries of the cache
+    # of S + keep + W tokens against the dense cache of the whole prompt
+    L, G, Hkv, d, S, W = 2, 2, 1, 2, 64, 2048
+    keep = kept - S - W
+    x = np.zeros((n, Hkv, d), dtype=np.uint16)
+    sel = np.arange(keep, dtype=np.int32)[None, :]
+    c = po.Cache(L, G, Hkv, d, S, W, 1, n)
+    for l in range(L):
+        c.fill(l, 0, ps.compact_sequence(x, sel, S, W), ps.compact_sequence(x, sel, S, W))
+    dense = 2 * L * n * Hkv * d
+    own = (1 - 1 / G) * keep / (2 * kept)                      # the cache's own saving on the kept tokens (Eq. 3's ranges)
+    assert c.stored_elems() == round(2 * L * kept * Hkv * d * (1 - own))
+    assert abs((1 - c.stored_elems() / dense) - (1 - (kept / n) * (1 - own))) < 1e-12
