@@ -309,3 +309,45 @@ def test_selection_at_the_benchmark_shape():
         for layer in range(L):
             assert_close(outs[layer], c.decode_ref(layer, [m + step + 1]), f"step {step} layer {layer}")
     c.gpu.pod_cache_check()
+
+
+def test_selection_on_a_128k_prompt_with_blocks_of_four_layers():
+    # the long-context shape (131072 tokens, S 128, W 4096, one block of 4 layers), 2 kv heads x 4 query heads:
+    # 126848 distant tokens per head (more than the selection kernel keeps in registers), 3968 kept -> 8192 stored
+    L, G, Hq, Hkv, d, S, W, n, obs, keep = 4, 4, 8, 2, 128, 128, 4096, 131072, 64, 3968
+    c = Case(L, G, Hq, Hkv, d, S, W, 1, n + 16, seed=5151, with_oracle_cache=False)
+    for layer in range(L):
+        c.gpu.pod_cache_fill(layer, 0, c.keys(layer, 0, n, c.dev), c.values(layer, 0, n, c.dev))
+    ws = c.gpu.new_select_workspace(n, obs, keep)
+    q_obs = c.queries(0, 0, obs, c.dev, pos0=n - obs).contiguous()
+    votes = c.gpu.pod_select_votes(0, q_obs, None, c.scale, ws, seq_slot=0, n=n)       # keys from the cache
+    sel_gpu = torch.full((L, Hkv, keep), -1, dtype=torch.int32, device=c.dev)
+    c.gpu.pod_select_top(0, n, votes, 5, pod.POOL_AVG, keep, sel_gpu, ws)
+    ref = ps.distant_votes(gen.bf16_bits(c.queries(0, 0, obs, "cpu", pos0=n - obs)), gen.bf16_bits(c.keys(0, 0, n, "cpu")),
+                           S, W, c.scale)
+    assert_votes_close(votes.cpu().numpy().astype(np.float64), ref, "128K prompt")
+    # pooled in float64 by a cumulative sum (the plain loop takes minutes at this length; same definition)
+    pad = np.pad(ref, ((0, 0), (3, 2)))
+    cs = np.cumsum(pad, axis=1)
+    pooled = (cs[:, 5:] - cs[:, :-5]) / 5.0
+    assert np.allclose(pooled[:, 1000:1004], ps.pool_votes(ref[:, 990:1014], 5, "avg")[:, 10:14], rtol=1e-12)
+    got = sel_gpu.cpu().numpy()
+    for h in range(Hkv):
+        assert_valid_selection(got[0, h], pooled[h], keep, 4e-4, f"head {h}")
+    assert (got[1:] == -1).all()
+    # compaction from a selection made here from the oracle's votes (top by sorting)
+    want = np.full((L, Hkv, keep), -1, dtype=np.int32)
+    for h in range(Hkv):
+        order = np.lexsort((np.arange(pooled.shape[1]), -pooled[h]))
+        want[0, h] = np.sort(order[:keep])
+    sel_dev = torch.from_numpy(want).to(c.dev)
+    for layer in range(L):
+        c.gpu.pod_cache_compact(layer, 0, sel_dev, ws)
+    c.cpu = _oracle_compacted_cache(c, n, 0, want, 1)
+    for layer in range(L):
+        c.assert_cache_equal(layer, 0)
+    m = S + keep + W
+    outs = [c.step(layer, [m]) for layer in range(L)]
+    for layer in range(L):
+        assert_close(outs[layer], c.decode_ref(layer, [m + 1]), f"layer {layer}")
+    c.gpu.pod_cache_check()
