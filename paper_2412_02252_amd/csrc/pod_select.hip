@@ -304,13 +304,12 @@ __device__ inline unsigned ordered_bits(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// One workgroup per kv head: pool the votes, find the keep-th largest pooled vote by four rounds of 8-bit
+// Selection, one workgroup per kv head, over the pooled votes: find the keep-th largest by four rounds of 8-bit
 // histograms over the ordered bit patterns, then write the indices of the selected tokens in ascending order
 // (everything above the threshold, and the first `need` of those equal to it).  A thread owns a run of
-// ceil(m / 1024) consecutive tokens and keeps the pooled votes of the first kTopCache of them in registers, so the
-// five passes over the votes read memory only for prompts of more than 1024 * kTopCache distant tokens (the rest
-// of a run then goes through `pooled`); token order is thread order, so one scan over the threads' counts gives
-// every thread the place of its first selected token.
+// ceil(m / 1024) consecutive tokens and keeps the first kTopCache of them in registers, so the five passes read
+// memory only for prompts of more than 1024 * kTopCache distant tokens; token order is thread order, so one scan
+// over the threads' counts gives every thread the place of its first selected token.
 constexpr int kTopCache = 32;
 
 __device__ inline float pooled_vote(const float *__restrict__ v, int t, int m, int r, int width, int use_max)
@@ -326,23 +325,35 @@ __device__ inline float pooled_vote(const float *__restrict__ v, int t, int m, i
     return acc / (float)width;
 }
 
-__global__ __launch_bounds__(kTopThreads) void select_top_kernel(const float *__restrict__ votes, int m, uint64_t head_mask,
-                                                                 int width, int use_max, int keep, float *pooled,
+// pooling: one thread per (kv head, distant token), so that the window's loads of many tokens are in flight together
+// (a thread of select_top_kernel walking its own run would wait for them one after the other)
+__global__ __launch_bounds__(256) void select_pool_kernel(const float *__restrict__ votes, int m, uint64_t head_mask, int width,
+                                                          int use_max, float *__restrict__ pooled)
+{
+    const int h = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
+    if (!((head_mask >> h) & 1) || t >= m) return;
+    pooled[(size_t)h * m + t] = pooled_vote(votes + (size_t)h * m, t, m, width / 2, width, use_max);
+}
+
+__global__ __launch_bounds__(kTopThreads) void select_top_kernel(const float *__restrict__ pooled, int m, uint64_t head_mask, int keep,
                                                                  int32_t *sel, int sel_stride)
 {
     const int h = blockIdx.x;
     if (!((head_mask >> h) & 1)) return;
-    const float *v = votes + (size_t)h * m;
-    float *pl = pooled + (size_t)h * m;
+    const float *pl = pooled + (size_t)h * m;
     int32_t *out = sel + (size_t)h * sel_stride;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = width / 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int span = (m + kTopThreads - 1) / kTopThreads; // tokens per thread: t0 .. t0 + span - 1 (those below m)
     const int t0 = tid * span;
     unsigned ck[kTopCache]; // ordered bit patterns of the pooled votes of tokens t0 + j
 #pragma unroll
-    for (int j = 0; j < kTopCache; ++j) ck[j] = j < span && t0 + j < m ? ordered_bits(pooled_vote(v, t0 + j, m, r, width, use_max)) : 0u;
-    for (int j = kTopCache; j < span; ++j)
-        if (t0 + j < m) pl[t0 + j] = pooled_vote(v, t0 + j, m, r, width, use_max); // read back by this thread only
+    for (int j = 0; j < kTopCache; ++j) { // (loads of clamped addresses, all in flight; what is not this thread's is zeroed after)
+        const int t = t0 + j < m ? t0 + j : m - 1;
+        ck[j] = ordered_bits(pl[t]);
+    }
+#pragma unroll
+    for (int j = 0; j < kTopCache; ++j)
+        if (!(j < span && t0 + j < m)) ck[j] = 0u;
     __shared__ unsigned hist[256];
     __shared__ unsigned s_prefix, s_need;
     __shared__ unsigned wave_tot[2][kTopThreads / 64];
@@ -360,7 +371,7 @@ __global__ __launch_bounds__(kTopThreads) void select_top_kernel(const float *__
                 unsigned long long todo = __ballot(valid);
                 while (todo) {
                     const int leader = __ffsll((long long)todo) - 1;
-                    const unsigned d = __shfl(digit, leader);
+                    const unsigned d = (unsigned)__builtin_amdgcn_readlane((int)digit, leader); // (leader is the same in every lane)
                     const unsigned long long same = __ballot(valid && digit == d);
                     if (lane == leader) atomicAdd(&hist[d], (unsigned)__popcll(same));
                     todo &= ~same;
@@ -546,8 +557,8 @@ int pod_launch_select_votes(const pod_cache *c, int layer, int b, uint64_t head_
 int pod_launch_select_top(int Hkv, uint64_t head_mask, const float *votes, int m, int width, int use_max, int keep,
                           float *pooled, int32_t *sel, int sel_stride, hipStream_t st)
 {
-    hipLaunchKernelGGL(select_top_kernel, dim3(Hkv), dim3(kTopThreads), 0, st, votes, m, head_mask, width, use_max, keep, pooled,
-                       sel, sel_stride);
+    hipLaunchKernelGGL(select_pool_kernel, dim3((m + 255) / 256, Hkv), dim3(256), 0, st, votes, m, head_mask, width, use_max, pooled);
+    hipLaunchKernelGGL(select_top_kernel, dim3(Hkv), dim3(kTopThreads), 0, st, (const float *)pooled, m, head_mask, keep, sel, sel_stride);
     POD_HIP_TRY(hipGetLastError());
     return POD_OK;
 }
