@@ -451,7 +451,8 @@ int pod_prefill_attention_chunk(pod_cache *cache, int layer, int seq_slot, int T
  *           n prompt tokens (POD_ERR_STATE otherwise) -- the way for a prompt that was stored in chunks.
  *           The votes are the same bits either way.  seq_slot is not used when k is given.
  *   votes : float [Hkv][n - S - W]; rows of kv heads whose block does not start at `layer` are
- *           neither written (votes) nor read (top)
+ *           neither written (votes) nor read (top).  pod_select_top takes any finite floats (what
+ *           pod_select_votes writes is >= 0); its result for rows that hold NaNs is unspecified
  *   sel   : int32 [num_layers][Hkv][keep]; pod_select_top writes rows (layer, h) of the heads whose
  *           block starts at `layer`; pod_cache_compact reads, for head h, the row of the lowest
  *           layer of h's block.  1 <= keep <= n - S - W.

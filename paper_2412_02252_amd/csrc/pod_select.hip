@@ -300,7 +300,8 @@ __global__ __launch_bounds__(kSelThreads) void select_vote_kernel(select_params 
 // order-preserving map of a float's bits to an unsigned (larger float = larger unsigned)
 __device__ inline unsigned ordered_bits(float x)
 {
-    const unsigned u = __builtin_bit_cast(unsigned, x);
+    unsigned u = __builtin_bit_cast(unsigned, x);
+    if (u == 0x80000000u) u = 0u; // -0 and +0 are one value
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

@@ -99,7 +99,7 @@ def test_selection_is_identical_on_the_same_float32_votes(m, keep, width, kind):
     rng = np.random.default_rng(m * 31 + keep)
     votes = np.stack([rng.random(m).astype(np.float32) * np.float32(3),                 # spread, no ties
                       rng.integers(0, 5, m).astype(np.float32) / np.float32(8),          # five levels: ties everywhere
-                      np.where(rng.random(m) < 0.3, 0, rng.standard_normal(m)).astype(np.float32)])   # signs and zeros
+                      np.where(rng.random(m) < 0.3, np.where(rng.random(m) < 0.5, 0.0, -0.0), rng.standard_normal(m)).astype(np.float32)])   # signs, +0 and -0
     want = ps.select_top(ps.pool_votes(votes, width, kind), keep)
     sel = torch.full((1, Hkv, keep), -1, dtype=torch.int32, device=DEV)
     cache.pod_select_top(0, n, torch.from_numpy(votes).to(DEV), width, pod.POOL_MAX if kind == "max" else pod.POOL_AVG,
