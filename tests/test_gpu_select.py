@@ -55,6 +55,8 @@ def assert_valid_selection(sel, pooled_ref, keep, eps_rel, what=""):
     (64, 6, 3, 3, 33, 431, 5),         # rep 2, 10 query rows: one padded row block
     (128, 16, 1, 8, 64, 1000, 64),     # rep 16: 1024 query rows, 32 row blocks
     (128, 5, 5, 0, 16, 300, 16),       # no sink, rep 1
+    (128, 5, 1, 2, 70, 900, 60),       # rep 5: 300 query rows = one full chunk of 256 and a second of 44 (two row blocks, the last ragged)
+    (64, 12, 2, 1, 64, 520, 64),       # rep 6: 384 rows, d 64
     (64, 4, 4, 16, 100, 117, 1),       # a single distant token, a single query
 ])
 def test_votes_match_the_oracle(d, Hq, Hkv, S, W, n, obs):
