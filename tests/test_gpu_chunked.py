@@ -157,9 +157,10 @@ def test_chunked_prefill_matches_the_oracle(d, Hq, Hkv, chunks, in_place, monkey
     (8, 40, [700]),                          # one chunk far longer than the window: most of it goes straight to the distant stores
     (8, 300, [50, 100, 100]),                # everything still inside the window (no distant token)
 ])
-def test_chunked_prefill_region_edges_and_key_tiles(S, W, chunks):
+def test_chunked_prefill_region_edges_and_key_tiles(S, W, chunks, monkeypatch):
     """Where the sink, the distant stores, the rows kept for this call and the two parts of the ring meet, relative to
     the 64-key tiles the kernel requests by one address each."""
+    monkeypatch.delenv("POD_CHUNK_IN_PLACE", raising=False)   # (read when the cache is created: this is about the usual way)
     c = Case(2, 2, 4, 2, 128, S, W, 1, 1024, seed=340 + len(chunks))
     run_chunks(c, chunks, small_workspace=True)
 
@@ -256,9 +257,10 @@ def test_chunked_prefill_contract_violations():
     assert pod.pod_prefill_chunk_in_place_bytes(c.cfg, 200, 50) < pod.pod_prefill_chunk_workspace_bytes(c.cfg, 200)
 
 
-def test_chunk_on_a_mirror_that_is_ahead_of_the_device_stores_nothing_and_raises_the_flag():
+def test_chunk_on_a_mirror_that_is_ahead_of_the_device_stores_nothing_and_raises_the_flag(monkeypatch):
     """A rejected append leaves the host mirror one token ahead of the stored length.  The next chunk call then starts
     from the wrong position: both of its launches see that, the cache keeps its content, the flag goes up."""
+    monkeypatch.delenv("POD_CHUNK_IN_PLACE", raising=False)   # (read when the cache is created: this is about the usual way)
     c = Case(1, 1, 4, 2, 128, 8, 40, 1, 400, seed=335)
     run_chunks(c, [100])
     k1 = c.keys(0, 0, 1, c.dev, pos0=100).contiguous()

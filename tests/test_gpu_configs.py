@@ -287,12 +287,13 @@ def test_config4_prompt_in_chunks_sampled_rows_and_cache():
 
 
 @pytest.mark.parametrize("cuts", [None, [0, 30000, 30001, 65536, 69700, 100003]], ids=["one-call", "five-chunks"])
-def test_long_prompt_100k_sampled_rows(cuts):
+def test_long_prompt_100k_sampled_rows(cuts, monkeypatch):
     """A prompt of 100003 tokens (config 5's geometry: S=128, W=4096, 32/8 heads): index arithmetic far beyond the
     benchmark's 16384; sampled rows of the upper layer against the definition, and the distant stores it fills.
     In one call, and in chunks (keys and values read where the cache holds them; the scratch is the small one)."""
     L, G, Hq, Hkv, d, S, W, n = 2, 2, 32, 8, 128, 128, 4096, 100003
     seed = SEED0 + 6
+    monkeypatch.delenv("POD_CHUNK_IN_PLACE", raising=False)   # (read when the cache is created: the small scratch needs the usual way)
     cache = pod.PodCache(pod.make_config(L, G, Hq, Hkv, d, S, W, 1, n), DEV)
     scale = 1.0 / math.sqrt(d)
     Q = [gen.queries_bf16(seed, l, 0, n, Hq, d, device=DEV) for l in range(L)]

@@ -218,12 +218,13 @@ def test_merge_inside_the_streaming_kernel_equals_the_separate_merge_kernel(monk
 @pytest.mark.parametrize("d,Hq,Hkv,n", [(128, 4, 1, 20000), (128, 16, 1, 12000), (64, 8, 1, 20000), (128, 16, 2, 9000),
                                         (128, 64, 8, 12000), (64, 32, 8, 11000)],
                          ids=["rep4-1pair", "rep16-1pair", "d64-rep8-1pair", "rep8-2pairs", "rep8-8pairs", "d64-rep4-8pairs"])
-def test_merge_inside_the_launch_with_many_pieces_per_pair(d, Hq, Hkv, n):
+def test_merge_inside_the_launch_with_many_pieces_per_pair(d, Hq, Hkv, n, monkeypatch):
     """One sequence and few kv heads with a long context: the launch is still one resident round, so the last workgroup
     of a pair merges - with one or two pairs more partials than one wave's block of 32, so the merge runs several
     blocks joined by its running maximum, with one wave per head (16 or 8 query heads per kv head) and with two;
     8 pairs take the XCD-local hand-off, fewer the device-scope one.  Decode on the filled cache, then three steps."""
     S, W = 8, 32
+    monkeypatch.delenv("POD_DECODE_FUSED", raising=False)   # (read when the cache is created)
     c = Case(2, 2, Hq, Hkv, d, S, W, 1, n + 8, seed=510 + Hq)
     for layer in range(2):
         c.fill(layer, 0, n)
