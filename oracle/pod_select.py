@@ -16,8 +16,11 @@ combination can shrink, the distant tokens (the proximal ones are kept in full b
              tokens, i.e. it is the cache of that shorter sequence.
 
 Plain numpy in float64 (steps 2-3 also in the precision they are handed, since they decide integers); loops over
-heads and queries, no blocking.  Pins: tests/test_oracle_pins.py (library softmax, convolution and rank-filter
-routines, closed forms for constant queries, brute force, conservation of the attention mass).
+heads and queries, no blocking.  Pins: tests/test_oracle_select_pins.py (library softmax, convolution and rank-filter
+routines, closed forms for constant queries, brute force, conservation of the attention mass, the memory figures of
+the paper's efficiency table).  Each function is pinned to the mathematics stated above; that this rule is the one the
+paper's authors ran is a reading (the paper names the method and two settings, prints no rule and no worked example):
+against the paper's own combination, parity unpinned.
 """
 from __future__ import annotations
 
