@@ -409,9 +409,12 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void decode_partial_kernel(decode_
         nd_eff = min((n_dist + (hot.chunk & 0xffff) - 1) / (hot.chunk & 0xffff), max_nd);
         np_eff = min((n_prox + chunk_p - 1) / chunk_p, hot.nc - max_nd);
     }
-    // FUSE 2: the workgroup of the first proximal piece also takes the new token and the cache update; it arrives once
-    // for both partials, also when the cache was empty and it has no piece of its own
-    const bool hosts_step = STEP && c == max_nd;
+    // A step: one workgroup of the pair also takes the new token and the cache update; it arrives once for both
+    // partials.  FUSE 2: the workgroup of the LAST distant piece, which is the pair's shortest on average (the first
+    // proximal piece, which hosted the step before, is its longest: its tile loop ended 1.35 us after the others' and
+    // its pair waited for it); the first proximal piece where there is no distant token, also when the cache is empty
+    // and that workgroup has no piece of its own.
+    const bool hosts_step = STEP && c == (FUSE == 2 && nd_eff > 0 ? nd_eff - 1 : max_nd);
     const int expected = nd_eff + (FUSE == 2 && np_eff == 0 ? 1 : np_eff);
     if (hosts_step) step_workgroup<D, LOC, NW, MODE>(p, hot, b, h, n, head_arg);
     const bool distant = c < max_nd;
