@@ -319,9 +319,10 @@ __device__ void step_workgroup(const decode_params &p, const decode_hot &hot, in
 
 // FUSE 0: partials only, decode_combine_kernel follows.  FUSE 1 (MODE 0 only): the last workgroup of a (sequence, kv
 // head) pair to store its partial merges them all and writes the output rows.  FUSE 2: FUSE 1 for a decode STEP: the
-// cache holds the tokens before the new one; the workgroup of a pair's first proximal piece first handles the new token
-// and the token it displaces from the window and performs the cache update (step_workgroup), then walks its piece
-// like everybody else walks theirs: over the old rows.  FUSE 3: a step whose partials decode_combine_kernel merges
+// cache holds the tokens before the new one; one workgroup of the pair (that of its last distant piece; of its first
+// proximal piece where there is no distant token, and in FUSE 3) first handles the new token and the token it displaces
+// from the window and performs the cache update (step_workgroup), then walks its piece like everybody else walks
+// theirs: over the old rows.  FUSE 3: a step whose partials decode_combine_kernel merges
 // (launches of several rounds of workgroups: there a workgroup that waits for its arrival to be counted holds its
 // slot idle, which costs more than the second launch).
 template <int D, int MODE, int FUSE = 0, bool LOC = false, int NW = fuse_waves(FUSE)>
@@ -978,8 +979,8 @@ __device__ inline float dot8_bf16(u32x4 a, u32x4 b)
     return s;
 }
 
-// A decode step's extra work for one (sequence, kv head) pair, done by the workgroup of the pair's first proximal piece
-// before it turns to that piece: the new token at position pos and, once the
+// A decode step's extra work for one (sequence, kv head) pair, done by one of the pair's workgroups (the even split:
+// by a workgroup of its own) before it turns to its piece: the new token at position pos and, once the
 // window is full, the token at pos - W that it displaces (derived from the index ranges of Eq. 3: that token turns
 // distant).  It (1) checks the position against the stored length, (2) stores a partial over these two tokens - the
 // new one proximal, with the layer's own query and the new key; the displaced one distant, with the key the block's
